@@ -1,0 +1,139 @@
+/*
+ * alst.h -- C ABI of the MI355X (gfx950) sequence-tiled LM-head projection + cross-entropy.
+ *
+ * The operation (ALST paper, section "Sequence Tiling for Reducing Activation Memory
+ * Footprint", the tiled logits + loss computation): the LM-head logits z = hidden * W^T are
+ * never held for the whole sequence.  The sequence is cut into tiles of `tile` rows; for each
+ * tile the logits are produced, consumed by the loss and by the gradients, and dropped, so the
+ * memory the logits need is O(tile * V) instead of O(N * V).  Rows carry no cross-sequence
+ * dependency, therefore the result equals the untiled projection + cross-entropy.
+ * Labels (section "Loss Sharding in Hugging Face Transformers") are ALREADY shifted to line up
+ * with the hidden rows; the library does no shifting.  A label equal to `ignore_index`
+ * (-100 in the paper) leaves its token out of the loss.
+ *
+ *   z[i,v]  = sum_k hidden[i,k] W[v,k]            fp32 accumulation of bf16 products
+ *   lse[i]  = log sum_v exp z[i,v]
+ *   L       = (1/M) sum_{valid i} (lse[i] - z[i,label_i]),  M = #valid   (M == 0: L = 0, grads 0)
+ *   dz[i,v] = (g/M) valid_i (exp(z[i,v]-lse[i]) - [v == label_i])
+ *   dHidden = dz W          dW = dz^T hidden
+ *
+ * Conventions for every entry point
+ *   - All pointers are DEVICE pointers unless the comment says host.  `stream` is a hipStream_t
+ *     passed as void* (NULL = the default stream).
+ *   - Layout: dense row-major, no strides: hidden[N,H], W[V,H], dHidden[N,H], dW[V,H].
+ *     bf16 = bfloat16 (upper half of an IEEE binary32).  H must be a multiple of 8 and every
+ *     base pointer 16-byte aligned, else ALST_ERR_ALIGN.
+ *   - Ownership: the caller owns every buffer, including `workspace`; the library allocates and
+ *     frees no device memory and keeps no state between calls, so peak device memory is
+ *     inputs + outputs + alst_tiled_ce_workspace_bytes().  Calls that share a workspace must be
+ *     ordered on one stream.
+ *   - The functions validate on the host, enqueue work on `stream` and return without
+ *     synchronising.  Outputs are valid once the stream has been synchronised.
+ *   - Errors: an alst_status value is returned; host-detectable errors are returned before
+ *     anything is enqueued.  Conditions only the device can see (a label that is neither
+ *     ignore_index nor in [0,V), a non-finite loss) are recorded in a status word inside the
+ *     workspace, read with alst_last_device_status().  A row with an out-of-range label is
+ *     treated as ignored, so nothing is read or written out of bounds.
+ *   - tile: any value >= 1; a tile larger than N is clamped; N need not be a multiple of tile.
+ *     The tile size changes scheduling and memory only: the loss bits do not depend on it.
+ */
+#ifndef ALST_H
+#define ALST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ALST_OK = 0,
+    ALST_ERR_NULL = 1,        /* a required pointer is NULL */
+    ALST_ERR_SHAPE = 2,       /* N, H, V or tile < 1, or a size beyond the supported range */
+    ALST_ERR_ALIGN = 3,       /* H % 8 != 0 or a base pointer not 16-byte aligned */
+    ALST_ERR_WORKSPACE = 4,   /* workspace_bytes smaller than alst_tiled_ce_workspace_bytes() */
+    ALST_ERR_LABEL_RANGE = 5, /* device: a label outside [0,V) that is not ignore_index */
+    ALST_ERR_HIP = 6,         /* a HIP runtime call or kernel launch failed */
+    ALST_ERR_UNSUPPORTED = 7, /* unknown flag bits */
+    ALST_ERR_NONFINITE = 8    /* device: the loss is not finite */
+} alst_status;
+
+/* dW is written as fp32 instead of bf16. */
+#define ALST_FLAG_DW_FP32 1u
+/* dW += gradient instead of dW = gradient (dHidden is always overwritten). */
+#define ALST_FLAG_DW_ACCUMULATE 2u
+
+/* Static, NUL-terminated description of a status value.  Host only. */
+const char* alst_status_string(int status);
+
+/* Library version, major * 10000 + minor * 100 + patch.  Host only. */
+int alst_version(void);
+
+/*
+ * Bytes of device scratch the three compute entry points need for this problem, 0 if the
+ * shape is invalid.  Pure host arithmetic, no device access.  The value is independent of N
+ * except for 8 * N bytes (per-row loss and lse): this is the memory contract of Sequence
+ * Tiling, peak = O(N * H) for the activations and their gradients + O(tile * V) + O(V * H).
+ */
+size_t alst_tiled_ce_workspace_bytes(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_t flags);
+
+/*
+ * Forward only: mean cross-entropy of the tiled LM-head projection (one logits sweep, 2NHV flop).
+ *   hidden  [N,H] bf16, W [V,H] bf16, labels [N] int32     inputs, not modified
+ *   loss_out    [1] fp32    mean over non-ignored tokens
+ *   lse_out     [N] fp32    per-row log-sum-exp, the only state backward needs; may be NULL
+ *   n_valid_out [1] int64   number of non-ignored tokens; may be NULL
+ */
+int alst_tiled_ce_forward(const void* hidden, const void* W, const int32_t* labels,
+                          int64_t N, int64_t H, int64_t V, int64_t tile, int32_t ignore_index,
+                          float* loss_out, float* lse_out, int64_t* n_valid_out,
+                          void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
+
+/*
+ * Backward only, from the lse a forward call produced (recomputes each tile's logits: 6NHV flop).
+ *   lse       [N] fp32      from alst_tiled_ce_forward
+ *   grad_loss host scalar   upstream gradient g of the loss (1.0f normally)
+ *   dHidden   [N,H] bf16    overwritten, every row; rows of ignored tokens are exactly 0
+ *   dW        [V,H] bf16 (fp32 with ALST_FLAG_DW_FP32); overwritten, or += with
+ *             ALST_FLAG_DW_ACCUMULATE.  Accumulation over the tiles is always fp32.
+ */
+int alst_tiled_ce_backward(const void* hidden, const void* W, const int32_t* labels,
+                           const float* lse,
+                           int64_t N, int64_t H, int64_t V, int64_t tile, int32_t ignore_index,
+                           float grad_loss, void* dHidden, void* dW,
+                           void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
+
+/*
+ * Forward and backward of every tile in one sweep, as the paper's method does it ("compute the
+ * forward and backward passes on each shard independently"): 6NHV flop, each tile's logits are
+ * computed once.  Arguments as in the two calls above; lse_out and n_valid_out may be NULL.
+ */
+int alst_tiled_ce_forward_backward(const void* hidden, const void* W, const int32_t* labels,
+                                   int64_t N, int64_t H, int64_t V, int64_t tile,
+                                   int32_t ignore_index, float grad_loss,
+                                   float* loss_out, float* lse_out, int64_t* n_valid_out,
+                                   void* dHidden, void* dW,
+                                   void* workspace, size_t workspace_bytes, uint32_t flags,
+                                   void* stream);
+
+/*
+ * Synchronises `stream`, then reads and clears the device status word that the last call on this
+ * workspace left: ALST_OK, ALST_ERR_LABEL_RANGE or ALST_ERR_NONFINITE (ALST_ERR_HIP if the copy
+ * fails).  `workspace` must be one that a compute entry point has used.
+ */
+int alst_last_device_status(void* workspace, void* stream);
+
+/*
+ * Label utility for the boundary convention above (section "Loss Sharding in Hugging Face
+ * Transformers"): shift_labels[i] = labels[i+1] for i < N-1, shift_labels[N-1] = ignore_index,
+ * done on the whole sequence BEFORE it is cut along the sequence dimension, so no shard loses
+ * its first label.  labels and shift_labels are device int32 [N] and must not overlap.
+ */
+int alst_shift_labels(const int32_t* labels, int32_t* shift_labels, int64_t N,
+                      int32_t ignore_index, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ALST_H */

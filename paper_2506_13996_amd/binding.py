@@ -1,0 +1,141 @@
+"""Thin ctypes binding of libalst.so (include/alst.h).  Argument marshalling only.
+
+torch is used for device memory and the current HIP stream; every step of the path runs inside
+the library's kernels.  There is no fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libalst.so")
+
+ALST_OK = 0
+ALST_ERR_NULL, ALST_ERR_SHAPE, ALST_ERR_ALIGN, ALST_ERR_WORKSPACE = 1, 2, 3, 4
+ALST_ERR_LABEL_RANGE, ALST_ERR_HIP, ALST_ERR_UNSUPPORTED, ALST_ERR_NONFINITE = 5, 6, 7, 8
+ALST_FLAG_DW_FP32 = 1
+ALST_FLAG_DW_ACCUMULATE = 2
+
+EXPORTS = (
+    "alst_status_string", "alst_version", "alst_tiled_ce_workspace_bytes", "alst_tiled_ce_forward",
+    "alst_tiled_ce_backward", "alst_tiled_ce_forward_backward", "alst_last_device_status",
+    "alst_shift_labels",
+)
+
+_lib = None
+
+
+class AlstError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({alst_status_string(status)})")
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libalst.so (built by `python -m paper_2506_13996_amd.build`); raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2506_13996_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    vp, i64, i32, u32, f32, sz = c.c_void_p, c.c_int64, c.c_int32, c.c_uint32, c.c_float, c.c_size_t
+    lib.alst_status_string.restype = c.c_char_p
+    lib.alst_status_string.argtypes = [c.c_int]
+    lib.alst_version.restype = c.c_int
+    lib.alst_version.argtypes = []
+    lib.alst_tiled_ce_workspace_bytes.restype = sz
+    lib.alst_tiled_ce_workspace_bytes.argtypes = [i64, i64, i64, i64, u32]
+    lib.alst_tiled_ce_forward.restype = c.c_int
+    lib.alst_tiled_ce_forward.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, vp, vp, vp, vp, sz, u32, vp]
+    lib.alst_tiled_ce_backward.restype = c.c_int
+    lib.alst_tiled_ce_backward.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i32, f32, vp, vp, vp, sz, u32, vp]
+    lib.alst_tiled_ce_forward_backward.restype = c.c_int
+    lib.alst_tiled_ce_forward_backward.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, f32, vp, vp, vp, vp, vp, vp, sz, u32, vp]
+    lib.alst_last_device_status.restype = c.c_int
+    lib.alst_last_device_status.argtypes = [vp, vp]
+    lib.alst_shift_labels.restype = c.c_int
+    lib.alst_shift_labels.argtypes = [vp, vp, i64, i32, vp]
+    _lib = lib
+    return lib
+
+
+def alst_status_string(status: int) -> str:
+    return load_library().alst_status_string(int(status)).decode()
+
+
+def alst_version() -> int:
+    return load_library().alst_version()
+
+
+def alst_tiled_ce_workspace_bytes(N: int, H: int, V: int, tile: int, flags: int = 0) -> int:
+    return int(load_library().alst_tiled_ce_workspace_bytes(N, H, V, tile, flags))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status: int, where: str) -> None:
+    if status != ALST_OK:
+        raise AlstError(status, where)
+
+
+def alloc_workspace(N: int, H: int, V: int, tile: int, flags: int = 0, device="cuda") -> torch.Tensor:
+    nbytes = alst_tiled_ce_workspace_bytes(N, H, V, tile, flags)
+    if nbytes == 0:
+        raise AlstError(ALST_ERR_SHAPE, "alst_tiled_ce_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def alst_tiled_ce_forward(hidden, W, labels, tile: int, ignore_index: int = -100, *, loss_out,
+                          lse_out=None, n_valid_out=None, workspace, flags: int = 0) -> None:
+    """hidden [N,H] bf16, W [V,H] bf16, labels [N] int32 (device tensors); results are written
+    into loss_out [1] f32, lse_out [N] f32, n_valid_out [1] int64.  Asynchronous on the current
+    stream."""
+    N, H = hidden.shape
+    V = W.shape[0]
+    st = load_library().alst_tiled_ce_forward(
+        _ptr(hidden), _ptr(W), _ptr(labels), N, H, V, tile, ignore_index, _ptr(loss_out),
+        _ptr(lse_out), _ptr(n_valid_out), _ptr(workspace), workspace.numel(), flags, _stream())
+    _check(st, "alst_tiled_ce_forward")
+
+
+def alst_tiled_ce_backward(hidden, W, labels, lse, tile: int, ignore_index: int = -100,
+                           grad_loss: float = 1.0, *, dHidden, dW, workspace, flags: int = 0) -> None:
+    N, H = hidden.shape
+    V = W.shape[0]
+    st = load_library().alst_tiled_ce_backward(
+        _ptr(hidden), _ptr(W), _ptr(labels), _ptr(lse), N, H, V, tile, ignore_index, grad_loss,
+        _ptr(dHidden), _ptr(dW), _ptr(workspace), workspace.numel(), flags, _stream())
+    _check(st, "alst_tiled_ce_backward")
+
+
+def alst_tiled_ce_forward_backward(hidden, W, labels, tile: int, ignore_index: int = -100,
+                                   grad_loss: float = 1.0, *, loss_out, lse_out=None,
+                                   n_valid_out=None, dHidden, dW, workspace, flags: int = 0) -> None:
+    N, H = hidden.shape
+    V = W.shape[0]
+    st = load_library().alst_tiled_ce_forward_backward(
+        _ptr(hidden), _ptr(W), _ptr(labels), N, H, V, tile, ignore_index, grad_loss,
+        _ptr(loss_out), _ptr(lse_out), _ptr(n_valid_out), _ptr(dHidden), _ptr(dW),
+        _ptr(workspace), workspace.numel(), flags, _stream())
+    _check(st, "alst_tiled_ce_forward_backward")
+
+
+def alst_last_device_status(workspace) -> int:
+    return int(load_library().alst_last_device_status(_ptr(workspace), _stream()))
+
+
+def alst_shift_labels(labels, shift_labels, ignore_index: int = -100) -> None:
+    st = load_library().alst_shift_labels(_ptr(labels), _ptr(shift_labels), labels.numel(),
+                                          ignore_index, _stream())
+    _check(st, "alst_shift_labels")

@@ -1,0 +1,820 @@
+// Sequence-tiled LM-head projection + cross-entropy for gfx950: kernels and the C ABI (alst.h).
+//
+// Per sequence tile of T rows (paper, section "Sequence Tiling for Reducing Activation Memory
+// Footprint": forward and backward of each logits shard are done together and the shard's
+// intermediates are dropped before the next shard):
+//
+//   1. logits_kernel     Z = H_t W^T in 256x256 blocks, fp32 accumulators.  The logits never
+//                        leave the registers: the epilogue reduces each row over the block's
+//                        columns to (max, sum exp) partials per 128-column group, picks out the
+//                        label logit, and writes e = exp(z - group max) as bf16 to a [T, V]
+//                        scratch ("stash").
+//   2. row_combine       partials -> lse, per-row loss, and the factor exp(group max - lse)
+//                        that turns e into the softmax probability.
+//   3. dz_finalize       dZ = valid * (e * factor - onehot) as bf16, in place, plus its transpose.
+//   4. dhidden_kernel    dH_t = (g/M) dZ W          (contraction over V)
+//   5. dw_kernel         acc += dZ^T H_t            (contraction over the tile's rows, fp32)
+//
+// After the last tile: loss = sum(per-row loss) / M in a fixed order, dW = (g/M) acc.
+// All three contractions use the same k-contiguous block GEMM (gemm_tile.h); W^T and H_t^T are
+// made by a padded transpose so that every operand has its contraction index contiguous.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <math.h>
+
+#include "../../include/alst.h"
+#include "gemm_tile.h"
+
+namespace alst {
+
+// ---------------------------------------------------------------------------------------------
+// workspace
+// ---------------------------------------------------------------------------------------------
+struct Header {
+    int status;            // alst_status set by kernels
+    int pad0;
+    long long n_valid;     // M
+    float inv;             // g / M (0 when M == 0)
+    float pad1;
+    double loss_sum;
+};
+
+struct Layout {
+    int64_t Tp, Vp, ng;    // padded tile rows, padded vocabulary, 128-column groups
+    size_t header, loss_rows, lse, zlabel, pm, ps, sc, stash, dzt, wt, ht, acc, total;
+};
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static Layout make_layout(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_t flags) {
+    Layout L;
+    const int64_t T = tile < N ? tile : N;
+    L.Tp = (T + 255) / 256 * 256;
+    L.Vp = (V + 255) / 256 * 256;
+    L.ng = L.Vp / 128;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    L.header = take(sizeof(Header));
+    L.loss_rows = take((size_t)N * 4);
+    L.lse = take((size_t)N * 4);
+    L.zlabel = take((size_t)L.Tp * 4);
+    L.pm = take((size_t)L.ng * L.Tp * 4);
+    L.ps = take((size_t)L.ng * L.Tp * 4);
+    L.sc = take((size_t)L.ng * L.Tp * 4);
+    L.stash = take((size_t)L.Tp * L.Vp * 2);
+    L.dzt = take((size_t)L.Vp * L.Tp * 2);
+    L.wt = take((size_t)H * L.Vp * 2);
+    L.ht = take((size_t)H * L.Tp * 2);
+    const bool acc_in_dw = (flags & ALST_FLAG_DW_FP32) && !(flags & ALST_FLAG_DW_ACCUMULATE);
+    L.acc = take(acc_in_dw ? 0 : (size_t)V * H * 4);
+    L.total = o;
+    return L;
+}
+
+// ---------------------------------------------------------------------------------------------
+// small kernels
+// ---------------------------------------------------------------------------------------------
+__global__ void init_header_kernel(Header* h) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        h->status = 0;
+        h->n_valid = 0;
+        h->inv = 0.f;
+        h->loss_sum = 0.0;
+    }
+}
+
+__device__ __forceinline__ bool label_valid(int y, int ignore_index, int V) {
+    return y != ignore_index && y >= 0 && y < V;
+}
+
+// M = number of labels that take part in the loss; flags labels outside [0, V).
+__global__ void count_valid_kernel(const int32_t* __restrict__ labels, int64_t N, int ignore_index,
+                                   int V, Header* h) {
+    int cnt = 0;
+    bool bad = false;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int y = labels[i];
+        if (y != ignore_index) {
+            if (y >= 0 && y < V) ++cnt; else bad = true;
+        }
+    }
+    __shared__ int s_cnt;
+    __shared__ int s_bad;
+    if (threadIdx.x == 0) { s_cnt = 0; s_bad = 0; }
+    __syncthreads();
+    if (cnt) atomicAdd(&s_cnt, cnt);
+    if (bad) atomicOr(&s_bad, 1);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        if (s_cnt) atomicAdd((unsigned long long*)&h->n_valid, (unsigned long long)s_cnt);
+        if (s_bad) atomicMax(&h->status, (int)ALST_ERR_LABEL_RANGE);
+    }
+}
+
+__global__ void set_scale_kernel(Header* h, float grad_loss, int64_t* n_valid_out) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        const long long M = h->n_valid;
+        h->inv = M > 0 ? grad_loss / (float)M : 0.f;
+        if (n_valid_out) *n_valid_out = M;
+    }
+}
+
+// out[c][r] = in[r][c] for r < R, 0 for R <= r < Rpad; c < C.  16-byte accesses on both sides.
+__global__ __launch_bounds__(256) void transpose_pad_kernel(const uint16_t* __restrict__ in,
+                                                            int64_t ld_in, int R, int C,
+                                                            uint16_t* __restrict__ out,
+                                                            int64_t ld_out, int Rpad) {
+    __shared__ uint16_t t[64][66];
+    const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int chunk = tid + 256 * q;
+        const int row = chunk >> 3, cc = chunk & 7;
+        const int r = r0 + row, c = c0 + cc * 8;
+        u32x4_t v = {0u, 0u, 0u, 0u};
+        if (r < R && c + 8 <= C) v = *reinterpret_cast<const u32x4_t*>(in + (int64_t)r * ld_in + c);
+        const uint16_t* e = reinterpret_cast<const uint16_t*>(&v);
+#pragma unroll
+        for (int x = 0; x < 8; ++x) t[row][cc * 8 + x] = e[x];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int chunk = tid + 256 * q;
+        const int crow = chunk >> 3, rc = chunk & 7;
+        const int c = c0 + crow, r = r0 + rc * 8;
+        if (c < C && r + 8 <= Rpad) {
+            u32x4_t v;
+            uint16_t* e = reinterpret_cast<uint16_t*>(&v);
+#pragma unroll
+            for (int x = 0; x < 8; ++x) e[x] = t[rc * 8 + x][crow];
+            *reinterpret_cast<u32x4_t*>(out + (int64_t)c * ld_out + r) = v;
+        }
+    }
+}
+
+// Per row of the tile: combine the per-group (max, sum exp) partials into lse, the row's loss
+// term, and (fused mode) the factor that turns the stashed e into a probability.
+__global__ void row_combine_kernel(const float* __restrict__ pm, const float* __restrict__ ps,
+                                   const float* __restrict__ zlabel,
+                                   const int32_t* __restrict__ labels_t, int T_cur, int Tr, int Tp,
+                                   int ng, int ignore_index, int V, float* __restrict__ lse_t,
+                                   float* __restrict__ loss_rows_t, float* __restrict__ sc) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= Tr) return;
+    const bool inrow = i < T_cur;
+    float M = -INFINITY;
+    for (int g = 0; g < ng; ++g) M = fmaxf(M, pm[(int64_t)g * Tp + i]);
+    float S = 0.f;
+    for (int g = 0; g < ng; ++g) S += ps[(int64_t)g * Tp + i] * __expf(pm[(int64_t)g * Tp + i] - M);
+    const float lse = M + __logf(S);
+    const bool valid = inrow && label_valid(labels_t[inrow ? i : 0], ignore_index, V);
+    if (inrow) {
+        lse_t[i] = lse;
+        loss_rows_t[i] = valid ? lse - zlabel[i] : 0.f;
+    }
+    if (sc) {
+        for (int g = 0; g < ng; ++g)
+            sc[(int64_t)g * Tp + i] = valid ? __expf(pm[(int64_t)g * Tp + i] - lse) : 0.f;
+    }
+}
+
+// dZ = valid * (e * factor - onehot), bf16, written over the stash and transposed into dzt.
+// Rows >= T_cur and columns >= V come out as exact zeros, which is what pads the k dimension of
+// the two gradient GEMMs.
+template <bool FUSED>
+__global__ __launch_bounds__(256) void dz_finalize_kernel(uint16_t* __restrict__ stash,
+                                                          uint16_t* __restrict__ dzt,
+                                                          const float* __restrict__ sc,
+                                                          const int32_t* __restrict__ labels_t,
+                                                          int T_cur, int Tp, int Vp, int V,
+                                                          int ignore_index) {
+    __shared__ uint16_t t[64][66];
+    const int v0 = blockIdx.x * 64, i0 = blockIdx.y * 64;
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int chunk = tid + 256 * q;
+        const int row = chunk >> 3, cc = chunk & 7;
+        const int i = i0 + row, v = v0 + cc * 8;
+        uint16_t* p = stash + (int64_t)i * Vp + v;
+        const bf16x8_t e = *reinterpret_cast<const bf16x8_t*>(p);
+        const int y = i < T_cur ? labels_t[i] : ignore_index;
+        const bool valid = i < T_cur && label_valid(y, ignore_index, V);
+        float f = valid ? 1.f : 0.f;
+        if (FUSED) f = valid ? sc[(int64_t)(v >> 7) * Tp + i] : 0.f;
+        bf16x8_t d;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            float val = (float)e[x] * f;
+            if (valid && v + x == y) val -= 1.f;
+            d[x] = (__bf16)val;
+        }
+        *reinterpret_cast<bf16x8_t*>(p) = d;
+        const uint16_t* du = reinterpret_cast<const uint16_t*>(&d);
+#pragma unroll
+        for (int x = 0; x < 8; ++x) t[row][cc * 8 + x] = du[x];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int chunk = tid + 256 * q;
+        const int vrow = chunk >> 3, ic = chunk & 7;
+        u32x4_t o;
+        uint16_t* e = reinterpret_cast<uint16_t*>(&o);
+#pragma unroll
+        for (int x = 0; x < 8; ++x) e[x] = t[ic * 8 + x][vrow];
+        *reinterpret_cast<u32x4_t*>(dzt + (int64_t)(v0 + vrow) * Tp + i0 + ic * 8) = o;
+    }
+}
+
+// loss = (sum of the per-row terms in a fixed order) / M.  One block.
+__global__ __launch_bounds__(1024) void loss_reduce_kernel(const float* __restrict__ loss_rows,
+                                                           int64_t N, Header* h,
+                                                           float* __restrict__ loss_out) {
+    __shared__ double part[1024];
+    double s = 0.0;
+    for (int64_t i = threadIdx.x; i < N; i += 1024) s += (double)loss_rows[i];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 512; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) part[threadIdx.x] += part[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const long long M = h->n_valid;
+        const double L = M > 0 ? part[0] / (double)M : 0.0;
+        h->loss_sum = part[0];
+        *loss_out = (float)L;
+        if (!isfinite(L)) atomicMax(&h->status, (int)ALST_ERR_NONFINITE);
+    }
+}
+
+// dW = (g/M) acc  (bf16 or fp32, overwrite or +=).  acc may alias dW (fp32 overwrite mode).
+template <bool OUT_F32, bool ACCUM>
+__global__ void dw_finalize_kernel(const float* acc, void* dW, int64_t n4, const Header* h) {
+    const float inv = h->inv;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        f32x4_t a = reinterpret_cast<const f32x4_t*>(acc)[i];
+        a *= inv;
+        if (OUT_F32) {
+            f32x4_t* o = reinterpret_cast<f32x4_t*>(dW) + i;
+            if (ACCUM) a += *o;
+            *o = a;
+        } else {
+            bf16x4_t* o = reinterpret_cast<bf16x4_t*>(dW) + i;
+            if (ACCUM) {
+                const bf16x4_t old = *o;
+#pragma unroll
+                for (int x = 0; x < 4; ++x) a[x] += (float)old[x];
+            }
+            bf16x4_t r;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) r[x] = (__bf16)a[x];
+            *o = r;
+        }
+    }
+}
+
+__global__ void shift_labels_kernel(const int32_t* __restrict__ labels, int32_t* __restrict__ out,
+                                    int64_t N, int ignore_index) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N;
+         i += (int64_t)gridDim.x * blockDim.x)
+        out[i] = i + 1 < N ? labels[i + 1] : ignore_index;
+}
+
+// ---------------------------------------------------------------------------------------------
+// the three block GEMMs
+// ---------------------------------------------------------------------------------------------
+enum { MODE_FWD = 0, MODE_FUSED = 1, MODE_BWD = 2 };
+
+struct LogitsParams {
+    const uint16_t* hidden_t;   // [T_cur, H]
+    const uint16_t* W;          // [V, H]
+    const int32_t* labels_t;    // [T_cur]
+    const float* lse_t;         // [T_cur]      MODE_BWD
+    float* pm;                  // [ng, Tp]     MODE_FWD / MODE_FUSED
+    float* ps;                  // [ng, Tp]
+    float* zlabel;              // [Tp]
+    uint16_t* stash;            // [Tp, Vp]     MODE_FUSED / MODE_BWD
+    int T_cur, Tr, Tp, H, V, Vp, ignore_index;   // Tr = T_cur rounded up to 256, Tp = row stride
+};
+
+// r = token row of the tile (MFMA lane dimension), c = vocabulary id (register dimension).
+template <bool GUARD, int MODE>
+__global__ __launch_bounds__(kThreads) void logits_kernel(const LogitsParams p) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    int tr, tc;
+    if (!tile_of_block<4, 8>(blockIdx.x, p.Tr / kBlockR, p.Vp / kBlockC, tr, tc)) return;
+    const int r0 = tr * kBlockR, c0 = tc * kBlockC;
+
+    f32x16_t acc[kMT][kNT];
+#pragma unroll
+    for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < kNT; ++nt)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
+
+    block_gemm<GUARD>(p.hidden_t, p.H, p.T_cur, p.W, p.H, p.V, p.H, r0, c0, smem, acc);
+
+    const LanePos lp;
+    const bool mask_cols = c0 + kBlockC > p.V;
+#pragma unroll
+    for (int nt = 0; nt < kNT; ++nt) {
+        const int i = r0 + lp.r(nt);
+        const bool rowok = i < p.T_cur;
+        if (mask_cols) {
+#pragma unroll
+            for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    if (c0 + lp.c(mt, j >> 2) + (j & 3) >= p.V) acc[mt][nt][j] = -INFINITY;
+        }
+        float ref;
+        if (MODE == MODE_BWD) {
+            ref = rowok ? p.lse_t[i] : 0.f;
+        } else {
+            float m = -INFINITY;
+#pragma unroll
+            for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) m = fmaxf(m, acc[mt][nt][j]);
+            m = fmaxf(m, __shfl_xor(m, 32));
+            ref = (m == -INFINITY) ? 0.f : m;
+            // label logit: exactly one lane of one block holds column y of row i
+            int y = rowok ? p.labels_t[i] : -1;
+            if (y == p.ignore_index) y = -1;
+            const unsigned d = (unsigned)(y - (c0 + lp.wc * kWaveC));
+            if (y >= 0 && d < (unsigned)kWaveC && ((d >> 2) & 1u) == (unsigned)lp.half) {
+                float zl = 0.f;
+#pragma unroll
+                for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j)
+                        if (d == (unsigned)(mt * 32 + (j >> 2) * 8 + lp.half * 4 + (j & 3)))
+                            zl = acc[mt][nt][j];
+                p.zlabel[i] = zl;
+            }
+            float s = 0.f;
+#pragma unroll
+            for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const float e = __expf(acc[mt][nt][j] - ref);
+                    acc[mt][nt][j] = e;
+                    s += e;
+                }
+            s += __shfl_xor(s, 32);
+            if (lp.half == 0) {
+                const int64_t g = (c0 + lp.wc * kWaveC) >> 7;
+                p.pm[g * p.Tp + i] = m;
+                p.ps[g * p.Tp + i] = s;
+            }
+        }
+        if (MODE != MODE_FWD) {
+            uint16_t* row = p.stash + (int64_t)i * p.Vp + c0;
+#pragma unroll
+            for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    bf16x4_t o;
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) {
+                        const float z = acc[mt][nt][q * 4 + x];
+                        o[x] = (__bf16)(MODE == MODE_BWD ? __expf(z - ref) : z);
+                    }
+                    *reinterpret_cast<bf16x4_t*>(row + lp.c(mt, q)) = o;
+                }
+        }
+    }
+}
+
+struct DHiddenParams {
+    const uint16_t* dz;      // [Tp, Vp]
+    const uint16_t* wt;      // [H, Vp]
+    uint16_t* dH_t;          // [T_cur, H]
+    const Header* hdr;
+    int T_cur, Tr, Tp, H, Vp;
+};
+
+// r = token row (lane dimension), c = hidden index (register dimension), k = vocabulary.
+template <bool GUARD>
+__global__ __launch_bounds__(kThreads) void dhidden_kernel(const DHiddenParams p) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    int tr, tc;
+    const int tiles_c = (p.H + kBlockC - 1) / kBlockC;
+    if (!tile_of_block<4, 8>(blockIdx.x, p.Tr / kBlockR, tiles_c, tr, tc)) return;
+    const int r0 = tr * kBlockR, c0 = tc * kBlockC;
+    if (r0 >= p.T_cur) return;      // rows that do not exist in a ragged tile
+
+    f32x16_t acc[kMT][kNT];
+#pragma unroll
+    for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < kNT; ++nt)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
+
+    block_gemm<GUARD>(p.dz, p.Vp, p.Tr, p.wt, p.Vp, p.H, p.Vp, r0, c0, smem, acc);
+
+    const LanePos lp;
+    const float inv = p.hdr->inv;
+#pragma unroll
+    for (int nt = 0; nt < kNT; ++nt) {
+        const int i = r0 + lp.r(nt);
+        if (i >= p.T_cur) continue;
+        uint16_t* row = p.dH_t + (int64_t)i * p.H;
+#pragma unroll
+        for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int h = c0 + lp.c(mt, q);
+                if (GUARD && h >= p.H) continue;
+                bf16x4_t o;
+#pragma unroll
+                for (int x = 0; x < 4; ++x) o[x] = (__bf16)(acc[mt][nt][q * 4 + x] * inv);
+                *reinterpret_cast<bf16x4_t*>(row + h) = o;
+            }
+    }
+}
+
+struct DWParams {
+    const uint16_t* dzt;     // [Vp, Tp]
+    const uint16_t* ht;      // [H, Tp]
+    float* acc;              // [V, H]
+    int Tk;                  // rows of the tile rounded up to 64 (k extent)
+    int Tp, H, V, Vp;
+    int first;               // first tile: store instead of add
+};
+
+// r = vocabulary id (lane dimension), c = hidden index (register dimension), k = token row.
+template <bool GUARD>
+__global__ __launch_bounds__(kThreads) void dw_kernel(const DWParams p) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    int tr, tc;
+    const int tiles_c = (p.H + kBlockC - 1) / kBlockC;
+    if (!tile_of_block<8, 4>(blockIdx.x, p.Vp / kBlockR, tiles_c, tr, tc)) return;
+    const int r0 = tr * kBlockR, c0 = tc * kBlockC;
+
+    f32x16_t acc[kMT][kNT];
+#pragma unroll
+    for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < kNT; ++nt)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
+
+    block_gemm<GUARD>(p.dzt, p.Tp, p.Vp, p.ht, p.Tp, p.H, p.Tk, r0, c0, smem, acc);
+
+    const LanePos lp;
+#pragma unroll
+    for (int nt = 0; nt < kNT; ++nt) {
+        const int v = r0 + lp.r(nt);
+        if (v >= p.V) continue;
+        float* row = p.acc + (int64_t)v * p.H;
+#pragma unroll
+        for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int h = c0 + lp.c(mt, q);
+                if (GUARD && h >= p.H) continue;
+                f32x4_t a;
+#pragma unroll
+                for (int x = 0; x < 4; ++x) a[x] = acc[mt][nt][q * 4 + x];
+                f32x4_t* o = reinterpret_cast<f32x4_t*>(row + h);
+                if (!p.first) a += *o;
+                *o = a;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+#define ALST_HIP(call)                                   \
+    do {                                                 \
+        if ((call) != hipSuccess) return ALST_ERR_HIP;   \
+    } while (0)
+
+template <typename K>
+static int allow_big_lds(K kernel) {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) == hipSuccess
+               ? ALST_OK : ALST_ERR_HIP;
+}
+
+static int prepare_kernels() {
+    static int state = -1;      // same value whichever thread gets here first
+    if (state >= 0) return state;
+    int rc = ALST_OK;
+    auto acc = [&](int r) { if (r != ALST_OK) rc = r; };
+    acc(allow_big_lds(logits_kernel<false, MODE_FWD>));
+    acc(allow_big_lds(logits_kernel<true, MODE_FWD>));
+    acc(allow_big_lds(logits_kernel<false, MODE_FUSED>));
+    acc(allow_big_lds(logits_kernel<true, MODE_FUSED>));
+    acc(allow_big_lds(logits_kernel<false, MODE_BWD>));
+    acc(allow_big_lds(logits_kernel<true, MODE_BWD>));
+    acc(allow_big_lds(dhidden_kernel<false>));
+    acc(allow_big_lds(dhidden_kernel<true>));
+    acc(allow_big_lds(dw_kernel<false>));
+    acc(allow_big_lds(dw_kernel<true>));
+    state = rc;
+    return rc;
+}
+
+struct Problem {
+    const uint16_t* hidden;
+    const uint16_t* W;
+    const int32_t* labels;
+    const float* lse_in;
+    int64_t N, H, V, tile;
+    int ignore_index;
+    float grad_loss;
+    float* loss_out;
+    float* lse_out;
+    int64_t* n_valid_out;
+    uint16_t* dHidden;
+    void* dW;
+    unsigned char* ws;
+    uint32_t flags;
+    hipStream_t stream;
+};
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static int validate(const Problem& P, size_t workspace_bytes, bool need_fwd_out, bool need_bwd_out,
+                    bool need_lse_in) {
+    if (!P.hidden || !P.W || !P.labels || !P.ws) return ALST_ERR_NULL;
+    if (need_fwd_out && !P.loss_out) return ALST_ERR_NULL;
+    if (need_bwd_out && (!P.dHidden || !P.dW)) return ALST_ERR_NULL;
+    if (need_lse_in && !P.lse_in) return ALST_ERR_NULL;
+    if (P.flags & ~(ALST_FLAG_DW_FP32 | ALST_FLAG_DW_ACCUMULATE)) return ALST_ERR_UNSUPPORTED;
+    if (P.N < 1 || P.H < 1 || P.V < 1 || P.tile < 1) return ALST_ERR_SHAPE;
+    if (P.N > (int64_t)1 << 30 || P.H > (int64_t)1 << 20 || P.V > (int64_t)1 << 24)
+        return ALST_ERR_SHAPE;
+    if (P.H % 8 != 0) return ALST_ERR_ALIGN;
+    if (!aligned16(P.hidden) || !aligned16(P.W) || !aligned16(P.ws)) return ALST_ERR_ALIGN;
+    if (need_bwd_out && (!aligned16(P.dHidden) || !aligned16(P.dW))) return ALST_ERR_ALIGN;
+    const Layout L = make_layout(P.N, P.H, P.V, P.tile, P.flags);
+    if (workspace_bytes < L.total) return ALST_ERR_WORKSPACE;
+    return ALST_OK;
+}
+
+static int launch_transpose(const uint16_t* in, int64_t ld_in, int R, int C, uint16_t* out,
+                            int64_t ld_out, int Rpad, hipStream_t s) {
+    dim3 grid((Rpad + 63) / 64, (C + 63) / 64);
+    hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, s, in, ld_in, R, C, out, ld_out,
+                       Rpad);
+    return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
+}
+
+template <int MODE>
+static int launch_logits(const LogitsParams& lp, bool guard, hipStream_t s) {
+    const int grid = grid_for_tiles<4, 8>(lp.Tr / kBlockR, lp.Vp / kBlockC);
+    if (guard)
+        hipLaunchKernelGGL((logits_kernel<true, MODE>), dim3(grid), dim3(kThreads), kLdsBytes, s, lp);
+    else
+        hipLaunchKernelGGL((logits_kernel<false, MODE>), dim3(grid), dim3(kThreads), kLdsBytes, s, lp);
+    return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
+}
+
+// do_fwd: produce loss / lse.  do_bwd: produce gradients.  Both: one fused sweep.
+static int run(const Problem& P, bool do_fwd, bool do_bwd) {
+    int rc = prepare_kernels();
+    if (rc != ALST_OK) return rc;
+    const Layout L = make_layout(P.N, P.H, P.V, P.tile, P.flags);
+    hipStream_t s = P.stream;
+    Header* hdr = reinterpret_cast<Header*>(P.ws + L.header);
+    float* loss_rows = reinterpret_cast<float*>(P.ws + L.loss_rows);
+    float* lse_buf = P.lse_out ? P.lse_out : reinterpret_cast<float*>(P.ws + L.lse);
+    float* zlabel = reinterpret_cast<float*>(P.ws + L.zlabel);
+    float* pm = reinterpret_cast<float*>(P.ws + L.pm);
+    float* ps = reinterpret_cast<float*>(P.ws + L.ps);
+    float* sc = reinterpret_cast<float*>(P.ws + L.sc);
+    uint16_t* stash = reinterpret_cast<uint16_t*>(P.ws + L.stash);
+    uint16_t* dzt = reinterpret_cast<uint16_t*>(P.ws + L.dzt);
+    uint16_t* wt = reinterpret_cast<uint16_t*>(P.ws + L.wt);
+    uint16_t* ht = reinterpret_cast<uint16_t*>(P.ws + L.ht);
+    const bool acc_in_dw = (P.flags & ALST_FLAG_DW_FP32) && !(P.flags & ALST_FLAG_DW_ACCUMULATE);
+    float* acc = acc_in_dw ? reinterpret_cast<float*>(P.dW) : reinterpret_cast<float*>(P.ws + L.acc);
+
+    const int H = (int)P.H, V = (int)P.V, Tp = (int)L.Tp, Vp = (int)L.Vp, ng = (int)L.ng;
+    const int64_t T = P.tile < P.N ? P.tile : P.N;
+
+    hipLaunchKernelGGL(init_header_kernel, dim3(1), dim3(64), 0, s, hdr);
+    {
+        int blocks = (int)((P.N + 255) / 256);
+        if (blocks > 1024) blocks = 1024;
+        hipLaunchKernelGGL(count_valid_kernel, dim3(blocks), dim3(256), 0, s, P.labels, P.N,
+                           P.ignore_index, V, hdr);
+    }
+    hipLaunchKernelGGL(set_scale_kernel, dim3(1), dim3(64), 0, s, hdr, P.grad_loss, P.n_valid_out);
+    ALST_HIP(hipGetLastError());
+
+    if (do_bwd) {
+        rc = launch_transpose(P.W, H, V, H, wt, Vp, Vp, s);
+        if (rc != ALST_OK) return rc;
+    }
+
+    const int64_t ntiles = (P.N + T - 1) / T;
+    for (int64_t t = 0; t < ntiles; ++t) {
+        const int64_t i0 = t * T;
+        const int T_cur = (int)((P.N - i0) < T ? (P.N - i0) : T);
+        const uint16_t* hidden_t = P.hidden + i0 * P.H;
+        const int32_t* labels_t = P.labels + i0;
+        const int Tr = (T_cur + kBlockR - 1) / kBlockR * kBlockR;
+        const bool guard_rows = (T_cur % kBlockR) != 0;
+
+        LogitsParams lp;
+        lp.hidden_t = hidden_t;
+        lp.W = P.W;
+        lp.labels_t = labels_t;
+        lp.lse_t = do_fwd ? nullptr : P.lse_in + i0;
+        lp.pm = pm; lp.ps = ps; lp.zlabel = zlabel; lp.stash = stash;
+        lp.T_cur = T_cur; lp.Tr = Tr; lp.Tp = Tp; lp.H = H; lp.V = V; lp.Vp = Vp;
+        lp.ignore_index = P.ignore_index;
+        const bool guard1 = guard_rows || (V % kBlockC) != 0 || (H % kBlockK) != 0;
+        if (do_fwd && do_bwd) rc = launch_logits<MODE_FUSED>(lp, guard1, s);
+        else if (do_fwd) rc = launch_logits<MODE_FWD>(lp, guard1, s);
+        else rc = launch_logits<MODE_BWD>(lp, guard1, s);
+        if (rc != ALST_OK) return rc;
+
+        if (do_fwd) {
+            hipLaunchKernelGGL(row_combine_kernel, dim3(Tr / 256), dim3(256), 0, s, pm, ps,
+                               zlabel, labels_t, T_cur, Tr, Tp, ng, P.ignore_index, V, lse_buf + i0,
+                               loss_rows + i0, do_bwd ? sc : nullptr);
+            ALST_HIP(hipGetLastError());
+        }
+        if (!do_bwd) continue;
+
+        {
+            dim3 grid(Vp / 64, Tr / 64);
+            if (do_fwd)
+                hipLaunchKernelGGL(dz_finalize_kernel<true>, grid, dim3(256), 0, s, stash, dzt, sc,
+                                   labels_t, T_cur, Tp, Vp, V, P.ignore_index);
+            else
+                hipLaunchKernelGGL(dz_finalize_kernel<false>, grid, dim3(256), 0, s, stash, dzt, sc,
+                                   labels_t, T_cur, Tp, Vp, V, P.ignore_index);
+            ALST_HIP(hipGetLastError());
+        }
+        rc = launch_transpose(hidden_t, H, T_cur, H, ht, Tp, Tr, s);
+        if (rc != ALST_OK) return rc;
+
+        const bool guard_h = (H % kBlockC) != 0;
+        {
+            DHiddenParams dp;
+            dp.dz = stash; dp.wt = wt; dp.dH_t = P.dHidden + i0 * P.H; dp.hdr = hdr;
+            dp.T_cur = T_cur; dp.Tr = Tr; dp.Tp = Tp; dp.H = H; dp.Vp = Vp;
+            const int grid = grid_for_tiles<4, 8>(Tr / kBlockR, (H + kBlockC - 1) / kBlockC);
+            if (guard_h)
+                hipLaunchKernelGGL(dhidden_kernel<true>, dim3(grid), dim3(kThreads), kLdsBytes, s, dp);
+            else
+                hipLaunchKernelGGL(dhidden_kernel<false>, dim3(grid), dim3(kThreads), kLdsBytes, s, dp);
+            ALST_HIP(hipGetLastError());
+        }
+        {
+            DWParams wp;
+            wp.dzt = dzt; wp.ht = ht; wp.acc = acc;
+            wp.Tk = (T_cur + kBlockK - 1) / kBlockK * kBlockK;
+            wp.Tp = Tp; wp.H = H; wp.V = V; wp.Vp = Vp; wp.first = (t == 0);
+            const int grid = grid_for_tiles<8, 4>(Vp / kBlockR, (H + kBlockC - 1) / kBlockC);
+            if (guard_h)
+                hipLaunchKernelGGL(dw_kernel<true>, dim3(grid), dim3(kThreads), kLdsBytes, s, wp);
+            else
+                hipLaunchKernelGGL(dw_kernel<false>, dim3(grid), dim3(kThreads), kLdsBytes, s, wp);
+            ALST_HIP(hipGetLastError());
+        }
+    }
+
+    if (do_fwd) {
+        hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, loss_rows, P.N, hdr,
+                           P.loss_out);
+        ALST_HIP(hipGetLastError());
+    }
+    if (do_bwd) {
+        const int64_t n4 = P.V * P.H / 4;
+        int blocks = (int)((n4 + 255) / 256);
+        if (blocks > 8192) blocks = 8192;
+        const bool f32 = P.flags & ALST_FLAG_DW_FP32, accum = P.flags & ALST_FLAG_DW_ACCUMULATE;
+        if (f32 && accum)
+            hipLaunchKernelGGL((dw_finalize_kernel<true, true>), dim3(blocks), dim3(256), 0, s, acc, P.dW, n4, hdr);
+        else if (f32)
+            hipLaunchKernelGGL((dw_finalize_kernel<true, false>), dim3(blocks), dim3(256), 0, s, acc, P.dW, n4, hdr);
+        else if (accum)
+            hipLaunchKernelGGL((dw_finalize_kernel<false, true>), dim3(blocks), dim3(256), 0, s, acc, P.dW, n4, hdr);
+        else
+            hipLaunchKernelGGL((dw_finalize_kernel<false, false>), dim3(blocks), dim3(256), 0, s, acc, P.dW, n4, hdr);
+        ALST_HIP(hipGetLastError());
+    }
+    return ALST_OK;
+}
+
+}  // namespace alst
+
+// ---------------------------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------------------------
+using namespace alst;
+
+extern "C" {
+
+const char* alst_status_string(int status) {
+    switch (status) {
+        case ALST_OK: return "ok";
+        case ALST_ERR_NULL: return "a required pointer is NULL";
+        case ALST_ERR_SHAPE: return "N, H, V and tile must be >= 1 and within the supported range";
+        case ALST_ERR_ALIGN: return "H must be a multiple of 8 and base pointers 16-byte aligned";
+        case ALST_ERR_WORKSPACE: return "workspace is smaller than alst_tiled_ce_workspace_bytes()";
+        case ALST_ERR_LABEL_RANGE: return "a label is neither ignore_index nor inside [0, V)";
+        case ALST_ERR_HIP: return "a HIP runtime call or kernel launch failed";
+        case ALST_ERR_UNSUPPORTED: return "unknown flag bits";
+        case ALST_ERR_NONFINITE: return "the loss is not finite";
+        default: return "unknown status";
+    }
+}
+
+int alst_version(void) { return 100; }
+
+size_t alst_tiled_ce_workspace_bytes(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_t flags) {
+    if (N < 1 || H < 1 || V < 1 || tile < 1) return 0;
+    if (N > (int64_t)1 << 30 || H > (int64_t)1 << 20 || V > (int64_t)1 << 24) return 0;
+    return make_layout(N, H, V, tile, flags).total;
+}
+
+int alst_tiled_ce_forward(const void* hidden, const void* W, const int32_t* labels, int64_t N,
+                          int64_t H, int64_t V, int64_t tile, int32_t ignore_index, float* loss_out,
+                          float* lse_out, int64_t* n_valid_out, void* workspace,
+                          size_t workspace_bytes, uint32_t flags, void* stream) {
+    Problem P = {};
+    P.hidden = (const uint16_t*)hidden; P.W = (const uint16_t*)W; P.labels = labels;
+    P.N = N; P.H = H; P.V = V; P.tile = tile; P.ignore_index = ignore_index; P.grad_loss = 1.f;
+    P.loss_out = loss_out; P.lse_out = lse_out; P.n_valid_out = n_valid_out;
+    P.ws = (unsigned char*)workspace; P.flags = flags; P.stream = (hipStream_t)stream;
+    const int rc = validate(P, workspace_bytes, true, false, false);
+    if (rc != ALST_OK) return rc;
+    return run(P, true, false);
+}
+
+int alst_tiled_ce_backward(const void* hidden, const void* W, const int32_t* labels,
+                           const float* lse, int64_t N, int64_t H, int64_t V, int64_t tile,
+                           int32_t ignore_index, float grad_loss, void* dHidden, void* dW,
+                           void* workspace, size_t workspace_bytes, uint32_t flags, void* stream) {
+    Problem P = {};
+    P.hidden = (const uint16_t*)hidden; P.W = (const uint16_t*)W; P.labels = labels;
+    P.lse_in = lse;
+    P.N = N; P.H = H; P.V = V; P.tile = tile; P.ignore_index = ignore_index;
+    P.grad_loss = grad_loss; P.dHidden = (uint16_t*)dHidden; P.dW = dW;
+    P.ws = (unsigned char*)workspace; P.flags = flags; P.stream = (hipStream_t)stream;
+    const int rc = validate(P, workspace_bytes, false, true, true);
+    if (rc != ALST_OK) return rc;
+    return run(P, false, true);
+}
+
+int alst_tiled_ce_forward_backward(const void* hidden, const void* W, const int32_t* labels,
+                                   int64_t N, int64_t H, int64_t V, int64_t tile,
+                                   int32_t ignore_index, float grad_loss, float* loss_out,
+                                   float* lse_out, int64_t* n_valid_out, void* dHidden, void* dW,
+                                   void* workspace, size_t workspace_bytes, uint32_t flags,
+                                   void* stream) {
+    Problem P = {};
+    P.hidden = (const uint16_t*)hidden; P.W = (const uint16_t*)W; P.labels = labels;
+    P.N = N; P.H = H; P.V = V; P.tile = tile; P.ignore_index = ignore_index;
+    P.grad_loss = grad_loss; P.loss_out = loss_out; P.lse_out = lse_out;
+    P.n_valid_out = n_valid_out; P.dHidden = (uint16_t*)dHidden; P.dW = dW;
+    P.ws = (unsigned char*)workspace; P.flags = flags; P.stream = (hipStream_t)stream;
+    const int rc = validate(P, workspace_bytes, true, true, false);
+    if (rc != ALST_OK) return rc;
+    return run(P, true, true);
+}
+
+int alst_last_device_status(void* workspace, void* stream) {
+    if (!workspace) return ALST_ERR_NULL;
+    Header h;
+    if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return ALST_ERR_HIP;
+    if (hipMemcpy(&h, workspace, sizeof(Header), hipMemcpyDeviceToHost) != hipSuccess)
+        return ALST_ERR_HIP;
+    const int st = h.status;
+    if (st != 0) {
+        hipLaunchKernelGGL(init_header_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream,
+                           reinterpret_cast<Header*>(workspace));
+        if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return ALST_ERR_HIP;
+    }
+    return st;
+}
+
+int alst_shift_labels(const int32_t* labels, int32_t* shift_labels, int64_t N, int32_t ignore_index,
+                      void* stream) {
+    if (!labels || !shift_labels) return ALST_ERR_NULL;
+    if (N < 1 || N > (int64_t)1 << 30) return ALST_ERR_SHAPE;
+    int blocks = (int)((N + 255) / 256);
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(shift_labels_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, labels,
+                       shift_labels, N, ignore_index);
+    return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
+}
+
+}  // extern "C"

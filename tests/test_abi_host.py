@@ -1,0 +1,100 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared symbol, sizes its
+workspace as documented, and rejects bad arguments before touching any device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2506_13996_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2506_13996_amd.build import build_library
+        build_library(verbose=False)
+    return B.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    hdr = open(os.path.join(ROOT, "include", "alst.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(alst_[a-z_0-9]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_version_and_status_strings(lib):
+    assert B.alst_version() >= 100
+    seen = set()
+    for s in range(0, 9):
+        msg = B.alst_status_string(s)
+        assert msg and msg != "unknown status"
+        seen.add(msg)
+    assert len(seen) == 9
+    assert B.alst_status_string(99) == "unknown status"
+
+
+def test_workspace_is_independent_of_n_beyond_8_bytes_per_row(lib):
+    H, V, T = 4096, 128256, 4096
+    w = [B.alst_tiled_ce_workspace_bytes(N, H, V, T) for N in (32768, 131072, 524288)]
+    assert 0 < w[0] < w[1] < w[2]
+    # difference between sequence lengths is exactly the per-row loss and lse (8 bytes per row)
+    assert w[1] - w[0] == 8 * (131072 - 32768)
+    assert w[2] - w[1] == 8 * (524288 - 131072)
+    # and far below the logits that are never materialised (4 * N * V bytes)
+    assert w[2] < 0.03 * 4 * 524288 * V
+    # a tile larger than N is clamped
+    assert B.alst_tiled_ce_workspace_bytes(100, 64, 300, 4096) == B.alst_tiled_ce_workspace_bytes(100, 64, 300, 100)
+    # fp32 overwrite mode accumulates directly in dW: no separate accumulator
+    assert w[1] - B.alst_tiled_ce_workspace_bytes(131072, H, V, T, B.ALST_FLAG_DW_FP32) == V * H * 4
+    assert B.alst_tiled_ce_workspace_bytes(0, H, V, T) == 0
+    assert B.alst_tiled_ce_workspace_bytes(10, H, 0, T) == 0
+    assert B.alst_tiled_ce_workspace_bytes(10, H, V, 0) == 0
+
+
+def test_paper_memory_arithmetic():
+    # section "Sequence Tiling ...": one fp32 copy of the logits at 16 000 tokens, V = 128 256
+    assert abs(4 * 16_000 * 128_256 / 2**30 - 7.65) < 0.01
+    # a 1 GiB shard of fp32 logits is about 2093 rows, i.e. about 8 shards at 16K tokens
+    rows = round(2**30 / (4 * 128_256))
+    assert rows == 2093 and round(16_000 / rows) == 8
+    # TiledMLP example: ceil(256 000 / 4096) = 63 shards, the last one ragged
+    assert -(-256_000 // 4096) == 63 and 256_000 % 4096 != 0
+
+
+def _call_forward(lib, hidden=0x1000, W=0x2000, labels=0x3000, N=16, H=64, V=32, tile=8, loss=0x4000,
+                  ws=0x5000, ws_bytes=1 << 40, flags=0):
+    vp = ctypes.c_void_p
+    return lib.alst_tiled_ce_forward(vp(hidden), vp(W), vp(labels), N, H, V, tile, -100, vp(loss),
+                                     None, None, vp(ws), ws_bytes, flags, None)
+
+
+def test_bad_arguments_are_rejected_on_the_host(lib):
+    # the pointers are fakes: every call below must fail validation before anything is launched
+    assert _call_forward(lib, hidden=None) == B.ALST_ERR_NULL
+    assert _call_forward(lib, labels=None) == B.ALST_ERR_NULL
+    assert _call_forward(lib, loss=None) == B.ALST_ERR_NULL
+    assert _call_forward(lib, ws=None) == B.ALST_ERR_NULL
+    assert _call_forward(lib, N=0) == B.ALST_ERR_SHAPE
+    assert _call_forward(lib, V=-3) == B.ALST_ERR_SHAPE
+    assert _call_forward(lib, tile=0) == B.ALST_ERR_SHAPE
+    assert _call_forward(lib, H=60) == B.ALST_ERR_ALIGN
+    assert _call_forward(lib, W=0x2004) == B.ALST_ERR_ALIGN
+    assert _call_forward(lib, ws_bytes=1024) == B.ALST_ERR_WORKSPACE
+    assert _call_forward(lib, flags=64) == B.ALST_ERR_UNSUPPORTED
+    vp = ctypes.c_void_p
+    rc = lib.alst_tiled_ce_backward(vp(0x1000), vp(0x2000), vp(0x3000), None, 16, 64, 32, 8, -100, 1.0,
+                                    vp(0x6000), vp(0x7000), vp(0x5000), 1 << 40, 0, None)
+    assert rc == B.ALST_ERR_NULL
+    rc = lib.alst_tiled_ce_forward_backward(vp(0x1000), vp(0x2000), vp(0x3000), 16, 64, 32, 8, -100, 1.0,
+                                            vp(0x4000), None, None, None, vp(0x7000), vp(0x5000),
+                                            1 << 40, 0, None)
+    assert rc == B.ALST_ERR_NULL
+    assert lib.alst_last_device_status(None, None) == B.ALST_ERR_NULL
+    assert lib.alst_shift_labels(None, vp(0x1000), 4, -100, None) == B.ALST_ERR_NULL
+    assert lib.alst_shift_labels(vp(0x1000), vp(0x2000), 0, -100, None) == B.ALST_ERR_SHAPE
