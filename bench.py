@@ -1,0 +1,154 @@
+#!/usr/bin/env python3
+"""Benchmark of the sequence-tiled LM-head + cross-entropy path on one MI355X.
+
+One "step" = one fused forward+backward pass (alst_tiled_ce_forward_backward) over the whole
+synthetic batch of the workload: every tile's logits GEMM, online log-sum-exp, dZ, dHidden GEMM and
+dW GEMM, plus the final loss and dW reductions.  Inputs are resident in HBM before the timed region.
+Prints ONE JSON line.  `--gpus N` with N > 1 is refused: this path is measured on one GPU only.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MI355X_BF16_MFMA_PEAK_TFLOPS = 2500.0      # dense bf16, vendor figure
+# HBM bytes per launch of the dominant kernel from `rocprofv3 --pmc` (FETCH_SIZE + WRITE_SIZE),
+# see profiles/; None until measured for the current kernels.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = None
+
+
+def cpu_baseline(wl, h_bits, W_bits, labels, rows: int) -> dict:
+    """The CPU fp64 oracle, as it stands, timed on a bounded sample of the same workload."""
+    import numpy as np
+    from oracle import tiled_ce_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    hs, ys = h_bits[:rows], labels[:rows]
+    t0 = time.perf_counter()
+    f = orc.forward(hs, W_bits, ys, ignore_index=-100, row_block=512)
+    orc.backward(hs, W_bits, ys, ignore_index=-100, row_block=512)
+    dt = time.perf_counter() - t0
+    return {"value": rows / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"full fp64 oracle forward + backward on the first {rows} rows of the "
+                      f"workload (all V={wl.V} columns), {dt:.1f} s; loss of the sample {f['loss']:.6f}"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="llama8b_128k")
+    ap.add_argument("--tile", type=int, default=0, help="override the workload's tile size")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=512)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures the one-GPU path only; run with --gpus 1 "
+              "(sharding over GPUs is described in DESIGN.md, not built)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2506_13996_amd import binding as B
+    from paper_2506_13996_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    B.load_library()                       # fails loudly if the HIP library is not built
+    wl = synth.WORKLOADS[args.workload]
+    tile = args.tile or wl.tile
+    N, H, V = wl.N, wl.H, wl.V
+
+    t0 = time.perf_counter()
+    h_bits, W_bits, labels = synth.make_inputs(wl)
+    t_gen = time.perf_counter() - t0
+    torch.cuda.reset_peak_memory_stats()
+    hd = torch.from_numpy(h_bits.view(np.int16)).cuda().view(torch.bfloat16)
+    Wd = torch.from_numpy(W_bits.view(np.int16)).cuda().view(torch.bfloat16)
+    yd = torch.from_numpy(labels).cuda()
+    flags = 0
+    ws = B.alloc_workspace(N, H, V, tile, flags)
+    loss = torch.zeros(1, device="cuda")
+    lse = torch.zeros(N, device="cuda")
+    nv = torch.zeros(1, dtype=torch.int64, device="cuda")
+    dH = torch.empty((N, H), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((V, H), dtype=torch.bfloat16, device="cuda")
+
+    def step():
+        B.alst_tiled_ce_forward_backward(hd, Wd, yd, tile, -100, 1.0, loss_out=loss, lse_out=lse,
+                                         n_valid_out=nv, dHidden=dH, dW=dW, workspace=ws, flags=flags)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.alst_profile_enable(True)
+    B.alst_profile_read()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prof = B.alst_profile_read()
+    B.alst_profile_enable(False)
+    status = B.alst_last_device_status(ws)
+    ms_per_step = ev0.elapsed_time(ev1) / args.steps
+    peak_bytes = torch.cuda.max_memory_allocated()
+
+    tokens_per_s = N / (ms_per_step * 1e-3)
+    useful_flop = 6.0 * N * H * V
+    tflops = useful_flop / (ms_per_step * 1e-3) / 1e12
+
+    # dominant kernel = the block GEMM kind with the largest summed time; every launch of a kind
+    # does 2 * rows * H * V flop (rows = the tile's rows), so per-launch algorithmic flop are
+    # 2 * tile * H * V for full tiles.
+    gemm = {k: v for k, v in prof.items() if k.endswith("_gemm") and v[1] > 0}
+    dom = max(gemm, key=lambda k: gemm[k][0])
+    dom_ms, dom_n = gemm[dom]
+    flop_per_launch = 2.0 * N * H * V * args.steps / dom_n
+    achieved = flop_per_launch / (dom_ms / dom_n * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved,
+                "peak": MI355X_BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / MI355X_BF16_MFMA_PEAK_TFLOPS,
+                "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH,
+                "avg_launch_ms": dom_ms / dom_n, "launches": dom_n,
+                "per_kind_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()}}
+
+    out = {
+        "metric": "tokens/sec, tiled LM-head+CE fwd+bwd, H=%d V=%d" % (H, V),
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "N": N, "H": H, "V": V, "tile": tile,
+                   "ignore_frac": wl.ignore_frac, "entry": "alst_tiled_ce_forward_backward"},
+        "tflops_useful_6NHV": tflops,
+        "mfma_peak_frac": tflops / MI355X_BF16_MFMA_PEAK_TFLOPS,
+        "peak_device_bytes": int(peak_bytes),
+        "would_be_fp32_logits_bytes": 4 * N * V,
+        "loss": float(loss.item()), "n_valid": int(nv.item()), "device_status": status,
+        "wall_s_timed_region": wall, "input_gen_s": t_gen,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, h_bits, W_bits, labels, args.cpu_rows)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -133,6 +133,18 @@ int alst_last_device_status(void* workspace, void* stream);
 int alst_shift_labels(const int32_t* labels, int32_t* shift_labels, int64_t N,
                       int32_t ignore_index, void* stream);
 
+/*
+ * Benchmarking aid (no counterpart in the paper).  While enabled, every launch of the three
+ * block GEMMs (logits, dHidden, dW) and the group of small kernels between them is bracketed by
+ * a pair of HIP events on the launch stream.  alst_profile_read() waits for the recorded events,
+ * writes per kind the summed milliseconds and the number of spans -- index 0 logits GEMM,
+ * 1 dHidden GEMM, 2 dW GEMM, 3 the small kernels of a tile -- into the HOST arrays
+ * ms_total[4] and launches[4], and forgets the spans.  This is the only state the library keeps
+ * between calls; it is process-wide and not thread-safe.
+ */
+int alst_profile_enable(int on);
+int alst_profile_read(double* ms_total, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

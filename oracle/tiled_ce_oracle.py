@@ -73,18 +73,18 @@ def _as_f64(x: np.ndarray) -> np.ndarray:
 
 
 def _contract(a: np.ndarray, b: np.ndarray, ordered: bool) -> np.ndarray:
-    """a[r, k] , b[c, k] -> out[r, c] = sum_k a[r, k] b[c, k]."""
+    """a[r, k] , b[k, c] -> out[r, c] = sum_k a[r, k] b[k, c]  (a and b may be transposed views)."""
     if not ordered:
-        return np.matmul(a, b.T)
-    out = np.zeros((a.shape[0], b.shape[0]), dtype=np.float64)
+        return np.matmul(a, b)
+    out = np.zeros((a.shape[0], b.shape[1]), dtype=np.float64)
     for k in range(a.shape[1]):
-        out += a[:, k : k + 1] * b[:, k][None, :]
+        out += a[:, k : k + 1] * b[k : k + 1, :]
     return out
 
 
 def logits(hidden: np.ndarray, W: np.ndarray, ordered: bool = False) -> np.ndarray:
     """z = hidden @ W^T with all V columns materialised (the LM-head projection)."""
-    return _contract(_as_f64(hidden), _as_f64(W), ordered)
+    return _contract(_as_f64(hidden), _as_f64(W).T, ordered)
 
 
 def row_lse(z: np.ndarray) -> np.ndarray:
@@ -124,7 +124,7 @@ def forward(hidden, W, labels, ignore_index: int = -100, row_block: int | None =
     lse = np.zeros(N, dtype=np.float64)
     zlab = np.zeros(N, dtype=np.float64)
     for lo, hi in _blocks(N, row_block):
-        z = _contract(_as_f64(hidden[lo:hi]), Wd, ordered)
+        z = _contract(_as_f64(hidden[lo:hi]), Wd.T, ordered)
         lse[lo:hi] = row_lse(z)
         vb = valid[lo:hi]
         idx = np.flatnonzero(vb)
@@ -155,14 +155,14 @@ def backward(hidden, W, labels, ignore_index: int = -100, grad_loss: float = 1.0
     coef = float(grad_loss) / M
     for lo, hi in _blocks(N, row_block):
         hb = _as_f64(hidden[lo:hi])
-        z = _contract(hb, Wd, ordered)
+        z = _contract(hb, Wd.T, ordered)
         p = np.exp(z - row_lse(z)[:, None])
         vb = valid[lo:hi]
         idx = np.flatnonzero(vb)
         p[idx, labels[lo:hi][idx]] -= 1.0
         dz = coef * vb[:, None].astype(np.float64) * p
-        dH[lo:hi] = _contract(dz, Wd.T.copy(), ordered)
-        dW += _contract(dz.T.copy(), hb.T.copy(), ordered)
+        dH[lo:hi] = _contract(dz, Wd, ordered)
+        dW += _contract(dz.T, hb, ordered)
     return dH, dW
 
 

@@ -22,7 +22,7 @@ ALST_FLAG_DW_ACCUMULATE = 2
 EXPORTS = (
     "alst_status_string", "alst_version", "alst_tiled_ce_workspace_bytes", "alst_tiled_ce_forward",
     "alst_tiled_ce_backward", "alst_tiled_ce_forward_backward", "alst_last_device_status",
-    "alst_shift_labels",
+    "alst_shift_labels", "alst_profile_enable", "alst_profile_read",
 )
 
 _lib = None
@@ -60,6 +60,10 @@ def load_library() -> ctypes.CDLL:
     lib.alst_last_device_status.argtypes = [vp, vp]
     lib.alst_shift_labels.restype = c.c_int
     lib.alst_shift_labels.argtypes = [vp, vp, i64, i32, vp]
+    lib.alst_profile_enable.restype = c.c_int
+    lib.alst_profile_enable.argtypes = [c.c_int]
+    lib.alst_profile_read.restype = c.c_int
+    lib.alst_profile_read.argtypes = [c.POINTER(c.c_double), c.POINTER(c.c_int64)]
     _lib = lib
     return lib
 
@@ -139,3 +143,18 @@ def alst_shift_labels(labels, shift_labels, ignore_index: int = -100) -> None:
     st = load_library().alst_shift_labels(_ptr(labels), _ptr(shift_labels), labels.numel(),
                                           ignore_index, _stream())
     _check(st, "alst_shift_labels")
+
+
+PROFILE_KINDS = ("logits_gemm", "dhidden_gemm", "dw_gemm", "tile_small_kernels")
+
+
+def alst_profile_enable(on: bool) -> None:
+    _check(load_library().alst_profile_enable(1 if on else 0), "alst_profile_enable")
+
+
+def alst_profile_read() -> dict:
+    """{kind: (total_ms, spans)} for the spans recorded since the last read."""
+    ms = (ctypes.c_double * 4)()
+    n = (ctypes.c_int64 * 4)()
+    _check(load_library().alst_profile_read(ms, n), "alst_profile_read")
+    return {k: (ms[i], int(n[i])) for i, k in enumerate(PROFILE_KINDS)}

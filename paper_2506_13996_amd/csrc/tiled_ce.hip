@@ -21,6 +21,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <math.h>
+#include <vector>
 
 #include "../../include/alst.h"
 #include "gemm_tile.h"
@@ -495,6 +496,45 @@ __global__ __launch_bounds__(kThreads) void dw_kernel(const DWParams p) {
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
+// Optional per-kernel timing (alst_profile_*): while enabled, each launch of a block GEMM is
+// bracketed by a pair of HIP events on the launch stream.  A benchmarking aid; it is the only
+// state the library keeps between calls and is not thread-safe.
+enum { PROF_LOGITS = 0, PROF_DHIDDEN = 1, PROF_DW = 2, PROF_OTHER = 3, PROF_KINDS = 4 };
+struct ProfSpan { hipEvent_t a, b; int kind; };
+static bool g_prof_on = false;
+static std::vector<ProfSpan> g_prof_spans;
+static std::vector<hipEvent_t> g_prof_pool;
+
+static hipEvent_t prof_event() {
+    if (!g_prof_pool.empty()) {
+        hipEvent_t e = g_prof_pool.back();
+        g_prof_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+struct ProfScope {
+    ProfSpan sp;
+    hipStream_t s;
+    bool on;
+    ProfScope(int kind, hipStream_t stream) : s(stream), on(g_prof_on) {
+        if (!on) return;
+        sp.a = prof_event();
+        sp.b = prof_event();
+        sp.kind = kind;
+        on = sp.a && sp.b;
+        if (on) (void)hipEventRecord(sp.a, s);
+    }
+    ~ProfScope() {
+        if (!on) return;
+        (void)hipEventRecord(sp.b, s);
+        g_prof_spans.push_back(sp);
+    }
+};
+
 #define ALST_HIP(call)                                   \
     do {                                                 \
         if ((call) != hipSuccess) return ALST_ERR_HIP;   \
@@ -638,31 +678,36 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
         lp.T_cur = T_cur; lp.Tr = Tr; lp.Tp = Tp; lp.H = H; lp.V = V; lp.Vp = Vp;
         lp.ignore_index = P.ignore_index;
         const bool guard1 = guard_rows || (V % kBlockC) != 0 || (H % kBlockK) != 0;
-        if (do_fwd && do_bwd) rc = launch_logits<MODE_FUSED>(lp, guard1, s);
-        else if (do_fwd) rc = launch_logits<MODE_FWD>(lp, guard1, s);
-        else rc = launch_logits<MODE_BWD>(lp, guard1, s);
-        if (rc != ALST_OK) return rc;
-
-        if (do_fwd) {
-            hipLaunchKernelGGL(row_combine_kernel, dim3(Tr / 256), dim3(256), 0, s, pm, ps,
-                               zlabel, labels_t, T_cur, Tr, Tp, ng, P.ignore_index, V, lse_buf + i0,
-                               loss_rows + i0, do_bwd ? sc : nullptr);
-            ALST_HIP(hipGetLastError());
+        {
+            ProfScope ps_(PROF_LOGITS, s);
+            if (do_fwd && do_bwd) rc = launch_logits<MODE_FUSED>(lp, guard1, s);
+            else if (do_fwd) rc = launch_logits<MODE_FWD>(lp, guard1, s);
+            else rc = launch_logits<MODE_BWD>(lp, guard1, s);
         }
-        if (!do_bwd) continue;
+        if (rc != ALST_OK) return rc;
 
         {
-            dim3 grid(Vp / 64, Tr / 64);
-            if (do_fwd)
-                hipLaunchKernelGGL(dz_finalize_kernel<true>, grid, dim3(256), 0, s, stash, dzt, sc,
-                                   labels_t, T_cur, Tp, Vp, V, P.ignore_index);
-            else
-                hipLaunchKernelGGL(dz_finalize_kernel<false>, grid, dim3(256), 0, s, stash, dzt, sc,
-                                   labels_t, T_cur, Tp, Vp, V, P.ignore_index);
-            ALST_HIP(hipGetLastError());
+            ProfScope small_(PROF_OTHER, s);
+            if (do_fwd) {
+                hipLaunchKernelGGL(row_combine_kernel, dim3(Tr / 256), dim3(256), 0, s, pm, ps,
+                                   zlabel, labels_t, T_cur, Tr, Tp, ng, P.ignore_index, V,
+                                   lse_buf + i0, loss_rows + i0, do_bwd ? sc : nullptr);
+                ALST_HIP(hipGetLastError());
+            }
+            if (do_bwd) {
+                dim3 grid(Vp / 64, Tr / 64);
+                if (do_fwd)
+                    hipLaunchKernelGGL(dz_finalize_kernel<true>, grid, dim3(256), 0, s, stash, dzt,
+                                       sc, labels_t, T_cur, Tp, Vp, V, P.ignore_index);
+                else
+                    hipLaunchKernelGGL(dz_finalize_kernel<false>, grid, dim3(256), 0, s, stash, dzt,
+                                       sc, labels_t, T_cur, Tp, Vp, V, P.ignore_index);
+                ALST_HIP(hipGetLastError());
+                rc = launch_transpose(hidden_t, H, T_cur, H, ht, Tp, Tr, s);
+                if (rc != ALST_OK) return rc;
+            }
         }
-        rc = launch_transpose(hidden_t, H, T_cur, H, ht, Tp, Tr, s);
-        if (rc != ALST_OK) return rc;
+        if (!do_bwd) continue;
 
         const bool guard_h = (H % kBlockC) != 0;
         {
@@ -670,6 +715,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             dp.dz = stash; dp.wt = wt; dp.dH_t = P.dHidden + i0 * P.H; dp.hdr = hdr;
             dp.T_cur = T_cur; dp.Tr = Tr; dp.Tp = Tp; dp.H = H; dp.Vp = Vp;
             const int grid = grid_for_tiles<4, 8>(Tr / kBlockR, (H + kBlockC - 1) / kBlockC);
+            ProfScope ps_(PROF_DHIDDEN, s);
             if (guard_h)
                 hipLaunchKernelGGL(dhidden_kernel<true>, dim3(grid), dim3(kThreads), kLdsBytes, s, dp);
             else
@@ -682,6 +728,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             wp.Tk = (T_cur + kBlockK - 1) / kBlockK * kBlockK;
             wp.Tp = Tp; wp.H = H; wp.V = V; wp.Vp = Vp; wp.first = (t == 0);
             const int grid = grid_for_tiles<8, 4>(Vp / kBlockR, (H + kBlockC - 1) / kBlockC);
+            ProfScope ps_(PROF_DW, s);
             if (guard_h)
                 hipLaunchKernelGGL(dw_kernel<true>, dim3(grid), dim3(kThreads), kLdsBytes, s, wp);
             else
@@ -804,6 +851,28 @@ int alst_last_device_status(void* workspace, void* stream) {
         if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return ALST_ERR_HIP;
     }
     return st;
+}
+
+int alst_profile_enable(int on) {
+    g_prof_on = on != 0;
+    return ALST_OK;
+}
+
+int alst_profile_read(double* ms_total, int64_t* launches) {
+    if (!ms_total || !launches) return ALST_ERR_NULL;
+    for (int k = 0; k < PROF_KINDS; ++k) { ms_total[k] = 0.0; launches[k] = 0; }
+    int rc = ALST_OK;
+    for (const ProfSpan& sp : g_prof_spans) {
+        float ms = 0.f;
+        if (hipEventSynchronize(sp.b) != hipSuccess ||
+            hipEventElapsedTime(&ms, sp.a, sp.b) != hipSuccess) rc = ALST_ERR_HIP;
+        ms_total[sp.kind] += ms;
+        launches[sp.kind] += 1;
+        g_prof_pool.push_back(sp.a);
+        g_prof_pool.push_back(sp.b);
+    }
+    g_prof_spans.clear();
+    return rc;
 }
 
 int alst_shift_labels(const int32_t* labels, int32_t* shift_labels, int64_t N, int32_t ignore_index,
