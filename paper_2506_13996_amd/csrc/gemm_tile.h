@@ -3,17 +3,23 @@
 //
 //     D[r][c] = sum_k X[r][k] * Y[c][k]          X, Y bf16 with k contiguous, fp32 accumulation
 //
-// One workgroup of 512 threads (8 wavefronts, 2 per SIMD) owns a 256 (r) x 256 (c) block of D and
-// walks k in steps of 64.  Operand tiles go global -> registers -> LDS (16-byte chunks, XOR
-// swizzled so that both the 16-byte stores and the MFMA operand reads are bank-conflict free) and
-// are double buffered: the global loads of step k+1 are in flight while step k is multiplied.
-// Wavefront w owns the 64 (r) x 128 (c) sub-block (w & 3, w >> 2) as 2 x 4 MFMA 32x32x16 tiles.
-// The c index is the MFMA row (register) dimension and r the MFMA column (lane) dimension, so a
-// lane holds, for one r, runs of 4 consecutive c: reductions over c stay mostly inside a lane and
-// stores along c are vector stores.
+// One workgroup owns a 256 (r) x 256 (c) block of D and walks k in steps of 64 through two LDS
+// stages.  The c index is the MFMA row (register) dimension and r the MFMA column (lane)
+// dimension (v_mfma_f32_32x32x16_bf16), so a lane holds, for one r, runs of 4 consecutive c:
+// reductions over c stay mostly inside a lane and stores along c are vector stores.
+//
+// Two cores with the same accumulator interface:
+//   DirectCore  4 wavefronts (one per SIMD), 128 x 128 per wavefront, operands DMA'd straight from
+//               global memory into LDS (global_load_lds_dwordx4), MFMA operands double buffered in
+//               registers, barrier placed three quarters through a k-step so that the next
+//               stage's first operands are read while the last quarter is multiplied.  Needs
+//               every extent block-aligned (no bounds checks in the DMA path).
+//   StagedCore  8 wavefronts, 64 x 128 per wavefront, operands staged through registers with
+//               zero fill outside the matrices: the fallback for ragged shapes.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace alst {
 
@@ -22,37 +28,13 @@ typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
 constexpr int kBlockR = 256;          // rows of X per block (MFMA lane dimension)
 constexpr int kBlockC = 256;          // rows of Y per block (MFMA register dimension)
 constexpr int kBlockK = 64;           // k per main-loop step
-constexpr int kThreads = 512;
-constexpr int kWaveR = 64, kWaveC = 128;
-constexpr int kMT = 4;                // 32-wide c tiles per wavefront
-constexpr int kNT = 2;                // 32-wide r tiles per wavefront
-constexpr int kTileBytes = kBlockR * kBlockK * 2;       // one operand tile in LDS
-constexpr int kLdsBytes = 4 * kTileBytes;               // X, Y, two stages each
-
-// Where the calling lane's accumulators sit inside the block.
-struct LanePos {
-    int lane, half, l31, wr, wc;
-    __device__ __forceinline__ LanePos() {
-        const int tid = threadIdx.x;
-        lane = tid & 63;
-        half = lane >> 5;
-        l31 = lane & 31;
-        const int wave = tid >> 6;
-        wr = wave & 3;
-        wc = wave >> 2;
-    }
-    // row of X (r index inside the block) of accumulator tile nt
-    __device__ __forceinline__ int r(int nt) const { return wr * kWaveR + nt * 32 + l31; }
-    // first of the 4 consecutive c held in registers 4q..4q+3 of accumulator tile mt
-    __device__ __forceinline__ int c(int mt, int q) const {
-        return wc * kWaveC + mt * 32 + q * 8 + half * 4;
-    }
-};
+constexpr int kGroupC = 128;          // c extent one wavefront covers (both cores)
+constexpr int kTileBytes = kBlockR * kBlockK * 2;       // one operand tile in LDS (32 KB)
+constexpr int kLdsBytes = 4 * kTileBytes;               // X, Y, two stages each (128 KB)
 
 // XCD-aware block -> tile mapping.  Workgroups are dealt round-robin to the 8 XCDs (each with its
 // own L2); the 32 workgroups that are resident together on one XCD get a compact PR x PC patch of
@@ -78,90 +60,268 @@ inline int grid_for_tiles(int tiles_r, int tiles_c) {
     return ((patches + 7) / 8) * 8 * PR * PC;
 }
 
-// acc[mt][nt] += X-block(r0) * Y-block(c0)^T over all of K.
-// GUARD = false requires r0 + 256 <= rows_x, c0 + 256 <= rows_y and K % 64 == 0.
-// GUARD = true zero-fills rows beyond rows_x / rows_y and k beyond K (K % 8 == 0 required).
-template <bool GUARD>
-__device__ __forceinline__ void block_gemm(const uint16_t* __restrict__ X, int64_t ldx, int rows_x,
-                                           const uint16_t* __restrict__ Y, int64_t ldy, int rows_y,
-                                           int K, int r0, int c0, unsigned char* smem,
-                                           f32x16_t (&acc)[kMT][kNT]) {
-    const int tid = threadIdx.x;
-    const LanePos lp;
-    const int lrow = tid >> 3;      // 0..63, row inside a 64-row slab of the operand tile
-    const int kc = tid & 7;         // 16-byte chunk along k
+// ---------------------------------------------------------------------------------------------
+// StagedCore: 8 wavefronts, register staging, optional bounds checks
+// ---------------------------------------------------------------------------------------------
+struct StagedCore {
+    static constexpr int kThreads = 512;
+    static constexpr int kMT = 4;     // 32-wide c tiles per wavefront
+    static constexpr int kNT = 2;     // 32-wide r tiles per wavefront
+    static constexpr bool kCanGuard = true;
 
-    const uint16_t* xp[4];
-    const uint16_t* yp[4];
-    bool xv[4], yv[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int gx = r0 + lrow + 64 * j, gy = c0 + lrow + 64 * j;
-        xv[j] = !GUARD || gx < rows_x;
-        yv[j] = !GUARD || gy < rows_y;
-        xp[j] = X + (int64_t)(xv[j] ? gx : 0) * ldx + kc * 8;
-        yp[j] = Y + (int64_t)(yv[j] ? gy : 0) * ldy + kc * 8;
-    }
-    const int wofs = (lrow * 8 + (kc ^ (lrow & 7))) * 16;          // + j * 64 rows * 128 B
-    int rofs[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) rofs[s] = ((2 * s + lp.half) ^ (lp.lane & 7)) * 16;
-    const int xbase = (lp.wr * kWaveR + lp.l31) * 128;
-    const int ybase = (lp.wc * kWaveC + lp.l31) * 128;
-
-    unsigned char* const Xs = smem;
-    unsigned char* const Ys = smem + 2 * kTileBytes;
-
-    u32x4_t xg[4], yg[4];
-    const u32x4_t zero4 = {0u, 0u, 0u, 0u};
-
-    auto load_global = [&](int kt) {
-        const int koff = kt * kBlockK;
-        const bool kok = !GUARD || (koff + kc * 8 + 8 <= K);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            xg[j] = (xv[j] && kok) ? *reinterpret_cast<const u32x4_t*>(xp[j] + koff) : zero4;
-            yg[j] = (yv[j] && kok) ? *reinterpret_cast<const u32x4_t*>(yp[j] + koff) : zero4;
+    // Where the calling lane's accumulators sit inside the block.
+    struct Lane {
+        int lane, half, l31, wr, wc;
+        __device__ __forceinline__ Lane() {
+            const int tid = threadIdx.x;
+            lane = tid & 63;
+            half = lane >> 5;
+            l31 = lane & 31;
+            const int wave = tid >> 6;
+            wr = wave & 3;
+            wc = wave >> 2;
         }
-    };
-    auto store_lds = [&](int stage) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            *reinterpret_cast<u32x4_t*>(Xs + stage * kTileBytes + wofs + j * 8192) = xg[j];
-            *reinterpret_cast<u32x4_t*>(Ys + stage * kTileBytes + wofs + j * 8192) = yg[j];
+        // row of X (r index inside the block) of accumulator tile nt
+        __device__ __forceinline__ int r(int nt) const { return wr * 64 + nt * 32 + l31; }
+        // first of the 4 consecutive c held in registers 4q..4q+3 of accumulator tile mt
+        __device__ __forceinline__ int c(int mt, int q) const {
+            return wc * kGroupC + mt * 32 + q * 8 + half * 4;
         }
     };
 
-    const int KT = (K + kBlockK - 1) / kBlockK;
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
+    // acc[mt][nt] += X-block(r0) * Y-block(c0)^T over all of K.
+    // GUARD = false requires r0 + 256 <= rows_x, c0 + 256 <= rows_y and K % 64 == 0.
+    // GUARD = true zero-fills rows beyond rows_x / rows_y and k beyond K (K % 8 == 0 required).
+    template <bool GUARD>
+    static __device__ __forceinline__ void gemm(const uint16_t* __restrict__ X, int64_t ldx,
+                                                int rows_x, const uint16_t* __restrict__ Y,
+                                                int64_t ldy, int rows_y, int K, int r0, int c0,
+                                                unsigned char* smem, f32x16_t (&acc)[kMT][kNT]) {
+        const int tid = threadIdx.x;
+        const Lane lp;
+        const int lrow = tid >> 3;      // 0..63, row inside a 64-row slab of the operand tile
+        const int kc = tid & 7;         // 16-byte chunk along k
 
-    for (int kt = 0; kt < KT; ++kt) {
-        const int cur = kt & 1;
-        const bool more = kt + 1 < KT;
-        if (more) load_global(kt + 1);
-        const unsigned char* xs = Xs + cur * kTileBytes + xbase;
-        const unsigned char* ys = Ys + cur * kTileBytes + ybase;
+        const uint16_t* xp[4];
+        const uint16_t* yp[4];
+        bool xv[4], yv[4];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            bf16x8_t yf[kMT], xf[kNT];
+        for (int j = 0; j < 4; ++j) {
+            const int gx = r0 + lrow + 64 * j, gy = c0 + lrow + 64 * j;
+            xv[j] = !GUARD || gx < rows_x;
+            yv[j] = !GUARD || gy < rows_y;
+            xp[j] = X + (int64_t)(xv[j] ? gx : 0) * ldx + kc * 8;
+            yp[j] = Y + (int64_t)(yv[j] ? gy : 0) * ldy + kc * 8;
+        }
+        // 16-byte chunk kc of row `row` lives at chunk slot kc ^ (row & 7) of its 128-byte row
+        const int wofs = (lrow * 8 + (kc ^ (lrow & 7))) * 16;          // + j * 64 rows * 128 B
+        int rofs[4];
 #pragma unroll
-            for (int mt = 0; mt < kMT; ++mt)
-                yf[mt] = *reinterpret_cast<const bf16x8_t*>(ys + mt * 4096 + rofs[s]);
+        for (int s = 0; s < 4; ++s) rofs[s] = ((2 * s + lp.half) ^ (lp.lane & 7)) * 16;
+        const int xbase = (lp.wr * 64 + lp.l31) * 128;
+        const int ybase = (lp.wc * kGroupC + lp.l31) * 128;
+
+        unsigned char* const Xs = smem;
+        unsigned char* const Ys = smem + 2 * kTileBytes;
+
+        u32x4_t xg[4], yg[4];
+        const u32x4_t zero4 = {0u, 0u, 0u, 0u};
+
+        auto load_global = [&](int kt) {
+            const int koff = kt * kBlockK;
+            const bool kok = !GUARD || (koff + kc * 8 + 8 <= K);
 #pragma unroll
-            for (int nt = 0; nt < kNT; ++nt)
-                xf[nt] = *reinterpret_cast<const bf16x8_t*>(xs + nt * 4096 + rofs[s]);
+            for (int j = 0; j < 4; ++j) {
+                xg[j] = (xv[j] && kok) ? *reinterpret_cast<const u32x4_t*>(xp[j] + koff) : zero4;
+                yg[j] = (yv[j] && kok) ? *reinterpret_cast<const u32x4_t*>(yp[j] + koff) : zero4;
+            }
+        };
+        auto store_lds = [&](int stage) {
 #pragma unroll
-            for (int mt = 0; mt < kMT; ++mt)
+            for (int j = 0; j < 4; ++j) {
+                *reinterpret_cast<u32x4_t*>(Xs + stage * kTileBytes + wofs + j * 8192) = xg[j];
+                *reinterpret_cast<u32x4_t*>(Ys + stage * kTileBytes + wofs + j * 8192) = yg[j];
+            }
+        };
+
+        const int KT = (K + kBlockK - 1) / kBlockK;
+        load_global(0);
+        store_lds(0);
+        __syncthreads();
+
+        for (int kt = 0; kt < KT; ++kt) {
+            const int cur = kt & 1;
+            const bool more = kt + 1 < KT;
+            if (more) load_global(kt + 1);
+            const unsigned char* xs = Xs + cur * kTileBytes + xbase;
+            const unsigned char* ys = Ys + cur * kTileBytes + ybase;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                bf16x8_t yf[kMT], xf[kNT];
+#pragma unroll
+                for (int mt = 0; mt < kMT; ++mt)
+                    yf[mt] = *reinterpret_cast<const bf16x8_t*>(ys + mt * 4096 + rofs[s]);
 #pragma unroll
                 for (int nt = 0; nt < kNT; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yf[mt], xf[nt],
-                                                                          acc[mt][nt], 0, 0, 0);
+                    xf[nt] = *reinterpret_cast<const bf16x8_t*>(xs + nt * 4096 + rofs[s]);
+#pragma unroll
+                for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < kNT; ++nt)
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(yf[mt], xf[nt],
+                                                                              acc[mt][nt], 0, 0, 0);
+            }
+            if (more) store_lds(cur ^ 1);
+            __syncthreads();
         }
-        if (more) store_lds(cur ^ 1);
-        __syncthreads();
     }
-}
+};
+
+// ---------------------------------------------------------------------------------------------
+// DirectCore: 4 wavefronts, global -> LDS DMA, aligned shapes only
+// ---------------------------------------------------------------------------------------------
+struct DirectCore {
+    static constexpr int kThreads = 256;
+    static constexpr int kMT = 4;
+    static constexpr int kNT = 4;
+    static constexpr bool kCanGuard = false;
+
+    struct Lane {
+        int lane, half, l31, wr, wc;
+        __device__ __forceinline__ Lane() {
+            const int tid = threadIdx.x;
+            lane = tid & 63;
+            half = lane >> 5;
+            l31 = lane & 31;
+            const int wave = tid >> 6;
+            wr = wave & 1;
+            wc = wave >> 1;
+        }
+        __device__ __forceinline__ int r(int nt) const { return wr * 128 + nt * 32 + l31; }
+        __device__ __forceinline__ int c(int mt, int q) const {
+            return wc * kGroupC + mt * 32 + q * 8 + half * 4;
+        }
+    };
+
+    // LDS row = 128 bytes = 8 chunks of 16 bytes; chunk kc of row `row` lives at slot
+    // kc ^ ((row >> 1) & 7): sixteen consecutive rows at one kc then cover all 64 banks once.
+    static __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
+
+    // Requires r0 + 256 <= rows of X, c0 + 256 <= rows of Y, K % 64 == 0, K >= 64, 16-byte
+    // aligned rows.  GUARD must be false (rows_x / rows_y are unused).
+    template <bool GUARD>
+    static __device__ __forceinline__ void gemm(const uint16_t* __restrict__ X, int64_t ldx,
+                                                int /*rows_x*/, const uint16_t* __restrict__ Y,
+                                                int64_t ldy, int /*rows_y*/, int K, int r0, int c0,
+                                                unsigned char* smem, f32x16_t (&acc)[kMT][kNT]) {
+        static_assert(!GUARD, "DirectCore has no bounds checks");
+        typedef const __attribute__((address_space(1))) void* gptr_t;
+        typedef __attribute__((address_space(3))) void* lptr_t;
+        const int tid = threadIdx.x, lane = tid & 63;
+        const int w = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave id, provably uniform
+        const int wr = w & 1, wc = w >> 1;
+        const int l31 = lane & 31, half = lane >> 5;
+
+        // One DMA instruction moves 8 rows x 128 bytes: lane -> (row = lane / 8, LDS chunk slot =
+        // lane % 8); the lane fetches the global chunk that belongs in its slot.  Wave w owns rows
+        // [64 w, 64 w + 64) of both operand tiles: 8 instructions per operand per k-step.
+        const int lr = lane >> 3, pc = lane & 7;
+        const uint16_t* xg[8];
+        const uint16_t* yg[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int row = (w * 8 + q) * 8 + lr;
+            const int kc = pc ^ swz(row);
+            xg[q] = X + (int64_t)(r0 + row) * ldx + kc * 8;
+            yg[q] = Y + (int64_t)(c0 + row) * ldy + kc * 8;
+        }
+        auto issue_loads = [&](int stage, int kt) {
+            unsigned char* xs = smem + stage * kTileBytes + w * 8192;
+            unsigned char* ys = smem + 2 * kTileBytes + stage * kTileBytes + w * 8192;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                __builtin_amdgcn_global_load_lds((gptr_t)(xg[q] + kt * kBlockK),
+                                                 (lptr_t)(xs + q * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((gptr_t)(yg[q] + kt * kBlockK),
+                                                 (lptr_t)(ys + q * 1024), 16, 0, 0);
+            }
+        };
+
+        int rofs[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) rofs[s] = ((2 * s + half) ^ swz(l31)) * 16;
+        const int xbase = (wr * 128 + l31) * 128;
+        const int ybase = 2 * kTileBytes + (wc * kGroupC + l31) * 128;
+
+        bf16x8_t fy0[4], fx0[4], fy1[4], fx1[4];
+        auto read_frags = [&](bf16x8_t (&fy)[4], bf16x8_t (&fx)[4], int stage, int s) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                fy[t] = *reinterpret_cast<const bf16x8_t*>(smem + stage * kTileBytes + ybase +
+                                                           t * 4096 + rofs[s]);
+                fx[t] = *reinterpret_cast<const bf16x8_t*>(smem + stage * kTileBytes + xbase +
+                                                           t * 4096 + rofs[s]);
+            }
+        };
+        auto mfmas = [&](const bf16x8_t (&fy)[4], const bf16x8_t (&fx)[4]) {
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[mt], fx[nt],
+                                                                          acc[mt][nt], 0, 0, 0);
+        };
+        // scheduling hint for a quarter step: one LDS read behind each of the first 8 MFMAs
+        auto sched_reads = [&]() {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        };
+
+        const int KT = K / kBlockK;
+        issue_loads(0, 0);
+        __syncthreads();                       // waits for the DMA (vmcnt) and joins the waves
+        if (KT > 1) issue_loads(1, 1);
+        read_frags(fy0, fx0, 0, 0);
+
+        // One k-step.  LOADS: refill the stage just consumed with step kt + 2.  NEXT: read the
+        // first quarter's operands of step kt + 1.  The tail steps skip them so that no DMA is in
+        // flight when the workgroup ends.
+        auto kstep = [&](int kt, auto loads, auto next) {
+            constexpr bool LOADS = decltype(loads)::value, NEXT = decltype(next)::value;
+            const int cur = kt & 1;
+            read_frags(fy1, fx1, cur, 1);
+            mfmas(fy0, fx0);
+            sched_reads();
+            read_frags(fy0, fx0, cur, 2);
+            mfmas(fy1, fx1);
+            sched_reads();
+            read_frags(fy1, fx1, cur, 3);
+            mfmas(fy0, fx0);
+            sched_reads();
+            __syncthreads();                   // stage cur fully read; stage cur ^ 1 has landed
+            if (LOADS) issue_loads(cur, kt + 2);
+            if (NEXT) read_frags(fy0, fx0, cur ^ 1, 0);
+            mfmas(fy1, fx1);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (LOADS) __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (NEXT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+        };
+        int kt = 0;
+        for (; kt + 2 < KT; ++kt) kstep(kt, std::true_type{}, std::true_type{});
+        if (KT >= 2) {
+            kstep(kt, std::false_type{}, std::true_type{});
+            ++kt;
+        }
+        kstep(kt, std::false_type{}, std::false_type{});
+    }
+};
 
 }  // namespace alst

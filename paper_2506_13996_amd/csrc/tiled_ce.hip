@@ -158,33 +158,52 @@ __global__ __launch_bounds__(256) void transpose_pad_kernel(const uint16_t* __re
 
 // Per row of the tile: combine the per-group (max, sum exp) partials into lse, the row's loss
 // term, and (fused mode) the factor that turns the stashed e into a probability.
-__global__ void row_combine_kernel(const float* __restrict__ pm, const float* __restrict__ ps,
-                                   const float* __restrict__ zlabel,
-                                   const int32_t* __restrict__ labels_t, int T_cur, int Tr, int Tp,
-                                   int ng, int ignore_index, int V, float* __restrict__ lse_t,
-                                   float* __restrict__ loss_rows_t, float* __restrict__ sc) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= Tr) return;
+// Block = 64 rows x 16 group lanes: thread (x, y) owns groups y, y + 16, ... of row x; the 16
+// lanes of a row are combined through LDS in a fixed order, so lse does not depend on anything
+// but the row's partials.
+constexpr int kCombineRows = 64, kCombineLanes = 16;
+__global__ __launch_bounds__(kCombineRows * kCombineLanes) void row_combine_kernel(
+    const float* __restrict__ pm, const float* __restrict__ ps, const float* __restrict__ zlabel,
+    const int32_t* __restrict__ labels_t, int T_cur, int Tr, int Tp, int ng, int ignore_index,
+    int V, float* __restrict__ lse_t, float* __restrict__ loss_rows_t, float* __restrict__ sc) {
+    __shared__ float red[kCombineLanes][kCombineRows];
+    const int x = threadIdx.x, y = threadIdx.y;
+    const int i = blockIdx.x * kCombineRows + x;          // Tr is a multiple of 256: i < Tr
     const bool inrow = i < T_cur;
-    float M = -INFINITY;
-    for (int g = 0; g < ng; ++g) M = fmaxf(M, pm[(int64_t)g * Tp + i]);
-    float S = 0.f;
-    for (int g = 0; g < ng; ++g) S += ps[(int64_t)g * Tp + i] * __expf(pm[(int64_t)g * Tp + i] - M);
+    float m = -INFINITY;
+    for (int g = y; g < ng; g += kCombineLanes) m = fmaxf(m, pm[(int64_t)g * Tp + i]);
+    red[y][x] = m;
+    __syncthreads();
+    float M = red[0][x];
+#pragma unroll
+    for (int l = 1; l < kCombineLanes; ++l) M = fmaxf(M, red[l][x]);
+    __syncthreads();
+    float sum = 0.f;
+    for (int g = y; g < ng; g += kCombineLanes)
+        sum += ps[(int64_t)g * Tp + i] * __expf(pm[(int64_t)g * Tp + i] - M);
+    red[y][x] = sum;
+    __syncthreads();
+    float S = red[0][x];
+#pragma unroll
+    for (int l = 1; l < kCombineLanes; ++l) S += red[l][x];
     const float lse = M + __logf(S);
     const bool valid = inrow && label_valid(labels_t[inrow ? i : 0], ignore_index, V);
-    if (inrow) {
+    if (inrow && y == 0) {
         lse_t[i] = lse;
         loss_rows_t[i] = valid ? lse - zlabel[i] : 0.f;
     }
     if (sc) {
-        for (int g = 0; g < ng; ++g)
+        for (int g = y; g < ng; g += kCombineLanes)
             sc[(int64_t)g * Tp + i] = valid ? __expf(pm[(int64_t)g * Tp + i] - lse) : 0.f;
     }
 }
 
 // dZ = valid * (e * factor - onehot), bf16, written over the stash and transposed into dzt.
 // Rows >= T_cur and columns >= V come out as exact zeros, which is what pads the k dimension of
-// the two gradient GEMMs.
+// the two gradient GEMMs.  One wavefront owns a 64 (rows) x 64 (columns) patch, one lane an 8 x 8
+// block of it: lanes run along v for the row-major reads and in-place writes (8 lanes = one
+// 128-byte line) and along i for the transposed writes, and the 8 x 8 transpose is done in
+// registers with byte permutes, so every global access is a full line and no LDS is used.
 template <bool FUSED>
 __global__ __launch_bounds__(256) void dz_finalize_kernel(uint16_t* __restrict__ stash,
                                                           uint16_t* __restrict__ dzt,
@@ -192,42 +211,44 @@ __global__ __launch_bounds__(256) void dz_finalize_kernel(uint16_t* __restrict__
                                                           const int32_t* __restrict__ labels_t,
                                                           int T_cur, int Tp, int Vp, int V,
                                                           int ignore_index) {
-    __shared__ uint16_t t[64][66];
-    const int v0 = blockIdx.x * 64, i0 = blockIdx.y * 64;
-    const int tid = threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int v0 = (blockIdx.x * 4 + wave) * 64 + (lane & 7) * 8;      // first of this lane's 8 columns
+    const int i0 = blockIdx.y * 64 + (lane >> 3) * 8;                 // first of this lane's 8 rows
+    if (v0 >= Vp) return;
+    uint32_t in[8][4];
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int chunk = tid + 256 * q;
-        const int row = chunk >> 3, cc = chunk & 7;
-        const int i = i0 + row, v = v0 + cc * 8;
-        uint16_t* p = stash + (int64_t)i * Vp + v;
+    for (int j = 0; j < 8; ++j) {
+        const int i = i0 + j;
+        uint16_t* p = stash + (int64_t)i * Vp + v0;
         const bf16x8_t e = *reinterpret_cast<const bf16x8_t*>(p);
         const int y = i < T_cur ? labels_t[i] : ignore_index;
         const bool valid = i < T_cur && label_valid(y, ignore_index, V);
         float f = valid ? 1.f : 0.f;
-        if (FUSED) f = valid ? sc[(int64_t)(v >> 7) * Tp + i] : 0.f;
+        if (FUSED) f = valid ? sc[(int64_t)(v0 >> 7) * Tp + i] : 0.f;
         bf16x8_t d;
 #pragma unroll
         for (int x = 0; x < 8; ++x) {
             float val = (float)e[x] * f;
-            if (valid && v + x == y) val -= 1.f;
+            if (valid && v0 + x == y) val -= 1.f;
             d[x] = (__bf16)val;
         }
         *reinterpret_cast<bf16x8_t*>(p) = d;
-        const uint16_t* du = reinterpret_cast<const uint16_t*>(&d);
+        const u32x4_t du = __builtin_bit_cast(u32x4_t, d);
 #pragma unroll
-        for (int x = 0; x < 8; ++x) t[row][cc * 8 + x] = du[x];
+        for (int x = 0; x < 4; ++x) in[j][x] = du[x];
     }
-    __syncthreads();
+    // out[x] = column v0 + x for rows i0 .. i0 + 7: halfword x of each input row
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int chunk = tid + 256 * q;
-        const int vrow = chunk >> 3, ic = chunk & 7;
+    for (int x = 0; x < 8; ++x) {
         u32x4_t o;
-        uint16_t* e = reinterpret_cast<uint16_t*>(&o);
 #pragma unroll
-        for (int x = 0; x < 8; ++x) e[x] = t[ic * 8 + x][vrow];
-        *reinterpret_cast<u32x4_t*>(dzt + (int64_t)(v0 + vrow) * Tp + i0 + ic * 8) = o;
+        for (int pr = 0; pr < 4; ++pr) {
+            const uint32_t lo = in[2 * pr][x >> 1], hi = in[2 * pr + 1][x >> 1];
+            // v_perm_b32 selector bytes index {hi (4..7), lo (0..3)}
+            o[pr] = (x & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u)
+                            : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+        }
+        *reinterpret_cast<u32x4_t*>(dzt + (int64_t)(v0 + x) * Tp + i0) = o;
     }
 }
 
@@ -305,8 +326,9 @@ struct LogitsParams {
 };
 
 // r = token row of the tile (MFMA lane dimension), c = vocabulary id (register dimension).
-template <bool GUARD, int MODE>
-__global__ __launch_bounds__(kThreads) void logits_kernel(const LogitsParams p) {
+template <class Core, bool GUARD, int MODE>
+__global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsParams p) {
+    constexpr int kMT = Core::kMT, kNT = Core::kNT;
     extern __shared__ __align__(16) unsigned char smem[];
     int tr, tc;
     if (!tile_of_block<4, 8>(blockIdx.x, p.Tr / kBlockR, p.Vp / kBlockC, tr, tc)) return;
@@ -320,9 +342,9 @@ __global__ __launch_bounds__(kThreads) void logits_kernel(const LogitsParams p) 
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
-    block_gemm<GUARD>(p.hidden_t, p.H, p.T_cur, p.W, p.H, p.V, p.H, r0, c0, smem, acc);
+    Core::template gemm<GUARD>(p.hidden_t, p.H, p.T_cur, p.W, p.H, p.V, p.H, r0, c0, smem, acc);
 
-    const LanePos lp;
+    const typename Core::Lane lp;
     const bool mask_cols = c0 + kBlockC > p.V;
 #pragma unroll
     for (int nt = 0; nt < kNT; ++nt) {
@@ -349,8 +371,8 @@ __global__ __launch_bounds__(kThreads) void logits_kernel(const LogitsParams p) 
             // label logit: exactly one lane of one block holds column y of row i
             int y = rowok ? p.labels_t[i] : -1;
             if (y == p.ignore_index) y = -1;
-            const unsigned d = (unsigned)(y - (c0 + lp.wc * kWaveC));
-            if (y >= 0 && d < (unsigned)kWaveC && ((d >> 2) & 1u) == (unsigned)lp.half) {
+            const unsigned d = (unsigned)(y - (c0 + lp.wc * kGroupC));
+            if (y >= 0 && d < (unsigned)kGroupC && ((d >> 2) & 1u) == (unsigned)lp.half) {
                 float zl = 0.f;
 #pragma unroll
                 for (int mt = 0; mt < kMT; ++mt)
@@ -371,7 +393,7 @@ __global__ __launch_bounds__(kThreads) void logits_kernel(const LogitsParams p) 
                 }
             s += __shfl_xor(s, 32);
             if (lp.half == 0) {
-                const int64_t g = (c0 + lp.wc * kWaveC) >> 7;
+                const int64_t g = (c0 + lp.wc * kGroupC) >> 7;
                 p.pm[g * p.Tp + i] = m;
                 p.ps[g * p.Tp + i] = s;
             }
@@ -403,8 +425,9 @@ struct DHiddenParams {
 };
 
 // r = token row (lane dimension), c = hidden index (register dimension), k = vocabulary.
-template <bool GUARD>
-__global__ __launch_bounds__(kThreads) void dhidden_kernel(const DHiddenParams p) {
+template <class Core, bool GUARD>
+__global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenParams p) {
+    constexpr int kMT = Core::kMT, kNT = Core::kNT;
     extern __shared__ __align__(16) unsigned char smem[];
     int tr, tc;
     const int tiles_c = (p.H + kBlockC - 1) / kBlockC;
@@ -420,9 +443,9 @@ __global__ __launch_bounds__(kThreads) void dhidden_kernel(const DHiddenParams p
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
-    block_gemm<GUARD>(p.dz, p.Vp, p.Tr, p.wt, p.Vp, p.H, p.Vp, r0, c0, smem, acc);
+    Core::template gemm<GUARD>(p.dz, p.Vp, p.Tr, p.wt, p.Vp, p.H, p.Vp, r0, c0, smem, acc);
 
-    const LanePos lp;
+    const typename Core::Lane lp;
     const float inv = p.hdr->inv;
 #pragma unroll
     for (int nt = 0; nt < kNT; ++nt) {
@@ -453,8 +476,9 @@ struct DWParams {
 };
 
 // r = vocabulary id (lane dimension), c = hidden index (register dimension), k = token row.
-template <bool GUARD>
-__global__ __launch_bounds__(kThreads) void dw_kernel(const DWParams p) {
+template <class Core, bool GUARD>
+__global__ __launch_bounds__(Core::kThreads) void dw_kernel(const DWParams p) {
+    constexpr int kMT = Core::kMT, kNT = Core::kNT;
     extern __shared__ __align__(16) unsigned char smem[];
     int tr, tc;
     const int tiles_c = (p.H + kBlockC - 1) / kBlockC;
@@ -469,14 +493,28 @@ __global__ __launch_bounds__(kThreads) void dw_kernel(const DWParams p) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
-    block_gemm<GUARD>(p.dzt, p.Tp, p.Vp, p.ht, p.Tp, p.H, p.Tk, r0, c0, smem, acc);
+    Core::template gemm<GUARD>(p.dzt, p.Tp, p.Vp, p.ht, p.Tp, p.H, p.Tk, r0, c0, smem, acc);
 
-    const LanePos lp;
+    const typename Core::Lane lp;
 #pragma unroll
     for (int nt = 0; nt < kNT; ++nt) {
         const int v = r0 + lp.r(nt);
         if (v >= p.V) continue;
         float* row = p.acc + (int64_t)v * p.H;
+        // all reads of the old sums first, then the adds and stores: the reads overlap instead of
+        // each waiting behind the previous store
+        f32x4_t old[kMT][4];
+        if (!p.first) {
+#pragma unroll
+            for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int h = c0 + lp.c(mt, q);
+                    old[mt][q] = (GUARD && h >= p.H)
+                                     ? f32x4_t{0.f, 0.f, 0.f, 0.f}
+                                     : __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(row + h));
+                }
+        }
 #pragma unroll
         for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
@@ -486,9 +524,8 @@ __global__ __launch_bounds__(kThreads) void dw_kernel(const DWParams p) {
                 f32x4_t a;
 #pragma unroll
                 for (int x = 0; x < 4; ++x) a[x] = acc[mt][nt][q * 4 + x];
-                f32x4_t* o = reinterpret_cast<f32x4_t*>(row + h);
-                if (!p.first) a += *o;
-                *o = a;
+                if (!p.first) a += old[mt][q];
+                *reinterpret_cast<f32x4_t*>(row + h) = a;
             }
     }
 }
@@ -552,16 +589,16 @@ static int prepare_kernels() {
     if (state >= 0) return state;
     int rc = ALST_OK;
     auto acc = [&](int r) { if (r != ALST_OK) rc = r; };
-    acc(allow_big_lds(logits_kernel<false, MODE_FWD>));
-    acc(allow_big_lds(logits_kernel<true, MODE_FWD>));
-    acc(allow_big_lds(logits_kernel<false, MODE_FUSED>));
-    acc(allow_big_lds(logits_kernel<true, MODE_FUSED>));
-    acc(allow_big_lds(logits_kernel<false, MODE_BWD>));
-    acc(allow_big_lds(logits_kernel<true, MODE_BWD>));
-    acc(allow_big_lds(dhidden_kernel<false>));
-    acc(allow_big_lds(dhidden_kernel<true>));
-    acc(allow_big_lds(dw_kernel<false>));
-    acc(allow_big_lds(dw_kernel<true>));
+    acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_FWD>));
+    acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_FWD>));
+    acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_FUSED>));
+    acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_FUSED>));
+    acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_BWD>));
+    acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_BWD>));
+    acc(allow_big_lds(dhidden_kernel<DirectCore, false>));
+    acc(allow_big_lds(dhidden_kernel<StagedCore, true>));
+    acc(allow_big_lds(dw_kernel<DirectCore, false>));
+    acc(allow_big_lds(dw_kernel<StagedCore, true>));
     state = rc;
     return rc;
 }
@@ -616,9 +653,11 @@ template <int MODE>
 static int launch_logits(const LogitsParams& lp, bool guard, hipStream_t s) {
     const int grid = grid_for_tiles<4, 8>(lp.Tr / kBlockR, lp.Vp / kBlockC);
     if (guard)
-        hipLaunchKernelGGL((logits_kernel<true, MODE>), dim3(grid), dim3(kThreads), kLdsBytes, s, lp);
+        hipLaunchKernelGGL((logits_kernel<StagedCore, true, MODE>), dim3(grid),
+                           dim3(StagedCore::kThreads), kLdsBytes, s, lp);
     else
-        hipLaunchKernelGGL((logits_kernel<false, MODE>), dim3(grid), dim3(kThreads), kLdsBytes, s, lp);
+        hipLaunchKernelGGL((logits_kernel<DirectCore, false, MODE>), dim3(grid),
+                           dim3(DirectCore::kThreads), kLdsBytes, s, lp);
     return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
 }
 
@@ -689,13 +728,14 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
         {
             ProfScope small_(PROF_OTHER, s);
             if (do_fwd) {
-                hipLaunchKernelGGL(row_combine_kernel, dim3(Tr / 256), dim3(256), 0, s, pm, ps,
+                hipLaunchKernelGGL(row_combine_kernel, dim3(Tr / kCombineRows),
+                                   dim3(kCombineRows, kCombineLanes), 0, s, pm, ps,
                                    zlabel, labels_t, T_cur, Tr, Tp, ng, P.ignore_index, V,
                                    lse_buf + i0, loss_rows + i0, do_bwd ? sc : nullptr);
                 ALST_HIP(hipGetLastError());
             }
             if (do_bwd) {
-                dim3 grid(Vp / 64, Tr / 64);
+                dim3 grid(Vp / 256, Tr / 64);
                 if (do_fwd)
                     hipLaunchKernelGGL(dz_finalize_kernel<true>, grid, dim3(256), 0, s, stash, dzt,
                                        sc, labels_t, T_cur, Tp, Vp, V, P.ignore_index);
@@ -717,9 +757,11 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             const int grid = grid_for_tiles<4, 8>(Tr / kBlockR, (H + kBlockC - 1) / kBlockC);
             ProfScope ps_(PROF_DHIDDEN, s);
             if (guard_h)
-                hipLaunchKernelGGL(dhidden_kernel<true>, dim3(grid), dim3(kThreads), kLdsBytes, s, dp);
+                hipLaunchKernelGGL((dhidden_kernel<StagedCore, true>), dim3(grid),
+                                   dim3(StagedCore::kThreads), kLdsBytes, s, dp);
             else
-                hipLaunchKernelGGL(dhidden_kernel<false>, dim3(grid), dim3(kThreads), kLdsBytes, s, dp);
+                hipLaunchKernelGGL((dhidden_kernel<DirectCore, false>), dim3(grid),
+                                   dim3(DirectCore::kThreads), kLdsBytes, s, dp);
             ALST_HIP(hipGetLastError());
         }
         {
@@ -730,9 +772,11 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             const int grid = grid_for_tiles<8, 4>(Vp / kBlockR, (H + kBlockC - 1) / kBlockC);
             ProfScope ps_(PROF_DW, s);
             if (guard_h)
-                hipLaunchKernelGGL(dw_kernel<true>, dim3(grid), dim3(kThreads), kLdsBytes, s, wp);
+                hipLaunchKernelGGL((dw_kernel<StagedCore, true>), dim3(grid),
+                                   dim3(StagedCore::kThreads), kLdsBytes, s, wp);
             else
-                hipLaunchKernelGGL(dw_kernel<false>, dim3(grid), dim3(kThreads), kLdsBytes, s, wp);
+                hipLaunchKernelGGL((dw_kernel<DirectCore, false>), dim3(grid),
+                                   dim3(DirectCore::kThreads), kLdsBytes, s, wp);
             ALST_HIP(hipGetLastError());
         }
     }
