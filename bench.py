@@ -52,6 +52,10 @@ def main() -> int:
     ap.add_argument("--tile", type=int, default=0, help="override the workload's tile size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=512)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy before the timed region, so "
+                         "that a rocprofv3 --pmc run holds a kernel of known traffic to scale "
+                         "FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures the one-GPU path only; run with --gpus 1 "
@@ -90,6 +94,13 @@ def main() -> int:
         B.alst_tiled_ce_forward_backward(hd, Wd, yd, tile, -100, 1.0, loss_out=loss, lse_out=lse,
                                          n_valid_out=nv, dHidden=dH, dW=dW, workspace=ws, flags=flags)
 
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")       # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

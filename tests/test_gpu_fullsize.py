@@ -1,0 +1,117 @@
+"""Full-size GPU parity: the benchmark's launch configuration on the four large workloads.
+
+The oracle cannot materialise these problems inside a test, so the comparison is on sampled
+outputs it can compute exactly, plus properties that hold at any size:
+  * loss, n_valid, lse at sampled rows and dW at sampled (vocabulary id, column) entries against
+    tests/golden/<workload>.json, which tests/golden/make_golden.py wrote from the oracle alone;
+  * dHidden for sampled rows (ignored rows, both ends of ignore runs, first and last rows of
+    tiles) against oracle.dhidden_rows computed here;
+  * every column of dW sums to ~0 over the vocabulary, rows of ignored tokens are exact zeros,
+    and peak device memory stays far below the [N, V] logits.
+Bars as in test_gpu_parity.py: loss 1e-3 relative, gradients 2e-2 of max |oracle gradient| (the
+maximum is taken over the sampled oracle entries, a lower bound of the true one, so the check is
+stricter than the stated bar).
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import tiled_ce_oracle as orc
+from paper_2506_13996_amd import binding as B
+from paper_2506_13996_amd import synth
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+IGN = synth.IGNORE_INDEX
+
+
+def _sample_rows(wl, y):
+    ign = (y == IGN)
+    edges = np.flatnonzero(np.diff(ign.astype(np.int8)) != 0)
+    picks = [0, 1, wl.tile - 1, wl.tile, wl.N - wl.tile, wl.N - 1, wl.N // 2]
+    for e in edges[:3].tolist() + edges[-2:].tolist():
+        picks += [e, e + 1]
+    picks += np.flatnonzero(ign)[:2].tolist()
+    g = np.random.default_rng(4321)
+    picks += g.integers(0, wl.N, 6).tolist()
+    return np.unique(np.clip(np.array(picks, dtype=np.int64), 0, wl.N - 1))
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["llama8b_32k", "llama8b_128k", "llama8b_512k", "qwen32b_256k"])
+def test_full_size_workload(name):
+    path = os.path.join(GOLDEN, name + ".json")
+    assert os.path.exists(path), f"missing {path}: run tests/golden/make_golden.py {name}"
+    gold = json.load(open(path))
+    wl = synth.WORKLOADS[name]
+    N, H, V = wl.N, wl.H, wl.V
+    assert (gold["N"], gold["H"], gold["V"]) == (N, H, V)
+    print(f"[{name}] generating inputs", flush=True)
+    h, W, y = synth.make_inputs(wl)
+
+    torch.cuda.empty_cache()
+    torch.cuda.reset_peak_memory_stats()
+    base = torch.cuda.memory_allocated()
+    hd, Wd, yd = G.bits_to_dev(h), G.bits_to_dev(W), torch.from_numpy(y).cuda()
+    ws = B.alloc_workspace(N, H, V, wl.tile)
+    loss = torch.zeros(1, device="cuda")
+    lse = torch.zeros(N, device="cuda")
+    nv = torch.zeros(1, dtype=torch.int64, device="cuda")
+    dH = torch.empty((N, H), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((V, H), dtype=torch.bfloat16, device="cuda")
+    print(f"[{name}] running the fused pass, tile {wl.tile}", flush=True)
+    B.alst_tiled_ce_forward_backward(hd, Wd, yd, wl.tile, IGN, 1.0, loss_out=loss, lse_out=lse,
+                                     n_valid_out=nv, dHidden=dH, dW=dW, workspace=ws)
+    assert B.alst_last_device_status(ws) == B.ALST_OK
+    torch.cuda.synchronize()
+    peak = torch.cuda.max_memory_allocated() - base
+
+    # ---- memory: inputs + outputs + workspace, nothing of size N x V ---------------------------
+    expected = 2 * N * H * 2 + 2 * V * H * 2 + 4 * N + 4 * N + ws.numel()
+    assert peak <= expected + (64 << 20), (peak, expected)
+    assert peak < (0.2 if N >= 131072 else 0.6) * 4 * N * V
+    assert ws.numel() - 8 * N == B.alst_tiled_ce_workspace_bytes(wl.tile, H, V, wl.tile) - 8 * wl.tile
+
+    # ---- loss, count, lse ---------------------------------------------------------------------
+    assert int(nv.item()) == gold["n_valid"]
+    lg = float(loss.item())
+    assert abs(lg - gold["loss"]) / abs(gold["loss"]) <= 1e-3, (lg, gold["loss"])
+    lse_h = lse.cpu().numpy().astype(np.float64)
+    rows_g = np.array(gold["lse_rows"])
+    assert np.abs(lse_h[rows_g] - np.array(gold["lse_values"])).max() <= 1e-3 * 12.0
+    assert abs(lse_h.sum() - gold["lse_sum"]) / abs(gold["lse_sum"]) <= 1e-5
+    # closed-form sanity: logits ~ N(0, 0.0004 H), so E[loss] ~ ln V + 0.0002 H
+    assert abs(lg - (np.log(V) + 0.0002 * H)) < 0.02 * lg
+
+    # ---- dHidden: sampled rows against the oracle ------------------------------------------------
+    rows = _sample_rows(wl, y)
+    print(f"[{name}] oracle dHidden for {len(rows)} rows", flush=True)
+    ref, lse_r, _ = orc.dhidden_rows(h, W, y, rows, gold["n_valid"], ignore_index=IGN)
+    got = dH[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+    eh = G.grad_err(got, ref)
+    assert eh <= 2e-2, ("dHidden", eh)
+    assert np.abs(lse_h[rows] - lse_r).max() <= 1e-3 * 12.0
+    ign = torch.from_numpy(y == IGN).cuda()
+    assert bool((dH[ign].view(torch.int16) == 0).all()), "rows of ignored tokens must be exact zeros"
+    assert bool(torch.isfinite(dH.float().abs().max())) and bool(torch.isfinite(dW.float().abs().max()))
+
+    # ---- dW: stored oracle entries ------------------------------------------------------------------
+    ids = torch.tensor(gold["dw_ids"], device="cuda")
+    cols = torch.tensor(gold["dw_cols"], device="cuda")
+    got_w = dW[ids][:, cols].float().cpu().numpy().astype(np.float64)
+    ref_w = np.array(gold["dw_values"])
+    den = max(gold["dw_row_maxabs"])
+    ew = np.abs(got_w - ref_w).max() / den
+    assert ew <= 2e-2, ("dW", ew)
+    # the GPU's own maximum is of the same order as the sampled oracle maximum (label rows dominate)
+    gmax = float(dW.float().abs().max().item())
+    assert 0.5 * den <= gmax <= 50 * den, (gmax, den)
+    # sum_v dz[i, v] = 0  =>  every column of dW sums to zero over the vocabulary
+    colsum = dW.double().sum(dim=0).abs().max().item()
+    assert colsum <= 2e-2 * gmax * np.sqrt(V) / 16, (colsum, gmax)
+    print(f"[{name}] loss {lg:.6f} (oracle {gold['loss']:.6f})  dH err {eh:.2e}  dW err {ew:.2e}  "
+          f"colsum {colsum:.2e}  peak {peak / 2**30:.2f} GiB", flush=True)
