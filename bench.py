@@ -19,9 +19,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MI355X_BF16_MFMA_PEAK_TFLOPS = 2500.0      # dense bf16, vendor figure
-# HBM bytes per launch of the dominant kernel from `rocprofv3 --pmc` (FETCH_SIZE + WRITE_SIZE),
-# see profiles/; None until measured for the current kernels.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = None
+# Memory-side bytes per launch (calibrated FETCH_SIZE + WRITE_SIZE from two `rocprofv3 --pmc` runs of
+# this script on llama8b_128k, see profiles/bench_llama8b_128k_hbm_traffic.txt); other workloads: None.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
+    "llama8b_128k": {"dw_gemm": 10.912e9, "logits_gemm": 7.408e9, "dhidden_gemm": 6.339e9},
+}
 
 
 def cpu_baseline(wl, h_bits, W_bits, labels, rows: int) -> dict:
@@ -136,7 +138,7 @@ def main() -> int:
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved,
                 "peak": MI355X_BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / MI355X_BF16_MFMA_PEAK_TFLOPS,
-                "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH,
+                "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(wl.name, {}).get(dom) if tile == wl.tile else None,
                 "avg_launch_ms": dom_ms / dom_n, "launches": dom_n,
                 "per_kind_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()}}
 
