@@ -34,6 +34,9 @@
  *     ignore_index nor in [0,V), a non-finite loss) are recorded in a status word inside the
  *     workspace, read with alst_last_device_status().  A row with an out-of-range label is
  *     treated as ignored, so nothing is read or written out of bounds.
+ *   - Rows of ignored tokens are left out of all three contractions (each tile's valid rows are
+ *     gathered into a dense matrix first), so the executed work is 6 * M * H * V flop for M valid
+ *     tokens, not 6 * N * H * V.
  *   - tile: any value >= 1; a tile larger than N is clamped; N need not be a multiple of tile.
  *     The tile size changes scheduling and memory only: the loss bits do not depend on it.
  */
@@ -82,7 +85,9 @@ size_t alst_tiled_ce_workspace_bytes(int64_t N, int64_t H, int64_t V, int64_t ti
  * Forward only: mean cross-entropy of the tiled LM-head projection (one logits sweep, 2NHV flop).
  *   hidden  [N,H] bf16, W [V,H] bf16, labels [N] int32     inputs, not modified
  *   loss_out    [1] fp32    mean over non-ignored tokens
- *   lse_out     [N] fp32    per-row log-sum-exp, the only state backward needs; may be NULL
+ *   lse_out     [N] fp32    per-row log-sum-exp of the tokens that take part, the only state
+ *                           backward needs; 0 for ignored tokens (their rows are skipped: they
+ *                           enter neither the loss nor a gradient); may be NULL
  *   n_valid_out [1] int64   number of non-ignored tokens; may be NULL
  */
 int alst_tiled_ce_forward(const void* hidden, const void* W, const int32_t* labels,
@@ -92,7 +97,7 @@ int alst_tiled_ce_forward(const void* hidden, const void* W, const int32_t* labe
 
 /*
  * Backward only, from the lse a forward call produced (recomputes each tile's logits: 6NHV flop).
- *   lse       [N] fp32      from alst_tiled_ce_forward
+ *   lse       [N] fp32      from alst_tiled_ce_forward (entries of ignored tokens are not read)
  *   grad_loss host scalar   upstream gradient g of the loss (1.0f normally)
  *   dHidden   [N,H] bf16    overwritten, every row; rows of ignored tokens are exactly 0
  *   dW        [V,H] bf16 (fp32 with ALST_FLAG_DW_FP32); overwritten, or += with

@@ -4,7 +4,12 @@
 // Footprint": forward and backward of each logits shard are done together and the shard's
 // intermediates are dropped before the next shard):
 //
-//   1. logits_kernel     Z = H_t W^T in 256x256 blocks, fp32 accumulators.  The logits never
+//   0. compact_scan /    rows whose label is ignored take no part in the loss or in either gradient,
+//      gather_rows       so the tile's valid rows are gathered into a dense [Tc, H] copy and all
+//                        three contractions run on Tc <= T rows; the dHidden rows of ignored
+//                        tokens are zero-filled here.  Tc lives on the device: grids are sized
+//                        for T and surplus blocks leave at once, so nothing waits for the host.
+//   1. logits_kernel     Z = H_c W^T in 256x256 blocks, fp32 accumulators.  The logits never
 //                        leave the registers: the epilogue reduces each row over the block's
 //                        columns to (max, sum exp) partials per 128-column group, picks out the
 //                        label logit, and writes e = exp(z - group max) as bf16 to a [T, V]
@@ -12,8 +17,8 @@
 //   2. row_combine       partials -> lse, per-row loss, and the factor exp(group max - lse)
 //                        that turns e into the softmax probability.
 //   3. dz_finalize       dZ = valid * (e * factor - onehot) as bf16, in place, plus its transpose.
-//   4. dhidden_kernel    dH_t = (g/M) dZ W          (contraction over V)
-//   5. dw_kernel         acc += dZ^T H_t            (contraction over the tile's rows, fp32)
+//   4. dhidden_kernel    dH_t = (g/M) dZ W          (contraction over V), rows scattered back
+//   5. dw_kernel         acc += H_c^T dZ            (contraction over the tile's valid rows, fp32)
 //
 // After the last tile: loss = sum(per-row loss) / M in a fixed order, dW = (g/M) acc.
 // All three contractions use the same k-contiguous block GEMM (gemm_tile.h); W^T and H_t^T are
@@ -40,9 +45,31 @@ struct Header {
     double loss_sum;
 };
 
+// What compact_scan_kernel leaves for the other kernels of a tile.
+struct TileInfo {
+    int Tc;                // rows of the tile that take part (valid label)
+    int Trc;               // Tc rounded up to the block height (256)
+    int Tkc;               // Tc rounded up to the k-step (64)
+    int kofs;              // where the tile's dense rows start along k in the dW group buffers
+};
+
+// dW is accumulated into the fp32 [V, H] sums once per GROUP of consecutive tiles: dZ^T and H^T of
+// the group's tiles are packed side by side along k and one dW GEMM contracts over all of them,
+// so the read-modify-write of the 4*V*H-byte accumulator and the GEMM's epilogue are paid once
+// per group instead of once per tile.  The group spans about kDwGroupRows rows.
+constexpr int kDwGroupRows = 16384;
+constexpr int kDwGroupMax = 8;
+static inline int dw_group_size(int64_t Tp) {
+    int64_t g = kDwGroupRows / Tp;
+    return (int)(g < 1 ? 1 : (g > kDwGroupMax ? kDwGroupMax : g));
+}
+
 struct Layout {
     int64_t Tp, Vp, ng;    // padded tile rows, padded vocabulary, 128-column groups
-    size_t header, loss_rows, lse, zlabel, pm, ps, sc, stash, dzt, wt, ht, acc, total;
+    int g;                 // tiles per dW group
+    int64_t Kg;            // row stride of dzt / ht: g * Tp
+    size_t header, tinfo, loss_rows, lse, zlabel, yc, idx, pos, pm, ps, sc, hc, stash, dzt, wt, ht,
+        acc, total;
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -53,19 +80,26 @@ static Layout make_layout(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_
     L.Tp = (T + 255) / 256 * 256;
     L.Vp = (V + 255) / 256 * 256;
     L.ng = L.Vp / 128;
+    L.g = dw_group_size(L.Tp);
+    L.Kg = (int64_t)L.g * L.Tp;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     L.header = take(sizeof(Header));
+    L.tinfo = take(sizeof(TileInfo) * kDwGroupMax);
     L.loss_rows = take((size_t)N * 4);
     L.lse = take((size_t)N * 4);
     L.zlabel = take((size_t)L.Tp * 4);
+    L.yc = take((size_t)L.Tp * 4);
+    L.idx = take((size_t)L.Tp * 4);
+    L.pos = take((size_t)L.Tp * 4);
     L.pm = take((size_t)L.ng * L.Tp * 4);
     L.ps = take((size_t)L.ng * L.Tp * 4);
     L.sc = take((size_t)L.ng * L.Tp * 4);
+    L.hc = take((size_t)L.Tp * H * 2);
     L.stash = take((size_t)L.Tp * L.Vp * 2);
-    L.dzt = take((size_t)L.Vp * L.Tp * 2);
+    L.dzt = take((size_t)L.Vp * L.Kg * 2);
     L.wt = take((size_t)H * L.Vp * 2);
-    L.ht = take((size_t)H * L.Tp * 2);
+    L.ht = take((size_t)H * L.Kg * 2);
     const bool acc_in_dw = (flags & ALST_FLAG_DW_FP32) && !(flags & ALST_FLAG_DW_ACCUMULATE);
     L.acc = take(acc_in_dw ? 0 : (size_t)V * H * 4);
     L.total = o;
@@ -121,13 +155,98 @@ __global__ void set_scale_kernel(Header* h, float grad_loss, int64_t* n_valid_ou
     }
 }
 
+// Row compaction of one tile.  One block walks the tile's labels in chunks of 1024 and gives each
+// row with a valid label its rank among them:
+//   pos[i] = rank of row i (or -1), idx[rank] = i, yc[rank] = label,
+// and leaves the counts, and the tile's k offset inside its dW group, in *info.  Rows that do not take part get loss term 0 and lse 0 (forward).
+constexpr int kScanThreads = 1024;
+__global__ __launch_bounds__(kScanThreads) void compact_scan_kernel(
+    const int32_t* __restrict__ labels_t, int T_cur, int ignore_index, int V,
+    int32_t* __restrict__ yc, int32_t* __restrict__ idx, int32_t* __restrict__ pos,
+    TileInfo* __restrict__ info, const TileInfo* __restrict__ prev, float* __restrict__ lse_t,
+    float* __restrict__ loss_rows_t) {
+    __shared__ int wave_total[kScanThreads / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int carry = 0;
+    for (int base = 0; base < T_cur; base += kScanThreads) {
+        const int i = base + tid;
+        const int y = i < T_cur ? labels_t[i] : ignore_index;
+        const bool valid = i < T_cur && label_valid(y, ignore_index, V);
+        const unsigned long long mask = __ballot(valid);
+        const int below = __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
+                                                    __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
+        if (lane == 0) wave_total[wave] = __popcll(mask);
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < kScanThreads / 64; ++w) {
+            const int c = wave_total[w];
+            if (w < wave) before += c;
+            total += c;
+        }
+        if (i < T_cur) {
+            if (valid) {
+                const int j = carry + before + below;
+                pos[i] = j;
+                idx[j] = i;
+                yc[j] = y;
+            } else {
+                pos[i] = -1;
+                if (lse_t) lse_t[i] = 0.f;
+                if (loss_rows_t) loss_rows_t[i] = 0.f;
+            }
+        }
+        carry += total;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        info->Tc = carry;
+        info->Trc = (carry + kBlockR - 1) / kBlockR * kBlockR;
+        info->Tkc = (carry + kBlockK - 1) / kBlockK * kBlockK;
+        info->kofs = prev ? prev->kofs + prev->Tkc : 0;     // prev: the tile before, same dW group
+    }
+}
+
+// Block b: row b of the tile.  A valid row is copied to its place in the dense matrix Hc, the
+// dHidden row of any other row is zero-filled; rows Tc <= b < Trc of Hc are zero padding.
+__global__ __launch_bounds__(256) void gather_rows_kernel(
+    const uint16_t* __restrict__ hidden_t, int H, int T_cur, const int32_t* __restrict__ pos,
+    const TileInfo* __restrict__ info, uint16_t* __restrict__ Hc, uint16_t* __restrict__ dH_t) {
+    const int b = blockIdx.x;
+    const int chunks = H / 8;
+    const u32x4_t zero4 = {0u, 0u, 0u, 0u};
+    if (b < T_cur) {
+        const int p = pos[b];
+        if (p >= 0) {
+            const u32x4_t* src = reinterpret_cast<const u32x4_t*>(hidden_t + (int64_t)b * H);
+            u32x4_t* dst = reinterpret_cast<u32x4_t*>(Hc + (int64_t)p * H);
+            for (int c = threadIdx.x; c < chunks; c += 256) dst[c] = src[c];
+        } else if (dH_t) {
+            u32x4_t* dst = reinterpret_cast<u32x4_t*>(dH_t + (int64_t)b * H);
+            for (int c = threadIdx.x; c < chunks; c += 256) dst[c] = zero4;
+        }
+    }
+    if (b >= info->Tc && b < info->Trc) {
+        u32x4_t* dst = reinterpret_cast<u32x4_t*>(Hc + (int64_t)b * H);
+        for (int c = threadIdx.x; c < chunks; c += 256) dst[c] = zero4;
+    }
+}
+
 // out[c][r] = in[r][c] for r < R, 0 for R <= r < Rpad; c < C.  16-byte accesses on both sides.
+// With `info` the row extent is the tile's padded valid row count instead of R and Rpad, and the
+// output starts at the tile's k offset inside its dW group.
 __global__ __launch_bounds__(256) void transpose_pad_kernel(const uint16_t* __restrict__ in,
                                                             int64_t ld_in, int R, int C,
                                                             uint16_t* __restrict__ out,
-                                                            int64_t ld_out, int Rpad) {
+                                                            int64_t ld_out, int Rpad,
+                                                            const TileInfo* __restrict__ info) {
     __shared__ uint16_t t[64][66];
+    if (info) {
+        R = Rpad = info->Trc;
+        out += info->kofs;
+    }
     const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+    if (r0 >= Rpad) return;
     const int tid = threadIdx.x;
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
@@ -156,20 +275,22 @@ __global__ __launch_bounds__(256) void transpose_pad_kernel(const uint16_t* __re
     }
 }
 
-// Per row of the tile: combine the per-group (max, sum exp) partials into lse, the row's loss
-// term, and (fused mode) the factor that turns the stashed e into a probability.
+// Per dense row of the tile: combine the per-group (max, sum exp) partials into lse, the row's loss
+// term (both written to the row's original position), and (fused mode) the factor that turns the
+// stashed e into a probability.
 // Block = 64 rows x 16 group lanes: thread (x, y) owns groups y, y + 16, ... of row x; the 16
 // lanes of a row are combined through LDS in a fixed order, so lse does not depend on anything
 // but the row's partials.
 constexpr int kCombineRows = 64, kCombineLanes = 16;
 __global__ __launch_bounds__(kCombineRows * kCombineLanes) void row_combine_kernel(
     const float* __restrict__ pm, const float* __restrict__ ps, const float* __restrict__ zlabel,
-    const int32_t* __restrict__ labels_t, int T_cur, int Tr, int Tp, int ng, int ignore_index,
-    int V, float* __restrict__ lse_t, float* __restrict__ loss_rows_t, float* __restrict__ sc) {
+    const int32_t* __restrict__ idx, const TileInfo* __restrict__ info, int Tp, int ng,
+    float* __restrict__ lse_t, float* __restrict__ loss_rows_t, float* __restrict__ sc) {
     __shared__ float red[kCombineLanes][kCombineRows];
     const int x = threadIdx.x, y = threadIdx.y;
-    const int i = blockIdx.x * kCombineRows + x;          // Tr is a multiple of 256: i < Tr
-    const bool inrow = i < T_cur;
+    if ((int)blockIdx.x * kCombineRows >= info->Trc) return;
+    const int i = blockIdx.x * kCombineRows + x;          // dense row; Trc is a multiple of 256
+    const bool inrow = i < info->Tc;                      // every dense row below Tc is valid
     float m = -INFINITY;
     for (int g = y; g < ng; g += kCombineLanes) m = fmaxf(m, pm[(int64_t)g * Tp + i]);
     red[y][x] = m;
@@ -187,20 +308,20 @@ __global__ __launch_bounds__(kCombineRows * kCombineLanes) void row_combine_kern
 #pragma unroll
     for (int l = 1; l < kCombineLanes; ++l) S += red[l][x];
     const float lse = M + __logf(S);
-    const bool valid = inrow && label_valid(labels_t[inrow ? i : 0], ignore_index, V);
     if (inrow && y == 0) {
-        lse_t[i] = lse;
-        loss_rows_t[i] = valid ? lse - zlabel[i] : 0.f;
+        const int orig = idx[i];
+        lse_t[orig] = lse;
+        loss_rows_t[orig] = lse - zlabel[i];
     }
     if (sc) {
         for (int g = y; g < ng; g += kCombineLanes)
-            sc[(int64_t)g * Tp + i] = valid ? __expf(pm[(int64_t)g * Tp + i] - lse) : 0.f;
+            sc[(int64_t)g * Tp + i] = inrow ? __expf(pm[(int64_t)g * Tp + i] - lse) : 0.f;
     }
 }
 
-// dZ = valid * (e * factor - onehot), bf16, written over the stash and transposed into dzt.
-// Rows >= T_cur and columns >= V come out as exact zeros, which is what pads the k dimension of
-// the two gradient GEMMs.  One wavefront owns a 64 (rows) x 64 (columns) patch, one lane an 8 x 8
+// dZ = e * factor - onehot for the tile's dense rows, bf16, written over the stash and transposed
+// into dzt.  Rows Tc .. Trc and columns >= V come out as exact zeros, which is what pads the k
+// dimension of the two gradient GEMMs.  One wavefront owns a 64 (rows) x 64 (columns) patch, one lane an 8 x 8
 // block of it: lanes run along v for the row-major reads and in-place writes (8 lanes = one
 // 128-byte line) and along i for the transposed writes, and the 8 x 8 transpose is done in
 // registers with byte permutes, so every global access is a full line and no LDS is used.
@@ -208,21 +329,23 @@ template <bool FUSED>
 __global__ __launch_bounds__(256) void dz_finalize_kernel(uint16_t* __restrict__ stash,
                                                           uint16_t* __restrict__ dzt,
                                                           const float* __restrict__ sc,
-                                                          const int32_t* __restrict__ labels_t,
-                                                          int T_cur, int Tp, int Vp, int V,
-                                                          int ignore_index) {
+                                                          const int32_t* __restrict__ yc,
+                                                          const TileInfo* __restrict__ info,
+                                                          int Tp, int Vp, int64_t Kg) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int v0 = (blockIdx.x * 4 + wave) * 64 + (lane & 7) * 8;      // first of this lane's 8 columns
     const int i0 = blockIdx.y * 64 + (lane >> 3) * 8;                 // first of this lane's 8 rows
-    if (v0 >= Vp) return;
+    if (v0 >= Vp || (int)blockIdx.y * 64 >= info->Trc) return;
+    const int T_cur = info->Tc;
+    dzt += info->kofs;                                   // dzt is [Vp, Kg]
     uint32_t in[8][4];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const int i = i0 + j;
         uint16_t* p = stash + (int64_t)i * Vp + v0;
         const bf16x8_t e = *reinterpret_cast<const bf16x8_t*>(p);
-        const int y = i < T_cur ? labels_t[i] : ignore_index;
-        const bool valid = i < T_cur && label_valid(y, ignore_index, V);
+        const bool valid = i < T_cur;                   // dense rows below Tc all carry a valid label
+        const int y = valid ? yc[i] : -1;
         float f = valid ? 1.f : 0.f;
         if (FUSED) f = valid ? sc[(int64_t)(v0 >> 7) * Tp + i] : 0.f;
         bf16x8_t d;
@@ -248,7 +371,7 @@ __global__ __launch_bounds__(256) void dz_finalize_kernel(uint16_t* __restrict__
             o[pr] = (x & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u)
                             : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
         }
-        *reinterpret_cast<u32x4_t*>(dzt + (int64_t)(v0 + x) * Tp + i0) = o;
+        *reinterpret_cast<u32x4_t*>(dzt + (int64_t)(v0 + x) * Kg + i0) = o;
     }
 }
 
@@ -314,15 +437,17 @@ __global__ void shift_labels_kernel(const int32_t* __restrict__ labels, int32_t*
 enum { MODE_FWD = 0, MODE_FUSED = 1, MODE_BWD = 2 };
 
 struct LogitsParams {
-    const uint16_t* hidden_t;   // [T_cur, H]
+    const uint16_t* hidden_t;   // [Tp, H]      the tile's dense (valid) rows, zero padded to Trc
     const uint16_t* W;          // [V, H]
-    const int32_t* labels_t;    // [T_cur]
-    const float* lse_t;         // [T_cur]      MODE_BWD
+    const int32_t* labels_t;    // [Tp]         labels of the dense rows
+    const int32_t* idx;         // [Tp]         dense row -> row of the tile
+    const TileInfo* info;
+    const float* lse_t;         // [T_cur]      MODE_BWD, indexed by the row of the tile
     float* pm;                  // [ng, Tp]     MODE_FWD / MODE_FUSED
     float* ps;                  // [ng, Tp]
     float* zlabel;              // [Tp]
     uint16_t* stash;            // [Tp, Vp]     MODE_FUSED / MODE_BWD
-    int T_cur, Tr, Tp, H, V, Vp, ignore_index;   // Tr = T_cur rounded up to 256, Tp = row stride
+    int Tp, H, V, Vp;           // Tp = row stride of the per-tile arrays
 };
 
 // r = token row of the tile (MFMA lane dimension), c = vocabulary id (register dimension).
@@ -331,7 +456,9 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
     constexpr int kMT = Core::kMT, kNT = Core::kNT;
     extern __shared__ __align__(16) unsigned char smem[];
     int tr, tc;
-    if (!tile_of_block<4, 8>(blockIdx.x, p.Tr / kBlockR, p.Vp / kBlockC, tr, tc)) return;
+    const int T_cur = p.info->Tc, Trc = p.info->Trc;
+    if (T_cur == 0) return;
+    if (!tile_of_block<4, 8>(blockIdx.x, Trc / kBlockR, p.Vp / kBlockC, tr, tc)) return;
     const int r0 = tr * kBlockR, c0 = tc * kBlockC;
 
     f32x16_t acc[kMT][kNT];
@@ -342,14 +469,14 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
-    Core::template gemm<GUARD>(p.hidden_t, p.H, p.T_cur, p.W, p.H, p.V, p.H, r0, c0, smem, acc);
+    Core::template gemm<GUARD>(p.hidden_t, p.H, Trc, p.W, p.H, p.V, p.H, r0, c0, smem, acc);
 
     const typename Core::Lane lp;
     const bool mask_cols = c0 + kBlockC > p.V;
 #pragma unroll
     for (int nt = 0; nt < kNT; ++nt) {
         const int i = r0 + lp.r(nt);
-        const bool rowok = i < p.T_cur;
+        const bool rowok = i < T_cur;
         if (mask_cols) {
 #pragma unroll
             for (int mt = 0; mt < kMT; ++mt)
@@ -359,7 +486,7 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
         }
         float ref;
         if (MODE == MODE_BWD) {
-            ref = rowok ? p.lse_t[i] : 0.f;
+            ref = rowok ? p.lse_t[p.idx[i]] : 0.f;
         } else {
             float m = -INFINITY;
 #pragma unroll
@@ -369,8 +496,7 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
             m = fmaxf(m, __shfl_xor(m, 32));
             ref = (m == -INFINITY) ? 0.f : m;
             // label logit: exactly one lane of one block holds column y of row i
-            int y = rowok ? p.labels_t[i] : -1;
-            if (y == p.ignore_index) y = -1;
+            const int y = rowok ? p.labels_t[i] : -1;
             const unsigned d = (unsigned)(y - (c0 + lp.wc * kGroupC));
             if (y >= 0 && d < (unsigned)kGroupC && ((d >> 2) & 1u) == (unsigned)lp.half) {
                 float zl = 0.f;
@@ -417,11 +543,13 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
 }
 
 struct DHiddenParams {
-    const uint16_t* dz;      // [Tp, Vp]
+    const uint16_t* dz;      // [Tp, Vp]     dense rows
     const uint16_t* wt;      // [H, Vp]
-    uint16_t* dH_t;          // [T_cur, H]
+    uint16_t* dH_t;          // [T_cur, H]   rows of the tile; dense row i goes to row idx[i]
+    const int32_t* idx;
+    const TileInfo* info;
     const Header* hdr;
-    int T_cur, Tr, Tp, H, Vp;
+    int Tp, H, Vp;
 };
 
 // r = token row (lane dimension), c = hidden index (register dimension), k = vocabulary.
@@ -431,9 +559,10 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
     extern __shared__ __align__(16) unsigned char smem[];
     int tr, tc;
     const int tiles_c = (p.H + kBlockC - 1) / kBlockC;
-    if (!tile_of_block<4, 8>(blockIdx.x, p.Tr / kBlockR, tiles_c, tr, tc)) return;
+    const int T_cur = p.info->Tc, Trc = p.info->Trc;
+    if (T_cur == 0) return;
+    if (!tile_of_block<4, 8>(blockIdx.x, Trc / kBlockR, tiles_c, tr, tc)) return;
     const int r0 = tr * kBlockR, c0 = tc * kBlockC;
-    if (r0 >= p.T_cur) return;      // rows that do not exist in a ragged tile
 
     f32x16_t acc[kMT][kNT];
 #pragma unroll
@@ -443,15 +572,15 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
-    Core::template gemm<GUARD>(p.dz, p.Vp, p.Tr, p.wt, p.Vp, p.H, p.Vp, r0, c0, smem, acc);
+    Core::template gemm<GUARD>(p.dz, p.Vp, Trc, p.wt, p.Vp, p.H, p.Vp, r0, c0, smem, acc);
 
     const typename Core::Lane lp;
     const float inv = p.hdr->inv;
 #pragma unroll
     for (int nt = 0; nt < kNT; ++nt) {
         const int i = r0 + lp.r(nt);
-        if (i >= p.T_cur) continue;
-        uint16_t* row = p.dH_t + (int64_t)i * p.H;
+        if (i >= T_cur) continue;
+        uint16_t* row = p.dH_t + (int64_t)p.idx[i] * p.H;
 #pragma unroll
         for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
@@ -467,22 +596,30 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
 }
 
 struct DWParams {
-    const uint16_t* dzt;     // [Vp, Tp]
-    const uint16_t* ht;      // [H, Tp]
+    const uint16_t* ht;      // [H, Kg]      dense rows of the group's tiles, transposed
+    const uint16_t* dzt;     // [Vp, Kg]
     float* acc;              // [V, H]
-    int Tk;                  // rows of the tile rounded up to 64 (k extent)
-    int Tp, H, V, Vp;
-    int first;               // first tile: store instead of add
+    const TileInfo* info;    // of the group's last tile: k extent = kofs + Tkc
+    int64_t Kg;
+    int H, V, Vp;
+    int first;               // first group: store instead of add
 };
 
-// r = vocabulary id (lane dimension), c = hidden index (register dimension), k = token row.
+// r = hidden index (lane dimension), c = vocabulary id (register dimension), k = dense token row.
+// With the hidden index along the lanes, each accumulator register of a wavefront covers 32
+// consecutive floats of one row of acc: the accumulate is one fire-and-forget fp32 atomic add per
+// register on full 128-byte lines, and the wavefront does not wait for the old sums.  Each element
+// is touched by exactly one lane per launch and launches are ordered on the stream, so the sums
+// are formed in tile order: deterministic.
 template <class Core, bool GUARD>
 __global__ __launch_bounds__(Core::kThreads) void dw_kernel(const DWParams p) {
     constexpr int kMT = Core::kMT, kNT = Core::kNT;
     extern __shared__ __align__(16) unsigned char smem[];
     int tr, tc;
-    const int tiles_c = (p.H + kBlockC - 1) / kBlockC;
-    if (!tile_of_block<8, 4>(blockIdx.x, p.Vp / kBlockR, tiles_c, tr, tc)) return;
+    const int tiles_r = (p.H + kBlockR - 1) / kBlockR;
+    const int Tkc = p.info->kofs + p.info->Tkc;      // k extent of the whole group
+    if (Tkc == 0 && !p.first) return;
+    if (!tile_of_block<4, 8>(blockIdx.x, tiles_r, p.Vp / kBlockC, tr, tc)) return;
     const int r0 = tr * kBlockR, c0 = tc * kBlockC;
 
     f32x16_t acc[kMT][kNT];
@@ -493,39 +630,23 @@ __global__ __launch_bounds__(Core::kThreads) void dw_kernel(const DWParams p) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
-    Core::template gemm<GUARD>(p.dzt, p.Tp, p.Vp, p.ht, p.Tp, p.H, p.Tk, r0, c0, smem, acc);
+    if (Tkc > 0)
+        Core::template gemm<GUARD>(p.ht, p.Kg, p.H, p.dzt, p.Kg, p.Vp, Tkc, r0, c0, smem, acc);
 
     const typename Core::Lane lp;
 #pragma unroll
     for (int nt = 0; nt < kNT; ++nt) {
-        const int v = r0 + lp.r(nt);
-        if (v >= p.V) continue;
-        float* row = p.acc + (int64_t)v * p.H;
-        // all reads of the old sums first, then the adds and stores: the reads overlap instead of
-        // each waiting behind the previous store
-        f32x4_t old[kMT][4];
-        if (!p.first) {
-#pragma unroll
-            for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int h = c0 + lp.c(mt, q);
-                    old[mt][q] = (GUARD && h >= p.H)
-                                     ? f32x4_t{0.f, 0.f, 0.f, 0.f}
-                                     : __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(row + h));
-                }
-        }
+        const int h = r0 + lp.r(nt);
+        if (GUARD && h >= p.H) continue;
 #pragma unroll
         for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int h = c0 + lp.c(mt, q);
-                if (GUARD && h >= p.H) continue;
-                f32x4_t a;
-#pragma unroll
-                for (int x = 0; x < 4; ++x) a[x] = acc[mt][nt][q * 4 + x];
-                if (!p.first) a += old[mt][q];
-                *reinterpret_cast<f32x4_t*>(row + h) = a;
+            for (int j = 0; j < 16; ++j) {
+                const int v = c0 + lp.c(mt, j >> 2) + (j & 3);
+                if (v >= p.V) continue;
+                float* dst = p.acc + (int64_t)v * p.H + h;
+                if (p.first) *dst = acc[mt][nt][j];
+                else unsafeAtomicAdd(dst, acc[mt][nt][j]);
             }
     }
 }
@@ -642,16 +763,18 @@ static int validate(const Problem& P, size_t workspace_bytes, bool need_fwd_out,
 }
 
 static int launch_transpose(const uint16_t* in, int64_t ld_in, int R, int C, uint16_t* out,
-                            int64_t ld_out, int Rpad, hipStream_t s) {
+                            int64_t ld_out, int Rpad, const TileInfo* info, hipStream_t s) {
     dim3 grid((Rpad + 63) / 64, (C + 63) / 64);
     hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, s, in, ld_in, R, C, out, ld_out,
-                       Rpad);
+                       Rpad, info);
     return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
 }
 
+// Grids are sized for Tr (the tile's rows rounded up to the block height); the kernels read the
+// number of rows that take part from the device and surplus blocks leave at once.
 template <int MODE>
-static int launch_logits(const LogitsParams& lp, bool guard, hipStream_t s) {
-    const int grid = grid_for_tiles<4, 8>(lp.Tr / kBlockR, lp.Vp / kBlockC);
+static int launch_logits(const LogitsParams& lp, int Tr, bool guard, hipStream_t s) {
+    const int grid = grid_for_tiles<4, 8>(Tr / kBlockR, lp.Vp / kBlockC);
     if (guard)
         hipLaunchKernelGGL((logits_kernel<StagedCore, true, MODE>), dim3(grid),
                            dim3(StagedCore::kThreads), kLdsBytes, s, lp);
@@ -668,12 +791,17 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
     const Layout L = make_layout(P.N, P.H, P.V, P.tile, P.flags);
     hipStream_t s = P.stream;
     Header* hdr = reinterpret_cast<Header*>(P.ws + L.header);
+    TileInfo* infos = reinterpret_cast<TileInfo*>(P.ws + L.tinfo);
     float* loss_rows = reinterpret_cast<float*>(P.ws + L.loss_rows);
     float* lse_buf = P.lse_out ? P.lse_out : reinterpret_cast<float*>(P.ws + L.lse);
     float* zlabel = reinterpret_cast<float*>(P.ws + L.zlabel);
+    int32_t* yc = reinterpret_cast<int32_t*>(P.ws + L.yc);
+    int32_t* idx = reinterpret_cast<int32_t*>(P.ws + L.idx);
+    int32_t* pos = reinterpret_cast<int32_t*>(P.ws + L.pos);
     float* pm = reinterpret_cast<float*>(P.ws + L.pm);
     float* ps = reinterpret_cast<float*>(P.ws + L.ps);
     float* sc = reinterpret_cast<float*>(P.ws + L.sc);
+    uint16_t* hc = reinterpret_cast<uint16_t*>(P.ws + L.hc);
     uint16_t* stash = reinterpret_cast<uint16_t*>(P.ws + L.stash);
     uint16_t* dzt = reinterpret_cast<uint16_t*>(P.ws + L.dzt);
     uint16_t* wt = reinterpret_cast<uint16_t*>(P.ws + L.wt);
@@ -695,9 +823,14 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
     ALST_HIP(hipGetLastError());
 
     if (do_bwd) {
-        rc = launch_transpose(P.W, H, V, H, wt, Vp, Vp, s);
+        rc = launch_transpose(P.W, H, V, H, wt, Vp, Vp, nullptr, s);
         if (rc != ALST_OK) return rc;
     }
+
+    // unguarded kernels need every extent block-aligned; the row extent always is (dense rows are
+    // zero padded to a multiple of the block height)
+    const bool guard_logits = (V % kBlockC) != 0 || (H % kBlockK) != 0;
+    const bool guard_h = (H % kBlockC) != 0;
 
     const int64_t ntiles = (P.N + T - 1) / T;
     for (int64_t t = 0; t < ntiles; ++t) {
@@ -706,22 +839,34 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
         const uint16_t* hidden_t = P.hidden + i0 * P.H;
         const int32_t* labels_t = P.labels + i0;
         const int Tr = (T_cur + kBlockR - 1) / kBlockR * kBlockR;
-        const bool guard_rows = (T_cur % kBlockR) != 0;
+        const int slot = (int)(t % L.g);                // position inside the dW group
+        TileInfo* info = infos + slot;
+
+        {
+            ProfScope small_(PROF_OTHER, s);
+            hipLaunchKernelGGL(compact_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, labels_t,
+                               T_cur, P.ignore_index, V, yc, idx, pos, info,
+                               slot ? info - 1 : nullptr,
+                               do_fwd ? lse_buf + i0 : nullptr, do_fwd ? loss_rows + i0 : nullptr);
+            hipLaunchKernelGGL(gather_rows_kernel, dim3(Tr), dim3(256), 0, s, hidden_t, H, T_cur,
+                               pos, info, hc, do_bwd ? P.dHidden + i0 * P.H : nullptr);
+            ALST_HIP(hipGetLastError());
+        }
 
         LogitsParams lp;
-        lp.hidden_t = hidden_t;
+        lp.hidden_t = hc;
         lp.W = P.W;
-        lp.labels_t = labels_t;
+        lp.labels_t = yc;
+        lp.idx = idx;
+        lp.info = info;
         lp.lse_t = do_fwd ? nullptr : P.lse_in + i0;
         lp.pm = pm; lp.ps = ps; lp.zlabel = zlabel; lp.stash = stash;
-        lp.T_cur = T_cur; lp.Tr = Tr; lp.Tp = Tp; lp.H = H; lp.V = V; lp.Vp = Vp;
-        lp.ignore_index = P.ignore_index;
-        const bool guard1 = guard_rows || (V % kBlockC) != 0 || (H % kBlockK) != 0;
+        lp.Tp = Tp; lp.H = H; lp.V = V; lp.Vp = Vp;
         {
             ProfScope ps_(PROF_LOGITS, s);
-            if (do_fwd && do_bwd) rc = launch_logits<MODE_FUSED>(lp, guard1, s);
-            else if (do_fwd) rc = launch_logits<MODE_FWD>(lp, guard1, s);
-            else rc = launch_logits<MODE_BWD>(lp, guard1, s);
+            if (do_fwd && do_bwd) rc = launch_logits<MODE_FUSED>(lp, Tr, guard_logits, s);
+            else if (do_fwd) rc = launch_logits<MODE_FWD>(lp, Tr, guard_logits, s);
+            else rc = launch_logits<MODE_BWD>(lp, Tr, guard_logits, s);
         }
         if (rc != ALST_OK) return rc;
 
@@ -729,31 +874,31 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             ProfScope small_(PROF_OTHER, s);
             if (do_fwd) {
                 hipLaunchKernelGGL(row_combine_kernel, dim3(Tr / kCombineRows),
-                                   dim3(kCombineRows, kCombineLanes), 0, s, pm, ps,
-                                   zlabel, labels_t, T_cur, Tr, Tp, ng, P.ignore_index, V,
-                                   lse_buf + i0, loss_rows + i0, do_bwd ? sc : nullptr);
+                                   dim3(kCombineRows, kCombineLanes), 0, s, pm, ps, zlabel, idx,
+                                   info, Tp, ng, lse_buf + i0, loss_rows + i0,
+                                   do_bwd ? sc : nullptr);
                 ALST_HIP(hipGetLastError());
             }
             if (do_bwd) {
                 dim3 grid(Vp / 256, Tr / 64);
                 if (do_fwd)
                     hipLaunchKernelGGL(dz_finalize_kernel<true>, grid, dim3(256), 0, s, stash, dzt,
-                                       sc, labels_t, T_cur, Tp, Vp, V, P.ignore_index);
+                                       sc, yc, info, Tp, Vp, L.Kg);
                 else
                     hipLaunchKernelGGL(dz_finalize_kernel<false>, grid, dim3(256), 0, s, stash, dzt,
-                                       sc, labels_t, T_cur, Tp, Vp, V, P.ignore_index);
+                                       sc, yc, info, Tp, Vp, L.Kg);
                 ALST_HIP(hipGetLastError());
-                rc = launch_transpose(hidden_t, H, T_cur, H, ht, Tp, Tr, s);
+                rc = launch_transpose(hc, H, Tr, H, ht, L.Kg, Tr, info, s);
                 if (rc != ALST_OK) return rc;
             }
         }
         if (!do_bwd) continue;
 
-        const bool guard_h = (H % kBlockC) != 0;
         {
             DHiddenParams dp;
-            dp.dz = stash; dp.wt = wt; dp.dH_t = P.dHidden + i0 * P.H; dp.hdr = hdr;
-            dp.T_cur = T_cur; dp.Tr = Tr; dp.Tp = Tp; dp.H = H; dp.Vp = Vp;
+            dp.dz = stash; dp.wt = wt; dp.dH_t = P.dHidden + i0 * P.H; dp.idx = idx;
+            dp.info = info; dp.hdr = hdr;
+            dp.Tp = Tp; dp.H = H; dp.Vp = Vp;
             const int grid = grid_for_tiles<4, 8>(Tr / kBlockR, (H + kBlockC - 1) / kBlockC);
             ProfScope ps_(PROF_DHIDDEN, s);
             if (guard_h)
@@ -764,12 +909,11 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
                                    dim3(DirectCore::kThreads), kLdsBytes, s, dp);
             ALST_HIP(hipGetLastError());
         }
-        {
+        if (slot == L.g - 1 || t == ntiles - 1) {           // the group is complete
             DWParams wp;
-            wp.dzt = dzt; wp.ht = ht; wp.acc = acc;
-            wp.Tk = (T_cur + kBlockK - 1) / kBlockK * kBlockK;
-            wp.Tp = Tp; wp.H = H; wp.V = V; wp.Vp = Vp; wp.first = (t == 0);
-            const int grid = grid_for_tiles<8, 4>(Vp / kBlockR, (H + kBlockC - 1) / kBlockC);
+            wp.ht = ht; wp.dzt = dzt; wp.acc = acc; wp.info = info;
+            wp.Kg = L.Kg; wp.H = H; wp.V = V; wp.Vp = Vp; wp.first = (t < L.g);
+            const int grid = grid_for_tiles<4, 8>((H + kBlockR - 1) / kBlockR, Vp / kBlockC);
             ProfScope ps_(PROF_DW, s);
             if (guard_h)
                 hipLaunchKernelGGL((dw_kernel<StagedCore, true>), dim3(grid),

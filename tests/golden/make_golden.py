@@ -4,7 +4,8 @@ the CPU fp64 oracle ALONE (nothing here touches the HIP library).
 
 The full-size checks need lse of every row (2*N*H*V fp64 flop: minutes to an hour of CPU time), too
 slow to recompute inside a GPU test, so they are computed once here from the seeded inputs and
-stored: the loss, the number of valid tokens, lse at sampled rows, and exact dW entries for a sample
+stored: the loss, the number of valid tokens, lse at sampled rows, the sum of lse over all rows and
+over the rows with a valid label (the library skips the rows of ignored tokens), and exact dW entries for a sample
 of vocabulary ids (always including id 0, V-1, ids at 256-column block edges, the most frequent
 labels, ids that never occur as a label) at a sample of hidden columns, plus each sampled dW row's
 max |.| for the normaliser.  dHidden rows are cheap and are computed by the test itself.
@@ -61,6 +62,7 @@ def main():
             "workload": name, "N": wl.N, "H": wl.H, "V": wl.V,
             "loss": f["loss"], "n_valid": f["n_valid"],
             "lse_sum": float(np.sum(f["lse"])),
+            "lse_sum_valid": float(np.sum(f["lse"][y != synth.IGNORE_INDEX])),
             "lse_rows": rows.tolist(), "lse_values": [float(x) for x in f["lse"][rows]],
             "dw_ids": ids.tolist(), "dw_label_counts": [int(counts[v]) for v in ids],
             "dw_cols": cols.tolist(),

