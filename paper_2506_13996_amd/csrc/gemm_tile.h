@@ -34,7 +34,9 @@ constexpr int kBlockC = 256;          // rows of Y per block (MFMA register dime
 constexpr int kBlockK = 64;           // k per main-loop step
 constexpr int kGroupC = 128;          // c extent one wavefront covers (both cores)
 constexpr int kTileBytes = kBlockR * kBlockK * 2;       // one operand tile in LDS (32 KB)
-constexpr int kLdsBytes = 4 * kTileBytes;               // X, Y, two stages each (128 KB)
+constexpr int kStageBytes = 4 * kTileBytes;             // X, Y, two stages each (128 KB)
+constexpr int kLdsBytes = kStageBytes + 1024;           // + landing area of the L2 warm-up loads
+constexpr int kWarmAhead = 3;                           // k-steps between warm-up and DMA of a line
 
 // XCD-aware block -> tile mapping.  Workgroups are dealt round-robin to the 8 XCDs (each with its
 // own L2); the 32 workgroups that are resident together on one XCD get a compact PR x PC patch of
@@ -58,6 +60,24 @@ template <int PR, int PC>
 inline int grid_for_tiles(int tiles_r, int tiles_c) {
     const int patches = ((tiles_r + PR - 1) / PR) * ((tiles_c + PC - 1) / PC);
     return ((patches + 7) / 8) * 8 * PR * PC;
+}
+
+// L2 warm-up.  The blocks of a patch that share an operand tile walk k in step, so each of them
+// would meet every line of the tile as an L2 miss at the same moment.  Instead the sharers split
+// the tile's rows between them and each touches one dword per line of its share kWarmAhead
+// k-steps before the DMA needs it: the miss latency is paid early and once, and the sixteen DMA
+// instructions of a k-step find their lines in L2.  Returns this lane's row of X or Y (the
+// pointer to its first element); every lane gets a valid row, surplus lanes repeat one.
+template <int PR, int PC>
+__device__ __forceinline__ const uint16_t* warm_row(const uint16_t* X, int64_t ldx, int r0, int tr,
+                                                    const uint16_t* Y, int64_t ldy, int c0, int tc) {
+    constexpr int nx = kBlockR / PC, ny = kBlockC / PR, total = nx + ny, per = (total + 3) / 4;
+    static_assert(per <= 64, "one warm-up instruction per wavefront");
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int l = w * per + (lane < per ? lane : per - 1);
+    if (l > total - 1) l = total - 1;
+    if (l < nx) return X + (int64_t)(r0 + (tc % PC) * nx + l) * ldx;
+    return Y + (int64_t)(c0 + (tr % PR) * ny + (l - nx)) * ldy;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -96,7 +116,8 @@ struct StagedCore {
     static __device__ __forceinline__ void gemm(const uint16_t* __restrict__ X, int64_t ldx,
                                                 int rows_x, const uint16_t* __restrict__ Y,
                                                 int64_t ldy, int rows_y, int K, int r0, int c0,
-                                                unsigned char* smem, f32x16_t (&acc)[kMT][kNT]) {
+                                                unsigned char* smem, f32x16_t (&acc)[kMT][kNT],
+                                                const uint16_t* /*warm*/ = nullptr) {
         const int tid = threadIdx.x;
         const Lane lp;
         const int lrow = tid >> 3;      // 0..63, row inside a 64-row slab of the operand tile
@@ -213,7 +234,8 @@ struct DirectCore {
     static __device__ __forceinline__ void gemm(const uint16_t* __restrict__ X, int64_t ldx,
                                                 int /*rows_x*/, const uint16_t* __restrict__ Y,
                                                 int64_t ldy, int /*rows_y*/, int K, int r0, int c0,
-                                                unsigned char* smem, f32x16_t (&acc)[kMT][kNT]) {
+                                                unsigned char* smem, f32x16_t (&acc)[kMT][kNT],
+                                                const uint16_t* warm) {
         static_assert(!GUARD, "DirectCore has no bounds checks");
         typedef const __attribute__((address_space(1))) void* gptr_t;
         typedef __attribute__((address_space(3))) void* lptr_t;
@@ -282,6 +304,22 @@ struct DirectCore {
         };
 
         const int KT = K / kBlockK;
+        // One 4-byte DMA per wavefront and k-step into a landing area nobody reads: it only pulls
+        // the line into L2.  `warm` (see warm_row) must be a valid row pointer in every lane.
+        constexpr bool warming = true;
+        unsigned char* const dump = smem + kStageBytes + w * 256;
+        auto warm_step = [&](int kt) {
+            const int kk = kt < KT ? kt : KT - 1;
+            __builtin_amdgcn_global_load_lds((gptr_t)(warm + kk * kBlockK), (lptr_t)dump, 4, 0, 0);
+        };
+        // Joins the wavefronts once this wavefront's DMA of the next stage has landed.  The warm-up
+        // load issued after that DMA may still be in flight (loads complete in order).
+        auto stage_barrier = [&](bool one_behind) {
+            if (one_behind) asm volatile("s_waitcnt vmcnt(1) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        };
+        if (warming)
+            for (int p = 2; p < 2 + kWarmAhead; ++p) warm_step(p);
         issue_loads(0, 0);
         __syncthreads();                       // waits for the DMA (vmcnt) and joins the waves
         if (KT > 1) issue_loads(1, 1);
@@ -290,7 +328,11 @@ struct DirectCore {
         // One k-step.  LOADS: refill the stage just consumed with step kt + 2.  NEXT: read the
         // first quarter's operands of step kt + 1.  The tail steps skip them so that no DMA is in
         // flight when the workgroup ends.
-        auto kstep = [&](int kt, auto loads, auto next) {
+        // The last quarter is ordered by hand, in eight fenced slices of two MFMAs, two DMA
+        // instructions and one operand read: left to the scheduler the sixteen DMA instructions
+        // come out back to back and the matrix pipe idles behind their issue.
+        // BEHIND: the previous k-step issued a warm-up load after its DMA.
+        auto kstep = [&](int kt, auto loads, auto next, bool behind) {
             constexpr bool LOADS = decltype(loads)::value, NEXT = decltype(next)::value;
             const int cur = kt & 1;
             read_frags(fy1, fx1, cur, 1);
@@ -302,25 +344,43 @@ struct DirectCore {
             read_frags(fy1, fx1, cur, 3);
             mfmas(fy0, fx0);
             sched_reads();
-            __syncthreads();                   // stage cur fully read; stage cur ^ 1 has landed
-            if (LOADS) issue_loads(cur, kt + 2);
-            if (NEXT) read_frags(fy0, fx0, cur ^ 1, 0);
-            mfmas(fy1, fx1);
+            stage_barrier(behind);             // stage cur fully read; stage cur ^ 1 has landed
+            __builtin_amdgcn_sched_barrier(0);
+            unsigned char* const xs = smem + cur * kTileBytes + w * 8192;
+            unsigned char* const ys = smem + 2 * kTileBytes + cur * kTileBytes + w * 8192;
+            const unsigned char* const nx = smem + (cur ^ 1) * kTileBytes;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                if (LOADS) __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                if (NEXT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                const int mt = i >> 1, n0 = (i & 1) * 2;
+                acc[mt][n0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy1[mt], fx1[n0],
+                                                                      acc[mt][n0], 0, 0, 0);
+                acc[mt][n0 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy1[mt], fx1[n0 + 1],
+                                                                          acc[mt][n0 + 1], 0, 0, 0);
+                if (LOADS) {
+                    __builtin_amdgcn_global_load_lds((gptr_t)(xg[i] + (kt + 2) * kBlockK),
+                                                     (lptr_t)(xs + i * 1024), 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds((gptr_t)(yg[i] + (kt + 2) * kBlockK),
+                                                     (lptr_t)(ys + i * 1024), 16, 0, 0);
+                }
+                if (NEXT) {
+                    if (i < 4)
+                        fy0[i] = *reinterpret_cast<const bf16x8_t*>(nx + ybase + i * 4096 + rofs[0]);
+                    else
+                        fx0[i - 4] = *reinterpret_cast<const bf16x8_t*>(nx + xbase + (i - 4) * 4096 +
+                                                                        rofs[0]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
+            if (LOADS && warming) warm_step(kt + 2 + kWarmAhead);
         };
+        // a step's barrier may leave one load in flight iff the step before it had LOADS and warmed
         int kt = 0;
-        for (; kt + 2 < KT; ++kt) kstep(kt, std::true_type{}, std::true_type{});
+        for (; kt + 2 < KT; ++kt) kstep(kt, std::true_type{}, std::true_type{}, warming && kt > 0);
         if (KT >= 2) {
-            kstep(kt, std::false_type{}, std::true_type{});
+            kstep(kt, std::false_type{}, std::true_type{}, warming && kt > 0);
             ++kt;
         }
-        kstep(kt, std::false_type{}, std::false_type{});
+        kstep(kt, std::false_type{}, std::false_type{}, false);
     }
 };
 

@@ -469,7 +469,9 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
-    Core::template gemm<GUARD>(p.hidden_t, p.H, Trc, p.W, p.H, p.V, p.H, r0, c0, smem, acc);
+    const uint16_t* warm = Core::kCanGuard ? nullptr
+                                           : warm_row<4, 8>(p.hidden_t, p.H, r0, tr, p.W, p.H, c0, tc);
+    Core::template gemm<GUARD>(p.hidden_t, p.H, Trc, p.W, p.H, p.V, p.H, r0, c0, smem, acc, warm);
 
     const typename Core::Lane lp;
     const bool mask_cols = c0 + kBlockC > p.V;
@@ -572,7 +574,9 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
-    Core::template gemm<GUARD>(p.dz, p.Vp, Trc, p.wt, p.Vp, p.H, p.Vp, r0, c0, smem, acc);
+    const uint16_t* warm = Core::kCanGuard ? nullptr
+                                           : warm_row<4, 8>(p.dz, p.Vp, r0, tr, p.wt, p.Vp, c0, tc);
+    Core::template gemm<GUARD>(p.dz, p.Vp, Trc, p.wt, p.Vp, p.H, p.Vp, r0, c0, smem, acc, warm);
 
     const typename Core::Lane lp;
     const float inv = p.hdr->inv;
@@ -630,8 +634,11 @@ __global__ __launch_bounds__(Core::kThreads) void dw_kernel(const DWParams p) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
-    if (Tkc > 0)
-        Core::template gemm<GUARD>(p.ht, p.Kg, p.H, p.dzt, p.Kg, p.Vp, Tkc, r0, c0, smem, acc);
+    if (Tkc > 0) {
+        const uint16_t* warm = Core::kCanGuard ? nullptr
+                                               : warm_row<4, 8>(p.ht, p.Kg, r0, tr, p.dzt, p.Kg, c0, tc);
+        Core::template gemm<GUARD>(p.ht, p.Kg, p.H, p.dzt, p.Kg, p.Vp, Tkc, r0, c0, smem, acc, warm);
+    }
 
     const typename Core::Lane lp;
 #pragma unroll
