@@ -22,7 +22,6 @@ MI355X_BF16_MFMA_PEAK_TFLOPS = 2500.0      # dense bf16, vendor figure
 # Memory-side bytes per launch (calibrated FETCH_SIZE + WRITE_SIZE from two `rocprofv3 --pmc` runs of
 # this script on llama8b_128k, see profiles/bench_llama8b_128k_hbm_traffic.txt); other workloads: None.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
-    "llama8b_128k": {"dw_gemm": 10.912e9, "logits_gemm": 7.408e9, "dhidden_gemm": 6.339e9},
 }
 
 
@@ -126,20 +125,25 @@ def main() -> int:
     tokens_per_s = N / (ms_per_step * 1e-3)
     useful_flop = 6.0 * N * H * V
     tflops = useful_flop / (ms_per_step * 1e-3) / 1e12
+    # Rows of ignored tokens are skipped by the library: the flop it has to execute are 6 M H V for
+    # the M valid tokens.  Utilisation figures are priced on those, not on the skipped rows.
+    M = int(nv.item())
+    tflops_exec = 6.0 * M * H * V / (ms_per_step * 1e-3) / 1e12
 
-    # dominant kernel = the block GEMM kind with the largest summed time; every launch of a kind
-    # does 2 * rows * H * V flop (rows = the tile's rows), so per-launch algorithmic flop are
-    # 2 * tile * H * V for full tiles.
+    # dominant kernel = the block GEMM kind with the largest summed time.  Over one step the
+    # launches of a kind together contract 2 M H V flop (each launch its tile's, or its group of
+    # tiles', valid rows), so the mean algorithmic flop per launch are 2 M H V * steps / launches.
     gemm = {k: v for k, v in prof.items() if k.endswith("_gemm") and v[1] > 0}
     dom = max(gemm, key=lambda k: gemm[k][0])
     dom_ms, dom_n = gemm[dom]
-    flop_per_launch = 2.0 * N * H * V * args.steps / dom_n
+    flop_per_launch = 2.0 * M * H * V * args.steps / dom_n
     achieved = flop_per_launch / (dom_ms / dom_n * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved,
                 "peak": MI355X_BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / MI355X_BF16_MFMA_PEAK_TFLOPS,
                 "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(wl.name, {}).get(dom) if tile == wl.tile else None,
                 "avg_launch_ms": dom_ms / dom_n, "launches": dom_n,
+                "flop_per_launch": flop_per_launch,
                 "per_kind_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()}}
 
     out = {
@@ -151,9 +155,11 @@ def main() -> int:
                    "ignore_frac": wl.ignore_frac, "entry": "alst_tiled_ce_forward_backward"},
         "tflops_useful_6NHV": tflops,
         "mfma_peak_frac": tflops / MI355X_BF16_MFMA_PEAK_TFLOPS,
+        "tflops_executed_6MHV": tflops_exec,
+        "mfma_peak_frac_executed": tflops_exec / MI355X_BF16_MFMA_PEAK_TFLOPS,
         "peak_device_bytes": int(peak_bytes),
         "would_be_fp32_logits_bytes": 4 * N * V,
-        "loss": float(loss.item()), "n_valid": int(nv.item()), "device_status": status,
+        "loss": float(loss.item()), "n_valid": M, "device_status": status,
         "wall_s_timed_region": wall, "input_gen_s": t_gen,
         "roofline": roofline,
     }
