@@ -34,9 +34,10 @@
  *     ignore_index nor in [0,V), a non-finite loss) are recorded in a status word inside the
  *     workspace, read with alst_last_device_status().  A row with an out-of-range label is
  *     treated as ignored, so nothing is read or written out of bounds.
- *   - Rows of ignored tokens are left out of all three contractions (each tile's valid rows are
- *     gathered into a dense matrix first), so the executed work is 6 * M * H * V flop for M valid
- *     tokens, not 6 * N * H * V.
+ *   - Rows of ignored tokens are left out of all three contractions: the rows with a valid label
+ *     are numbered densely in sequence order and the tiles are cut from that dense numbering
+ *     (tile t = valid rows t*tile .. t*tile+tile-1, gathered into a dense matrix), so the executed
+ *     work is 6 * M * H * V flop for M valid tokens, not 6 * N * H * V.
  *   - tile: any value >= 1; a tile larger than N is clamped; N need not be a multiple of tile.
  *     The tile size changes scheduling and memory only: the loss bits do not depend on it.
  */
@@ -76,8 +77,9 @@ int alst_version(void);
 /*
  * Bytes of device scratch the three compute entry points need for this problem, 0 if the
  * shape is invalid.  Pure host arithmetic, no device access.  The value is independent of N
- * except for 8 * N bytes (per-row loss and lse): this is the memory contract of Sequence
- * Tiling, peak = O(N * H) for the activations and their gradients + O(tile * V) + O(V * H).
+ * except for about 12 * N bytes (per-row loss term, lse and dense-row index): this is the
+ * memory contract of Sequence Tiling, peak = O(N * H) for the activations and their gradients
+ * + O(tile * V) + O(V * H).
  */
 size_t alst_tiled_ce_workspace_bytes(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_t flags);
 

@@ -45,7 +45,7 @@ struct Header {
     double loss_sum;
 };
 
-// What compact_scan_kernel leaves for the other kernels of a tile.
+// What tile_info_kernel leaves for the other kernels of a tile.
 struct TileInfo {
     int Tc;                // rows of the tile that take part (valid label)
     int Trc;               // Tc rounded up to the block height (256)
@@ -64,12 +64,14 @@ static inline int dw_group_size(int64_t Tp) {
     return (int)(g < 1 ? 1 : (g > kDwGroupMax ? kDwGroupMax : g));
 }
 
+constexpr int kScanThreads = 1024;   // rows per block of the compaction kernels
+
 struct Layout {
     int64_t Tp, Vp, ng;    // padded tile rows, padded vocabulary, 128-column groups
     int g;                 // tiles per dW group
     int64_t Kg;            // row stride of dzt / ht: g * Tp
-    size_t header, tinfo, loss_rows, lse, zlabel, yc, idx, pos, pm, ps, sc, hc, stash, dzt, wt, ht,
-        acc, total;
+    size_t header, tinfo, loss_rows, lse, idx, block_cnt, block_ofs, zlabel, yc, pm, ps, sc, hc,
+        stash, dzt, wt, ht, acc, total;
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -86,12 +88,15 @@ static Layout make_layout(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     L.header = take(sizeof(Header));
     L.tinfo = take(sizeof(TileInfo) * kDwGroupMax);
+    // the O(N) part: 12 bytes per row + 12 bytes per kScanThreads rows
+    const size_t nblocks = ((size_t)N + kScanThreads - 1) / kScanThreads;
     L.loss_rows = take((size_t)N * 4);
     L.lse = take((size_t)N * 4);
+    L.idx = take((size_t)N * 4);
+    L.block_cnt = take(nblocks * 4);
+    L.block_ofs = take(nblocks * 8);
     L.zlabel = take((size_t)L.Tp * 4);
     L.yc = take((size_t)L.Tp * 4);
-    L.idx = take((size_t)L.Tp * 4);
-    L.pos = take((size_t)L.Tp * 4);
     L.pm = take((size_t)L.ng * L.Tp * 4);
     L.ps = take((size_t)L.ng * L.Tp * 4);
     L.sc = take((size_t)L.ng * L.Tp * 4);
@@ -122,112 +127,135 @@ __device__ __forceinline__ bool label_valid(int y, int ignore_index, int V) {
     return y != ignore_index && y >= 0 && y < V;
 }
 
-// M = number of labels that take part in the loss; flags labels outside [0, V).
-__global__ void count_valid_kernel(const int32_t* __restrict__ labels, int64_t N, int ignore_index,
-                                   int V, Header* h) {
-    int cnt = 0;
-    bool bad = false;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N;
-         i += (int64_t)gridDim.x * blockDim.x) {
-        const int y = labels[i];
-        if (y != ignore_index) {
-            if (y >= 0 && y < V) ++cnt; else bad = true;
-        }
-    }
-    __shared__ int s_cnt;
-    __shared__ int s_bad;
-    if (threadIdx.x == 0) { s_cnt = 0; s_bad = 0; }
+// Row compaction of the whole sequence: idx[j] = row of the j-th token with a valid label, in
+// sequence order.  Three small kernels over blocks of kScanThreads rows:
+//   block_count_kernel   valid rows per block
+//   block_offsets_kernel exclusive scan of the block counts (one workgroup), M = their sum
+//   scatter_index_kernel rank inside the block + block offset -> idx; rows that take no part get
+//                        loss term 0 and lse 0 (forward) and a zero dHidden row (backward).
+// The dense rows are then cut into tiles of T rows: tile t = dense rows [t T, min((t + 1) T, M)).
+__device__ __forceinline__ int block_rank(bool valid, int* wave_total, int& total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const unsigned long long mask = __ballot(valid);
+    const int below = __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
+                                                __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
+    if (lane == 0) wave_total[wave] = __popcll(mask);
     __syncthreads();
-    if (cnt) atomicAdd(&s_cnt, cnt);
-    if (bad) atomicOr(&s_bad, 1);
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        if (s_cnt) atomicAdd((unsigned long long*)&h->n_valid, (unsigned long long)s_cnt);
-        if (s_bad) atomicMax(&h->status, (int)ALST_ERR_LABEL_RANGE);
-    }
-}
-
-__global__ void set_scale_kernel(Header* h, float grad_loss, int64_t* n_valid_out) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) {
-        const long long M = h->n_valid;
-        h->inv = M > 0 ? grad_loss / (float)M : 0.f;
-        if (n_valid_out) *n_valid_out = M;
-    }
-}
-
-// Row compaction of one tile.  One block walks the tile's labels in chunks of 1024 and gives each
-// row with a valid label its rank among them:
-//   pos[i] = rank of row i (or -1), idx[rank] = i, yc[rank] = label,
-// and leaves the counts, and the tile's k offset inside its dW group, in *info.  Rows that do not take part get loss term 0 and lse 0 (forward).
-constexpr int kScanThreads = 1024;
-__global__ __launch_bounds__(kScanThreads) void compact_scan_kernel(
-    const int32_t* __restrict__ labels_t, int T_cur, int ignore_index, int V,
-    int32_t* __restrict__ yc, int32_t* __restrict__ idx, int32_t* __restrict__ pos,
-    TileInfo* __restrict__ info, const TileInfo* __restrict__ prev, float* __restrict__ lse_t,
-    float* __restrict__ loss_rows_t) {
-    __shared__ int wave_total[kScanThreads / 64];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    int carry = 0;
-    for (int base = 0; base < T_cur; base += kScanThreads) {
-        const int i = base + tid;
-        const int y = i < T_cur ? labels_t[i] : ignore_index;
-        const bool valid = i < T_cur && label_valid(y, ignore_index, V);
-        const unsigned long long mask = __ballot(valid);
-        const int below = __builtin_amdgcn_mbcnt_hi((unsigned)(mask >> 32),
-                                                    __builtin_amdgcn_mbcnt_lo((unsigned)mask, 0));
-        if (lane == 0) wave_total[wave] = __popcll(mask);
-        __syncthreads();
-        int before = 0, total = 0;
+    int before = 0;
+    total = 0;
 #pragma unroll
-        for (int w = 0; w < kScanThreads / 64; ++w) {
-            const int c = wave_total[w];
-            if (w < wave) before += c;
-            total += c;
-        }
-        if (i < T_cur) {
-            if (valid) {
-                const int j = carry + before + below;
-                pos[i] = j;
-                idx[j] = i;
-                yc[j] = y;
-            } else {
-                pos[i] = -1;
-                if (lse_t) lse_t[i] = 0.f;
-                if (loss_rows_t) loss_rows_t[i] = 0.f;
-            }
-        }
-        carry += total;
-        __syncthreads();
+    for (int w = 0; w < kScanThreads / 64; ++w) {
+        const int c = wave_total[w];
+        if (w < wave) before += c;
+        total += c;
     }
+    __syncthreads();
+    return before + below;
+}
+
+__global__ __launch_bounds__(kScanThreads) void block_count_kernel(
+    const int32_t* __restrict__ labels, int64_t N, int ignore_index, int V,
+    int32_t* __restrict__ block_cnt, Header* h) {
+    __shared__ int wave_total[kScanThreads / 64];
+    const int64_t i = (int64_t)blockIdx.x * kScanThreads + threadIdx.x;
+    const int y = i < N ? labels[i] : ignore_index;
+    const bool valid = i < N && label_valid(y, ignore_index, V);
+    if (i < N && y != ignore_index && !valid) atomicMax(&h->status, (int)ALST_ERR_LABEL_RANGE);
+    int total;
+    (void)block_rank(valid, wave_total, total);
+    if (threadIdx.x == 0) block_cnt[blockIdx.x] = total;
+}
+
+// One workgroup: block_ofs[b] = sum of block_cnt[0 .. b), M and g/M into the header.
+__global__ __launch_bounds__(kScanThreads) void block_offsets_kernel(
+    const int32_t* __restrict__ block_cnt, int64_t nblocks, int64_t* __restrict__ block_ofs,
+    Header* h, float grad_loss, int64_t* __restrict__ n_valid_out) {
+    __shared__ long long part[kScanThreads];
+    const int tid = threadIdx.x;
+    // thread t owns the contiguous chunk [t * per, (t + 1) * per)
+    const int64_t per = (nblocks + kScanThreads - 1) / kScanThreads;
+    const int64_t lo = tid * per, hi = lo + per < nblocks ? lo + per : nblocks;
+    long long sum = 0;
+    for (int64_t b = lo; b < hi; ++b) sum += block_cnt[b];
+    part[tid] = sum;
+    __syncthreads();
     if (tid == 0) {
-        info->Tc = carry;
-        info->Trc = (carry + kBlockR - 1) / kBlockR * kBlockR;
-        info->Tkc = (carry + kBlockK - 1) / kBlockK * kBlockK;
-        info->kofs = prev ? prev->kofs + prev->Tkc : 0;     // prev: the tile before, same dW group
+        long long run = 0;
+        for (int t = 0; t < kScanThreads; ++t) {
+            const long long c = part[t];
+            part[t] = run;
+            run += c;
+        }
+        h->n_valid = run;
+        h->inv = run > 0 ? grad_loss / (float)run : 0.f;
+        if (n_valid_out) *n_valid_out = run;
+    }
+    __syncthreads();
+    long long run = part[tid];
+    for (int64_t b = lo; b < hi; ++b) {
+        block_ofs[b] = run;
+        run += block_cnt[b];
     }
 }
 
-// Block b: row b of the tile.  A valid row is copied to its place in the dense matrix Hc, the
-// dHidden row of any other row is zero-filled; rows Tc <= b < Trc of Hc are zero padding.
-__global__ __launch_bounds__(256) void gather_rows_kernel(
-    const uint16_t* __restrict__ hidden_t, int H, int T_cur, const int32_t* __restrict__ pos,
-    const TileInfo* __restrict__ info, uint16_t* __restrict__ Hc, uint16_t* __restrict__ dH_t) {
-    const int b = blockIdx.x;
+__global__ __launch_bounds__(kScanThreads) void scatter_index_kernel(
+    const int32_t* __restrict__ labels, int64_t N, int H, int ignore_index, int V,
+    const int64_t* __restrict__ block_ofs, int32_t* __restrict__ idx, float* __restrict__ lse,
+    float* __restrict__ loss_rows, uint16_t* __restrict__ dHidden) {
+    __shared__ int wave_total[kScanThreads / 64];
+    __shared__ unsigned char is_valid[kScanThreads];
+    const int64_t row0 = (int64_t)blockIdx.x * kScanThreads;
+    const int64_t i = row0 + threadIdx.x;
+    const int y = i < N ? labels[i] : ignore_index;
+    const bool valid = i < N && label_valid(y, ignore_index, V);
+    int total;
+    const int rank = block_rank(valid, wave_total, total);
+    is_valid[threadIdx.x] = valid ? 1 : 0;
+    if (valid) idx[block_ofs[blockIdx.x] + rank] = (int32_t)i;
+    else if (i < N) {
+        if (lse) lse[i] = 0.f;
+        if (loss_rows) loss_rows[i] = 0.f;
+    }
+    if (!dHidden || total == kScanThreads) return;
+    __syncthreads();
     const int chunks = H / 8;
     const u32x4_t zero4 = {0u, 0u, 0u, 0u};
-    if (b < T_cur) {
-        const int p = pos[b];
-        if (p >= 0) {
-            const u32x4_t* src = reinterpret_cast<const u32x4_t*>(hidden_t + (int64_t)b * H);
-            u32x4_t* dst = reinterpret_cast<u32x4_t*>(Hc + (int64_t)p * H);
-            for (int c = threadIdx.x; c < chunks; c += 256) dst[c] = src[c];
-        } else if (dH_t) {
-            u32x4_t* dst = reinterpret_cast<u32x4_t*>(dH_t + (int64_t)b * H);
-            for (int c = threadIdx.x; c < chunks; c += 256) dst[c] = zero4;
-        }
+    for (int r = 0; r < kScanThreads && row0 + r < N; ++r) {
+        if (is_valid[r]) continue;
+        u32x4_t* dst = reinterpret_cast<u32x4_t*>(dHidden + (row0 + r) * H);
+        for (int c = threadIdx.x; c < chunks; c += kScanThreads) dst[c] = zero4;
     }
-    if (b >= info->Tc && b < info->Trc) {
-        u32x4_t* dst = reinterpret_cast<u32x4_t*>(Hc + (int64_t)b * H);
+}
+
+// The counts of tile t (dense rows [t T, t T + T) cut at M) and its k offset inside its dW group.
+__global__ void tile_info_kernel(const Header* __restrict__ h, int64_t t, int64_t T,
+                                 TileInfo* __restrict__ info, const TileInfo* __restrict__ prev) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    long long left = h->n_valid - t * T;
+    const int Tc = (int)(left < 0 ? 0 : (left > T ? T : left));
+    info->Tc = Tc;
+    info->Trc = (Tc + kBlockR - 1) / kBlockR * kBlockR;
+    info->Tkc = (Tc + kBlockK - 1) / kBlockK * kBlockK;
+    info->kofs = prev ? prev->kofs + prev->Tkc : 0;     // prev: the tile before, same dW group
+}
+
+// Block b: dense row b of the tile.  Copies the hidden row of token idx_t[b] into the dense
+// matrix Hc and its label into yc; rows Tc <= b < Trc of Hc are zero padding.
+__global__ __launch_bounds__(256) void gather_rows_kernel(
+    const uint16_t* __restrict__ hidden, const int32_t* __restrict__ labels, int H,
+    const int32_t* __restrict__ idx_t, const TileInfo* __restrict__ info,
+    uint16_t* __restrict__ Hc, int32_t* __restrict__ yc) {
+    const int b = blockIdx.x;
+    const int chunks = H / 8;
+    if (b >= info->Trc) return;
+    u32x4_t* dst = reinterpret_cast<u32x4_t*>(Hc + (int64_t)b * H);
+    if (b < info->Tc) {
+        const int64_t row = idx_t[b];
+        const u32x4_t* src = reinterpret_cast<const u32x4_t*>(hidden + row * H);
+        for (int c = threadIdx.x; c < chunks; c += 256) dst[c] = src[c];
+        if (threadIdx.x == 0) yc[b] = labels[row];
+    } else {
+        const u32x4_t zero4 = {0u, 0u, 0u, 0u};
         for (int c = threadIdx.x; c < chunks; c += 256) dst[c] = zero4;
     }
 }
@@ -440,9 +468,9 @@ struct LogitsParams {
     const uint16_t* hidden_t;   // [Tp, H]      the tile's dense (valid) rows, zero padded to Trc
     const uint16_t* W;          // [V, H]
     const int32_t* labels_t;    // [Tp]         labels of the dense rows
-    const int32_t* idx;         // [Tp]         dense row -> row of the tile
+    const int32_t* idx;         // [Tp]         dense row of the tile -> row of the sequence
     const TileInfo* info;
-    const float* lse_t;         // [T_cur]      MODE_BWD, indexed by the row of the tile
+    const float* lse_t;         // [N]          MODE_BWD, indexed by the row of the sequence
     float* pm;                  // [ng, Tp]     MODE_FWD / MODE_FUSED
     float* ps;                  // [ng, Tp]
     float* zlabel;              // [Tp]
@@ -547,7 +575,7 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
 struct DHiddenParams {
     const uint16_t* dz;      // [Tp, Vp]     dense rows
     const uint16_t* wt;      // [H, Vp]
-    uint16_t* dH_t;          // [T_cur, H]   rows of the tile; dense row i goes to row idx[i]
+    uint16_t* dH_t;          // [N, H]       whole dHidden; dense row i goes to row idx[i]
     const int32_t* idx;
     const TileInfo* info;
     const Header* hdr;
@@ -804,7 +832,8 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
     float* zlabel = reinterpret_cast<float*>(P.ws + L.zlabel);
     int32_t* yc = reinterpret_cast<int32_t*>(P.ws + L.yc);
     int32_t* idx = reinterpret_cast<int32_t*>(P.ws + L.idx);
-    int32_t* pos = reinterpret_cast<int32_t*>(P.ws + L.pos);
+    int32_t* block_cnt = reinterpret_cast<int32_t*>(P.ws + L.block_cnt);
+    int64_t* block_ofs = reinterpret_cast<int64_t*>(P.ws + L.block_ofs);
     float* pm = reinterpret_cast<float*>(P.ws + L.pm);
     float* ps = reinterpret_cast<float*>(P.ws + L.ps);
     float* sc = reinterpret_cast<float*>(P.ws + L.sc);
@@ -821,12 +850,16 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
 
     hipLaunchKernelGGL(init_header_kernel, dim3(1), dim3(64), 0, s, hdr);
     {
-        int blocks = (int)((P.N + 255) / 256);
-        if (blocks > 1024) blocks = 1024;
-        hipLaunchKernelGGL(count_valid_kernel, dim3(blocks), dim3(256), 0, s, P.labels, P.N,
-                           P.ignore_index, V, hdr);
+        const int64_t nblocks = (P.N + kScanThreads - 1) / kScanThreads;
+        hipLaunchKernelGGL(block_count_kernel, dim3((unsigned)nblocks), dim3(kScanThreads), 0, s,
+                           P.labels, P.N, P.ignore_index, V, block_cnt, hdr);
+        hipLaunchKernelGGL(block_offsets_kernel, dim3(1), dim3(kScanThreads), 0, s, block_cnt,
+                           nblocks, block_ofs, hdr, P.grad_loss, P.n_valid_out);
+        hipLaunchKernelGGL(scatter_index_kernel, dim3((unsigned)nblocks), dim3(kScanThreads), 0, s,
+                           P.labels, P.N, H, P.ignore_index, V, block_ofs, idx,
+                           do_fwd ? lse_buf : nullptr, do_fwd ? loss_rows : nullptr,
+                           do_bwd ? P.dHidden : nullptr);
     }
-    hipLaunchKernelGGL(set_scale_kernel, dim3(1), dim3(64), 0, s, hdr, P.grad_loss, P.n_valid_out);
     ALST_HIP(hipGetLastError());
 
     if (do_bwd) {
@@ -839,24 +872,22 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
     const bool guard_logits = (V % kBlockC) != 0 || (H % kBlockK) != 0;
     const bool guard_h = (H % kBlockC) != 0;
 
+    // The host does not know M: it walks ceil(N / T) tiles, the most there can be; the kernels of
+    // a tile beyond the dense rows find Tc = 0 on the device and leave at once.
     const int64_t ntiles = (P.N + T - 1) / T;
     for (int64_t t = 0; t < ntiles; ++t) {
-        const int64_t i0 = t * T;
-        const int T_cur = (int)((P.N - i0) < T ? (P.N - i0) : T);
-        const uint16_t* hidden_t = P.hidden + i0 * P.H;
-        const int32_t* labels_t = P.labels + i0;
+        const int T_cur = (int)T;
         const int Tr = (T_cur + kBlockR - 1) / kBlockR * kBlockR;
         const int slot = (int)(t % L.g);                // position inside the dW group
         TileInfo* info = infos + slot;
+        const int32_t* idx_t = idx + t * T;             // the tile's dense rows -> sequence rows
 
         {
             ProfScope small_(PROF_OTHER, s);
-            hipLaunchKernelGGL(compact_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, labels_t,
-                               T_cur, P.ignore_index, V, yc, idx, pos, info,
-                               slot ? info - 1 : nullptr,
-                               do_fwd ? lse_buf + i0 : nullptr, do_fwd ? loss_rows + i0 : nullptr);
-            hipLaunchKernelGGL(gather_rows_kernel, dim3(Tr), dim3(256), 0, s, hidden_t, H, T_cur,
-                               pos, info, hc, do_bwd ? P.dHidden + i0 * P.H : nullptr);
+            hipLaunchKernelGGL(tile_info_kernel, dim3(1), dim3(64), 0, s, hdr, t, T, info,
+                               slot ? info - 1 : nullptr);
+            hipLaunchKernelGGL(gather_rows_kernel, dim3(Tr), dim3(256), 0, s, P.hidden, P.labels, H,
+                               idx_t, info, hc, yc);
             ALST_HIP(hipGetLastError());
         }
 
@@ -864,9 +895,9 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
         lp.hidden_t = hc;
         lp.W = P.W;
         lp.labels_t = yc;
-        lp.idx = idx;
+        lp.idx = idx_t;
         lp.info = info;
-        lp.lse_t = do_fwd ? nullptr : P.lse_in + i0;
+        lp.lse_t = do_fwd ? nullptr : P.lse_in;
         lp.pm = pm; lp.ps = ps; lp.zlabel = zlabel; lp.stash = stash;
         lp.Tp = Tp; lp.H = H; lp.V = V; lp.Vp = Vp;
         {
@@ -881,9 +912,8 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             ProfScope small_(PROF_OTHER, s);
             if (do_fwd) {
                 hipLaunchKernelGGL(row_combine_kernel, dim3(Tr / kCombineRows),
-                                   dim3(kCombineRows, kCombineLanes), 0, s, pm, ps, zlabel, idx,
-                                   info, Tp, ng, lse_buf + i0, loss_rows + i0,
-                                   do_bwd ? sc : nullptr);
+                                   dim3(kCombineRows, kCombineLanes), 0, s, pm, ps, zlabel, idx_t,
+                                   info, Tp, ng, lse_buf, loss_rows, do_bwd ? sc : nullptr);
                 ALST_HIP(hipGetLastError());
             }
             if (do_bwd) {
@@ -903,7 +933,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
 
         {
             DHiddenParams dp;
-            dp.dz = stash; dp.wt = wt; dp.dH_t = P.dHidden + i0 * P.H; dp.idx = idx;
+            dp.dz = stash; dp.wt = wt; dp.dH_t = P.dHidden; dp.idx = idx_t;
             dp.info = info; dp.hdr = hdr;
             dp.Tp = Tp; dp.H = H; dp.Vp = Vp;
             const int grid = grid_for_tiles<4, 8>(Tr / kBlockR, (H + kBlockC - 1) / kBlockC);

@@ -74,7 +74,9 @@ def test_full_size_workload(name):
     expected = 2 * N * H * 2 + 2 * V * H * 2 + 4 * N + 4 * N + ws.numel()
     assert peak <= expected + (64 << 20), (peak, expected)
     assert peak < (0.2 if N >= 131072 else 0.7) * 4 * N * V
-    assert ws.numel() - 8 * N == B.alst_tiled_ce_workspace_bytes(wl.tile, H, V, wl.tile) - 8 * wl.tile
+    # the workspace grows with N only by 12 bytes per row (+ 12 bytes per 1024 rows)
+    grow = ws.numel() - B.alst_tiled_ce_workspace_bytes(wl.tile, H, V, wl.tile)
+    assert 0 <= grow - 12 * (N - wl.tile) <= 12 * N // 1024 + 512
 
     # ---- loss, count, lse ---------------------------------------------------------------------
     assert int(nv.item()) == gold["n_valid"]
