@@ -502,72 +502,73 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
     Core::template gemm<GUARD>(p.hidden_t, p.H, Trc, p.W, p.H, p.V, p.H, r0, c0, smem, acc, warm);
 
     const typename Core::Lane lp;
-    const bool mask_cols = c0 + kBlockC > p.V;
+    constexpr float kLog2e = 1.4426950408889634f;
 #pragma unroll
     for (int nt = 0; nt < kNT; ++nt) {
         const int i = r0 + lp.r(nt);
         const bool rowok = i < T_cur;
-        if (mask_cols) {
+        if (GUARD) {                    // unguarded builds run on V % 256 == 0 only
+            if (c0 + kBlockC > p.V) {
 #pragma unroll
-            for (int mt = 0; mt < kMT; ++mt)
+                for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
-                for (int j = 0; j < 16; ++j)
-                    if (c0 + lp.c(mt, j >> 2) + (j & 3) >= p.V) acc[mt][nt][j] = -INFINITY;
+                    for (int j = 0; j < 16; ++j)
+                        if (c0 + lp.c(mt, j >> 2) + (j & 3) >= p.V) acc[mt][nt][j] = -INFINITY;
+            }
         }
-        float ref;
+        float ref, m = 0.f;
         if (MODE == MODE_BWD) {
             ref = rowok ? p.lse_t[p.idx[i]] : 0.f;
         } else {
-            float m = -INFINITY;
+            m = -INFINITY;
 #pragma unroll
             for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
                 for (int j = 0; j < 16; ++j) m = fmaxf(m, acc[mt][nt][j]);
             m = fmaxf(m, __shfl_xor(m, 32));
             ref = (m == -INFINITY) ? 0.f : m;
-            // label logit: exactly one lane of one block holds column y of row i
+            // label logit: exactly one lane of one block holds column y of row i.  Few wavefronts
+            // hold any (32 rows x 128 of V columns), so the search sits behind a uniform branch.
             const int y = rowok ? p.labels_t[i] : -1;
             const unsigned d = (unsigned)(y - (c0 + lp.wc * kGroupC));
-            if (y >= 0 && d < (unsigned)kGroupC && ((d >> 2) & 1u) == (unsigned)lp.half) {
-                float zl = 0.f;
+            const bool mine = y >= 0 && d < (unsigned)kGroupC && ((d >> 2) & 1u) == (unsigned)lp.half;
+            if (__ballot(mine) != 0ull) {
+                if (mine) {
+                    float zl = 0.f;
 #pragma unroll
-                for (int mt = 0; mt < kMT; ++mt)
+                    for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
-                    for (int j = 0; j < 16; ++j)
-                        if (d == (unsigned)(mt * 32 + (j >> 2) * 8 + lp.half * 4 + (j & 3)))
-                            zl = acc[mt][nt][j];
-                p.zlabel[i] = zl;
-            }
-            float s = 0.f;
-#pragma unroll
-            for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const float e = __expf(acc[mt][nt][j] - ref);
-                    acc[mt][nt][j] = e;
-                    s += e;
+                        for (int j = 0; j < 16; ++j)
+                            if (d == (unsigned)(mt * 32 + (j >> 2) * 8 + lp.half * 4 + (j & 3)))
+                                zl = acc[mt][nt][j];
+                    p.zlabel[i] = zl;
                 }
+            }
+        }
+        // e = exp(z - ref) as exp2(z * log2(e) - ref * log2(e)); summed in fp32, stored as bf16
+        const float ref2 = ref * kLog2e;
+        uint16_t* row = p.stash + (int64_t)i * p.Vp + c0;
+        float s = 0.f;
+#pragma unroll
+        for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                bf16x4_t o;
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const float e = __builtin_amdgcn_exp2f(fmaf(acc[mt][nt][q * 4 + x], kLog2e, -ref2));
+                    s += e;
+                    o[x] = (__bf16)e;
+                }
+                if (MODE != MODE_FWD) *reinterpret_cast<bf16x4_t*>(row + lp.c(mt, q)) = o;
+            }
+        if (MODE != MODE_BWD) {
             s += __shfl_xor(s, 32);
             if (lp.half == 0) {
                 const int64_t g = (c0 + lp.wc * kGroupC) >> 7;
                 p.pm[g * p.Tp + i] = m;
                 p.ps[g * p.Tp + i] = s;
             }
-        }
-        if (MODE != MODE_FWD) {
-            uint16_t* row = p.stash + (int64_t)i * p.Vp + c0;
-#pragma unroll
-            for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    bf16x4_t o;
-#pragma unroll
-                    for (int x = 0; x < 4; ++x) {
-                        const float z = acc[mt][nt][q * 4 + x];
-                        o[x] = (__bf16)(MODE == MODE_BWD ? __expf(z - ref) : z);
-                    }
-                    *reinterpret_cast<bf16x4_t*>(row + lp.c(mt, q)) = o;
-                }
         }
     }
 }
