@@ -275,32 +275,24 @@ struct DirectCore {
         const int xbase = (wr * 128 + l31) * 128;
         const int ybase = 2 * kTileBytes + (wc * kGroupC + l31) * 128;
 
-        bf16x8_t fy0[4], fx0[4], fy1[4], fx1[4];
-        auto read_frags = [&](bf16x8_t (&fy)[4], bf16x8_t (&fx)[4], int stage, int s) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                fy[t] = *reinterpret_cast<const bf16x8_t*>(smem + stage * kTileBytes + ybase +
-                                                           t * 4096 + rofs[s]);
-                fx[t] = *reinterpret_cast<const bf16x8_t*>(smem + stage * kTileBytes + xbase +
-                                                           t * 4096 + rofs[s]);
-            }
+        // MFMA operands of the four k-slices of a step: fy[s][t], fx[s][t] for slice s.
+        bf16x8_t fy[4][4], fx[4][4];
+        // item 0..3: the Y operand of accumulator row t = item, 4..7: the X operand of column t
+        auto read_item = [&](int stage, int s, int item) {
+            const unsigned char* base = smem + stage * kTileBytes;
+            if (item < 4)
+                fy[s][item] = *reinterpret_cast<const bf16x8_t*>(base + ybase + item * 4096 + rofs[s]);
+            else
+                fx[s][item - 4] =
+                    *reinterpret_cast<const bf16x8_t*>(base + xbase + (item - 4) * 4096 + rofs[s]);
         };
-        auto mfmas = [&](const bf16x8_t (&fy)[4], const bf16x8_t (&fx)[4]) {
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                for (int nt = 0; nt < 4; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[mt], fx[nt],
-                                                                          acc[mt][nt], 0, 0, 0);
-        };
-        // scheduling hint for a quarter step: one LDS read behind each of the first 8 MFMAs
-        auto sched_reads = [&]() {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        // the two MFMAs of slot i (0..7) of a quarter step on slice s
+        auto mfma_pair = [&](int s, int i) {
+            const int mt = i >> 1, n0 = (i & 1) * 2;
+            acc[mt][n0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[s][mt], fx[s][n0], acc[mt][n0],
+                                                                  0, 0, 0);
+            acc[mt][n0 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[s][mt], fx[s][n0 + 1],
+                                                                      acc[mt][n0 + 1], 0, 0, 0);
         };
 
         const int KT = K / kBlockK;
@@ -323,52 +315,60 @@ struct DirectCore {
         issue_loads(0, 0);
         __syncthreads();                       // waits for the DMA (vmcnt) and joins the waves
         if (KT > 1) issue_loads(1, 1);
-        read_frags(fy0, fx0, 0, 0);
+#pragma unroll
+        for (int item = 0; item < 8; ++item) read_item(0, 0, item);
+#pragma unroll
+        for (int item = 0; item < 8; ++item) read_item(0, 1, item);
 
-        // One k-step.  LOADS: refill the stage just consumed with step kt + 2.  NEXT: read the
-        // first quarter's operands of step kt + 1.  The tail steps skip them so that no DMA is in
-        // flight when the workgroup ends.
-        // The last quarter is ordered by hand, in eight fenced slices of two MFMAs, two DMA
-        // instructions and one operand read: left to the scheduler the sixteen DMA instructions
-        // come out back to back and the matrix pipe idles behind their issue.
+        // One k-step = four quarters of sixteen MFMAs, each quarter eight fenced slots of two MFMAs
+        // plus the memory instructions that ride along, in this order:
+        //   Q0  MFMA slice 0 | read slices 2 and 3 of this stage
+        //   Q1  MFMA slice 1 |
+        //   -- all of this stage has been read, the next stage has landed: workgroup barrier --
+        //   Q2  MFMA slice 2 | DMA of step kt + 2, X half, into this stage | read slice 0 of kt + 1
+        //   Q3  MFMA slice 3 | DMA of step kt + 2, Y half                  | read slice 1 of kt + 1
+        // Every operand read is issued at least a quarter and a half before its first MFMA, so a
+        // burst of DMA writes into LDS delays reads without draining the matrix pipe, and the DMA
+        // issue is spread over half a step (left to the scheduler the sixteen DMA instructions
+        // come out back to back and the matrix pipe idles behind their issue).
+        // LOADS: step kt + 2 exists.  NEXT: step kt + 1 exists.  The tail steps skip the DMA so
+        // that none is in flight when the workgroup ends.
         // BEHIND: the previous k-step issued a warm-up load after its DMA.
         auto kstep = [&](int kt, auto loads, auto next, bool behind) {
             constexpr bool LOADS = decltype(loads)::value, NEXT = decltype(next)::value;
             const int cur = kt & 1;
-            read_frags(fy1, fx1, cur, 1);
-            mfmas(fy0, fx0);
-            sched_reads();
-            read_frags(fy0, fx0, cur, 2);
-            mfmas(fy1, fx1);
-            sched_reads();
-            read_frags(fy1, fx1, cur, 3);
-            mfmas(fy0, fx0);
-            sched_reads();
-            stage_barrier(behind);             // stage cur fully read; stage cur ^ 1 has landed
-            __builtin_amdgcn_sched_barrier(0);
             unsigned char* const xs = smem + cur * kTileBytes + w * 8192;
             unsigned char* const ys = smem + 2 * kTileBytes + cur * kTileBytes + w * 8192;
-            const unsigned char* const nx = smem + (cur ^ 1) * kTileBytes;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const int mt = i >> 1, n0 = (i & 1) * 2;
-                acc[mt][n0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy1[mt], fx1[n0],
-                                                                      acc[mt][n0], 0, 0, 0);
-                acc[mt][n0 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy1[mt], fx1[n0 + 1],
-                                                                          acc[mt][n0 + 1], 0, 0, 0);
-                if (LOADS) {
+                mfma_pair(0, i);
+                read_item(cur, i < 4 ? 2 : 3, (2 * i) & 7);
+                read_item(cur, i < 4 ? 2 : 3, (2 * i + 1) & 7);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                mfma_pair(1, i);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            stage_barrier(behind);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                mfma_pair(2, i);
+                if (LOADS)
                     __builtin_amdgcn_global_load_lds((gptr_t)(xg[i] + (kt + 2) * kBlockK),
                                                      (lptr_t)(xs + i * 1024), 16, 0, 0);
+                if (NEXT) read_item(cur ^ 1, 0, i);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                mfma_pair(3, i);
+                if (LOADS)
                     __builtin_amdgcn_global_load_lds((gptr_t)(yg[i] + (kt + 2) * kBlockK),
                                                      (lptr_t)(ys + i * 1024), 16, 0, 0);
-                }
-                if (NEXT) {
-                    if (i < 4)
-                        fy0[i] = *reinterpret_cast<const bf16x8_t*>(nx + ybase + i * 4096 + rofs[0]);
-                    else
-                        fx0[i - 4] = *reinterpret_cast<const bf16x8_t*>(nx + xbase + (i - 4) * 4096 +
-                                                                        rofs[0]);
-                }
+                if (NEXT) read_item(cur ^ 1, 1, i);
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (LOADS && warming) warm_step(kt + 2 + kWarmAhead);
