@@ -103,6 +103,8 @@ struct StagedCore {
         }
         // row of X (r index inside the block) of accumulator tile nt
         __device__ __forceinline__ int r(int nt) const { return wr * 64 + nt * 32 + l31; }
+        // first of the 32 rows of accumulator tile nt that this wavefront holds
+        __device__ __forceinline__ int rbase(int nt) const { return wr * 64 + nt * 32; }
         // first of the 4 consecutive c held in registers 4q..4q+3 of accumulator tile mt
         __device__ __forceinline__ int c(int mt, int q) const {
             return wc * kGroupC + mt * 32 + q * 8 + half * 4;
@@ -219,6 +221,7 @@ struct DirectCore {
             wc = wave >> 1;
         }
         __device__ __forceinline__ int r(int nt) const { return wr * 128 + nt * 32 + l31; }
+        __device__ __forceinline__ int rbase(int nt) const { return wr * 128 + nt * 32; }
         __device__ __forceinline__ int c(int mt, int q) const {
             return wc * kGroupC + mt * 32 + q * 8 + half * 4;
         }

@@ -503,6 +503,7 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
 
     const typename Core::Lane lp;
     constexpr float kLog2e = 1.4426950408889634f;
+    constexpr int kTurnPitch = 272;     // bytes per row of the turn-around area: 256 + 16 of padding
 #pragma unroll
     for (int nt = 0; nt < kNT; ++nt) {
         const int i = r0 + lp.r(nt);
@@ -545,9 +546,14 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
                 }
             }
         }
-        // e = exp(z - ref) as exp2(z * log2(e) - ref * log2(e)); summed in fp32, stored as bf16
+        // e = exp(z - ref) as exp2(z * log2(e) - ref * log2(e)); summed in fp32, stored as bf16.
+        // In the accumulators a lane holds 4 consecutive columns of one row, so a direct store
+        // would scatter 16-byte pieces over 32 rows per instruction.  The wavefront instead turns
+        // its 32 x 128 piece around in LDS (free once the k-loop is over; each wavefront has its
+        // own region and LDS serves a wavefront's accesses in order, so no barrier is needed) and
+        // stores whole 256-byte row segments.
         const float ref2 = ref * kLog2e;
-        uint16_t* row = p.stash + (int64_t)i * p.Vp + c0;
+        unsigned char* const tw = smem + (threadIdx.x >> 6) * (32 * kTurnPitch);
         float s = 0.f;
 #pragma unroll
         for (int mt = 0; mt < kMT; ++mt)
@@ -560,8 +566,21 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
                     s += e;
                     o[x] = (__bf16)e;
                 }
-                if (MODE != MODE_FWD) *reinterpret_cast<bf16x4_t*>(row + lp.c(mt, q)) = o;
+                if (MODE != MODE_FWD)
+                    *reinterpret_cast<bf16x4_t*>(tw + lp.l31 * kTurnPitch +
+                                                 (mt * 32 + q * 8 + lp.half * 4) * 2) = o;
             }
+        if (MODE != MODE_FWD) {
+            const int lrow = lp.lane >> 4, lcol = lp.lane & 15;        // 4 rows x 16 chunks of 16 B
+            uint16_t* const out = p.stash + (int64_t)(r0 + lp.rbase(nt)) * p.Vp + c0 +
+                                  lp.wc * kGroupC + lcol * 8;
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int row = it * 4 + lrow;
+                const u32x4_t v = *reinterpret_cast<const u32x4_t*>(tw + row * kTurnPitch + lcol * 16);
+                *reinterpret_cast<u32x4_t*>(out + (int64_t)row * p.Vp) = v;
+            }
+        }
         if (MODE != MODE_BWD) {
             s += __shfl_xor(s, 32);
             if (lp.half == 0) {
