@@ -361,9 +361,13 @@ __global__ __launch_bounds__(256) void dz_finalize_kernel(uint16_t* __restrict__
                                                           const TileInfo* __restrict__ info,
                                                           int Tp, int Vp, int64_t Kg) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int v0 = (blockIdx.x * 4 + wave) * 64 + (lane & 7) * 8;      // first of this lane's 8 columns
-    const int i0 = blockIdx.y * 64 + (lane >> 3) * 8;                 // first of this lane's 8 rows
-    if (v0 >= Vp || (int)blockIdx.y * 64 >= info->Trc) return;
+    // one-dimensional grid (the row-block count can exceed the limit of gridDim.y):
+    // block -> (column block bx of 256 columns, row block by of 64 rows), bx fastest
+    const int nbx = Vp / 256;
+    const int bx = blockIdx.x % nbx, by = blockIdx.x / nbx;
+    const int v0 = (bx * 4 + wave) * 64 + (lane & 7) * 8;             // first of this lane's 8 columns
+    const int i0 = by * 64 + (lane >> 3) * 8;                         // first of this lane's 8 rows
+    if (by * 64 >= info->Trc) return;
     const int T_cur = info->Tc;
     dzt += info->kofs;                                   // dzt is [Vp, Kg]
     uint32_t in[8][4];
@@ -937,7 +941,9 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
                 ALST_HIP(hipGetLastError());
             }
             if (do_bwd) {
-                dim3 grid(Vp / 256, Tr / 64);
+                const int64_t nblk = (int64_t)(Vp / 256) * (Tr / 64);
+                if (nblk > 0x7fffffff) return ALST_ERR_SHAPE;
+                dim3 grid((unsigned)nblk);
                 if (do_fwd)
                     hipLaunchKernelGGL(dz_finalize_kernel<true>, grid, dim3(256), 0, s, stash, dzt,
                                        sc, yc, info, Tp, Vp, L.Kg);
