@@ -53,7 +53,7 @@ def main() -> int:
     ap.add_argument("--workload", default="llama8b_128k")
     ap.add_argument("--tile", type=int, default=0, help="override the workload's tile size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=512)
+    ap.add_argument("--cpu-rows", type=int, default=2048)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy before the timed region, so "
                          "that a rocprofv3 --pmc run holds a kernel of known traffic to scale "

@@ -67,6 +67,9 @@ typedef enum {
 #define ALST_FLAG_DW_FP32 1u
 /* dW += gradient instead of dW = gradient (dHidden is always overwritten). */
 #define ALST_FLAG_DW_ACCUMULATE 2u
+/* The loss is the SUM of the token losses of the non-ignored tokens instead of their mean, and
+ * the gradients are those of that sum (scaled by grad_loss instead of grad_loss / M). */
+#define ALST_FLAG_REDUCE_SUM 4u
 
 /* Static, NUL-terminated description of a status value.  Host only. */
 const char* alst_status_string(int status);
@@ -130,6 +133,16 @@ int alst_tiled_ce_forward_backward(const void* hidden, const void* W, const int3
  * fails).  `workspace` must be one that a compute entry point has used.
  */
 int alst_last_device_status(void* workspace, void* stream);
+
+/*
+ * The unreduced loss: token_loss_out[i] = lse[i] - z[i, label_i] for every non-ignored token and 0
+ * for ignored ones, [N] fp32, as left in `workspace` by the last alst_tiled_ce_forward or
+ * alst_tiled_ce_forward_backward call on it with the same N, H, V, tile and flags (the per-token
+ * loss computations the paper's section "Sequence Tiling ..." lists among the operations without
+ * cross-sequence dependency).  Enqueued on `stream` after that call.
+ */
+int alst_tiled_ce_token_losses(const void* workspace, int64_t N, int64_t H, int64_t V, int64_t tile,
+                               uint32_t flags, float* token_loss_out, void* stream);
 
 /*
  * Label utility for the boundary convention above (section "Loss Sharding in Hugging Face

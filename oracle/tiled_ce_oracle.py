@@ -23,6 +23,7 @@ the label value -100 marks a token that is left out of the loss):
 
 Readings where the paper is silent: the reduction is the mean over non-ignored tokens of the
 whole sequence (a sum over all shards divided by the global count, not a mean of shard means);
+reduction="sum" leaves out the division, and loss_rows is the unreduced per-token loss;
 M == 0 gives L = 0 and zero gradients; a label outside [0, V) that is not ignore_index is an
 error; g is a scalar upstream gradient.
 
@@ -111,8 +112,9 @@ def _blocks(n: int, row_block: int | None):
 
 
 def forward(hidden, W, labels, ignore_index: int = -100, row_block: int | None = None,
-            ordered: bool = False) -> dict:
-    """Mean cross-entropy over non-ignored tokens, plus the per-row pieces.
+            ordered: bool = False, reduction: str = "mean") -> dict:
+    """Cross-entropy over non-ignored tokens (their mean, or their sum with reduction="sum"),
+    plus the per-row pieces; loss_rows is the unreduced loss.
 
     Returns dict(loss=float, lse=[N] f64, loss_rows=[N] f64 (0 on ignored rows),
     zlabel=[N] f64 (0 on ignored rows), n_valid=int).
@@ -135,13 +137,16 @@ def forward(hidden, W, labels, ignore_index: int = -100, row_block: int | None =
     total = 0.0
     for x in loss_rows.tolist():
         total += x
-    loss = total / M if M > 0 else 0.0
+    if reduction not in ("mean", "sum"):
+        raise ValueError("reduction must be 'mean' or 'sum'")
+    loss = (total if reduction == "sum" else total / M) if M > 0 else 0.0
     return dict(loss=loss, lse=lse, loss_rows=loss_rows, zlabel=zlab, n_valid=M)
 
 
 def backward(hidden, W, labels, ignore_index: int = -100, grad_loss: float = 1.0,
-             row_block: int | None = None, ordered: bool = False):
-    """Gradients of the mean loss: returns (dHidden [N, H] f64, dW [V, H] f64)."""
+             row_block: int | None = None, ordered: bool = False, reduction: str = "mean"):
+    """Gradients of the mean (or, with reduction="sum", the summed) loss: returns
+    (dHidden [N, H] f64, dW [V, H] f64)."""
     Wd = _as_f64(W)
     N, H = hidden.shape
     V = Wd.shape[0]
@@ -152,7 +157,9 @@ def backward(hidden, W, labels, ignore_index: int = -100, grad_loss: float = 1.0
     dW = np.zeros((V, H), dtype=np.float64)
     if M == 0:
         return dH, dW
-    coef = float(grad_loss) / M
+    if reduction not in ("mean", "sum"):
+        raise ValueError("reduction must be 'mean' or 'sum'")
+    coef = float(grad_loss) if reduction == "sum" else float(grad_loss) / M
     for lo, hi in _blocks(N, row_block):
         hb = _as_f64(hidden[lo:hi])
         z = _contract(hb, Wd.T, ordered)

@@ -18,11 +18,12 @@ ALST_ERR_NULL, ALST_ERR_SHAPE, ALST_ERR_ALIGN, ALST_ERR_WORKSPACE = 1, 2, 3, 4
 ALST_ERR_LABEL_RANGE, ALST_ERR_HIP, ALST_ERR_UNSUPPORTED, ALST_ERR_NONFINITE = 5, 6, 7, 8
 ALST_FLAG_DW_FP32 = 1
 ALST_FLAG_DW_ACCUMULATE = 2
+ALST_FLAG_REDUCE_SUM = 4
 
 EXPORTS = (
     "alst_status_string", "alst_version", "alst_tiled_ce_workspace_bytes", "alst_tiled_ce_forward",
     "alst_tiled_ce_backward", "alst_tiled_ce_forward_backward", "alst_last_device_status",
-    "alst_shift_labels", "alst_profile_enable", "alst_profile_read",
+    "alst_shift_labels", "alst_tiled_ce_token_losses", "alst_profile_enable", "alst_profile_read",
 )
 
 _lib = None
@@ -60,6 +61,8 @@ def load_library() -> ctypes.CDLL:
     lib.alst_last_device_status.argtypes = [vp, vp]
     lib.alst_shift_labels.restype = c.c_int
     lib.alst_shift_labels.argtypes = [vp, vp, i64, i32, vp]
+    lib.alst_tiled_ce_token_losses.restype = c.c_int
+    lib.alst_tiled_ce_token_losses.argtypes = [vp, i64, i64, i64, i64, u32, vp, vp]
     lib.alst_profile_enable.restype = c.c_int
     lib.alst_profile_enable.argtypes = [c.c_int]
     lib.alst_profile_read.restype = c.c_int
@@ -143,6 +146,13 @@ def alst_shift_labels(labels, shift_labels, ignore_index: int = -100) -> None:
     st = load_library().alst_shift_labels(_ptr(labels), _ptr(shift_labels), labels.numel(),
                                           ignore_index, _stream())
     _check(st, "alst_shift_labels")
+
+
+def alst_tiled_ce_token_losses(workspace, N: int, H: int, V: int, tile: int, token_loss_out,
+                               flags: int = 0) -> None:
+    st = load_library().alst_tiled_ce_token_losses(_ptr(workspace), N, H, V, tile, flags,
+                                                   _ptr(token_loss_out), _stream())
+    _check(st, "alst_tiled_ce_token_losses")
 
 
 PROFILE_KINDS = ("logits_gemm", "dhidden_gemm", "dw_gemm", "tile_small_kernels")

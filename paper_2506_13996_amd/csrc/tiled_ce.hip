@@ -169,7 +169,7 @@ __global__ __launch_bounds__(kScanThreads) void block_count_kernel(
 // One workgroup: block_ofs[b] = sum of block_cnt[0 .. b), M and g/M into the header.
 __global__ __launch_bounds__(kScanThreads) void block_offsets_kernel(
     const int32_t* __restrict__ block_cnt, int64_t nblocks, int64_t* __restrict__ block_ofs,
-    Header* h, float grad_loss, int64_t* __restrict__ n_valid_out) {
+    Header* h, float grad_loss, int sum_mode, int64_t* __restrict__ n_valid_out) {
     __shared__ long long part[kScanThreads];
     const int tid = threadIdx.x;
     // thread t owns the contiguous chunk [t * per, (t + 1) * per)
@@ -187,7 +187,8 @@ __global__ __launch_bounds__(kScanThreads) void block_offsets_kernel(
             run += c;
         }
         h->n_valid = run;
-        h->inv = run > 0 ? grad_loss / (float)run : 0.f;
+        // gradient scale: g / M for the mean, g for the sum of the token losses
+        h->inv = run > 0 ? (sum_mode ? grad_loss : grad_loss / (float)run) : 0.f;
         if (n_valid_out) *n_valid_out = run;
     }
     __syncthreads();
@@ -407,9 +408,9 @@ __global__ __launch_bounds__(256) void dz_finalize_kernel(uint16_t* __restrict__
     }
 }
 
-// loss = (sum of the per-row terms in a fixed order) / M.  One block.
+// loss = (sum of the per-row terms in a fixed order) / M, or the sum itself.  One block.
 __global__ __launch_bounds__(1024) void loss_reduce_kernel(const float* __restrict__ loss_rows,
-                                                           int64_t N, Header* h,
+                                                           int64_t N, Header* h, int sum_mode,
                                                            float* __restrict__ loss_out) {
     __shared__ double part[1024];
     double s = 0.0;
@@ -422,7 +423,7 @@ __global__ __launch_bounds__(1024) void loss_reduce_kernel(const float* __restri
     }
     if (threadIdx.x == 0) {
         const long long M = h->n_valid;
-        const double L = M > 0 ? part[0] / (double)M : 0.0;
+        const double L = M > 0 ? (sum_mode ? part[0] : part[0] / (double)M) : 0.0;
         h->loss_sum = part[0];
         *loss_out = (float)L;
         if (!isfinite(L)) atomicMax(&h->status, (int)ALST_ERR_NONFINITE);
@@ -454,6 +455,12 @@ __global__ void dw_finalize_kernel(const float* acc, void* dW, int64_t n4, const
             *o = r;
         }
     }
+}
+
+__global__ void copy_f32_kernel(const float* __restrict__ in, float* __restrict__ out, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * blockDim.x)
+        out[i] = in[i];
 }
 
 __global__ void shift_labels_kernel(const int32_t* __restrict__ labels, int32_t* __restrict__ out,
@@ -809,7 +816,8 @@ static int validate(const Problem& P, size_t workspace_bytes, bool need_fwd_out,
     if (need_fwd_out && !P.loss_out) return ALST_ERR_NULL;
     if (need_bwd_out && (!P.dHidden || !P.dW)) return ALST_ERR_NULL;
     if (need_lse_in && !P.lse_in) return ALST_ERR_NULL;
-    if (P.flags & ~(ALST_FLAG_DW_FP32 | ALST_FLAG_DW_ACCUMULATE)) return ALST_ERR_UNSUPPORTED;
+    if (P.flags & ~(ALST_FLAG_DW_FP32 | ALST_FLAG_DW_ACCUMULATE | ALST_FLAG_REDUCE_SUM))
+        return ALST_ERR_UNSUPPORTED;
     if (P.N < 1 || P.H < 1 || P.V < 1 || P.tile < 1) return ALST_ERR_SHAPE;
     if (P.N > (int64_t)1 << 30 || P.H > (int64_t)1 << 20 || P.V > (int64_t)1 << 24)
         return ALST_ERR_SHAPE;
@@ -878,7 +886,8 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
         hipLaunchKernelGGL(block_count_kernel, dim3((unsigned)nblocks), dim3(kScanThreads), 0, s,
                            P.labels, P.N, P.ignore_index, V, block_cnt, hdr);
         hipLaunchKernelGGL(block_offsets_kernel, dim3(1), dim3(kScanThreads), 0, s, block_cnt,
-                           nblocks, block_ofs, hdr, P.grad_loss, P.n_valid_out);
+                           nblocks, block_ofs, hdr, P.grad_loss,
+                           (P.flags & ALST_FLAG_REDUCE_SUM) ? 1 : 0, P.n_valid_out);
         hipLaunchKernelGGL(scatter_index_kernel, dim3((unsigned)nblocks), dim3(kScanThreads), 0, s,
                            P.labels, P.N, H, P.ignore_index, V, block_ofs, idx,
                            do_fwd ? lse_buf : nullptr, do_fwd ? loss_rows : nullptr,
@@ -990,7 +999,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
 
     if (do_fwd) {
         hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(1024), 0, s, loss_rows, P.N, hdr,
-                           P.loss_out);
+                           (P.flags & ALST_FLAG_REDUCE_SUM) ? 1 : 0, P.loss_out);
         ALST_HIP(hipGetLastError());
     }
     if (do_bwd) {
@@ -1102,6 +1111,20 @@ int alst_last_device_status(void* workspace, void* stream) {
         if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return ALST_ERR_HIP;
     }
     return st;
+}
+
+int alst_tiled_ce_token_losses(const void* workspace, int64_t N, int64_t H, int64_t V, int64_t tile,
+                               uint32_t flags, float* token_loss_out, void* stream) {
+    if (!workspace || !token_loss_out) return ALST_ERR_NULL;
+    if (N < 1 || H < 1 || V < 1 || tile < 1) return ALST_ERR_SHAPE;
+    if (N > (int64_t)1 << 30 || H > (int64_t)1 << 20 || V > (int64_t)1 << 24) return ALST_ERR_SHAPE;
+    const Layout L = make_layout(N, H, V, tile, flags);
+    const float* rows = reinterpret_cast<const float*>((const unsigned char*)workspace + L.loss_rows);
+    int blocks = (int)((N + 255) / 256);
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, rows,
+                       token_loss_out, N);
+    return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
 }
 
 int alst_profile_enable(int on) {

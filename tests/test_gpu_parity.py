@@ -187,3 +187,30 @@ def test_shift_labels_matches_paper_example():
     B.alst_shift_labels(lab, out)
     torch.cuda.synchronize()
     assert out.cpu().tolist() == [2, 3, 4, 5, 6, 7, 8, -100]
+
+
+def test_sum_reduction_and_token_losses():
+    wl = synth.custom("sum", 700, 128, 1000, 256, ignore_frac=0.1, seed=12)
+    h, W, y = synth.make_inputs(wl)
+    f = orc.forward(h, W, y, row_block=256, reduction="sum")
+    dH, dW = orc.backward(h, W, y, grad_loss=0.25, row_block=256, reduction="sum")
+    flags = B.ALST_FLAG_REDUCE_SUM | B.ALST_FLAG_DW_FP32
+    N, H = h.shape
+    V = W.shape[0]
+    hd, Wd, yd = G.bits_to_dev(h), G.bits_to_dev(W), torch.from_numpy(y).cuda()
+    ws = B.alloc_workspace(N, H, V, 256, flags)
+    loss = torch.zeros(1, device="cuda")
+    gH = torch.empty((N, H), dtype=torch.bfloat16, device="cuda")
+    gW = torch.empty((V, H), dtype=torch.float32, device="cuda")
+    B.alst_tiled_ce_forward_backward(hd, Wd, yd, 256, IGN, 0.25, loss_out=loss, dHidden=gH, dW=gW,
+                                     workspace=ws, flags=flags)
+    tok = torch.full((N,), float("nan"), device="cuda")
+    B.alst_tiled_ce_token_losses(ws, N, H, V, 256, tok, flags=flags)
+    assert B.alst_last_device_status(ws) == B.ALST_OK
+    torch.cuda.synchronize()
+    assert abs(float(loss) - f["loss"]) / abs(f["loss"]) <= LOSS_RTOL
+    t = tok.cpu().numpy().astype(np.float64)
+    assert (t[y == IGN] == 0.0).all()
+    assert np.abs(t - f["loss_rows"]).max() <= 1e-3 * np.abs(f["loss_rows"]).max()
+    assert G.grad_err(G.bf16_dev_to_f64(gH), dH) <= GRAD_TOL
+    assert G.grad_err(gW.cpu().numpy().astype(np.float64), dW) <= GRAD_TOL

@@ -272,3 +272,32 @@ def test_bf16_widening_is_exact():
     assert v.tolist() == exp
     t = torch.tensor(bits.astype(np.int16)).view(torch.bfloat16).double().numpy()
     assert (t == v).all()
+
+
+def test_sum_and_unreduced_losses_against_torch():
+    """reduction='sum' and the unreduced token losses against the library routine."""
+    g = np.random.default_rng(31)
+    N, H, V = 40, 16, 50
+    h = g.standard_normal((N, H))
+    W = g.standard_normal((V, H)) * 0.4
+    y = g.integers(0, V, N).astype(np.int64)
+    y[[3, 17, 18]] = IGN
+    f = orc.forward(h, W, y, reduction="sum")
+    ht = torch.tensor(h, requires_grad=True)
+    Wt = torch.tensor(W, requires_grad=True)
+    z = torch.nn.functional.linear(ht, Wt)
+    none = torch.nn.functional.cross_entropy(z, torch.tensor(y), ignore_index=IGN, reduction="none")
+    tot = torch.nn.functional.cross_entropy(z, torch.tensor(y), ignore_index=IGN, reduction="sum")
+    np.testing.assert_allclose(f["loss_rows"], none.detach().numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(f["loss"], float(tot.detach()), rtol=1e-13)
+    (1.5 * tot).backward()
+    dH, dW = orc.backward(h, W, y, grad_loss=1.5, reduction="sum")
+    np.testing.assert_allclose(dH, ht.grad.numpy(), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(dW, Wt.grad.numpy(), rtol=0, atol=1e-12)
+    # the sum is M times the mean, for the loss and for both gradients
+    fm = orc.forward(h, W, y)
+    M = fm["n_valid"]
+    assert abs(f["loss"] - M * fm["loss"]) <= 1e-12 * abs(f["loss"])
+    dHm, dWm = orc.backward(h, W, y, grad_loss=1.5)
+    np.testing.assert_allclose(dH, M * dHm, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(dW, M * dWm, rtol=1e-12, atol=1e-15)
