@@ -154,13 +154,14 @@ int alst_shift_labels(const int32_t* labels, int32_t* shift_labels, int64_t N,
                       int32_t ignore_index, void* stream);
 
 /*
- * Benchmarking aid (no counterpart in the paper).  While enabled, every launch of the three
- * block GEMMs (logits, dHidden, dW) and the group of small kernels between them is bracketed by
- * a pair of HIP events on the launch stream.  alst_profile_read() waits for the recorded events,
- * writes per kind the summed milliseconds and the number of spans -- index 0 logits GEMM,
- * 1 dHidden GEMM, 2 dW GEMM, 3 the small kernels of a tile -- into the HOST arrays
- * ms_total[4] and launches[4], and forgets the spans.  This is the only state the library keeps
- * between calls; it is process-wide and not thread-safe.
+ * Benchmarking aid (no counterpart in the paper).  While enabled, every launch of a block GEMM and
+ * each group of small kernels between them is bracketed by a pair of HIP events on the launch
+ * stream.  alst_profile_read() waits for the recorded events, writes per kind the summed
+ * milliseconds and the number of spans into the HOST arrays ms_total[8] and launches[8], and
+ * forgets the spans.  Kinds: 0 logits GEMM, 1 dHidden GEMM, 2 dW GEMM, 3 the small kernels of a
+ * cross-entropy tile; 4 the projection GEMMs of the tiled MLP (alst_mlp.h), 5 its weight-gradient
+ * GEMMs, 6 its small kernels; 7 unused.  This is the only state the library keeps between calls;
+ * it is process-wide and not thread-safe.
  */
 int alst_profile_enable(int on);
 int alst_profile_read(double* ms_total, int64_t* launches);

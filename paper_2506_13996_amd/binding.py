@@ -24,6 +24,7 @@ EXPORTS = (
     "alst_status_string", "alst_version", "alst_tiled_ce_workspace_bytes", "alst_tiled_ce_forward",
     "alst_tiled_ce_backward", "alst_tiled_ce_forward_backward", "alst_last_device_status",
     "alst_shift_labels", "alst_tiled_ce_token_losses", "alst_profile_enable", "alst_profile_read",
+    "alst_tiled_mlp_workspace_bytes", "alst_tiled_mlp_forward", "alst_tiled_mlp_backward",
 )
 
 _lib = None
@@ -63,6 +64,13 @@ def load_library() -> ctypes.CDLL:
     lib.alst_shift_labels.argtypes = [vp, vp, i64, i32, vp]
     lib.alst_tiled_ce_token_losses.restype = c.c_int
     lib.alst_tiled_ce_token_losses.argtypes = [vp, i64, i64, i64, i64, u32, vp, vp]
+    lib.alst_tiled_mlp_workspace_bytes.restype = sz
+    lib.alst_tiled_mlp_workspace_bytes.argtypes = [i64, i64, i64, i64, c.c_int, u32]
+    lib.alst_tiled_mlp_forward.restype = c.c_int
+    lib.alst_tiled_mlp_forward.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, vp, vp, sz, u32, vp]
+    lib.alst_tiled_mlp_backward.restype = c.c_int
+    lib.alst_tiled_mlp_backward.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, vp, vp, vp, vp, vp,
+                                            sz, u32, vp]
     lib.alst_profile_enable.restype = c.c_int
     lib.alst_profile_enable.argtypes = [c.c_int]
     lib.alst_profile_read.restype = c.c_int
@@ -155,7 +163,40 @@ def alst_tiled_ce_token_losses(workspace, N: int, H: int, V: int, tile: int, tok
     _check(st, "alst_tiled_ce_token_losses")
 
 
-PROFILE_KINDS = ("logits_gemm", "dhidden_gemm", "dw_gemm", "tile_small_kernels")
+def alst_tiled_mlp_workspace_bytes(N: int, H: int, I: int, tile: int, backward: bool, flags: int = 0) -> int:
+    return int(load_library().alst_tiled_mlp_workspace_bytes(N, H, I, tile, 1 if backward else 0, flags))
+
+
+def alloc_mlp_workspace(N: int, H: int, I: int, tile: int, backward: bool, flags: int = 0,
+                        device="cuda") -> torch.Tensor:
+    nbytes = alst_tiled_mlp_workspace_bytes(N, H, I, tile, backward, flags)
+    if nbytes == 0:
+        raise AlstError(ALST_ERR_SHAPE, "alst_tiled_mlp_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def alst_tiled_mlp_forward(x, Wg, Wu, Wd, tile: int, *, y, workspace, flags: int = 0) -> None:
+    """x [N,H], Wg/Wu [I,H], Wd [H,I] bf16 device tensors; y [N,H] bf16 is overwritten."""
+    N, H = x.shape
+    I = Wg.shape[0]
+    st = load_library().alst_tiled_mlp_forward(_ptr(x), _ptr(Wg), _ptr(Wu), _ptr(Wd), N, H, I, tile,
+                                               _ptr(y), _ptr(workspace), workspace.numel(), flags,
+                                               _stream())
+    _check(st, "alst_tiled_mlp_forward")
+
+
+def alst_tiled_mlp_backward(x, Wg, Wu, Wd, dy, tile: int, *, dx, dWg, dWu, dWd, workspace,
+                            flags: int = 0) -> None:
+    N, H = x.shape
+    I = Wg.shape[0]
+    st = load_library().alst_tiled_mlp_backward(_ptr(x), _ptr(Wg), _ptr(Wu), _ptr(Wd), _ptr(dy), N, H,
+                                                I, tile, _ptr(dx), _ptr(dWg), _ptr(dWu), _ptr(dWd),
+                                                _ptr(workspace), workspace.numel(), flags, _stream())
+    _check(st, "alst_tiled_mlp_backward")
+
+
+PROFILE_KINDS = ("logits_gemm", "dhidden_gemm", "dw_gemm", "tile_small_kernels",
+                 "mlp_linear_gemm", "mlp_wgrad_gemm", "mlp_small_kernels", "unused")
 
 
 def alst_profile_enable(on: bool) -> None:
@@ -164,7 +205,7 @@ def alst_profile_enable(on: bool) -> None:
 
 def alst_profile_read() -> dict:
     """{kind: (total_ms, spans)} for the spans recorded since the last read."""
-    ms = (ctypes.c_double * 4)()
-    n = (ctypes.c_int64 * 4)()
+    ms = (ctypes.c_double * 8)()
+    n = (ctypes.c_int64 * 8)()
     _check(load_library().alst_profile_read(ms, n), "alst_profile_read")
     return {k: (ms[i], int(n[i])) for i, k in enumerate(PROFILE_KINDS)}

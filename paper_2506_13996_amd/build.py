@@ -25,7 +25,7 @@ def hipcc_path() -> str:
 
 
 def build_library(verbose: bool = True) -> str:
-    srcs = [os.path.join(CSRC, "tiled_ce.hip")]
+    srcs = [os.path.join(CSRC, f) for f in ("tiled_ce.hip", "tiled_mlp.hip", "prof.hip")]
     cmd = [hipcc_path(), *HIPCC_FLAGS, "-I", os.path.join(PKG_DIR, "..", "include"), *srcs,
            "-o", LIB_PATH + ".tmp"]
     if verbose:

@@ -1,0 +1,82 @@
+// Pieces shared by the translation units of libalst: error macro, per-kernel timing, the padded
+// transpose.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/alst.h"
+#include "gemm_tile.h"
+
+namespace alst {
+
+#define ALST_HIP(call)                                   \
+    do {                                                 \
+        if ((call) != hipSuccess) return ALST_ERR_HIP;   \
+    } while (0)
+
+// Optional per-kernel timing (alst_profile_*): while enabled, each launch of a block GEMM (and each
+// group of small kernels between them) is bracketed by a pair of HIP events on the launch stream.
+// A benchmarking aid; it is the only state the library keeps between calls and is not thread-safe.
+// The kinds are the indices of alst_profile_read().
+enum {
+    PROF_LOGITS = 0, PROF_DHIDDEN = 1, PROF_DW = 2, PROF_OTHER = 3,
+    PROF_MLP_LINEAR = 4, PROF_MLP_WGRAD = 5, PROF_MLP_OTHER = 6, PROF_KINDS = 8
+};
+
+struct ProfScope {
+    hipEvent_t a, b;
+    int kind;
+    hipStream_t s;
+    bool on;
+    ProfScope(int kind, hipStream_t stream);
+    ~ProfScope();
+};
+
+// out[c][r] = in[r][c] for r < R, 0 for R <= r < Rpad; c < C.  16-byte accesses on both sides.
+// With `dyn_rows` the row extent (both R and Rpad) is read from the device instead, and with
+// `dyn_ofs` the output starts that many elements further along its rows.
+static __global__ __launch_bounds__(256) void transpose_pad_kernel(
+    const uint16_t* __restrict__ in, int64_t ld_in, int R, int C, uint16_t* __restrict__ out,
+    int64_t ld_out, int Rpad, const int* __restrict__ dyn_rows, const int* __restrict__ dyn_ofs) {
+    __shared__ uint16_t t[64][66];
+    if (dyn_rows) R = Rpad = *dyn_rows;
+    if (dyn_ofs) out += *dyn_ofs;
+    const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+    if (r0 >= Rpad) return;
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int chunk = tid + 256 * q;
+        const int row = chunk >> 3, cc = chunk & 7;
+        const int r = r0 + row, c = c0 + cc * 8;
+        u32x4_t v = {0u, 0u, 0u, 0u};
+        if (r < R && c + 8 <= C) v = *reinterpret_cast<const u32x4_t*>(in + (int64_t)r * ld_in + c);
+        const uint16_t* e = reinterpret_cast<const uint16_t*>(&v);
+#pragma unroll
+        for (int x = 0; x < 8; ++x) t[row][cc * 8 + x] = e[x];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int chunk = tid + 256 * q;
+        const int crow = chunk >> 3, rc = chunk & 7;
+        const int c = c0 + crow, r = r0 + rc * 8;
+        if (c < C && r + 8 <= Rpad) {
+            u32x4_t v;
+            uint16_t* e = reinterpret_cast<uint16_t*>(&v);
+#pragma unroll
+            for (int x = 0; x < 8; ++x) e[x] = t[rc * 8 + x][crow];
+            *reinterpret_cast<u32x4_t*>(out + (int64_t)c * ld_out + r) = v;
+        }
+    }
+}
+
+// Lets a kernel use the whole LDS of a compute unit.
+template <typename K>
+static int allow_big_lds(K kernel) {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) == hipSuccess
+               ? ALST_OK : ALST_ERR_HIP;
+}
+
+}  // namespace alst

@@ -387,4 +387,75 @@ struct DirectCore {
     }
 };
 
+// ---------------------------------------------------------------------------------------------
+// Epilogues shared by the kernels built on the two cores
+// ---------------------------------------------------------------------------------------------
+constexpr int kTurnPitch = 272;     // bytes per row of the LDS turn-around area: 256 + 16 of padding
+
+// D[(r0 + r) * ldd + c0 + c] = bf16(acc) for the block's 256 x 256 accumulators, D row-major with c
+// contiguous.  In the accumulators a lane holds 4 consecutive c of one r, so a direct store would
+// scatter 8-byte pieces over 32 rows per instruction: each wavefront instead turns its 32 x 128
+// pieces around in LDS (free once the k-loop is over; each wavefront has its own region and LDS
+// serves a wavefront's accesses in order, so no barrier is needed) and stores whole 256-byte row
+// segments.  GUARD: rows >= rows_out and 8-column chunks beyond cols_out are not written.
+template <class Core, bool GUARD>
+__device__ __forceinline__ void store_block_bf16(const f32x16_t (&acc)[Core::kMT][Core::kNT],
+                                                 uint16_t* __restrict__ D, int64_t ldd, int r0,
+                                                 int c0, int rows_out, int cols_out,
+                                                 unsigned char* smem) {
+    const typename Core::Lane lp;
+    unsigned char* const tw = smem + (threadIdx.x >> 6) * (32 * kTurnPitch);
+    const int lrow = lp.lane >> 4, lcol = lp.lane & 15;            // 4 rows x 16 chunks of 16 B
+    const int gc = c0 + lp.wc * kGroupC + lcol * 8;
+#pragma unroll
+    for (int nt = 0; nt < Core::kNT; ++nt) {
+#pragma unroll
+        for (int mt = 0; mt < Core::kMT; ++mt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                bf16x4_t o;
+#pragma unroll
+                for (int x = 0; x < 4; ++x) o[x] = (__bf16)acc[mt][nt][q * 4 + x];
+                *reinterpret_cast<bf16x4_t*>(tw + lp.l31 * kTurnPitch +
+                                             (mt * 32 + q * 8 + lp.half * 4) * 2) = o;
+            }
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int row = it * 4 + lrow;
+            const int gr = r0 + lp.rbase(nt) + row;
+            const u32x4_t v = *reinterpret_cast<const u32x4_t*>(tw + row * kTurnPitch + lcol * 16);
+            if (!GUARD || (gr < rows_out && gc + 8 <= cols_out))
+                *reinterpret_cast<u32x4_t*>(D + (int64_t)gr * ldd + gc) = v;
+        }
+    }
+}
+
+// out[(c0 + c) * ld + r0 + r] (+)= acc: the transposed fp32 accumulate used by the weight-gradient
+// GEMMs.  r runs along the MFMA lane dimension, so each accumulator register of a wavefront
+// covers 32 consecutive floats of one row of `out` and the accumulate is one fire-and-forget fp32
+// atomic add per register on full 128-byte lines (a plain store when `first`).  Each element
+// belongs to exactly one lane per launch; launches on one stream are ordered, so the sums are
+// formed in launch order: deterministic.  Rows r >= r_valid (GUARD) and c >= c_valid are skipped.
+template <class Core, bool GUARD>
+__device__ __forceinline__ void accumulate_block_f32(const f32x16_t (&acc)[Core::kMT][Core::kNT],
+                                                     float* __restrict__ out, int64_t ld, int r0,
+                                                     int c0, int r_valid, int c_valid, bool first) {
+    const typename Core::Lane lp;
+#pragma unroll
+    for (int nt = 0; nt < Core::kNT; ++nt) {
+        const int r = r0 + lp.r(nt);
+        if (GUARD && r >= r_valid) continue;
+#pragma unroll
+        for (int mt = 0; mt < Core::kMT; ++mt)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int c = c0 + lp.c(mt, j >> 2) + (j & 3);
+                if (c >= c_valid) continue;
+                float* dst = out + (int64_t)c * ld + r;
+                if (first) *dst = acc[mt][nt][j];
+                else unsafeAtomicAdd(dst, acc[mt][nt][j]);
+            }
+    }
+}
+
 }  // namespace alst

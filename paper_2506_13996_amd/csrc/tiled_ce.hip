@@ -26,10 +26,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <math.h>
-#include <vector>
 
 #include "../../include/alst.h"
 #include "gemm_tile.h"
+#include "common.h"
 
 namespace alst {
 
@@ -261,49 +261,6 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(
     }
 }
 
-// out[c][r] = in[r][c] for r < R, 0 for R <= r < Rpad; c < C.  16-byte accesses on both sides.
-// With `info` the row extent is the tile's padded valid row count instead of R and Rpad, and the
-// output starts at the tile's k offset inside its dW group.
-__global__ __launch_bounds__(256) void transpose_pad_kernel(const uint16_t* __restrict__ in,
-                                                            int64_t ld_in, int R, int C,
-                                                            uint16_t* __restrict__ out,
-                                                            int64_t ld_out, int Rpad,
-                                                            const TileInfo* __restrict__ info) {
-    __shared__ uint16_t t[64][66];
-    if (info) {
-        R = Rpad = info->Trc;
-        out += info->kofs;
-    }
-    const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-    if (r0 >= Rpad) return;
-    const int tid = threadIdx.x;
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int chunk = tid + 256 * q;
-        const int row = chunk >> 3, cc = chunk & 7;
-        const int r = r0 + row, c = c0 + cc * 8;
-        u32x4_t v = {0u, 0u, 0u, 0u};
-        if (r < R && c + 8 <= C) v = *reinterpret_cast<const u32x4_t*>(in + (int64_t)r * ld_in + c);
-        const uint16_t* e = reinterpret_cast<const uint16_t*>(&v);
-#pragma unroll
-        for (int x = 0; x < 8; ++x) t[row][cc * 8 + x] = e[x];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int chunk = tid + 256 * q;
-        const int crow = chunk >> 3, rc = chunk & 7;
-        const int c = c0 + crow, r = r0 + rc * 8;
-        if (c < C && r + 8 <= Rpad) {
-            u32x4_t v;
-            uint16_t* e = reinterpret_cast<uint16_t*>(&v);
-#pragma unroll
-            for (int x = 0; x < 8; ++x) e[x] = t[rc * 8 + x][crow];
-            *reinterpret_cast<u32x4_t*>(out + (int64_t)c * ld_out + r) = v;
-        }
-    }
-}
-
 // Per dense row of the tile: combine the per-group (max, sum exp) partials into lse, the row's loss
 // term (both written to the row's original position), and (fused mode) the factor that turns the
 // stashed e into a probability.
@@ -514,7 +471,6 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
 
     const typename Core::Lane lp;
     constexpr float kLog2e = 1.4426950408889634f;
-    constexpr int kTurnPitch = 272;     // bytes per row of the turn-around area: 256 + 16 of padding
 #pragma unroll
     for (int nt = 0; nt < kNT; ++nt) {
         const int i = r0 + lp.r(nt);
@@ -669,11 +625,8 @@ struct DWParams {
 };
 
 // r = hidden index (lane dimension), c = vocabulary id (register dimension), k = dense token row.
-// With the hidden index along the lanes, each accumulator register of a wavefront covers 32
-// consecutive floats of one row of acc: the accumulate is one fire-and-forget fp32 atomic add per
-// register on full 128-byte lines, and the wavefront does not wait for the old sums.  Each element
-// is touched by exactly one lane per launch and launches are ordered on the stream, so the sums
-// are formed in tile order: deterministic.
+// With the hidden index along the lanes the accumulate moves full 128-byte lines of acc
+// (accumulate_block_f32).
 template <class Core, bool GUARD>
 __global__ __launch_bounds__(Core::kThreads) void dw_kernel(const DWParams p) {
     constexpr int kMT = Core::kMT, kNT = Core::kNT;
@@ -699,78 +652,12 @@ __global__ __launch_bounds__(Core::kThreads) void dw_kernel(const DWParams p) {
         Core::template gemm<GUARD>(p.ht, p.Kg, p.H, p.dzt, p.Kg, p.Vp, Tkc, r0, c0, smem, acc, warm);
     }
 
-    const typename Core::Lane lp;
-#pragma unroll
-    for (int nt = 0; nt < kNT; ++nt) {
-        const int h = r0 + lp.r(nt);
-        if (GUARD && h >= p.H) continue;
-#pragma unroll
-        for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int v = c0 + lp.c(mt, j >> 2) + (j & 3);
-                if (v >= p.V) continue;
-                float* dst = p.acc + (int64_t)v * p.H + h;
-                if (p.first) *dst = acc[mt][nt][j];
-                else unsafeAtomicAdd(dst, acc[mt][nt][j]);
-            }
-    }
+    accumulate_block_f32<Core, GUARD>(acc, p.acc, p.H, r0, c0, p.H, p.V, p.first != 0);
 }
 
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
-// Optional per-kernel timing (alst_profile_*): while enabled, each launch of a block GEMM is
-// bracketed by a pair of HIP events on the launch stream.  A benchmarking aid; it is the only
-// state the library keeps between calls and is not thread-safe.
-enum { PROF_LOGITS = 0, PROF_DHIDDEN = 1, PROF_DW = 2, PROF_OTHER = 3, PROF_KINDS = 4 };
-struct ProfSpan { hipEvent_t a, b; int kind; };
-static bool g_prof_on = false;
-static std::vector<ProfSpan> g_prof_spans;
-static std::vector<hipEvent_t> g_prof_pool;
-
-static hipEvent_t prof_event() {
-    if (!g_prof_pool.empty()) {
-        hipEvent_t e = g_prof_pool.back();
-        g_prof_pool.pop_back();
-        return e;
-    }
-    hipEvent_t e = nullptr;
-    if (hipEventCreate(&e) != hipSuccess) return nullptr;
-    return e;
-}
-
-struct ProfScope {
-    ProfSpan sp;
-    hipStream_t s;
-    bool on;
-    ProfScope(int kind, hipStream_t stream) : s(stream), on(g_prof_on) {
-        if (!on) return;
-        sp.a = prof_event();
-        sp.b = prof_event();
-        sp.kind = kind;
-        on = sp.a && sp.b;
-        if (on) (void)hipEventRecord(sp.a, s);
-    }
-    ~ProfScope() {
-        if (!on) return;
-        (void)hipEventRecord(sp.b, s);
-        g_prof_spans.push_back(sp);
-    }
-};
-
-#define ALST_HIP(call)                                   \
-    do {                                                 \
-        if ((call) != hipSuccess) return ALST_ERR_HIP;   \
-    } while (0)
-
-template <typename K>
-static int allow_big_lds(K kernel) {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) == hipSuccess
-               ? ALST_OK : ALST_ERR_HIP;
-}
-
 static int prepare_kernels() {
     static int state = -1;      // same value whichever thread gets here first
     if (state >= 0) return state;
@@ -833,7 +720,7 @@ static int launch_transpose(const uint16_t* in, int64_t ld_in, int R, int C, uin
                             int64_t ld_out, int Rpad, const TileInfo* info, hipStream_t s) {
     dim3 grid((Rpad + 63) / 64, (C + 63) / 64);
     hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, s, in, ld_in, R, C, out, ld_out,
-                       Rpad, info);
+                       Rpad, info ? &info->Trc : nullptr, info ? &info->kofs : nullptr);
     return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
 }
 
@@ -1125,28 +1012,6 @@ int alst_tiled_ce_token_losses(const void* workspace, int64_t N, int64_t H, int6
     hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks), dim3(256), 0, (hipStream_t)stream, rows,
                        token_loss_out, N);
     return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
-}
-
-int alst_profile_enable(int on) {
-    g_prof_on = on != 0;
-    return ALST_OK;
-}
-
-int alst_profile_read(double* ms_total, int64_t* launches) {
-    if (!ms_total || !launches) return ALST_ERR_NULL;
-    for (int k = 0; k < PROF_KINDS; ++k) { ms_total[k] = 0.0; launches[k] = 0; }
-    int rc = ALST_OK;
-    for (const ProfSpan& sp : g_prof_spans) {
-        float ms = 0.f;
-        if (hipEventSynchronize(sp.b) != hipSuccess ||
-            hipEventElapsedTime(&ms, sp.a, sp.b) != hipSuccess) rc = ALST_ERR_HIP;
-        ms_total[sp.kind] += ms;
-        launches[sp.kind] += 1;
-        g_prof_pool.push_back(sp.a);
-        g_prof_pool.push_back(sp.b);
-    }
-    g_prof_spans.clear();
-    return rc;
 }
 
 int alst_shift_labels(const int32_t* labels, int32_t* shift_labels, int64_t N, int32_t ignore_index,

@@ -1,0 +1,514 @@
+// Sequence-tiled gated MLP for gfx950: kernels and the C ABI (alst_mlp.h).
+//
+// Paper, subsection "TiledMLP": forward and backward of the MLP are run on tiles of the sequence,
+// the [tile, intermediate] activations exist only for the tile in flight and backward recomputes
+// them.  Per tile of T rows, all contractions on the block GEMM of gemm_tile.h (operands with the
+// contraction index contiguous):
+//
+//   forward    gu = [x Wg^T | x Wu^T]         two launches into the halves of a [T, 2I] buffer
+//              a  = silu(g) * u               swiglu_fwd_kernel
+//              y  = a Wd^T
+//   backward   gu as above (recomputed), da = dy (Wd^T)^T with Wd^T made once per call
+//              a, [dg | du]                   swiglu_bwd_kernel
+//              dx = [dg | du] [Wg^T | Wu^T]^T one launch, K = 2I, the transposed weights made once
+//              x^T, dy^T, a^T, [dg | du]^T    appended along k to the buffers of the tile's group
+//   per group  dWg += dg^T x, dWu += du^T x, dWd += dy^T a   (fp32, contraction over the group's rows)
+//
+// As in the cross-entropy path the weight gradients are accumulated once per group of tiles
+// (about 16384 rows), so the read-modify-write of the fp32 sums is paid once per group.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <math.h>
+
+#include "../../include/alst_mlp.h"
+#include "gemm_tile.h"
+#include "common.h"
+
+namespace alst {
+
+constexpr int kMlpGroupRows = 16384;
+constexpr int kMlpGroupMax = 8;
+
+struct MlpLayout {
+    int64_t Tp, Kg;        // tile rows rounded up to 256; row stride of the transposed group buffers
+    int g;                 // tiles per weight-gradient group
+    size_t gu, a, da, dgu, wdt, wgut, xt, dyt, at, dgut, acc_g, acc_u, acc_d, total;
+};
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static MlpLayout make_mlp_layout(int64_t N, int64_t H, int64_t I, int64_t tile, bool backward,
+                                 uint32_t flags) {
+    MlpLayout L = {};
+    const int64_t T = tile < N ? tile : N;
+    L.Tp = (T + 255) / 256 * 256;
+    int64_t g = kMlpGroupRows / L.Tp;
+    L.g = (int)(g < 1 ? 1 : (g > kMlpGroupMax ? kMlpGroupMax : g));
+    L.Kg = (int64_t)L.g * L.Tp;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    L.gu = take((size_t)L.Tp * 2 * I * 2);
+    L.a = take((size_t)L.Tp * I * 2);
+    if (backward) {
+        L.da = take((size_t)L.Tp * I * 2);
+        L.dgu = take((size_t)L.Tp * 2 * I * 2);
+        L.wdt = take((size_t)I * H * 2);
+        L.wgut = take((size_t)H * 2 * I * 2);
+        L.xt = take((size_t)H * L.Kg * 2);
+        L.dyt = take((size_t)H * L.Kg * 2);
+        L.at = take((size_t)I * L.Kg * 2);
+        L.dgut = take((size_t)2 * I * L.Kg * 2);
+        // fp32 overwrite outputs hold the sums themselves
+        const bool in_out = (flags & ALST_FLAG_DW_FP32) && !(flags & ALST_FLAG_DW_ACCUMULATE);
+        L.acc_g = take(in_out ? 0 : (size_t)I * H * 4);
+        L.acc_u = take(in_out ? 0 : (size_t)I * H * 4);
+        L.acc_d = take(in_out ? 0 : (size_t)H * I * 4);
+    }
+    L.total = o;
+    return L;
+}
+
+// ---------------------------------------------------------------------------------------------
+// kernels
+// ---------------------------------------------------------------------------------------------
+struct LinearParams {
+    const uint16_t* X;       // [rows_x, ldx]   k contiguous
+    const uint16_t* Y;       // [rows_y, ldy]
+    uint16_t* D;             // [.., ldd]       D[r][c] = sum_k X[r][k] Y[c][k], bf16
+    int64_t ldx, ldy, ldd;
+    int rows_x, rows_y, K;
+    int rows_out, cols_out;  // guarded builds write only r < rows_out, 8-column chunks below cols_out
+};
+
+template <class Core, bool GUARD>
+__global__ __launch_bounds__(Core::kThreads) void linear_kernel(const LinearParams p) {
+    constexpr int kMT = Core::kMT, kNT = Core::kNT;
+    extern __shared__ __align__(16) unsigned char smem[];
+    int tr, tc;
+    const int tiles_r = (p.rows_x + kBlockR - 1) / kBlockR, tiles_c = (p.rows_y + kBlockC - 1) / kBlockC;
+    if (!tile_of_block<4, 8>(blockIdx.x, tiles_r, tiles_c, tr, tc)) return;
+    const int r0 = tr * kBlockR, c0 = tc * kBlockC;
+
+    f32x16_t acc[kMT][kNT];
+#pragma unroll
+    for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < kNT; ++nt)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
+
+    const uint16_t* warm = Core::kCanGuard ? nullptr
+                                           : warm_row<4, 8>(p.X, p.ldx, r0, tr, p.Y, p.ldy, c0, tc);
+    Core::template gemm<GUARD>(p.X, p.ldx, p.rows_x, p.Y, p.ldy, p.rows_y, p.K, r0, c0, smem, acc, warm);
+    store_block_bf16<Core, GUARD>(acc, p.D, p.ldd, r0, c0, p.rows_out, p.cols_out, smem);
+}
+
+struct WgradParams {
+    const uint16_t* X;       // [rows_x, ldk]   r: the contiguous index of `out`
+    const uint16_t* Y;       // [rows_y, ldk]   c: the row index of `out`
+    float* out;              // [rows_y, ld]    out[c][r] (+)= sum_k X[r][k] Y[c][k]
+    int64_t ldk, ld;
+    int rows_x, rows_y, K;
+    int first;               // store instead of add
+};
+
+template <class Core, bool GUARD>
+__global__ __launch_bounds__(Core::kThreads) void wgrad_kernel(const WgradParams p) {
+    constexpr int kMT = Core::kMT, kNT = Core::kNT;
+    extern __shared__ __align__(16) unsigned char smem[];
+    int tr, tc;
+    const int tiles_r = (p.rows_x + kBlockR - 1) / kBlockR, tiles_c = (p.rows_y + kBlockC - 1) / kBlockC;
+    if (!tile_of_block<4, 8>(blockIdx.x, tiles_r, tiles_c, tr, tc)) return;
+    const int r0 = tr * kBlockR, c0 = tc * kBlockC;
+
+    f32x16_t acc[kMT][kNT];
+#pragma unroll
+    for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < kNT; ++nt)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
+
+    const uint16_t* warm = Core::kCanGuard ? nullptr
+                                           : warm_row<4, 8>(p.X, p.ldk, r0, tr, p.Y, p.ldk, c0, tc);
+    Core::template gemm<GUARD>(p.X, p.ldk, p.rows_x, p.Y, p.ldk, p.rows_y, p.K, r0, c0, smem, acc, warm);
+    accumulate_block_f32<Core, GUARD>(acc, p.out, p.ld, r0, c0, p.rows_x, p.rows_y, p.first != 0);
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// a = silu(g) * u over `rows` rows; gu is [rows, 2I] with g in the first I columns, u in the last.
+__global__ __launch_bounds__(256) void swiglu_fwd_kernel(const uint16_t* __restrict__ gu,
+                                                         uint16_t* __restrict__ a, int64_t rows,
+                                                         int I) {
+    const int64_t chunks_per_row = I / 8, n = rows * chunks_per_row;
+    for (int64_t ch = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; ch < n;
+         ch += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = ch / chunks_per_row;
+        const int col = (int)(ch % chunks_per_row) * 8;
+        const u32x4_t gv = *reinterpret_cast<const u32x4_t*>(gu + row * 2 * I + col);
+        const u32x4_t uv = *reinterpret_cast<const u32x4_t*>(gu + row * 2 * I + I + col);
+        const uint16_t* ge = reinterpret_cast<const uint16_t*>(&gv);
+        const uint16_t* ue = reinterpret_cast<const uint16_t*>(&uv);
+        bf16x8_t o;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const float g = bf16_to_f32(ge[x]), u = bf16_to_f32(ue[x]);
+            const float s = 1.f / (1.f + __expf(-g));
+            o[x] = (__bf16)(g * s * u);
+        }
+        *reinterpret_cast<bf16x8_t*>(a + row * I + col) = o;
+    }
+}
+
+// a = silu(g) * u,  dg = da * u * silu'(g),  du = da * silu(g);  dgu is [rows, 2I] = [dg | du].
+__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const uint16_t* __restrict__ gu,
+                                                         const uint16_t* __restrict__ da,
+                                                         uint16_t* __restrict__ a,
+                                                         uint16_t* __restrict__ dgu, int64_t rows,
+                                                         int I) {
+    const int64_t chunks_per_row = I / 8, n = rows * chunks_per_row;
+    for (int64_t ch = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; ch < n;
+         ch += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = ch / chunks_per_row;
+        const int col = (int)(ch % chunks_per_row) * 8;
+        const u32x4_t gv = *reinterpret_cast<const u32x4_t*>(gu + row * 2 * I + col);
+        const u32x4_t uv = *reinterpret_cast<const u32x4_t*>(gu + row * 2 * I + I + col);
+        const u32x4_t dv = *reinterpret_cast<const u32x4_t*>(da + row * I + col);
+        const uint16_t* ge = reinterpret_cast<const uint16_t*>(&gv);
+        const uint16_t* ue = reinterpret_cast<const uint16_t*>(&uv);
+        const uint16_t* de = reinterpret_cast<const uint16_t*>(&dv);
+        bf16x8_t oa, og, ou;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const float g = bf16_to_f32(ge[x]), u = bf16_to_f32(ue[x]), d = bf16_to_f32(de[x]);
+            const float s = 1.f / (1.f + __expf(-g));
+            const float sg = g * s;
+            oa[x] = (__bf16)(sg * u);
+            og[x] = (__bf16)(d * u * (s * (1.f + g * (1.f - s))));
+            ou[x] = (__bf16)(d * sg);
+        }
+        *reinterpret_cast<bf16x8_t*>(a + row * I + col) = oa;
+        *reinterpret_cast<bf16x8_t*>(dgu + row * 2 * I + col) = og;
+        *reinterpret_cast<bf16x8_t*>(dgu + row * 2 * I + I + col) = ou;
+    }
+}
+
+// out = sums (bf16 or fp32, overwrite or +=).  `sums` may alias `out` (fp32 overwrite mode).
+template <bool OUT_F32, bool ACCUM>
+__global__ void convert_sums_kernel(const float* sums, void* out, int64_t n4) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        f32x4_t a = reinterpret_cast<const f32x4_t*>(sums)[i];
+        if (OUT_F32) {
+            f32x4_t* o = reinterpret_cast<f32x4_t*>(out) + i;
+            if (ACCUM) a += *o;
+            *o = a;
+        } else {
+            bf16x4_t* o = reinterpret_cast<bf16x4_t*>(out) + i;
+            if (ACCUM) {
+                const bf16x4_t old = *o;
+#pragma unroll
+                for (int x = 0; x < 4; ++x) a[x] += (float)old[x];
+            }
+            bf16x4_t r;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) r[x] = (__bf16)a[x];
+            *o = r;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+static int prepare_mlp_kernels() {
+    static int state = -1;
+    if (state >= 0) return state;
+    int rc = ALST_OK;
+    auto acc = [&](int r) { if (r != ALST_OK) rc = r; };
+    acc(allow_big_lds(linear_kernel<DirectCore, false>));
+    acc(allow_big_lds(linear_kernel<StagedCore, true>));
+    acc(allow_big_lds(wgrad_kernel<DirectCore, false>));
+    acc(allow_big_lds(wgrad_kernel<StagedCore, true>));
+    state = rc;
+    return rc;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static int launch_linear(const LinearParams& p, hipStream_t s) {
+    const int tiles_r = (p.rows_x + kBlockR - 1) / kBlockR, tiles_c = (p.rows_y + kBlockC - 1) / kBlockC;
+    const int grid = grid_for_tiles<4, 8>(tiles_r, tiles_c);
+    // the unguarded core needs every extent block-aligned and writes every row it computes
+    const bool direct = p.rows_x % kBlockR == 0 && p.rows_y % kBlockC == 0 && p.K % kBlockK == 0 &&
+                        p.K >= kBlockK && p.rows_out >= p.rows_x && p.cols_out >= p.rows_y;
+    ProfScope ps(PROF_MLP_LINEAR, s);
+    if (direct)
+        hipLaunchKernelGGL((linear_kernel<DirectCore, false>), dim3(grid), dim3(DirectCore::kThreads),
+                           kLdsBytes, s, p);
+    else
+        hipLaunchKernelGGL((linear_kernel<StagedCore, true>), dim3(grid), dim3(StagedCore::kThreads),
+                           kLdsBytes, s, p);
+    return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
+}
+
+static int launch_wgrad(const WgradParams& p, hipStream_t s) {
+    const int tiles_r = (p.rows_x + kBlockR - 1) / kBlockR, tiles_c = (p.rows_y + kBlockC - 1) / kBlockC;
+    const int grid = grid_for_tiles<4, 8>(tiles_r, tiles_c);
+    const bool direct = p.rows_x % kBlockR == 0 && p.rows_y % kBlockC == 0 && p.K % kBlockK == 0 &&
+                        p.K >= kBlockK;
+    ProfScope ps(PROF_MLP_WGRAD, s);
+    if (direct)
+        hipLaunchKernelGGL((wgrad_kernel<DirectCore, false>), dim3(grid), dim3(DirectCore::kThreads),
+                           kLdsBytes, s, p);
+    else
+        hipLaunchKernelGGL((wgrad_kernel<StagedCore, true>), dim3(grid), dim3(StagedCore::kThreads),
+                           kLdsBytes, s, p);
+    return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
+}
+
+static int launch_transpose(const uint16_t* in, int64_t ld_in, int R, int C, uint16_t* out,
+                            int64_t ld_out, int Rpad, hipStream_t s) {
+    dim3 grid((Rpad + 63) / 64, (C + 63) / 64);
+    if (grid.y > 65535u) return ALST_ERR_SHAPE;
+    hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, s, in, ld_in, R, C, out, ld_out,
+                       Rpad, (const int*)nullptr, (const int*)nullptr);
+    return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
+}
+
+static int elementwise_blocks(int64_t chunks) {
+    int64_t b = (chunks + 255) / 256;
+    return (int)(b > 16384 ? 16384 : (b < 1 ? 1 : b));
+}
+
+struct MlpProblem {
+    const uint16_t *x, *Wg, *Wu, *Wd, *dy;
+    uint16_t *y, *dx;
+    void *dWg, *dWu, *dWd;
+    int64_t N, H, I, tile;
+    unsigned char* ws;
+    uint32_t flags;
+    hipStream_t stream;
+};
+
+static int validate_mlp(const MlpProblem& P, size_t workspace_bytes, bool backward) {
+    if (!P.x || !P.Wg || !P.Wu || !P.Wd || !P.ws) return ALST_ERR_NULL;
+    if (!backward && !P.y) return ALST_ERR_NULL;
+    if (backward && (!P.dy || !P.dx || !P.dWg || !P.dWu || !P.dWd)) return ALST_ERR_NULL;
+    if (P.flags & ~(ALST_FLAG_DW_FP32 | ALST_FLAG_DW_ACCUMULATE)) return ALST_ERR_UNSUPPORTED;
+    if (P.N < 1 || P.H < 1 || P.I < 1 || P.tile < 1) return ALST_ERR_SHAPE;
+    if (P.N > (int64_t)1 << 30 || P.H > (int64_t)1 << 20 || P.I > (int64_t)1 << 20) return ALST_ERR_SHAPE;
+    if (P.H % 8 != 0 || P.I % 8 != 0) return ALST_ERR_ALIGN;
+    const void* ptrs[] = {P.x, P.Wg, P.Wu, P.Wd, P.ws, P.y, P.dy, P.dx, P.dWg, P.dWu, P.dWd};
+    for (const void* q : ptrs)
+        if (q && !aligned16(q)) return ALST_ERR_ALIGN;
+    const MlpLayout L = make_mlp_layout(P.N, P.H, P.I, P.tile, backward, P.flags);
+    if (workspace_bytes < L.total) return ALST_ERR_WORKSPACE;
+    return ALST_OK;
+}
+
+// gu = [x_t Wg^T | x_t Wu^T] for the tile's T_cur rows (rows up to Tr come out as zeros)
+static int gate_up(const MlpProblem& P, const uint16_t* x_t, int T_cur, int Tr, uint16_t* gu,
+                   hipStream_t s) {
+    const int H = (int)P.H, I = (int)P.I;
+    LinearParams lp = {};
+    lp.X = x_t; lp.ldx = H; lp.rows_x = T_cur; lp.K = H;
+    lp.ldy = H; lp.rows_y = I; lp.ldd = 2 * (int64_t)I; lp.rows_out = Tr; lp.cols_out = I;
+    lp.Y = P.Wg; lp.D = gu;
+    int rc = launch_linear(lp, s);
+    if (rc != ALST_OK) return rc;
+    lp.Y = P.Wu; lp.D = gu + I;
+    return launch_linear(lp, s);
+}
+
+static int run_mlp_forward(const MlpProblem& P) {
+    int rc = prepare_mlp_kernels();
+    if (rc != ALST_OK) return rc;
+    const MlpLayout L = make_mlp_layout(P.N, P.H, P.I, P.tile, false, P.flags);
+    hipStream_t s = P.stream;
+    uint16_t* gu = reinterpret_cast<uint16_t*>(P.ws + L.gu);
+    uint16_t* a = reinterpret_cast<uint16_t*>(P.ws + L.a);
+    const int H = (int)P.H, I = (int)P.I;
+    const int64_t T = P.tile < P.N ? P.tile : P.N;
+    const int64_t ntiles = (P.N + T - 1) / T;
+    for (int64_t t = 0; t < ntiles; ++t) {
+        const int64_t i0 = t * T;
+        const int T_cur = (int)((P.N - i0) < T ? (P.N - i0) : T);
+        const int Tr = (T_cur + kBlockR - 1) / kBlockR * kBlockR;
+        rc = gate_up(P, P.x + i0 * P.H, T_cur, Tr, gu, s);
+        if (rc != ALST_OK) return rc;
+        {
+            ProfScope ps(PROF_MLP_OTHER, s);
+            hipLaunchKernelGGL(swiglu_fwd_kernel, dim3(elementwise_blocks((int64_t)Tr * I / 8)),
+                               dim3(256), 0, s, gu, a, (int64_t)Tr, I);
+            ALST_HIP(hipGetLastError());
+        }
+        LinearParams lp = {};
+        lp.X = a; lp.ldx = I; lp.rows_x = Tr; lp.K = I;
+        lp.Y = P.Wd; lp.ldy = I; lp.rows_y = H;
+        lp.D = P.y + i0 * P.H; lp.ldd = H; lp.rows_out = T_cur; lp.cols_out = H;
+        rc = launch_linear(lp, s);
+        if (rc != ALST_OK) return rc;
+    }
+    return ALST_OK;
+}
+
+template <bool F32, bool ACC>
+static void launch_convert(const float* sums, void* out, int64_t n, hipStream_t s) {
+    const int64_t n4 = n / 4;
+    int blocks = (int)((n4 + 255) / 256);
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL((convert_sums_kernel<F32, ACC>), dim3(blocks), dim3(256), 0, s, sums, out, n4);
+}
+
+static int run_mlp_backward(const MlpProblem& P) {
+    int rc = prepare_mlp_kernels();
+    if (rc != ALST_OK) return rc;
+    const MlpLayout L = make_mlp_layout(P.N, P.H, P.I, P.tile, true, P.flags);
+    hipStream_t s = P.stream;
+    uint16_t* gu = reinterpret_cast<uint16_t*>(P.ws + L.gu);
+    uint16_t* a = reinterpret_cast<uint16_t*>(P.ws + L.a);
+    uint16_t* da = reinterpret_cast<uint16_t*>(P.ws + L.da);
+    uint16_t* dgu = reinterpret_cast<uint16_t*>(P.ws + L.dgu);
+    uint16_t* wdt = reinterpret_cast<uint16_t*>(P.ws + L.wdt);
+    uint16_t* wgut = reinterpret_cast<uint16_t*>(P.ws + L.wgut);
+    uint16_t* xt = reinterpret_cast<uint16_t*>(P.ws + L.xt);
+    uint16_t* dyt = reinterpret_cast<uint16_t*>(P.ws + L.dyt);
+    uint16_t* at = reinterpret_cast<uint16_t*>(P.ws + L.at);
+    uint16_t* dgut = reinterpret_cast<uint16_t*>(P.ws + L.dgut);
+    const bool f32 = P.flags & ALST_FLAG_DW_FP32, accum = P.flags & ALST_FLAG_DW_ACCUMULATE;
+    const bool in_out = f32 && !accum;
+    float* acc_g = in_out ? reinterpret_cast<float*>(P.dWg) : reinterpret_cast<float*>(P.ws + L.acc_g);
+    float* acc_u = in_out ? reinterpret_cast<float*>(P.dWu) : reinterpret_cast<float*>(P.ws + L.acc_u);
+    float* acc_d = in_out ? reinterpret_cast<float*>(P.dWd) : reinterpret_cast<float*>(P.ws + L.acc_d);
+    const int H = (int)P.H, I = (int)P.I;
+    const int64_t I2 = 2 * (int64_t)I;
+
+    {   // once per call: Wd^T [I, H] and [Wg^T | Wu^T] [H, 2I]
+        ProfScope ps(PROF_MLP_OTHER, s);
+        rc = launch_transpose(P.Wd, I, H, I, wdt, H, H, s);
+        if (rc == ALST_OK) rc = launch_transpose(P.Wg, H, I, H, wgut, I2, I, s);
+        if (rc == ALST_OK) rc = launch_transpose(P.Wu, H, I, H, wgut + I, I2, I, s);
+        if (rc != ALST_OK) return rc;
+    }
+
+    const int64_t T = P.tile < P.N ? P.tile : P.N;
+    const int64_t ntiles = (P.N + T - 1) / T;
+    int kofs = 0;                                   // rows of the group appended so far (x 64)
+    for (int64_t t = 0; t < ntiles; ++t) {
+        const int64_t i0 = t * T;
+        const int T_cur = (int)((P.N - i0) < T ? (P.N - i0) : T);
+        const int Tr = (T_cur + kBlockR - 1) / kBlockR * kBlockR;
+        const int Tk = (T_cur + kBlockK - 1) / kBlockK * kBlockK;
+        const int slot = (int)(t % L.g);
+        if (slot == 0) kofs = 0;
+        const uint16_t* x_t = P.x + i0 * P.H;
+        const uint16_t* dy_t = P.dy + i0 * P.H;
+
+        rc = gate_up(P, x_t, T_cur, Tr, gu, s);
+        if (rc != ALST_OK) return rc;
+        {   // da = dy_t Wd: contraction over H
+            LinearParams lp = {};
+            lp.X = dy_t; lp.ldx = H; lp.rows_x = T_cur; lp.K = H;
+            lp.Y = wdt; lp.ldy = H; lp.rows_y = I;
+            lp.D = da; lp.ldd = I; lp.rows_out = Tr; lp.cols_out = I;
+            rc = launch_linear(lp, s);
+            if (rc != ALST_OK) return rc;
+        }
+        {
+            ProfScope ps(PROF_MLP_OTHER, s);
+            hipLaunchKernelGGL(swiglu_bwd_kernel, dim3(elementwise_blocks((int64_t)Tr * I / 8)),
+                               dim3(256), 0, s, gu, da, a, dgu, (int64_t)Tr, I);
+            ALST_HIP(hipGetLastError());
+        }
+        {   // dx = [dg | du] [Wg^T | Wu^T]^T: contraction over 2I
+            LinearParams lp = {};
+            lp.X = dgu; lp.ldx = I2; lp.rows_x = Tr; lp.K = (int)I2;
+            lp.Y = wgut; lp.ldy = I2; lp.rows_y = H;
+            lp.D = P.dx + i0 * P.H; lp.ldd = H; lp.rows_out = T_cur; lp.cols_out = H;
+            rc = launch_linear(lp, s);
+            if (rc != ALST_OK) return rc;
+        }
+        {   // the tile's rows go behind those already in the group's transposed buffers
+            ProfScope ps(PROF_MLP_OTHER, s);
+            rc = launch_transpose(x_t, H, T_cur, H, xt + kofs, L.Kg, Tk, s);
+            if (rc == ALST_OK) rc = launch_transpose(dy_t, H, T_cur, H, dyt + kofs, L.Kg, Tk, s);
+            if (rc == ALST_OK) rc = launch_transpose(a, I, T_cur, I, at + kofs, L.Kg, Tk, s);
+            if (rc == ALST_OK) rc = launch_transpose(dgu, I2, T_cur, (int)I2, dgut + kofs, L.Kg, Tk, s);
+            if (rc != ALST_OK) return rc;
+        }
+        kofs += Tk;
+        if (slot == L.g - 1 || t == ntiles - 1) {       // the group is complete
+            const int first = t < L.g;
+            WgradParams wp = {};
+            wp.ldk = L.Kg; wp.K = kofs; wp.first = first;
+            wp.X = xt; wp.rows_x = H; wp.ld = H; wp.rows_y = I;
+            wp.Y = dgut; wp.out = acc_g;
+            rc = launch_wgrad(wp, s);                               // dWg[i][h]
+            if (rc != ALST_OK) return rc;
+            wp.Y = dgut + (int64_t)I * L.Kg; wp.out = acc_u;
+            rc = launch_wgrad(wp, s);                               // dWu[i][h]
+            if (rc != ALST_OK) return rc;
+            wp.X = at; wp.rows_x = I; wp.ld = I; wp.Y = dyt; wp.rows_y = H; wp.out = acc_d;
+            rc = launch_wgrad(wp, s);                               // dWd[h][i]
+            if (rc != ALST_OK) return rc;
+        }
+    }
+    if (!in_out) {
+        ProfScope ps(PROF_MLP_OTHER, s);
+        const int64_t n = P.I * P.H;
+        float* sums[3] = {acc_g, acc_u, acc_d};
+        void* outs[3] = {P.dWg, P.dWu, P.dWd};
+        for (int k = 0; k < 3; ++k) {
+            if (f32) launch_convert<true, true>(sums[k], outs[k], n, s);          // fp32 +=
+            else if (accum) launch_convert<false, true>(sums[k], outs[k], n, s);
+            else launch_convert<false, false>(sums[k], outs[k], n, s);
+        }
+        ALST_HIP(hipGetLastError());
+    }
+    return ALST_OK;
+}
+
+}  // namespace alst
+
+using namespace alst;
+
+extern "C" {
+
+size_t alst_tiled_mlp_workspace_bytes(int64_t N, int64_t H, int64_t I, int64_t tile, int backward,
+                                      uint32_t flags) {
+    if (N < 1 || H < 1 || I < 1 || tile < 1) return 0;
+    if (N > (int64_t)1 << 30 || H > (int64_t)1 << 20 || I > (int64_t)1 << 20) return 0;
+    return make_mlp_layout(N, H, I, tile, backward != 0, flags).total;
+}
+
+int alst_tiled_mlp_forward(const void* x, const void* Wg, const void* Wu, const void* Wd, int64_t N,
+                           int64_t H, int64_t I, int64_t tile, void* y, void* workspace,
+                           size_t workspace_bytes, uint32_t flags, void* stream) {
+    MlpProblem P = {};
+    P.x = (const uint16_t*)x; P.Wg = (const uint16_t*)Wg; P.Wu = (const uint16_t*)Wu;
+    P.Wd = (const uint16_t*)Wd; P.y = (uint16_t*)y;
+    P.N = N; P.H = H; P.I = I; P.tile = tile;
+    P.ws = (unsigned char*)workspace; P.flags = flags; P.stream = (hipStream_t)stream;
+    const int rc = validate_mlp(P, workspace_bytes, false);
+    if (rc != ALST_OK) return rc;
+    return run_mlp_forward(P);
+}
+
+int alst_tiled_mlp_backward(const void* x, const void* Wg, const void* Wu, const void* Wd,
+                            const void* dy, int64_t N, int64_t H, int64_t I, int64_t tile, void* dx,
+                            void* dWg, void* dWu, void* dWd, void* workspace, size_t workspace_bytes,
+                            uint32_t flags, void* stream) {
+    MlpProblem P = {};
+    P.x = (const uint16_t*)x; P.Wg = (const uint16_t*)Wg; P.Wu = (const uint16_t*)Wu;
+    P.Wd = (const uint16_t*)Wd; P.dy = (const uint16_t*)dy; P.dx = (uint16_t*)dx;
+    P.dWg = dWg; P.dWu = dWu; P.dWd = dWd;
+    P.N = N; P.H = H; P.I = I; P.tile = tile;
+    P.ws = (unsigned char*)workspace; P.flags = flags; P.stream = (hipStream_t)stream;
+    const int rc = validate_mlp(P, workspace_bytes, true);
+    if (rc != ALST_OK) return rc;
+    return run_mlp_backward(P);
+}
+
+}  // extern "C"

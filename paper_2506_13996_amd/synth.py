@@ -152,3 +152,37 @@ def make_inputs(wl: Workload):
 def custom(name: str, N: int, H: int, V: int, tile: int, ignore_frac: float = 0.05,
            seed: int = 0, label_law: str = "uniform", ignore_law: str = "iid") -> Workload:
     return Workload(name, N, H, V, tile, label_law, ignore_law, ignore_frac, seed)
+
+
+# ---------------------------------------------------------------------------------------------
+# tiled MLP workloads (the Llama-8B MLP layer of the paper's TiledMLP example)
+# ---------------------------------------------------------------------------------------------
+STREAM_MLP_X, STREAM_MLP_WG, STREAM_MLP_WU, STREAM_MLP_WD, STREAM_MLP_DY = 11, 12, 13, 14, 15
+
+
+@dataclass(frozen=True)
+class MlpWorkload:
+    name: str
+    N: int
+    H: int
+    I: int
+    tile: int
+    seed: int = 0
+
+
+MLP_WORKLOADS = {
+    "mlp_tiny": MlpWorkload("mlp_tiny", 512, 256, 768, 128),
+    # the paper's example: a bf16 [1, 256 000, 4096] input through one Llama-8B MLP layer
+    # (intermediate size 14336 from that model's configuration), tile = hidden size -> 63 tiles
+    "mlp_llama8b_256k": MlpWorkload("mlp_llama8b_256k", 256000, 4096, 14336, 4096),
+}
+
+
+def make_mlp_inputs(wl: MlpWorkload):
+    """bf16 bits of (x [N,H] ~ N(0,1), Wg [I,H], Wu [I,H], Wd [H,I] ~ N(0, 0.02^2), dy [N,H] ~ N(0,1))."""
+    x = normal_bf16(wl.N, wl.H, 1.0, wl.seed, STREAM_MLP_X)
+    Wg = normal_bf16(wl.I, wl.H, 0.02, wl.seed, STREAM_MLP_WG)
+    Wu = normal_bf16(wl.I, wl.H, 0.02, wl.seed, STREAM_MLP_WU)
+    Wd = normal_bf16(wl.H, wl.I, 0.02, wl.seed, STREAM_MLP_WD)
+    dy = normal_bf16(wl.N, wl.H, 1.0, wl.seed, STREAM_MLP_DY)
+    return x, Wg, Wu, Wd, dy

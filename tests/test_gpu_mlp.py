@@ -1,0 +1,112 @@
+"""GPU parity of the sequence-tiled MLP (through its C ABI) against the CPU fp64 oracle.
+
+Bars: for every output, max |got - ref| / max |ref| <= 2e-2 (the bar of the cross-entropy path:
+bf16 rounding of the intermediates and of the outputs, fp32 accumulation; observed ~3e-3)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import tiled_mlp_oracle as orc
+from paper_2506_13996_amd import binding as B
+from paper_2506_13996_amd import synth
+from tests import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+def _run(x, Wg, Wu, Wd, dy, tile, flags=0, init=None):
+    N, H = x.shape
+    I = Wg.shape[0]
+    d = [G.bits_to_dev(t) for t in (x, Wg, Wu, Wd, dy)]
+    y = torch.full((N, H), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws = B.alloc_mlp_workspace(N, H, I, tile, False)
+    B.alst_tiled_mlp_forward(d[0], d[1], d[2], d[3], tile, y=y, workspace=ws)
+    wdt = torch.float32 if flags & B.ALST_FLAG_DW_FP32 else torch.bfloat16
+    dx = torch.full((N, H), float("nan"), dtype=torch.bfloat16, device="cuda")
+    if init is None:
+        gW = [torch.full(s, float("nan"), dtype=wdt, device="cuda") for s in ((I, H), (I, H), (H, I))]
+    else:
+        gW = [t.clone() for t in init]
+    ws2 = B.alloc_mlp_workspace(N, H, I, tile, True, flags)
+    B.alst_tiled_mlp_backward(d[0], d[1], d[2], d[3], d[4], tile, dx=dx, dWg=gW[0], dWu=gW[1],
+                              dWd=gW[2], workspace=ws2, flags=flags)
+    torch.cuda.synchronize()
+    f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
+    return f64(y), f64(dx), [f64(t) for t in gW]
+
+
+CASES = [
+    # name, N, H, I, tile
+    ("tiny", 512, 256, 768, 128),                 # the mlp_tiny workload: aligned, 4 tiles, one group
+    ("aligned_two_groups", 2304, 256, 512, 256),  # 9 tiles of 256 rows: a group of 8 and a group of 1
+    ("ragged", 700, 136, 200, 300),               # H % 64 != 0, I % 256 != 0, ragged tiles
+    ("tile_gt_n", 200, 64, 96, 4096),
+    ("one_row_tiles", 5, 64, 64, 1),
+]
+
+
+@pytest.mark.parametrize("name,N,H,I,tile", CASES, ids=[c[0] for c in CASES])
+def test_mlp_matches_oracle(name, N, H, I, tile):
+    wl = synth.MlpWorkload(name, N, H, I, tile, seed=3)
+    x, Wg, Wu, Wd, dy = synth.make_mlp_inputs(wl)
+    # larger weights than the workload law, so that silu is exercised away from its linear part
+    Wg = synth.normal_bf16(I, H, 0.25, 3, synth.STREAM_MLP_WG)
+    yr = orc.forward(x, Wg, Wu, Wd, row_block=256)
+    ref = orc.backward(x, Wg, Wu, Wd, dy, row_block=256)
+    y, dx, gW = _run(x, Wg, Wu, Wd, dy, tile)
+    errs = [G.grad_err(y, yr), G.grad_err(dx, ref[0])] + [G.grad_err(a, b) for a, b in zip(gW, ref[1:])]
+    print(f"{name}: y {errs[0]:.2e} dx {errs[1]:.2e} dWg {errs[2]:.2e} dWu {errs[3]:.2e} dWd {errs[4]:.2e}")
+    for e in errs:
+        assert e <= TOL, errs
+
+
+def test_mlp_tile_size_changes_nothing_but_rounding_order():
+    wl = synth.MlpWorkload("t", 1000, 192, 320, 0, seed=5)
+    x, Wg, Wu, Wd, dy = synth.make_mlp_inputs(wl)
+    outs = [_run(x, Wg, Wu, Wd, dy, tile) for tile in (1000, 512, 300)]
+    # y and dx rows do not depend on the tiling at all: bit-identical
+    for o in outs[1:]:
+        assert (o[0] == outs[0][0]).all() and (o[1] == outs[0][1]).all()
+
+
+def test_mlp_fp32_and_accumulate_flags():
+    wl = synth.MlpWorkload("f", 600, 128, 264, 256, seed=6)
+    x, Wg, Wu, Wd, dy = synth.make_mlp_inputs(wl)
+    ref = orc.backward(x, Wg, Wu, Wd, dy, row_block=256)
+    _, _, g32 = _run(x, Wg, Wu, Wd, dy, 256, flags=B.ALST_FLAG_DW_FP32)
+    for a, b in zip(g32, ref[1:]):
+        assert G.grad_err(a, b) <= TOL
+    gen = torch.Generator().manual_seed(1)
+    base = [(torch.randn(s, generator=gen) * float(np.abs(r).max())).cuda()
+            for s, r in zip(((264, 128), (264, 128), (128, 264)), ref[1:])]
+    _, _, acc = _run(x, Wg, Wu, Wd, dy, 256, flags=B.ALST_FLAG_DW_FP32 | B.ALST_FLAG_DW_ACCUMULATE, init=base)
+    for a, b0, b in zip(acc, base, ref[1:]):
+        assert G.grad_err(a - b0.cpu().numpy().astype(np.float64), b) <= TOL
+    base16 = [t.to(torch.bfloat16) for t in base]
+    _, _, acc = _run(x, Wg, Wu, Wd, dy, 256, flags=B.ALST_FLAG_DW_ACCUMULATE, init=base16)
+    for a, b0, b in zip(acc, base16, ref[1:]):
+        assert G.grad_err(a, b0.float().cpu().numpy().astype(np.float64) + b) <= TOL
+
+
+def test_mlp_zero_input_gives_zero_everything():
+    wl = synth.MlpWorkload("z", 300, 64, 128, 128, seed=7)
+    x, Wg, Wu, Wd, dy = synth.make_mlp_inputs(wl)
+    x[:] = 0
+    y, dx, gW = _run(x, Wg, Wu, Wd, dy, 128)
+    assert (y == 0).all() and (dx == 0).all()
+    for t in gW:
+        assert (t == 0).all()
+
+
+def test_mlp_bad_arguments_are_rejected_on_the_host():
+    lib = B.load_library()
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    t = torch.empty(64, 64, dtype=torch.bfloat16, device="cuda")
+    args = lambda H=64, I=64, tile=8, wsz=1 << 20: (t.data_ptr(), t.data_ptr(), t.data_ptr(), t.data_ptr(),
+                                                     16, H, I, tile, t.data_ptr(), ws.data_ptr(), wsz, 0, None)
+    assert lib.alst_tiled_mlp_forward(*args()) == B.ALST_OK
+    assert lib.alst_tiled_mlp_forward(*args(H=60)) == B.ALST_ERR_ALIGN
+    assert lib.alst_tiled_mlp_forward(*args(tile=0)) == B.ALST_ERR_SHAPE
+    assert lib.alst_tiled_mlp_forward(*args(wsz=16)) == B.ALST_ERR_WORKSPACE
+    torch.cuda.synchronize()
