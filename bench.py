@@ -45,12 +45,104 @@ def cpu_baseline(wl, h_bits, W_bits, labels, rows: int) -> dict:
                       f"workload (all V={wl.V} columns), {dt:.1f} s; loss of the sample {f['loss']:.6f}"}
 
 
+def bench_mlp(args) -> int:
+    """The tiled MLP (next row after the LM-head path): one step = forward + backward over the
+    whole synthetic [N, H] input of the workload.  Same JSON shape as the headline benchmark."""
+    import numpy as np
+    import torch
+    from paper_2506_13996_amd import binding as B
+    from paper_2506_13996_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    B.load_library()
+    wl = synth.MLP_WORKLOADS[args.workload]
+    tile = args.tile or wl.tile
+    N, H, I = wl.N, wl.H, wl.I
+    t0 = time.perf_counter()
+    bits = synth.make_mlp_inputs(wl)
+    t_gen = time.perf_counter() - t0
+    torch.cuda.reset_peak_memory_stats()
+    x, Wg, Wu, Wd, dy = [torch.from_numpy(b.view(np.int16)).cuda().view(torch.bfloat16) for b in bits]
+    ws_f = B.alloc_mlp_workspace(N, H, I, tile, False)
+    ws_b = B.alloc_mlp_workspace(N, H, I, tile, True)
+    y = torch.empty((N, H), dtype=torch.bfloat16, device="cuda")
+    dx = torch.empty((N, H), dtype=torch.bfloat16, device="cuda")
+    gW = [torch.empty(sh, dtype=torch.bfloat16, device="cuda") for sh in ((I, H), (I, H), (H, I))]
+
+    def step():
+        B.alst_tiled_mlp_forward(x, Wg, Wu, Wd, tile, y=y, workspace=ws_f)
+        B.alst_tiled_mlp_backward(x, Wg, Wu, Wd, dy, tile, dx=dx, dWg=gW[0], dWu=gW[1], dWd=gW[2],
+                                  workspace=ws_b)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.alst_profile_enable(True)
+    B.alst_profile_read()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    prof = B.alst_profile_read()
+    B.alst_profile_enable(False)
+    ms_per_step = ev0.elapsed_time(ev1) / args.steps
+    peak_bytes = torch.cuda.max_memory_allocated()
+    # forward 3 projections (6 N H I flop); backward recomputes 2, plus dy Wd, the K = 2I product for
+    # dx (4 N H I) and three weight gradients: 22 N H I in all, 16 of them in the projection kind
+    flop = 22.0 * N * H * I
+    tflops = flop / (ms_per_step * 1e-3) / 1e12
+    kind_flop = {"mlp_linear_gemm": 16.0 * N * H * I, "mlp_wgrad_gemm": 6.0 * N * H * I}
+    gemm = {k: v for k, v in prof.items() if k in kind_flop and v[1] > 0}
+    dom = max(gemm, key=lambda k: gemm[k][0])
+    dom_ms, dom_n = gemm[dom]
+    flop_per_launch = kind_flop[dom] * args.steps / dom_n
+    achieved = flop_per_launch / (dom_ms / dom_n * 1e-3) / 1e12
+    out = {
+        "metric": "tokens/sec, tiled MLP fwd+bwd, H=%d I=%d" % (H, I),
+        "value": N / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "N": N, "H": H, "I": I, "tile": tile,
+                   "entry": "alst_tiled_mlp_forward + alst_tiled_mlp_backward"},
+        "tflops_22NHI": tflops, "mfma_peak_frac": tflops / MI355X_BF16_MFMA_PEAK_TFLOPS,
+        "peak_device_bytes": int(peak_bytes),
+        "untiled_intermediate_bytes": 2 * 3 * N * I,     # g, u and a of the whole sequence in bf16
+        "wall_s_timed_region": wall, "input_gen_s": t_gen,
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved,
+                     "peak": MI355X_BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MI355X_BF16_MFMA_PEAK_TFLOPS, "traffic": None,
+                     "avg_launch_ms": dom_ms / dom_n, "launches": dom_n,
+                     "flop_per_launch": flop_per_launch,
+                     "per_kind_ms_per_step": {k: v[0] / args.steps for k, v in prof.items() if v[1]}},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import tiled_mlp_oracle as morc
+        rows = min(args.cpu_rows, N)
+        t0 = time.perf_counter()
+        morc.forward(bits[0][:rows], bits[1], bits[2], bits[3], row_block=512)
+        morc.backward(bits[0][:rows], bits[1], bits[2], bits[3], bits[4][:rows], row_block=512)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": rows / dt, "unit": "tokens/s", "cores": os.cpu_count() or 1,
+                               "kind": "oracle",
+                               "sample": f"fp64 MLP oracle forward + backward on the first {rows} rows, {dt:.1f} s"}
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="llama8b_128k")
+    ap.add_argument("--workload", default="llama8b_128k",
+                    help="an LM-head workload (headline metric) or an mlp_* workload (tiled MLP)")
     ap.add_argument("--tile", type=int, default=0, help="override the workload's tile size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=2048)
@@ -63,6 +155,8 @@ def main() -> int:
         print("bench.py: this build measures the one-GPU path only; run with --gpus 1 "
               "(sharding over GPUs is described in DESIGN.md, not built)", file=sys.stderr)
         return 2
+    if args.workload.startswith("mlp_"):
+        return bench_mlp(args)
 
     import numpy as np
     import torch
@@ -145,7 +239,7 @@ def main() -> int:
                 "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(wl.name, {}).get(dom) if tile == wl.tile else None,
                 "avg_launch_ms": dom_ms / dom_n, "launches": dom_n,
                 "flop_per_launch": flop_per_launch,
-                "per_kind_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()}}
+                "per_kind_ms_per_step": {k: v[0] / args.steps for k, v in prof.items() if v[1]}}
 
     out = {
         "metric": "tokens/sec, tiled LM-head+CE fwd+bwd, H=%d V=%d" % (H, V),

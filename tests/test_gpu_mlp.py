@@ -110,3 +110,55 @@ def test_mlp_bad_arguments_are_rejected_on_the_host():
     assert lib.alst_tiled_mlp_forward(*args(tile=0)) == B.ALST_ERR_SHAPE
     assert lib.alst_tiled_mlp_forward(*args(wsz=16)) == B.ALST_ERR_WORKSPACE
     torch.cuda.synchronize()
+
+
+@pytest.mark.timeout(600)
+def test_mlp_full_size_paper_shape():
+    """The paper's TiledMLP example shape ([256 000, 4096] through the Llama-8B MLP, tile 4096, 63
+    tiles, the last one ragged) in the launch configuration bench.py times.  The oracle computes
+    sampled outputs exactly: rows of y and dx, columns of dWd and rows of dWg / dWu (always the first
+    and last index and block edges); the normaliser max |ref| is taken over the sampled entries."""
+    wl = synth.MLP_WORKLOADS["mlp_llama8b_256k"]
+    N, H, I, tile = wl.N, wl.H, wl.I, wl.tile
+    print("[mlp] generating inputs", flush=True)
+    bits = synth.make_mlp_inputs(wl)
+    x, Wg, Wu, Wd, dy = bits
+    torch.cuda.empty_cache()
+    torch.cuda.reset_peak_memory_stats()
+    base = torch.cuda.memory_allocated()
+    d = [G.bits_to_dev(t) for t in bits]
+    y = torch.empty((N, H), dtype=torch.bfloat16, device="cuda")
+    dx = torch.empty((N, H), dtype=torch.bfloat16, device="cuda")
+    gW = [torch.empty(s, dtype=torch.bfloat16, device="cuda") for s in ((I, H), (I, H), (H, I))]
+    ws = B.alloc_mlp_workspace(N, H, I, tile, True)
+    print("[mlp] forward + backward on the GPU", flush=True)
+    B.alst_tiled_mlp_forward(d[0], d[1], d[2], d[3], tile, y=y, workspace=ws)
+    B.alst_tiled_mlp_backward(d[0], d[1], d[2], d[3], d[4], tile, dx=dx, dWg=gW[0], dWu=gW[1],
+                              dWd=gW[2], workspace=ws)
+    torch.cuda.synchronize()
+    peak = torch.cuda.max_memory_allocated() - base
+    # memory: inputs + outputs + workspace, nothing of size N x I (g, u, a in bf16 would be 22 GB)
+    expected = 4 * N * H * 2 + 6 * H * I * 2 + ws.numel()
+    assert peak <= expected + (64 << 20), (peak, expected)
+    assert ws.numel() == B.alst_tiled_mlp_workspace_bytes(tile, H, I, tile, True)   # independent of N
+
+    g = np.random.default_rng(77)
+    rows = np.unique(np.concatenate([[0, 1, tile - 1, tile, N - 1, N - 2048, N - 2049, N // 2],
+                                     g.integers(0, N, 6)]))
+    print(f"[mlp] oracle y and dx for {len(rows)} rows", flush=True)
+    f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
+    rt = torch.from_numpy(rows).cuda()
+    ey = G.grad_err(f64(y[rt]), orc.forward_rows(x, Wg, Wu, Wd, rows))
+    ex = G.grad_err(f64(dx[rt]), orc.dx_rows(x, Wg, Wu, Wd, dy, rows))
+    ids = np.unique(np.concatenate([[0, 1, 255, 256, I - 1, I - 256], g.integers(0, I, 4)]))
+    print(f"[mlp] oracle weight gradients at {len(ids)} intermediate indices", flush=True)
+    it = torch.from_numpy(ids).cuda()
+    ed = G.grad_err(f64(gW[2][:, it]), orc.dwd_columns(x, Wg, Wu, dy, ids, row_block=8192))
+    og, ou = orc.dwgu_rows(x, Wg, Wu, Wd, dy, ids, row_block=8192)
+    eg, eu = G.grad_err(f64(gW[0][it]), og), G.grad_err(f64(gW[1][it]), ou)
+    print(f"[mlp] y {ey:.2e} dx {ex:.2e} dWg {eg:.2e} dWu {eu:.2e} dWd {ed:.2e}  peak {peak / 2**30:.2f} GiB",
+          flush=True)
+    for e in (ey, ex, eg, eu, ed):
+        assert e <= TOL
+    for t in [y, dx] + gW:
+        assert bool(torch.isfinite(t.float().abs().max()))
