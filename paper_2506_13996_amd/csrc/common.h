@@ -71,6 +71,21 @@ static __global__ __launch_bounds__(256) void transpose_pad_kernel(
     }
 }
 
+// The attribute below is per device: the first call on each device (up to kMaxDevices) sets it.
+constexpr int kMaxDevices = 64;
+static inline int current_device_slot() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
+    return dev;
+}
+
+// Workgroups of a launch over tiles_r x tiles_c output blocks; 0 if that does not fit a grid.
+static inline int64_t checked_grid(int64_t tiles_r, int64_t tiles_c) {
+    const int64_t patches = ((tiles_r + 3) / 4) * ((tiles_c + 7) / 8);
+    const int64_t blocks = ((patches + 7) / 8) * 8 * 32;
+    return blocks <= 0x7fffffff ? blocks : 0;
+}
+
 // Lets a kernel use the whole LDS of a compute unit.
 template <typename K>
 static int allow_big_lds(K kernel) {

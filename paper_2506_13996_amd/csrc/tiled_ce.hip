@@ -659,8 +659,10 @@ __global__ __launch_bounds__(Core::kThreads) void dw_kernel(const DWParams p) {
 // host side
 // ---------------------------------------------------------------------------------------------
 static int prepare_kernels() {
-    static int state = -1;      // same value whichever thread gets here first
-    if (state >= 0) return state;
+    static int states[kMaxDevices];         // 0 = not yet prepared on that device, else status + 1
+    const int dev = current_device_slot();
+    if (dev < 0) return ALST_ERR_HIP;
+    if (states[dev] > 0) return states[dev] - 1;
     int rc = ALST_OK;
     auto acc = [&](int r) { if (r != ALST_OK) rc = r; };
     acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_FWD>));
@@ -673,7 +675,7 @@ static int prepare_kernels() {
     acc(allow_big_lds(dhidden_kernel<StagedCore, true>));
     acc(allow_big_lds(dw_kernel<DirectCore, false>));
     acc(allow_big_lds(dw_kernel<StagedCore, true>));
-    state = rc;
+    states[dev] = rc + 1;
     return rc;
 }
 
@@ -712,6 +714,11 @@ static int validate(const Problem& P, size_t workspace_bytes, bool need_fwd_out,
     if (!aligned16(P.hidden) || !aligned16(P.W) || !aligned16(P.ws)) return ALST_ERR_ALIGN;
     if (need_bwd_out && (!aligned16(P.dHidden) || !aligned16(P.dW))) return ALST_ERR_ALIGN;
     const Layout L = make_layout(P.N, P.H, P.V, P.tile, P.flags);
+    // every launch must fit a one-dimensional grid
+    if (!checked_grid(L.Tp / kBlockR, L.Vp / kBlockC) ||
+        !checked_grid((P.H + kBlockR - 1) / kBlockR, L.Vp / kBlockC) ||
+        (L.Vp / 256) * (L.Tp / 64) > 0x7fffffff)
+        return ALST_ERR_SHAPE;
     if (workspace_bytes < L.total) return ALST_ERR_WORKSPACE;
     return ALST_OK;
 }

@@ -223,15 +223,17 @@ __global__ void convert_sums_kernel(const float* sums, void* out, int64_t n4) {
 // host side
 // ---------------------------------------------------------------------------------------------
 static int prepare_mlp_kernels() {
-    static int state = -1;
-    if (state >= 0) return state;
+    static int states[kMaxDevices];         // 0 = not yet prepared on that device, else status + 1
+    const int dev = current_device_slot();
+    if (dev < 0) return ALST_ERR_HIP;
+    if (states[dev] > 0) return states[dev] - 1;
     int rc = ALST_OK;
     auto acc = [&](int r) { if (r != ALST_OK) rc = r; };
     acc(allow_big_lds(linear_kernel<DirectCore, false>));
     acc(allow_big_lds(linear_kernel<StagedCore, true>));
     acc(allow_big_lds(wgrad_kernel<DirectCore, false>));
     acc(allow_big_lds(wgrad_kernel<StagedCore, true>));
-    state = rc;
+    states[dev] = rc + 1;
     return rc;
 }
 
@@ -304,6 +306,10 @@ static int validate_mlp(const MlpProblem& P, size_t workspace_bytes, bool backwa
     for (const void* q : ptrs)
         if (q && !aligned16(q)) return ALST_ERR_ALIGN;
     const MlpLayout L = make_mlp_layout(P.N, P.H, P.I, P.tile, backward, P.flags);
+    // every launch must fit its grid (the widest are [T, 2I] and [2I, H] outputs)
+    if (!checked_grid(L.Tp / kBlockR, (2 * P.I + kBlockC - 1) / kBlockC) ||
+        !checked_grid((P.I + kBlockR - 1) / kBlockR, (P.H + kBlockC - 1) / kBlockC))
+        return ALST_ERR_SHAPE;
     if (workspace_bytes < L.total) return ALST_ERR_WORKSPACE;
     return ALST_OK;
 }

@@ -101,3 +101,35 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert lib.alst_last_device_status(None, None) == B.ALST_ERR_NULL
     assert lib.alst_shift_labels(None, vp(0x1000), 4, -100, None) == B.ALST_ERR_NULL
     assert lib.alst_shift_labels(vp(0x1000), vp(0x2000), 0, -100, None) == B.ALST_ERR_SHAPE
+
+
+def test_mlp_workspace_and_host_validation(lib):
+    H, I, T = 4096, 14336, 4096
+    # independent of the sequence length; backward needs more than forward
+    wf = [B.alst_tiled_mlp_workspace_bytes(N, H, I, T, False) for N in (4096, 256000, 1 << 20)]
+    wb = [B.alst_tiled_mlp_workspace_bytes(N, H, I, T, True) for N in (4096, 256000, 1 << 20)]
+    assert wf[0] == wf[1] == wf[2] > 0 and wb[0] == wb[1] == wb[2] > wf[0]
+    # far below the [N, I] activations of the untiled MLP (g, u, a in bf16) at the paper's shape
+    assert wb[1] < 0.2 * 3 * 2 * 256000 * I
+    # forward: exactly the tile's [T, 2I] and [T, I] bf16 buffers
+    assert wf[0] == T * 2 * I * 2 + T * I * 2
+    assert B.alst_tiled_mlp_workspace_bytes(100, 64, 96, 4096, True) == B.alst_tiled_mlp_workspace_bytes(100, 64, 96, 100, True)
+    assert B.alst_tiled_mlp_workspace_bytes(0, H, I, T, False) == 0
+    assert B.alst_tiled_mlp_workspace_bytes(10, H, 0, T, True) == 0
+    vp = ctypes.c_void_p
+
+    def fwd(x=0x1000, Wd=0x4000, y=0x5000, ws=0x6000, N=16, H=64, I=64, tile=8, wsb=1 << 40, flags=0):
+        return lib.alst_tiled_mlp_forward(vp(x), vp(0x2000), vp(0x3000), vp(Wd), N, H, I, tile, vp(y), vp(ws),
+                                          wsb, flags, None)
+    assert fwd(x=None) == B.ALST_ERR_NULL
+    assert fwd(y=None) == B.ALST_ERR_NULL
+    assert fwd(ws=None) == B.ALST_ERR_NULL
+    assert fwd(N=0) == B.ALST_ERR_SHAPE
+    assert fwd(tile=-1) == B.ALST_ERR_SHAPE
+    assert fwd(I=60) == B.ALST_ERR_ALIGN
+    assert fwd(Wd=0x4008) == B.ALST_ERR_ALIGN
+    assert fwd(wsb=64) == B.ALST_ERR_WORKSPACE
+    assert fwd(flags=4) == B.ALST_ERR_UNSUPPORTED           # the sum flag belongs to the loss, not here
+    rc = lib.alst_tiled_mlp_backward(vp(0x1000), vp(0x2000), vp(0x3000), vp(0x4000), None, 16, 64, 64, 8,
+                                     vp(0x5000), vp(0x6000), vp(0x7000), vp(0x8000), vp(0x9000), 1 << 40, 0, None)
+    assert rc == B.ALST_ERR_NULL
