@@ -25,6 +25,7 @@ EXPORTS = (
     "alst_tiled_ce_backward", "alst_tiled_ce_forward_backward", "alst_last_device_status",
     "alst_shift_labels", "alst_tiled_ce_token_losses", "alst_profile_enable", "alst_profile_read",
     "alst_tiled_mlp_workspace_bytes", "alst_tiled_mlp_forward", "alst_tiled_mlp_backward",
+    "alst_tiled_linear_workspace_bytes", "alst_tiled_linear_forward", "alst_tiled_linear_backward",
 )
 
 _lib = None
@@ -71,6 +72,12 @@ def load_library() -> ctypes.CDLL:
     lib.alst_tiled_mlp_backward.restype = c.c_int
     lib.alst_tiled_mlp_backward.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, vp, vp, vp, vp, vp,
                                             sz, u32, vp]
+    lib.alst_tiled_linear_workspace_bytes.restype = sz
+    lib.alst_tiled_linear_workspace_bytes.argtypes = [i64, i64, i64, i64, c.c_int, u32]
+    lib.alst_tiled_linear_forward.restype = c.c_int
+    lib.alst_tiled_linear_forward.argtypes = [vp, vp, i64, i64, i64, i64, vp, vp, sz, u32, vp]
+    lib.alst_tiled_linear_backward.restype = c.c_int
+    lib.alst_tiled_linear_backward.argtypes = [vp, vp, vp, i64, i64, i64, i64, vp, vp, vp, sz, u32, vp]
     lib.alst_profile_enable.restype = c.c_int
     lib.alst_profile_enable.argtypes = [c.c_int]
     lib.alst_profile_read.restype = c.c_int
@@ -193,6 +200,28 @@ def alst_tiled_mlp_backward(x, Wg, Wu, Wd, dy, tile: int, *, dx, dWg, dWu, dWd, 
                                                 I, tile, _ptr(dx), _ptr(dWg), _ptr(dWu), _ptr(dWd),
                                                 _ptr(workspace), workspace.numel(), flags, _stream())
     _check(st, "alst_tiled_mlp_backward")
+
+
+def alst_tiled_linear_workspace_bytes(N: int, K: int, M: int, tile: int, backward: bool, flags: int = 0) -> int:
+    return int(load_library().alst_tiled_linear_workspace_bytes(N, K, M, tile, 1 if backward else 0, flags))
+
+
+def alst_tiled_linear_forward(x, W, tile: int, *, y) -> None:
+    """y [N,M] = x [N,K] W[M,K]^T (bf16 device tensors)."""
+    N, K = x.shape
+    M = W.shape[0]
+    st = load_library().alst_tiled_linear_forward(_ptr(x), _ptr(W), N, K, M, tile, _ptr(y), None, 0, 0,
+                                                  _stream())
+    _check(st, "alst_tiled_linear_forward")
+
+
+def alst_tiled_linear_backward(x, W, dy, tile: int, *, dx, dW, workspace, flags: int = 0) -> None:
+    N, K = x.shape
+    M = W.shape[0]
+    st = load_library().alst_tiled_linear_backward(_ptr(x), _ptr(W), _ptr(dy), N, K, M, tile, _ptr(dx),
+                                                   _ptr(dW), _ptr(workspace), workspace.numel(), flags,
+                                                   _stream())
+    _check(st, "alst_tiled_linear_backward")
 
 
 PROFILE_KINDS = ("logits_gemm", "dhidden_gemm", "dw_gemm", "tile_small_kernels",

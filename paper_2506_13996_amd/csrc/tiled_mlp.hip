@@ -1,4 +1,5 @@
-// Sequence-tiled gated MLP for gfx950: kernels and the C ABI (alst_mlp.h).
+// Sequence-tiled gated MLP and sequence-tiled linear layer for gfx950: kernels and the C ABI
+// (alst_mlp.h, alst_linear.h).
 //
 // Paper, subsection "TiledMLP": forward and backward of the MLP are run on tiles of the sequence,
 // the [tile, intermediate] activations exist only for the tile in flight and backward recomputes
@@ -21,6 +22,7 @@
 #include <math.h>
 
 #include "../../include/alst_mlp.h"
+#include "../../include/alst_linear.h"
 #include "gemm_tile.h"
 #include "common.h"
 
@@ -476,6 +478,144 @@ static int run_mlp_backward(const MlpProblem& P) {
     return ALST_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// the single tiled linear layer: y = x W^T, dx = dy W, dW = dy^T x
+// ---------------------------------------------------------------------------------------------
+struct LinLayout {
+    int64_t Tp, Kg;
+    int g;
+    size_t wt, xt, dyt, acc, total;
+};
+
+static LinLayout make_lin_layout(int64_t N, int64_t K, int64_t M, int64_t tile, bool backward,
+                                 uint32_t flags) {
+    LinLayout L = {};
+    const int64_t T = tile < N ? tile : N;
+    L.Tp = (T + 255) / 256 * 256;
+    int64_t g = kMlpGroupRows / L.Tp;
+    L.g = (int)(g < 1 ? 1 : (g > kMlpGroupMax ? kMlpGroupMax : g));
+    L.Kg = (int64_t)L.g * L.Tp;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    if (backward) {
+        L.wt = take((size_t)K * M * 2);
+        L.xt = take((size_t)K * L.Kg * 2);
+        L.dyt = take((size_t)M * L.Kg * 2);
+        const bool in_out = (flags & ALST_FLAG_DW_FP32) && !(flags & ALST_FLAG_DW_ACCUMULATE);
+        L.acc = take(in_out ? 0 : (size_t)M * K * 4);
+    }
+    L.total = o;
+    return L;
+}
+
+struct LinProblem {
+    const uint16_t *x, *W, *dy;
+    uint16_t *y, *dx;
+    void* dW;
+    int64_t N, K, M, tile;
+    unsigned char* ws;
+    uint32_t flags;
+    hipStream_t stream;
+};
+
+static int validate_lin(const LinProblem& P, size_t workspace_bytes, bool backward) {
+    if (!P.x || !P.W) return ALST_ERR_NULL;
+    if (!backward && !P.y) return ALST_ERR_NULL;
+    if (backward && (!P.dy || !P.dx || !P.dW || !P.ws)) return ALST_ERR_NULL;
+    if (P.flags & ~(ALST_FLAG_DW_FP32 | ALST_FLAG_DW_ACCUMULATE)) return ALST_ERR_UNSUPPORTED;
+    if (P.N < 1 || P.K < 1 || P.M < 1 || P.tile < 1) return ALST_ERR_SHAPE;
+    if (P.N > (int64_t)1 << 30 || P.K > (int64_t)1 << 20 || P.M > (int64_t)1 << 24) return ALST_ERR_SHAPE;
+    if (P.K % 8 != 0 || P.M % 8 != 0) return ALST_ERR_ALIGN;
+    const void* ptrs[] = {P.x, P.W, P.dy, P.y, P.dx, P.dW, P.ws};
+    for (const void* q : ptrs)
+        if (q && !aligned16(q)) return ALST_ERR_ALIGN;
+    const LinLayout L = make_lin_layout(P.N, P.K, P.M, P.tile, backward, P.flags);
+    if (!checked_grid(L.Tp / kBlockR, (P.M + kBlockC - 1) / kBlockC) ||
+        !checked_grid((P.K + kBlockR - 1) / kBlockR, (P.M + kBlockC - 1) / kBlockC) ||
+        (P.M + 63) / 64 > 65535)
+        return ALST_ERR_SHAPE;
+    if (workspace_bytes < L.total) return ALST_ERR_WORKSPACE;
+    return ALST_OK;
+}
+
+static int run_lin_forward(const LinProblem& P) {
+    int rc = prepare_mlp_kernels();
+    if (rc != ALST_OK) return rc;
+    const int64_t T = P.tile < P.N ? P.tile : P.N;
+    const int64_t ntiles = (P.N + T - 1) / T;
+    for (int64_t t = 0; t < ntiles; ++t) {
+        const int64_t i0 = t * T;
+        const int T_cur = (int)((P.N - i0) < T ? (P.N - i0) : T);
+        LinearParams lp = {};
+        lp.X = P.x + i0 * P.K; lp.ldx = P.K; lp.rows_x = T_cur; lp.K = (int)P.K;
+        lp.Y = P.W; lp.ldy = P.K; lp.rows_y = (int)P.M;
+        lp.D = P.y + i0 * P.M; lp.ldd = P.M; lp.rows_out = T_cur; lp.cols_out = (int)P.M;
+        rc = launch_linear(lp, P.stream);
+        if (rc != ALST_OK) return rc;
+    }
+    return ALST_OK;
+}
+
+static int run_lin_backward(const LinProblem& P) {
+    int rc = prepare_mlp_kernels();
+    if (rc != ALST_OK) return rc;
+    const LinLayout L = make_lin_layout(P.N, P.K, P.M, P.tile, true, P.flags);
+    hipStream_t s = P.stream;
+    uint16_t* wt = reinterpret_cast<uint16_t*>(P.ws + L.wt);
+    uint16_t* xt = reinterpret_cast<uint16_t*>(P.ws + L.xt);
+    uint16_t* dyt = reinterpret_cast<uint16_t*>(P.ws + L.dyt);
+    const bool f32 = P.flags & ALST_FLAG_DW_FP32, accum = P.flags & ALST_FLAG_DW_ACCUMULATE;
+    const bool in_out = f32 && !accum;
+    float* acc = in_out ? reinterpret_cast<float*>(P.dW) : reinterpret_cast<float*>(P.ws + L.acc);
+    const int K = (int)P.K, M = (int)P.M;
+    {   // W^T [K, M], once per call: the k-contiguous operand of dx = dy W
+        ProfScope ps(PROF_MLP_OTHER, s);
+        rc = launch_transpose(P.W, K, M, K, wt, M, M, s);
+        if (rc != ALST_OK) return rc;
+    }
+    const int64_t T = P.tile < P.N ? P.tile : P.N;
+    const int64_t ntiles = (P.N + T - 1) / T;
+    int kofs = 0;
+    for (int64_t t = 0; t < ntiles; ++t) {
+        const int64_t i0 = t * T;
+        const int T_cur = (int)((P.N - i0) < T ? (P.N - i0) : T);
+        const int Tk = (T_cur + kBlockK - 1) / kBlockK * kBlockK;
+        const int slot = (int)(t % L.g);
+        if (slot == 0) kofs = 0;
+        const uint16_t* x_t = P.x + i0 * P.K;
+        const uint16_t* dy_t = P.dy + i0 * P.M;
+        LinearParams lp = {};
+        lp.X = dy_t; lp.ldx = M; lp.rows_x = T_cur; lp.K = M;
+        lp.Y = wt; lp.ldy = M; lp.rows_y = K;
+        lp.D = P.dx + i0 * P.K; lp.ldd = K; lp.rows_out = T_cur; lp.cols_out = K;
+        rc = launch_linear(lp, s);
+        if (rc != ALST_OK) return rc;
+        {
+            ProfScope ps(PROF_MLP_OTHER, s);
+            rc = launch_transpose(x_t, K, T_cur, K, xt + kofs, L.Kg, Tk, s);
+            if (rc == ALST_OK) rc = launch_transpose(dy_t, M, T_cur, M, dyt + kofs, L.Kg, Tk, s);
+            if (rc != ALST_OK) return rc;
+        }
+        kofs += Tk;
+        if (slot == L.g - 1 || t == ntiles - 1) {
+            WgradParams wp = {};
+            wp.X = xt; wp.rows_x = K; wp.Y = dyt; wp.rows_y = M; wp.ldk = L.Kg; wp.K = kofs;
+            wp.out = acc; wp.ld = K; wp.first = t < L.g;
+            rc = launch_wgrad(wp, s);
+            if (rc != ALST_OK) return rc;
+        }
+    }
+    if (!in_out) {
+        ProfScope ps(PROF_MLP_OTHER, s);
+        const int64_t n = P.M * P.K;
+        if (f32) launch_convert<true, true>(acc, P.dW, n, s);
+        else if (accum) launch_convert<false, true>(acc, P.dW, n, s);
+        else launch_convert<false, false>(acc, P.dW, n, s);
+        ALST_HIP(hipGetLastError());
+    }
+    return ALST_OK;
+}
+
 }  // namespace alst
 
 using namespace alst;
@@ -515,6 +655,38 @@ int alst_tiled_mlp_backward(const void* x, const void* Wg, const void* Wu, const
     const int rc = validate_mlp(P, workspace_bytes, true);
     if (rc != ALST_OK) return rc;
     return run_mlp_backward(P);
+}
+
+size_t alst_tiled_linear_workspace_bytes(int64_t N, int64_t K, int64_t M, int64_t tile, int backward,
+                                         uint32_t flags) {
+    if (N < 1 || K < 1 || M < 1 || tile < 1) return 0;
+    if (N > (int64_t)1 << 30 || K > (int64_t)1 << 20 || M > (int64_t)1 << 24) return 0;
+    return make_lin_layout(N, K, M, tile, backward != 0, flags).total;
+}
+
+int alst_tiled_linear_forward(const void* x, const void* W, int64_t N, int64_t K, int64_t M,
+                              int64_t tile, void* y, void* workspace, size_t workspace_bytes,
+                              uint32_t flags, void* stream) {
+    LinProblem P = {};
+    P.x = (const uint16_t*)x; P.W = (const uint16_t*)W; P.y = (uint16_t*)y;
+    P.N = N; P.K = K; P.M = M; P.tile = tile;
+    P.ws = (unsigned char*)workspace; P.flags = flags; P.stream = (hipStream_t)stream;
+    const int rc = validate_lin(P, workspace_bytes, false);
+    if (rc != ALST_OK) return rc;
+    return run_lin_forward(P);
+}
+
+int alst_tiled_linear_backward(const void* x, const void* W, const void* dy, int64_t N, int64_t K,
+                               int64_t M, int64_t tile, void* dx, void* dW, void* workspace,
+                               size_t workspace_bytes, uint32_t flags, void* stream) {
+    LinProblem P = {};
+    P.x = (const uint16_t*)x; P.W = (const uint16_t*)W; P.dy = (const uint16_t*)dy;
+    P.dx = (uint16_t*)dx; P.dW = dW;
+    P.N = N; P.K = K; P.M = M; P.tile = tile;
+    P.ws = (unsigned char*)workspace; P.flags = flags; P.stream = (hipStream_t)stream;
+    const int rc = validate_lin(P, workspace_bytes, true);
+    if (rc != ALST_OK) return rc;
+    return run_lin_backward(P);
 }
 
 }  // extern "C"

@@ -22,6 +22,7 @@ def lib():
 def test_every_declared_symbol_is_exported(lib):
     hdr = open(os.path.join(ROOT, "include", "alst.h")).read()
     hdr += open(os.path.join(ROOT, "include", "alst_mlp.h")).read()
+    hdr += open(os.path.join(ROOT, "include", "alst_linear.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     declared = set(re.findall(r"\b(alst_[a-z_0-9]+)\s*\(", hdr))
     assert declared == set(B.EXPORTS)
