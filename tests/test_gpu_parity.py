@@ -214,3 +214,32 @@ def test_sum_reduction_and_token_losses():
     assert np.abs(t - f["loss_rows"]).max() <= 1e-3 * np.abs(f["loss_rows"]).max()
     assert G.grad_err(G.bf16_dev_to_f64(gH), dH) <= GRAD_TOL
     assert G.grad_err(gW.cpu().numpy().astype(np.float64), dW) <= GRAD_TOL
+
+
+def test_random_shapes_against_oracle():
+    """A seeded sweep of odd shapes (ragged H, V, N, tiles of every alignment): guards and tails."""
+    g = np.random.default_rng(2024)
+    for case in range(14):
+        N = int(g.integers(1, 900))
+        H = int(g.integers(1, 40)) * 8
+        V = int(g.integers(2, 1400))
+        tile = int(g.choice([1, 7, 64, 100, 256, 300, 512, 1000]))
+        frac = float(g.choice([0.0, 0.1, 0.5, 0.95]))
+        wl = synth.custom(f"rnd{case}", N, H, V, tile, ignore_frac=frac, seed=100 + case)
+        h, W, y = synth.make_inputs(wl)
+        f, dH, dW = _oracle(h, W, y, grad_loss=1.25)
+        r = G.run_fused(h, W, y, tile, grad_loss=1.25)
+        tag = f"case {case}: N={N} H={H} V={V} tile={tile} ignored={frac}"
+        _check(r, f, dH, dW, tag, valid=(y != IGN))
+        assert (r.dH[y == IGN] == 0.0).all(), tag
+
+
+def test_large_logits_stay_finite_and_match():
+    """Weights 30x the workload law: logits of several tens, a peaked softmax, losses up to ~100."""
+    wl = synth.custom("big", 512, 256, 2048, 256, ignore_frac=0.05, seed=13)
+    h, W, y = synth.make_inputs(wl)
+    W = synth.normal_bf16(2048, 256, 0.6, 13, synth.STREAM_W)
+    f, dH, dW = _oracle(h, W, y)
+    assert np.abs(orc.logits(h[:8], W)).max() > 25.0 and f["loss"] > 10.0
+    r = G.run_fused(h, W, y, 256)
+    _check(r, f, dH, dW, "large logits", valid=(y != IGN))
