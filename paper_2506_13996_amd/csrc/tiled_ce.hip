@@ -4,11 +4,14 @@
 // Footprint": forward and backward of each logits shard are done together and the shard's
 // intermediates are dropped before the next shard):
 //
-//   0. compact_scan /    rows whose label is ignored take no part in the loss or in either gradient,
-//      gather_rows       so the tile's valid rows are gathered into a dense [Tc, H] copy and all
-//                        three contractions run on Tc <= T rows; the dHidden rows of ignored
-//                        tokens are zero-filled here.  Tc lives on the device: grids are sized
-//                        for T and surplus blocks leave at once, so nothing waits for the host.
+//   0. tile_info /       rows whose label is ignored take no part in the loss or in either gradient:
+//      gather_rows       once per call the valid rows are numbered densely in sequence order
+//                        (block_count / block_offsets / scatter_index, which also zero-fill the
+//                        dHidden rows and loss terms of ignored tokens), and a tile is T
+//                        consecutive dense rows, gathered into a dense [T, H] copy.  Their number
+//                        M lives on the device: the host walks ceil(N / T) tiles and the kernels
+//                        of a tile beyond the dense rows leave at once, so nothing waits for the
+//                        host.
 //   1. logits_kernel     Z = H_c W^T in 256x256 blocks, fp32 accumulators.  The logits never
 //                        leave the registers: the epilogue reduces each row over the block's
 //                        columns to (max, sum exp) partials per 128-column group, picks out the
@@ -16,12 +19,14 @@
 //                        scratch ("stash").
 //   2. row_combine       partials -> lse, per-row loss, and the factor exp(group max - lse)
 //                        that turns e into the softmax probability.
-//   3. dz_finalize       dZ = valid * (e * factor - onehot) as bf16, in place, plus its transpose.
-//   4. dhidden_kernel    dH_t = (g/M) dZ W          (contraction over V), rows scattered back
-//   5. dw_kernel         acc += H_c^T dZ            (contraction over the tile's valid rows, fp32)
+//   3. dz_finalize       dZ = e * factor - onehot as bf16, in place, plus its transpose appended to
+//                        the buffers of the tile's dW group.
+//   4. dhidden_kernel    dH = (g/M) dZ W            (contraction over V), rows scattered back
+//   5. dw_kernel         acc += H_c^T dZ            once per group of tiles (contraction over the
+//                        group's dense rows, fp32)
 //
 // After the last tile: loss = sum(per-row loss) / M in a fixed order, dW = (g/M) acc.
-// All three contractions use the same k-contiguous block GEMM (gemm_tile.h); W^T and H_t^T are
+// All three contractions use the same k-contiguous block GEMM (gemm_tile.h); W^T and H_c^T are
 // made by a padded transpose so that every operand has its contraction index contiguous.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
