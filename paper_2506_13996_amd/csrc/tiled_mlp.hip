@@ -82,13 +82,28 @@ struct LinearParams {
     int rows_out, cols_out;  // guarded builds write only r < rows_out, 8-column chunks below cols_out
 };
 
+// Up to three independent products in one launch: their grids are laid end to end (each a multiple
+// of 256 workgroups, so the block -> XCD patch mapping of each is undisturbed), and the tail of one
+// product is filled by the first workgroups of the next instead of leaving compute units idle.
+constexpr int kMaxBatch = 3;
+struct LinearBatch {
+    LinearParams p[kMaxBatch];
+    int first_block[kMaxBatch + 1];      // first_block[i] .. first_block[i + 1]: workgroups of p[i]
+    int n;
+};
+
 template <class Core, bool GUARD>
-__global__ __launch_bounds__(Core::kThreads) void linear_kernel(const LinearParams p) {
+__global__ __launch_bounds__(Core::kThreads) void linear_kernel(const LinearBatch b) {
     constexpr int kMT = Core::kMT, kNT = Core::kNT;
     extern __shared__ __align__(16) unsigned char smem[];
+    int which = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxBatch; ++i)
+        if (i < b.n && (int)blockIdx.x >= b.first_block[i]) which = i;
+    const LinearParams& p = b.p[which];
     int tr, tc;
     const int tiles_r = (p.rows_x + kBlockR - 1) / kBlockR, tiles_c = (p.rows_y + kBlockC - 1) / kBlockC;
-    if (!tile_of_block<4, 8>(blockIdx.x, tiles_r, tiles_c, tr, tc)) return;
+    if (!tile_of_block<4, 8>(blockIdx.x - b.first_block[which], tiles_r, tiles_c, tr, tc)) return;
     const int r0 = tr * kBlockR, c0 = tc * kBlockC;
 
     f32x16_t acc[kMT][kNT];
@@ -114,13 +129,24 @@ struct WgradParams {
     int first;               // store instead of add
 };
 
+struct WgradBatch {                      // as LinearBatch
+    WgradParams p[kMaxBatch];
+    int first_block[kMaxBatch + 1];
+    int n;
+};
+
 template <class Core, bool GUARD>
-__global__ __launch_bounds__(Core::kThreads) void wgrad_kernel(const WgradParams p) {
+__global__ __launch_bounds__(Core::kThreads) void wgrad_kernel(const WgradBatch b) {
     constexpr int kMT = Core::kMT, kNT = Core::kNT;
     extern __shared__ __align__(16) unsigned char smem[];
+    int which = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxBatch; ++i)
+        if (i < b.n && (int)blockIdx.x >= b.first_block[i]) which = i;
+    const WgradParams& p = b.p[which];
     int tr, tc;
     const int tiles_r = (p.rows_x + kBlockR - 1) / kBlockR, tiles_c = (p.rows_y + kBlockC - 1) / kBlockC;
-    if (!tile_of_block<4, 8>(blockIdx.x, tiles_r, tiles_c, tr, tc)) return;
+    if (!tile_of_block<4, 8>(blockIdx.x - b.first_block[which], tiles_r, tiles_c, tr, tc)) return;
     const int r0 = tr * kBlockR, c0 = tc * kBlockC;
 
     f32x16_t acc[kMT][kNT];
@@ -241,36 +267,63 @@ static int prepare_mlp_kernels() {
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-static int launch_linear(const LinearParams& p, hipStream_t s) {
-    const int tiles_r = (p.rows_x + kBlockR - 1) / kBlockR, tiles_c = (p.rows_y + kBlockC - 1) / kBlockC;
-    const int grid = grid_for_tiles<4, 8>(tiles_r, tiles_c);
-    // the unguarded core needs every extent block-aligned and writes every row it computes
-    const bool direct = p.rows_x % kBlockR == 0 && p.rows_y % kBlockC == 0 && p.K % kBlockK == 0 &&
-                        p.K >= kBlockK && p.rows_out >= p.rows_x && p.cols_out >= p.rows_y;
-    ProfScope ps(PROF_MLP_LINEAR, s);
+// One launch for the n products (n <= kMaxBatch).
+static int launch_linear(const LinearParams* ps, int n, hipStream_t s) {
+    LinearBatch b = {};
+    b.n = n;
+    bool direct = true;
+    int64_t blocks = 0;
+    for (int i = 0; i < n; ++i) {
+        const LinearParams& p = ps[i];
+        b.p[i] = p;
+        b.first_block[i] = (int)blocks;
+        const int tiles_r = (p.rows_x + kBlockR - 1) / kBlockR, tiles_c = (p.rows_y + kBlockC - 1) / kBlockC;
+        blocks += grid_for_tiles<4, 8>(tiles_r, tiles_c);
+        // the unguarded core needs every extent block-aligned and writes every row it computes
+        direct = direct && p.rows_x % kBlockR == 0 && p.rows_y % kBlockC == 0 && p.K % kBlockK == 0 &&
+                 p.K >= kBlockK && p.rows_out >= p.rows_x && p.cols_out >= p.rows_y;
+    }
+    if (blocks > 0x7fffffff) return ALST_ERR_SHAPE;
+    for (int i = n; i <= kMaxBatch; ++i) b.first_block[i] = (int)blocks;
+    ProfScope pr(PROF_MLP_LINEAR, s);
     if (direct)
-        hipLaunchKernelGGL((linear_kernel<DirectCore, false>), dim3(grid), dim3(DirectCore::kThreads),
-                           kLdsBytes, s, p);
+        hipLaunchKernelGGL((linear_kernel<DirectCore, false>), dim3((unsigned)blocks),
+                           dim3(DirectCore::kThreads), kLdsBytes, s, b);
     else
-        hipLaunchKernelGGL((linear_kernel<StagedCore, true>), dim3(grid), dim3(StagedCore::kThreads),
-                           kLdsBytes, s, p);
+        hipLaunchKernelGGL((linear_kernel<StagedCore, true>), dim3((unsigned)blocks),
+                           dim3(StagedCore::kThreads), kLdsBytes, s, b);
     return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
 }
 
-static int launch_wgrad(const WgradParams& p, hipStream_t s) {
-    const int tiles_r = (p.rows_x + kBlockR - 1) / kBlockR, tiles_c = (p.rows_y + kBlockC - 1) / kBlockC;
-    const int grid = grid_for_tiles<4, 8>(tiles_r, tiles_c);
-    const bool direct = p.rows_x % kBlockR == 0 && p.rows_y % kBlockC == 0 && p.K % kBlockK == 0 &&
-                        p.K >= kBlockK;
-    ProfScope ps(PROF_MLP_WGRAD, s);
+static int launch_linear(const LinearParams& p, hipStream_t s) { return launch_linear(&p, 1, s); }
+
+static int launch_wgrad(const WgradParams* ps, int n, hipStream_t s) {
+    WgradBatch b = {};
+    b.n = n;
+    bool direct = true;
+    int64_t blocks = 0;
+    for (int i = 0; i < n; ++i) {
+        const WgradParams& p = ps[i];
+        b.p[i] = p;
+        b.first_block[i] = (int)blocks;
+        const int tiles_r = (p.rows_x + kBlockR - 1) / kBlockR, tiles_c = (p.rows_y + kBlockC - 1) / kBlockC;
+        blocks += grid_for_tiles<4, 8>(tiles_r, tiles_c);
+        direct = direct && p.rows_x % kBlockR == 0 && p.rows_y % kBlockC == 0 && p.K % kBlockK == 0 &&
+                 p.K >= kBlockK;
+    }
+    if (blocks > 0x7fffffff) return ALST_ERR_SHAPE;
+    for (int i = n; i <= kMaxBatch; ++i) b.first_block[i] = (int)blocks;
+    ProfScope pr(PROF_MLP_WGRAD, s);
     if (direct)
-        hipLaunchKernelGGL((wgrad_kernel<DirectCore, false>), dim3(grid), dim3(DirectCore::kThreads),
-                           kLdsBytes, s, p);
+        hipLaunchKernelGGL((wgrad_kernel<DirectCore, false>), dim3((unsigned)blocks),
+                           dim3(DirectCore::kThreads), kLdsBytes, s, b);
     else
-        hipLaunchKernelGGL((wgrad_kernel<StagedCore, true>), dim3(grid), dim3(StagedCore::kThreads),
-                           kLdsBytes, s, p);
+        hipLaunchKernelGGL((wgrad_kernel<StagedCore, true>), dim3((unsigned)blocks),
+                           dim3(StagedCore::kThreads), kLdsBytes, s, b);
     return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
 }
+
+static int launch_wgrad(const WgradParams& p, hipStream_t s) { return launch_wgrad(&p, 1, s); }
 
 static int launch_transpose(const uint16_t* in, int64_t ld_in, int R, int C, uint16_t* out,
                             int64_t ld_out, int Rpad, hipStream_t s) {
@@ -316,18 +369,19 @@ static int validate_mlp(const MlpProblem& P, size_t workspace_bytes, bool backwa
     return ALST_OK;
 }
 
-// gu = [x_t Wg^T | x_t Wu^T] for the tile's T_cur rows (rows up to Tr come out as zeros)
+// gu = [x_t Wg^T | x_t Wu^T] for the tile's T_cur rows (rows up to Tr come out as zeros), in one
+// launch together with `extra` (backward: da = dy_t Wd), if given.
 static int gate_up(const MlpProblem& P, const uint16_t* x_t, int T_cur, int Tr, uint16_t* gu,
-                   hipStream_t s) {
+                   const LinearParams* extra, hipStream_t s) {
     const int H = (int)P.H, I = (int)P.I;
-    LinearParams lp = {};
-    lp.X = x_t; lp.ldx = H; lp.rows_x = T_cur; lp.K = H;
-    lp.ldy = H; lp.rows_y = I; lp.ldd = 2 * (int64_t)I; lp.rows_out = Tr; lp.cols_out = I;
-    lp.Y = P.Wg; lp.D = gu;
-    int rc = launch_linear(lp, s);
-    if (rc != ALST_OK) return rc;
-    lp.Y = P.Wu; lp.D = gu + I;
-    return launch_linear(lp, s);
+    LinearParams lp[kMaxBatch] = {};
+    lp[0].X = x_t; lp[0].ldx = H; lp[0].rows_x = T_cur; lp[0].K = H;
+    lp[0].ldy = H; lp[0].rows_y = I; lp[0].ldd = 2 * (int64_t)I; lp[0].rows_out = Tr; lp[0].cols_out = I;
+    lp[0].Y = P.Wg; lp[0].D = gu;
+    lp[1] = lp[0];
+    lp[1].Y = P.Wu; lp[1].D = gu + I;
+    if (extra) lp[2] = *extra;
+    return launch_linear(lp, extra ? 3 : 2, s);
 }
 
 static int run_mlp_forward(const MlpProblem& P) {
@@ -344,7 +398,7 @@ static int run_mlp_forward(const MlpProblem& P) {
         const int64_t i0 = t * T;
         const int T_cur = (int)((P.N - i0) < T ? (P.N - i0) : T);
         const int Tr = (T_cur + kBlockR - 1) / kBlockR * kBlockR;
-        rc = gate_up(P, P.x + i0 * P.H, T_cur, Tr, gu, s);
+        rc = gate_up(P, P.x + i0 * P.H, T_cur, Tr, gu, nullptr, s);
         if (rc != ALST_OK) return rc;
         {
             ProfScope ps(PROF_MLP_OTHER, s);
@@ -414,14 +468,12 @@ static int run_mlp_backward(const MlpProblem& P) {
         const uint16_t* x_t = P.x + i0 * P.H;
         const uint16_t* dy_t = P.dy + i0 * P.H;
 
-        rc = gate_up(P, x_t, T_cur, Tr, gu, s);
-        if (rc != ALST_OK) return rc;
-        {   // da = dy_t Wd: contraction over H
+        {   // g, u again, and da = dy_t Wd (contraction over H), one launch
             LinearParams lp = {};
             lp.X = dy_t; lp.ldx = H; lp.rows_x = T_cur; lp.K = H;
             lp.Y = wdt; lp.ldy = H; lp.rows_y = I;
             lp.D = da; lp.ldd = I; lp.rows_out = Tr; lp.cols_out = I;
-            rc = launch_linear(lp, s);
+            rc = gate_up(P, x_t, T_cur, Tr, gu, &lp, s);
             if (rc != ALST_OK) return rc;
         }
         {
@@ -449,17 +501,16 @@ static int run_mlp_backward(const MlpProblem& P) {
         kofs += Tk;
         if (slot == L.g - 1 || t == ntiles - 1) {       // the group is complete
             const int first = t < L.g;
-            WgradParams wp = {};
-            wp.ldk = L.Kg; wp.K = kofs; wp.first = first;
-            wp.X = xt; wp.rows_x = H; wp.ld = H; wp.rows_y = I;
-            wp.Y = dgut; wp.out = acc_g;
-            rc = launch_wgrad(wp, s);                               // dWg[i][h]
-            if (rc != ALST_OK) return rc;
-            wp.Y = dgut + (int64_t)I * L.Kg; wp.out = acc_u;
-            rc = launch_wgrad(wp, s);                               // dWu[i][h]
-            if (rc != ALST_OK) return rc;
-            wp.X = at; wp.rows_x = I; wp.ld = I; wp.Y = dyt; wp.rows_y = H; wp.out = acc_d;
-            rc = launch_wgrad(wp, s);                               // dWd[h][i]
+            WgradParams wp[kMaxBatch] = {};
+            wp[0].ldk = L.Kg; wp[0].K = kofs; wp[0].first = first;
+            wp[0].X = xt; wp[0].rows_x = H; wp[0].ld = H; wp[0].rows_y = I;
+            wp[0].Y = dgut; wp[0].out = acc_g;                                       // dWg[i][h]
+            wp[1] = wp[0];
+            wp[1].Y = dgut + (int64_t)I * L.Kg; wp[1].out = acc_u;                   // dWu[i][h]
+            wp[2] = wp[0];
+            wp[2].X = at; wp[2].rows_x = I; wp[2].ld = I; wp[2].Y = dyt; wp[2].rows_y = H;
+            wp[2].out = acc_d;                                                       // dWd[h][i]
+            rc = launch_wgrad(wp, 3, s);                                             // one launch
             if (rc != ALST_OK) return rc;
         }
     }
