@@ -62,6 +62,44 @@ inline int grid_for_tiles(int tiles_r, int tiles_c) {
     return ((patches + 7) / 8) * 8 * PR * PC;
 }
 
+// The same mapping with the patch shape chosen at run time and several products ("parts") in one
+// launch: the patches of all parts are numbered through, and patch P goes to XCD P % 8, so the
+// XCDs stay evenly loaded whatever the number of patches of one part is.
+struct PatchGrid {
+    int tiles_r, tiles_c;      // output blocks of one part
+    int PR, PC;                // patch shape, PR * PC = 32
+    __host__ __device__ int patches_r() const { return (tiles_r + PR - 1) / PR; }
+    __host__ __device__ int patches() const { return patches_r() * ((tiles_c + PC - 1) / PC); }
+};
+
+// Patch shape (of 2x16, 4x8, 8x4, 16x2) with the fewest padding blocks; ties go to the squarer one.
+inline PatchGrid choose_patches(int tiles_r, int tiles_c) {
+    const int shapes[4][2] = {{4, 8}, {8, 4}, {2, 16}, {16, 2}};
+    PatchGrid best = {tiles_r, tiles_c, 4, 8};
+    for (int i = 1; i < 4; ++i) {
+        const PatchGrid g = {tiles_r, tiles_c, shapes[i][0], shapes[i][1]};
+        if (g.patches() < best.patches()) best = g;
+    }
+    return best;
+}
+
+inline int grid_for_patches(int64_t patches) { return (int)(((patches + 7) / 8) * 8 * 32); }
+
+// Workgroup -> (global patch number, position inside the patch).
+__device__ __forceinline__ void patch_of_block(int bid, int& P, int& w) {
+    const int slot = bid >> 3;
+    P = (slot >> 5) * 8 + (bid & 7);
+    w = slot & 31;
+}
+
+// Block (tr, tc) of position w in local patch P of g; false if the patch sticks out there.
+__device__ __forceinline__ bool tile_in_patch(const PatchGrid& g, int P, int w, int& tr, int& tc) {
+    const int pr = g.patches_r();
+    tr = (P % pr) * g.PR + (w % g.PR);
+    tc = (P / pr) * g.PC + (w / g.PR);
+    return tr < g.tiles_r && tc < g.tiles_c;
+}
+
 // L2 warm-up.  The blocks of a patch that share an operand tile walk k in step, so each of them
 // would meet every line of the tile as an L2 miss at the same moment.  Instead the sharers split
 // the tile's rows between them and each touches one dword per line of its share kWarmAhead
@@ -73,6 +111,18 @@ __device__ __forceinline__ const uint16_t* warm_row(const uint16_t* X, int64_t l
                                                     const uint16_t* Y, int64_t ldy, int c0, int tc) {
     constexpr int nx = kBlockR / PC, ny = kBlockC / PR, total = nx + ny, per = (total + 3) / 4;
     static_assert(per <= 64, "one warm-up instruction per wavefront");
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int l = w * per + (lane < per ? lane : per - 1);
+    if (l > total - 1) l = total - 1;
+    if (l < nx) return X + (int64_t)(r0 + (tc % PC) * nx + l) * ldx;
+    return Y + (int64_t)(c0 + (tr % PR) * ny + (l - nx)) * ldy;
+}
+
+// The same for a patch shape chosen at run time (2x16, 4x8, 8x4 or 16x2).
+__device__ __forceinline__ const uint16_t* warm_row(int PR, int PC, const uint16_t* X, int64_t ldx,
+                                                    int r0, int tr, const uint16_t* Y, int64_t ldy,
+                                                    int c0, int tc) {
+    const int nx = kBlockR / PC, ny = kBlockC / PR, total = nx + ny, per = (total + 3) / 4;   // per <= 36
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     int l = w * per + (lane < per ? lane : per - 1);
     if (l > total - 1) l = total - 1;

@@ -75,11 +75,31 @@ struct Layout {
     int64_t Tp, Vp, ng;    // padded tile rows, padded vocabulary, 128-column groups
     int g;                 // tiles per dW group
     int64_t Kg;            // row stride of dzt / ht: g * Tp
+    int splits, ksteps;    // dHidden: ranges of the contraction over V, k-steps per range
     size_t header, tinfo, loss_rows, lse, idx, block_cnt, block_ofs, zlabel, yc, pm, ps, sc, hc,
-        stash, dzt, wt, ht, acc, total;
+        stash, dzt, wt, ht, part, acc, total;
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// dHidden has (Tp / 256) * (H / 256) output blocks.  Picks the number of ranges (1..8) the
+// contraction over V is cut into so that the workgroups fill the 256 compute units of the chip
+// most evenly (ties: fewest ranges), each range keeping at least 64 k-steps.
+constexpr int kComputeUnits = 256;
+static void dhidden_splits(int64_t Tp, int64_t H, int64_t Vp, int& splits, int& ksteps) {
+    const int64_t blocks = (Tp / kBlockR) * ((H + kBlockC - 1) / kBlockC);
+    const int KT = (int)(Vp / kBlockK);
+    double best = -1.0;
+    splits = 1;
+    for (int sp = 1; sp <= 8; ++sp) {
+        const int per = (KT + sp - 1) / sp;
+        if (sp > 1 && (per < 64 || (int64_t)(sp - 1) * per >= KT)) break;
+        const int64_t wg = blocks * sp, rounds = (wg + kComputeUnits - 1) / kComputeUnits;
+        const double fill = (double)wg / (double)(rounds * kComputeUnits);
+        if (fill > best + 1e-9) { best = fill; splits = sp; }
+    }
+    ksteps = (KT + splits - 1) / splits;
+}
 
 static Layout make_layout(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_t flags) {
     Layout L;
@@ -110,6 +130,8 @@ static Layout make_layout(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_
     L.dzt = take((size_t)L.Vp * L.Kg * 2);
     L.wt = take((size_t)H * L.Vp * 2);
     L.ht = take((size_t)H * L.Kg * 2);
+    dhidden_splits(L.Tp, H, L.Vp, L.splits, L.ksteps);
+    L.part = take(L.splits > 1 ? (size_t)L.splits * L.Tp * H * 4 : 0);
     const bool acc_in_dw = (flags & ALST_FLAG_DW_FP32) && !(flags & ALST_FLAG_DW_ACCUMULATE);
     L.acc = take(acc_in_dw ? 0 : (size_t)V * H * 4);
     L.total = o;
@@ -571,10 +593,18 @@ struct DHiddenParams {
     const int32_t* idx;
     const TileInfo* info;
     const Header* hdr;
+    float* part;             // [splits, Tp, H] fp32 partial products (splits > 1)
     int Tp, H, Vp;
+    int splits;              // the contraction over V is cut into this many ranges
+    int ksteps;              // k-steps of 64 per range (the last range may be shorter)
+    int PR, PC;              // patch shape of the block -> tile mapping
 };
 
 // r = token row (lane dimension), c = hidden index (register dimension), k = vocabulary.
+// The output has only (T / 256) * (H / 256) blocks, each with a long contraction: when that
+// number does not fill the compute units evenly, the contraction is cut into `splits` ranges, each
+// range's blocks write fp32 partial products, and dhidden_reduce_kernel adds them in a fixed
+// order.
 template <class Core, bool GUARD>
 __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenParams p) {
     constexpr int kMT = Core::kMT, kNT = Core::kNT;
@@ -583,8 +613,15 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
     const int tiles_c = (p.H + kBlockC - 1) / kBlockC;
     const int T_cur = p.info->Tc, Trc = p.info->Trc;
     if (T_cur == 0) return;
-    if (!tile_of_block<4, 8>(blockIdx.x, Trc / kBlockR, tiles_c, tr, tc)) return;
+    // the ranges are parts of one launch: their patches are numbered through
+    const PatchGrid pg = {Trc / kBlockR, tiles_c, p.PR, p.PC};
+    int P, w;
+    patch_of_block(blockIdx.x, P, w);
+    const int np = pg.patches(), split = P / np;
+    if (split >= p.splits || !tile_in_patch(pg, P - split * np, w, tr, tc)) return;
     const int r0 = tr * kBlockR, c0 = tc * kBlockC;
+    const int k0 = split * p.ksteps * kBlockK;
+    const int klen = min(p.ksteps * kBlockK, p.Vp - k0);        // > 0 by the host's choice of splits
 
     f32x16_t acc[kMT][kNT];
 #pragma unroll
@@ -595,10 +632,30 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
     const uint16_t* warm = Core::kCanGuard ? nullptr
-                                           : warm_row<4, 8>(p.dz, p.Vp, r0, tr, p.wt, p.Vp, c0, tc);
-    Core::template gemm<GUARD>(p.dz, p.Vp, Trc, p.wt, p.Vp, p.H, p.Vp, r0, c0, smem, acc, warm);
+                                           : warm_row(p.PR, p.PC, p.dz + k0, p.Vp, r0, tr, p.wt + k0,
+                                                      p.Vp, c0, tc);
+    Core::template gemm<GUARD>(p.dz + k0, p.Vp, Trc, p.wt + k0, p.Vp, p.H, klen, r0, c0, smem, acc, warm);
 
     const typename Core::Lane lp;
+    if (p.splits > 1) {
+        float* const part = p.part + (int64_t)split * p.Tp * p.H;
+#pragma unroll
+        for (int nt = 0; nt < kNT; ++nt) {
+            float* row = part + (int64_t)(r0 + lp.r(nt)) * p.H;
+#pragma unroll
+            for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int h = c0 + lp.c(mt, q);
+                    if (GUARD && h >= p.H) continue;
+                    f32x4_t o;
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) o[x] = acc[mt][nt][q * 4 + x];
+                    *reinterpret_cast<f32x4_t*>(row + h) = o;
+                }
+        }
+        return;
+    }
     const float inv = p.hdr->inv;
 #pragma unroll
     for (int nt = 0; nt < kNT; ++nt) {
@@ -616,6 +673,28 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
                 for (int x = 0; x < 4; ++x) o[x] = (__bf16)(acc[mt][nt][q * 4 + x] * inv);
                 *reinterpret_cast<bf16x4_t*>(row + h) = o;
             }
+    }
+}
+
+// dH[idx[i]] = (g/M) * sum over the ranges of the partial products of dense row i, in range order.
+__global__ __launch_bounds__(256) void dhidden_reduce_kernel(const float* __restrict__ part,
+                                                             int splits, int Tp, int H,
+                                                             const int32_t* __restrict__ idx,
+                                                             const TileInfo* __restrict__ info,
+                                                             const Header* __restrict__ hdr,
+                                                             uint16_t* __restrict__ dH) {
+    const int i = blockIdx.x;
+    if (i >= info->Tc) return;
+    const float inv = hdr->inv;
+    uint16_t* out = dH + (int64_t)idx[i] * H;
+    for (int c = threadIdx.x * 4; c < H; c += 256 * 4) {
+        f32x4_t a = *reinterpret_cast<const f32x4_t*>(part + (int64_t)i * H + c);
+        for (int sp = 1; sp < splits; ++sp)
+            a += *reinterpret_cast<const f32x4_t*>(part + ((int64_t)sp * Tp + i) * H + c);
+        bf16x4_t o;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) o[x] = (__bf16)(a[x] * inv);
+        *reinterpret_cast<bf16x4_t*>(out + c) = o;
     }
 }
 
@@ -869,8 +948,12 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             DHiddenParams dp;
             dp.dz = stash; dp.wt = wt; dp.dH_t = P.dHidden; dp.idx = idx_t;
             dp.info = info; dp.hdr = hdr;
+            dp.part = reinterpret_cast<float*>(P.ws + L.part);
             dp.Tp = Tp; dp.H = H; dp.Vp = Vp;
-            const int grid = grid_for_tiles<4, 8>(Tr / kBlockR, (H + kBlockC - 1) / kBlockC);
+            dp.splits = L.splits; dp.ksteps = L.ksteps;
+            const PatchGrid pg = choose_patches(Tr / kBlockR, (H + kBlockC - 1) / kBlockC);
+            dp.PR = pg.PR; dp.PC = pg.PC;
+            const int grid = grid_for_patches((int64_t)pg.patches() * L.splits);
             ProfScope ps_(PROF_DHIDDEN, s);
             if (guard_h)
                 hipLaunchKernelGGL((dhidden_kernel<StagedCore, true>), dim3(grid),
@@ -878,6 +961,9 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             else
                 hipLaunchKernelGGL((dhidden_kernel<DirectCore, false>), dim3(grid),
                                    dim3(DirectCore::kThreads), kLdsBytes, s, dp);
+            if (L.splits > 1)
+                hipLaunchKernelGGL(dhidden_reduce_kernel, dim3(Tr), dim3(256), 0, s, dp.part,
+                                   L.splits, Tp, H, idx_t, info, hdr, P.dHidden);
             ALST_HIP(hipGetLastError());
         }
         if (slot == L.g - 1 || t == ntiles - 1) {           // the group is complete

@@ -82,28 +82,40 @@ struct LinearParams {
     int rows_out, cols_out;  // guarded builds write only r < rows_out, 8-column chunks below cols_out
 };
 
-// Up to three independent products in one launch: their grids are laid end to end (each a multiple
-// of 256 workgroups, so the block -> XCD patch mapping of each is undisturbed), and the tail of one
-// product is filled by the first workgroups of the next instead of leaving compute units idle.
+// Up to three independent products in one launch: their patches of output blocks are numbered
+// through (gemm_tile.h), so the XCDs stay evenly loaded and the tail of one product is filled by
+// the first workgroups of the next instead of leaving compute units idle.
 constexpr int kMaxBatch = 3;
+struct BatchMap {
+    PatchGrid g[kMaxBatch];
+    int first_patch[kMaxBatch + 1];      // first_patch[i] .. first_patch[i + 1]: patches of part i
+    int n;
+    // which part and which of its blocks a workgroup works on; false for padding workgroups
+    __device__ __forceinline__ bool locate(int bid, int& which, int& tr, int& tc, int& PR, int& PC) const {
+        int P, w;
+        patch_of_block(bid, P, w);
+        if (P >= first_patch[n]) return false;
+        which = 0;
+#pragma unroll
+        for (int i = 1; i < kMaxBatch; ++i)
+            if (i < n && P >= first_patch[i]) which = i;
+        PR = g[which].PR;
+        PC = g[which].PC;
+        return tile_in_patch(g[which], P - first_patch[which], w, tr, tc);
+    }
+};
 struct LinearBatch {
     LinearParams p[kMaxBatch];
-    int first_block[kMaxBatch + 1];      // first_block[i] .. first_block[i + 1]: workgroups of p[i]
-    int n;
+    BatchMap map;
 };
 
 template <class Core, bool GUARD>
 __global__ __launch_bounds__(Core::kThreads) void linear_kernel(const LinearBatch b) {
     constexpr int kMT = Core::kMT, kNT = Core::kNT;
     extern __shared__ __align__(16) unsigned char smem[];
-    int which = 0;
-#pragma unroll
-    for (int i = 1; i < kMaxBatch; ++i)
-        if (i < b.n && (int)blockIdx.x >= b.first_block[i]) which = i;
+    int which, tr, tc, PR, PC;
+    if (!b.map.locate(blockIdx.x, which, tr, tc, PR, PC)) return;
     const LinearParams& p = b.p[which];
-    int tr, tc;
-    const int tiles_r = (p.rows_x + kBlockR - 1) / kBlockR, tiles_c = (p.rows_y + kBlockC - 1) / kBlockC;
-    if (!tile_of_block<4, 8>(blockIdx.x - b.first_block[which], tiles_r, tiles_c, tr, tc)) return;
     const int r0 = tr * kBlockR, c0 = tc * kBlockC;
 
     f32x16_t acc[kMT][kNT];
@@ -115,7 +127,7 @@ __global__ __launch_bounds__(Core::kThreads) void linear_kernel(const LinearBatc
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
     const uint16_t* warm = Core::kCanGuard ? nullptr
-                                           : warm_row<4, 8>(p.X, p.ldx, r0, tr, p.Y, p.ldy, c0, tc);
+                                           : warm_row(PR, PC, p.X, p.ldx, r0, tr, p.Y, p.ldy, c0, tc);
     Core::template gemm<GUARD>(p.X, p.ldx, p.rows_x, p.Y, p.ldy, p.rows_y, p.K, r0, c0, smem, acc, warm);
     store_block_bf16<Core, GUARD>(acc, p.D, p.ldd, r0, c0, p.rows_out, p.cols_out, smem);
 }
@@ -129,24 +141,18 @@ struct WgradParams {
     int first;               // store instead of add
 };
 
-struct WgradBatch {                      // as LinearBatch
+struct WgradBatch {
     WgradParams p[kMaxBatch];
-    int first_block[kMaxBatch + 1];
-    int n;
+    BatchMap map;
 };
 
 template <class Core, bool GUARD>
 __global__ __launch_bounds__(Core::kThreads) void wgrad_kernel(const WgradBatch b) {
     constexpr int kMT = Core::kMT, kNT = Core::kNT;
     extern __shared__ __align__(16) unsigned char smem[];
-    int which = 0;
-#pragma unroll
-    for (int i = 1; i < kMaxBatch; ++i)
-        if (i < b.n && (int)blockIdx.x >= b.first_block[i]) which = i;
+    int which, tr, tc, PR, PC;
+    if (!b.map.locate(blockIdx.x, which, tr, tc, PR, PC)) return;
     const WgradParams& p = b.p[which];
-    int tr, tc;
-    const int tiles_r = (p.rows_x + kBlockR - 1) / kBlockR, tiles_c = (p.rows_y + kBlockC - 1) / kBlockC;
-    if (!tile_of_block<4, 8>(blockIdx.x - b.first_block[which], tiles_r, tiles_c, tr, tc)) return;
     const int r0 = tr * kBlockR, c0 = tc * kBlockC;
 
     f32x16_t acc[kMT][kNT];
@@ -158,7 +164,7 @@ __global__ __launch_bounds__(Core::kThreads) void wgrad_kernel(const WgradBatch 
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
     const uint16_t* warm = Core::kCanGuard ? nullptr
-                                           : warm_row<4, 8>(p.X, p.ldk, r0, tr, p.Y, p.ldk, c0, tc);
+                                           : warm_row(PR, PC, p.X, p.ldk, r0, tr, p.Y, p.ldk, c0, tc);
     Core::template gemm<GUARD>(p.X, p.ldk, p.rows_x, p.Y, p.ldk, p.rows_y, p.K, r0, c0, smem, acc, warm);
     accumulate_block_f32<Core, GUARD>(acc, p.out, p.ld, r0, c0, p.rows_x, p.rows_y, p.first != 0);
 }
@@ -270,21 +276,23 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // One launch for the n products (n <= kMaxBatch).
 static int launch_linear(const LinearParams* ps, int n, hipStream_t s) {
     LinearBatch b = {};
-    b.n = n;
+    b.map.n = n;
     bool direct = true;
-    int64_t blocks = 0;
+    int64_t patches = 0;
     for (int i = 0; i < n; ++i) {
         const LinearParams& p = ps[i];
         b.p[i] = p;
-        b.first_block[i] = (int)blocks;
+        b.map.first_patch[i] = (int)patches;
         const int tiles_r = (p.rows_x + kBlockR - 1) / kBlockR, tiles_c = (p.rows_y + kBlockC - 1) / kBlockC;
-        blocks += grid_for_tiles<4, 8>(tiles_r, tiles_c);
+        b.map.g[i] = choose_patches(tiles_r, tiles_c);
+        patches += b.map.g[i].patches();
         // the unguarded core needs every extent block-aligned and writes every row it computes
         direct = direct && p.rows_x % kBlockR == 0 && p.rows_y % kBlockC == 0 && p.K % kBlockK == 0 &&
                  p.K >= kBlockK && p.rows_out >= p.rows_x && p.cols_out >= p.rows_y;
     }
-    if (blocks > 0x7fffffff) return ALST_ERR_SHAPE;
-    for (int i = n; i <= kMaxBatch; ++i) b.first_block[i] = (int)blocks;
+    if (patches * 32 > 0x7fffff00) return ALST_ERR_SHAPE;
+    for (int i = n; i <= kMaxBatch; ++i) b.map.first_patch[i] = (int)patches;
+    const int blocks = grid_for_patches(patches);
     ProfScope pr(PROF_MLP_LINEAR, s);
     if (direct)
         hipLaunchKernelGGL((linear_kernel<DirectCore, false>), dim3((unsigned)blocks),
@@ -299,20 +307,22 @@ static int launch_linear(const LinearParams& p, hipStream_t s) { return launch_l
 
 static int launch_wgrad(const WgradParams* ps, int n, hipStream_t s) {
     WgradBatch b = {};
-    b.n = n;
+    b.map.n = n;
     bool direct = true;
-    int64_t blocks = 0;
+    int64_t patches = 0;
     for (int i = 0; i < n; ++i) {
         const WgradParams& p = ps[i];
         b.p[i] = p;
-        b.first_block[i] = (int)blocks;
+        b.map.first_patch[i] = (int)patches;
         const int tiles_r = (p.rows_x + kBlockR - 1) / kBlockR, tiles_c = (p.rows_y + kBlockC - 1) / kBlockC;
-        blocks += grid_for_tiles<4, 8>(tiles_r, tiles_c);
+        b.map.g[i] = choose_patches(tiles_r, tiles_c);
+        patches += b.map.g[i].patches();
         direct = direct && p.rows_x % kBlockR == 0 && p.rows_y % kBlockC == 0 && p.K % kBlockK == 0 &&
                  p.K >= kBlockK;
     }
-    if (blocks > 0x7fffffff) return ALST_ERR_SHAPE;
-    for (int i = n; i <= kMaxBatch; ++i) b.first_block[i] = (int)blocks;
+    if (patches * 32 > 0x7fffff00) return ALST_ERR_SHAPE;
+    for (int i = n; i <= kMaxBatch; ++i) b.map.first_patch[i] = (int)patches;
+    const int blocks = grid_for_patches(patches);
     ProfScope pr(PROF_MLP_WGRAD, s);
     if (direct)
         hipLaunchKernelGGL((wgrad_kernel<DirectCore, false>), dim3((unsigned)blocks),

@@ -55,6 +55,9 @@ CASES = [
     ("tile_gt_n", 200, 64, 300, 4096, 0.0),
     ("one_row_tiles", 5, 64, 130, 1, 0.2),
     ("small_v", 300, 128, 7, 128, 0.1),
+    # few dHidden output blocks and a long vocabulary: the contraction over V is cut into ranges
+    ("split_v_direct", 600, 256, 16640, 256, 0.1),
+    ("split_v_guarded", 520, 136, 16392, 300, 0.1),
 ]
 
 
