@@ -16,6 +16,11 @@
 //               every extent block-aligned (no bounds checks in the DMA path).
 //   StagedCore  8 wavefronts, 64 x 128 per wavefront, operands staged through registers with
 //               zero fill outside the matrices: the fallback for ragged shapes.
+//   KMajorCore  DirectCore for operands stored with k as the slow index,
+//                   D[r][c] = sum_k X[k][r] * Y[k][c],
+//               which is how the weight-gradient products meet their operands (k = token row):
+//               the DMA lands k-rows in LDS as they are and the MFMA operands are formed by the
+//               transposing LDS read (ds_read_b64_tr_b16), so no transposed copy is ever written.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -28,6 +33,8 @@ typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef short i16x4_t __attribute__((ext_vector_type(4)));
+typedef short i16x8_t __attribute__((ext_vector_type(8)));
 
 constexpr int kBlockR = 256;          // rows of X per block (MFMA lane dimension)
 constexpr int kBlockC = 256;          // rows of Y per block (MFMA register dimension)
@@ -128,6 +135,27 @@ __device__ __forceinline__ const uint16_t* warm_row(int PR, int PC, const uint16
     if (l > total - 1) l = total - 1;
     if (l < nx) return X + (int64_t)(r0 + (tc % PC) * nx + l) * ldx;
     return Y + (int64_t)(c0 + (tr % PR) * ny + (l - nx)) * ldy;
+}
+
+// The same for k-major operands X[k][ldx], Y[k][ldy]: the 64 k-rows x 512 bytes of a k-step's tile
+// are 256 lines, line L = (k-row L / 4, 128-byte piece L % 4).  `step` = elements between the
+// lane's line in one k-step and the next.
+__device__ __forceinline__ const uint16_t* warm_line_kmajor(int PR, int PC, const uint16_t* X,
+                                                            int64_t ldx, int r0, int tr,
+                                                            const uint16_t* Y, int64_t ldy, int c0,
+                                                            int tc, int64_t& step) {
+    const int nx = kBlockR / PC, ny = kBlockC / PR, total = nx + ny, per = (total + 3) / 4;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int l = w * per + (lane < per ? lane : per - 1);
+    if (l > total - 1) l = total - 1;
+    if (l < nx) {
+        const int L = (tc % PC) * nx + l;
+        step = ldx * kBlockK;
+        return X + (int64_t)(L >> 2) * ldx + r0 + (L & 3) * 64;
+    }
+    const int L = (tr % PR) * ny + (l - nx);
+    step = ldy * kBlockK;
+    return Y + (int64_t)(L >> 2) * ldy + c0 + (L & 3) * 64;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -253,7 +281,8 @@ struct StagedCore {
 // ---------------------------------------------------------------------------------------------
 // DirectCore: 4 wavefronts, global -> LDS DMA, aligned shapes only
 // ---------------------------------------------------------------------------------------------
-struct DirectCore {
+template <bool KM>
+struct DirectCoreT {
     static constexpr int kThreads = 256;
     static constexpr int kMT = 4;
     static constexpr int kNT = 4;
@@ -281,14 +310,21 @@ struct DirectCore {
     // kc ^ ((row >> 1) & 7): sixteen consecutive rows at one kc then cover all 64 banks once.
     static __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
+    // k-major tiles: an LDS row is one k-row of 512 bytes = 8 granules of 64 bytes (32 r or c
+    // each); granule g of k-row k lives at granule slot g ^ kswz(k).  One transposing read covers
+    // k-rows {R .. R+3, R+8 .. R+11} (R % 4 == 0) at one granule: 8 different slots.
+    static __device__ __forceinline__ int kswz(int k) { return (k & 3) | (((k >> 3) & 1) << 2); }
+
     // Requires r0 + 256 <= rows of X, c0 + 256 <= rows of Y, K % 64 == 0, K >= 64, 16-byte
-    // aligned rows.  GUARD must be false (rows_x / rows_y are unused).
+    // aligned rows.  GUARD must be false (rows_x / rows_y are unused).  KM: X is [K][ldx] and the
+    // block takes its columns r0 .. r0 + 255, Y is [K][ldy] with columns c0 .. c0 + 255.
+    // warm_stride = elements between the lane's warm-up line of one k-step and the next.
     template <bool GUARD>
     static __device__ __forceinline__ void gemm(const uint16_t* __restrict__ X, int64_t ldx,
                                                 int /*rows_x*/, const uint16_t* __restrict__ Y,
                                                 int64_t ldy, int /*rows_y*/, int K, int r0, int c0,
                                                 unsigned char* smem, f32x16_t (&acc)[kMT][kNT],
-                                                const uint16_t* warm) {
+                                                const uint16_t* warm, int64_t warm_stride = kBlockK) {
         static_assert(!GUARD, "DirectCore has no bounds checks");
         typedef const __attribute__((address_space(1))) void* gptr_t;
         typedef __attribute__((address_space(3))) void* lptr_t;
@@ -300,40 +336,71 @@ struct DirectCore {
         // One DMA instruction moves 8 rows x 128 bytes: lane -> (row = lane / 8, LDS chunk slot =
         // lane % 8); the lane fetches the global chunk that belongs in its slot.  Wave w owns rows
         // [64 w, 64 w + 64) of both operand tiles: 8 instructions per operand per k-step.
+        // KM: one DMA instruction moves 2 k-rows x 512 bytes: lane -> (k-row = lane / 32, chunk
+        // slot = lane % 32); wave w owns k-rows [16 w, 16 w + 16) of both tiles.
         const int lr = lane >> 3, pc = lane & 7;
         const uint16_t* xg[8];
         const uint16_t* yg[8];
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-            const int row = (w * 8 + q) * 8 + lr;
-            const int kc = pc ^ swz(row);
-            xg[q] = X + (int64_t)(r0 + row) * ldx + kc * 8;
-            yg[q] = Y + (int64_t)(c0 + row) * ldy + kc * 8;
+            if (KM) {
+                const int krow = w * 16 + q * 2 + (lane >> 5);
+                const int ch = (lane & 31) ^ (kswz(krow) << 2);
+                xg[q] = X + (int64_t)krow * ldx + r0 + ch * 8;
+                yg[q] = Y + (int64_t)krow * ldy + c0 + ch * 8;
+            } else {
+                const int row = (w * 8 + q) * 8 + lr;
+                const int kc = pc ^ swz(row);
+                xg[q] = X + (int64_t)(r0 + row) * ldx + kc * 8;
+                yg[q] = Y + (int64_t)(c0 + row) * ldy + kc * 8;
+            }
         }
+        // elements from one k-step's tile to the next
+        const int64_t xstep = KM ? ldx * kBlockK : kBlockK, ystep = KM ? ldy * kBlockK : kBlockK;
         auto issue_loads = [&](int stage, int kt) {
             unsigned char* xs = smem + stage * kTileBytes + w * 8192;
             unsigned char* ys = smem + 2 * kTileBytes + stage * kTileBytes + w * 8192;
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                __builtin_amdgcn_global_load_lds((gptr_t)(xg[q] + kt * kBlockK),
+                __builtin_amdgcn_global_load_lds((gptr_t)(xg[q] + kt * xstep),
                                                  (lptr_t)(xs + q * 1024), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds((gptr_t)(yg[q] + kt * kBlockK),
+                __builtin_amdgcn_global_load_lds((gptr_t)(yg[q] + kt * ystep),
                                                  (lptr_t)(ys + q * 1024), 16, 0, 0);
             }
         };
 
-        int rofs[4];
+        // Operand reads.  Row-major tiles: one 16-byte read per operand.  KM: two transposing
+        // reads; in each, the 16 lanes of a quarter wave address 4 k-rows x 4 pieces of 8 bytes and
+        // lane i of the quarter receives the 4 k of column i (MFMA lane l: column l % 32,
+        // k = 8 (l / 32) .. + 7 of the slice: quarter = (l / 32, (l / 16) % 2)).
+        int rofs[4], xofs[4], yofs[4];
+        const int sl = lane & 15, b1 = (lane >> 4) & 1;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) rofs[s] = ((2 * s + half) ^ swz(l31)) * 16;
+        for (int s = 0; s < 4; ++s) {
+            rofs[s] = ((2 * s + half) ^ swz(l31)) * 16;
+            const int f = (sl >> 2) | (half << 2);              // kswz of the lane's k-rows
+            const int lane_ofs = (8 * half + (sl >> 2)) * 512 + b1 * 32 + (sl & 3) * 8;
+            xofs[s] = lane_ofs + (((wr * 4 + s) ^ f) * 64);      // s = accumulator tile here
+            yofs[s] = 2 * kTileBytes + lane_ofs + (((wc * 4 + s) ^ f) * 64);
+        }
         const int xbase = (wr * 128 + l31) * 128;
         const int ybase = 2 * kTileBytes + (wc * kGroupC + l31) * 128;
 
         // MFMA operands of the four k-slices of a step: fy[s][t], fx[s][t] for slice s.
         bf16x8_t fy[4][4], fx[4][4];
+        auto read_km = [&](const unsigned char* at) {
+            typedef __attribute__((address_space(3))) i16x4_t* tptr_t;
+            const i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tptr_t)(lptr_t)const_cast<unsigned char*>(at));
+            const i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tptr_t)(lptr_t)const_cast<unsigned char*>(at + 2048));
+            return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        };
         // item 0..3: the Y operand of accumulator row t = item, 4..7: the X operand of column t
         auto read_item = [&](int stage, int s, int item) {
             const unsigned char* base = smem + stage * kTileBytes;
-            if (item < 4)
+            if (KM) {
+                if (item < 4) fy[s][item] = read_km(base + yofs[item] + s * 8192);
+                else fx[s][item - 4] = read_km(base + xofs[item - 4] + s * 8192);
+            } else if (item < 4)
                 fy[s][item] = *reinterpret_cast<const bf16x8_t*>(base + ybase + item * 4096 + rofs[s]);
             else
                 fx[s][item - 4] =
@@ -355,7 +422,7 @@ struct DirectCore {
         unsigned char* const dump = smem + kStageBytes + w * 256;
         auto warm_step = [&](int kt) {
             const int kk = kt < KT ? kt : KT - 1;
-            __builtin_amdgcn_global_load_lds((gptr_t)(warm + kk * kBlockK), (lptr_t)dump, 4, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr_t)(warm + kk * warm_stride), (lptr_t)dump, 4, 0, 0);
         };
         // Joins the wavefronts once this wavefront's DMA of the next stage has landed.  The warm-up
         // load issued after that DMA may still be in flight (loads complete in order).
@@ -410,7 +477,7 @@ struct DirectCore {
             for (int i = 0; i < 8; ++i) {
                 mfma_pair(2, i);
                 if (LOADS)
-                    __builtin_amdgcn_global_load_lds((gptr_t)(xg[i] + (kt + 2) * kBlockK),
+                    __builtin_amdgcn_global_load_lds((gptr_t)(xg[i] + (kt + 2) * xstep),
                                                      (lptr_t)(xs + i * 1024), 16, 0, 0);
                 if (NEXT) read_item(cur ^ 1, 0, i);
                 __builtin_amdgcn_sched_barrier(0);
@@ -419,7 +486,7 @@ struct DirectCore {
             for (int i = 0; i < 8; ++i) {
                 mfma_pair(3, i);
                 if (LOADS)
-                    __builtin_amdgcn_global_load_lds((gptr_t)(yg[i] + (kt + 2) * kBlockK),
+                    __builtin_amdgcn_global_load_lds((gptr_t)(yg[i] + (kt + 2) * ystep),
                                                      (lptr_t)(ys + i * 1024), 16, 0, 0);
                 if (NEXT) read_item(cur ^ 1, 1, i);
                 __builtin_amdgcn_sched_barrier(0);
@@ -436,6 +503,8 @@ struct DirectCore {
         kstep(kt, std::false_type{}, std::false_type{}, false);
     }
 };
+typedef DirectCoreT<false> DirectCore;
+typedef DirectCoreT<true> KMajorCore;
 
 // ---------------------------------------------------------------------------------------------
 // Epilogues shared by the kernels built on the two cores

@@ -74,7 +74,8 @@ constexpr int kScanThreads = 1024;   // rows per block of the compaction kernels
 struct Layout {
     int64_t Tp, Vp, ng;    // padded tile rows, padded vocabulary, 128-column groups
     int g;                 // tiles per dW group
-    int64_t Kg;            // row stride of dzt / ht: g * Tp
+    int64_t Kg;            // dense rows a group can hold: g * Tp
+    bool km;               // the dW product reads its operands k-major: no transposed copies
     int splits, ksteps;    // dHidden: ranges of the contraction over V, k-steps per range
     size_t header, tinfo, loss_rows, lse, idx, block_cnt, block_ofs, zlabel, yc, pm, ps, sc, hc,
         stash, dzt, wt, ht, part, acc, total;
@@ -125,11 +126,15 @@ static Layout make_layout(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_
     L.pm = take((size_t)L.ng * L.Tp * 4);
     L.ps = take((size_t)L.ng * L.Tp * 4);
     L.sc = take((size_t)L.ng * L.Tp * 4);
-    L.hc = take((size_t)L.Tp * H * 2);
-    L.stash = take((size_t)L.Tp * L.Vp * 2);
-    L.dzt = take((size_t)L.Vp * L.Kg * 2);
+    // km: hc and stash hold the dense rows of the whole group (each tile at its k offset) and are
+    // the operands of the dW product as they are; otherwise they hold one tile and the group's
+    // rows are collected transposed in ht and dzt.
+    L.km = (H % kBlockR) == 0;
+    L.hc = take((size_t)(L.km ? L.Kg : L.Tp) * H * 2);
+    L.stash = take((size_t)(L.km ? L.Kg : L.Tp) * L.Vp * 2);
+    L.dzt = take(L.km ? 0 : (size_t)L.Vp * L.Kg * 2);
     L.wt = take((size_t)H * L.Vp * 2);
-    L.ht = take((size_t)H * L.Kg * 2);
+    L.ht = take(L.km ? 0 : (size_t)H * L.Kg * 2);
     dhidden_splits(L.Tp, H, L.Vp, L.splits, L.ksteps);
     L.part = take(L.splits > 1 ? (size_t)L.splits * L.Tp * H * 4 : 0);
     const bool acc_in_dw = (flags & ALST_FLAG_DW_FP32) && !(flags & ALST_FLAG_DW_ACCUMULATE);
@@ -268,14 +273,16 @@ __global__ void tile_info_kernel(const Header* __restrict__ h, int64_t t, int64_
 }
 
 // Block b: dense row b of the tile.  Copies the hidden row of token idx_t[b] into the dense
-// matrix Hc and its label into yc; rows Tc <= b < Trc of Hc are zero padding.
+// matrix Hc and its label into yc; rows Tc <= b < Trc of Hc are zero padding.  grouped: Hc holds
+// the whole dW group and the tile's rows start at its k offset.
 __global__ __launch_bounds__(256) void gather_rows_kernel(
     const uint16_t* __restrict__ hidden, const int32_t* __restrict__ labels, int H,
     const int32_t* __restrict__ idx_t, const TileInfo* __restrict__ info,
-    uint16_t* __restrict__ Hc, int32_t* __restrict__ yc) {
+    uint16_t* __restrict__ Hc, int32_t* __restrict__ yc, int grouped) {
     const int b = blockIdx.x;
     const int chunks = H / 8;
     if (b >= info->Trc) return;
+    if (grouped) Hc += (int64_t)info->kofs * H;
     u32x4_t* dst = reinterpret_cast<u32x4_t*>(Hc + (int64_t)b * H);
     if (b < info->Tc) {
         const int64_t row = idx_t[b];
@@ -338,7 +345,9 @@ __global__ __launch_bounds__(kCombineRows * kCombineLanes) void row_combine_kern
 // block of it: lanes run along v for the row-major reads and in-place writes (8 lanes = one
 // 128-byte line) and along i for the transposed writes, and the 8 x 8 transpose is done in
 // registers with byte permutes, so every global access is a full line and no LDS is used.
-template <bool FUSED>
+// TRANSPOSED = false: in place only; the stash holds the whole dW group, the tile's rows start
+// at its k offset, and the dW product reads it as it is.
+template <bool FUSED, bool TRANSPOSED>
 __global__ __launch_bounds__(256) void dz_finalize_kernel(uint16_t* __restrict__ stash,
                                                           uint16_t* __restrict__ dzt,
                                                           const float* __restrict__ sc,
@@ -354,7 +363,8 @@ __global__ __launch_bounds__(256) void dz_finalize_kernel(uint16_t* __restrict__
     const int i0 = by * 64 + (lane >> 3) * 8;                         // first of this lane's 8 rows
     if (by * 64 >= info->Trc) return;
     const int T_cur = info->Tc;
-    dzt += info->kofs;                                   // dzt is [Vp, Kg]
+    if (TRANSPOSED) dzt += info->kofs;                   // dzt is [Vp, Kg]
+    else stash += (int64_t)info->kofs * Vp;
     uint32_t in[8][4];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -377,6 +387,7 @@ __global__ __launch_bounds__(256) void dz_finalize_kernel(uint16_t* __restrict__
 #pragma unroll
         for (int x = 0; x < 4; ++x) in[j][x] = du[x];
     }
+    if (!TRANSPOSED) return;
     // out[x] = column v0 + x for rows i0 .. i0 + 7: halfword x of each input row
 #pragma unroll
     for (int x = 0; x < 8; ++x) {
@@ -471,6 +482,7 @@ struct LogitsParams {
     float* zlabel;              // [Tp]
     uint16_t* stash;            // [Tp, Vp]     MODE_FUSED / MODE_BWD
     int Tp, H, V, Vp;           // Tp = row stride of the per-tile arrays
+    int grouped;                // hidden_t and stash hold the dW group: the tile starts at its k offset
 };
 
 // r = token row of the tile (MFMA lane dimension), c = vocabulary id (register dimension).
@@ -492,9 +504,11 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
+    const int kofs = p.grouped ? p.info->kofs : 0;
+    const uint16_t* const hidden_t = p.hidden_t + (int64_t)kofs * p.H;
     const uint16_t* warm = Core::kCanGuard ? nullptr
-                                           : warm_row<4, 8>(p.hidden_t, p.H, r0, tr, p.W, p.H, c0, tc);
-    Core::template gemm<GUARD>(p.hidden_t, p.H, Trc, p.W, p.H, p.V, p.H, r0, c0, smem, acc, warm);
+                                           : warm_row<4, 8>(hidden_t, p.H, r0, tr, p.W, p.H, c0, tc);
+    Core::template gemm<GUARD>(hidden_t, p.H, Trc, p.W, p.H, p.V, p.H, r0, c0, smem, acc, warm);
 
     const typename Core::Lane lp;
     constexpr float kLog2e = 1.4426950408889634f;
@@ -566,7 +580,7 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
             }
         if (MODE != MODE_FWD) {
             const int lrow = lp.lane >> 4, lcol = lp.lane & 15;        // 4 rows x 16 chunks of 16 B
-            uint16_t* const out = p.stash + (int64_t)(r0 + lp.rbase(nt)) * p.Vp + c0 +
+            uint16_t* const out = p.stash + (int64_t)(kofs + r0 + lp.rbase(nt)) * p.Vp + c0 +
                                   lp.wc * kGroupC + lcol * 8;
 #pragma unroll
             for (int it = 0; it < 8; ++it) {
@@ -598,6 +612,7 @@ struct DHiddenParams {
     int splits;              // the contraction over V is cut into this many ranges
     int ksteps;              // k-steps of 64 per range (the last range may be shorter)
     int PR, PC;              // patch shape of the block -> tile mapping
+    int grouped;             // dz holds the dW group: the tile starts at its k offset
 };
 
 // r = token row (lane dimension), c = hidden index (register dimension), k = vocabulary.
@@ -631,10 +646,11 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
+    const uint16_t* const dz = p.dz + (p.grouped ? (int64_t)p.info->kofs * p.Vp : 0) + k0;
     const uint16_t* warm = Core::kCanGuard ? nullptr
-                                           : warm_row(p.PR, p.PC, p.dz + k0, p.Vp, r0, tr, p.wt + k0,
+                                           : warm_row(p.PR, p.PC, dz, p.Vp, r0, tr, p.wt + k0,
                                                       p.Vp, c0, tc);
-    Core::template gemm<GUARD>(p.dz + k0, p.Vp, Trc, p.wt + k0, p.Vp, p.H, klen, r0, c0, smem, acc, warm);
+    Core::template gemm<GUARD>(dz, p.Vp, Trc, p.wt + k0, p.Vp, p.H, klen, r0, c0, smem, acc, warm);
 
     const typename Core::Lane lp;
     if (p.splits > 1) {
@@ -699,8 +715,8 @@ __global__ __launch_bounds__(256) void dhidden_reduce_kernel(const float* __rest
 }
 
 struct DWParams {
-    const uint16_t* ht;      // [H, Kg]      dense rows of the group's tiles, transposed
-    const uint16_t* dzt;     // [Vp, Kg]
+    const uint16_t* ht;      // [H, Kg]      dense rows of the group's tiles, transposed;
+    const uint16_t* dzt;     // [Vp, Kg]     KMajorCore: as they are, [Kg, H] and [Kg, Vp]
     float* acc;              // [V, H]
     const TileInfo* info;    // of the group's last tile: k extent = kofs + Tkc
     int64_t Kg;
@@ -731,9 +747,15 @@ __global__ __launch_bounds__(Core::kThreads) void dw_kernel(const DWParams p) {
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
     if (Tkc > 0) {
-        const uint16_t* warm = Core::kCanGuard ? nullptr
-                                               : warm_row<4, 8>(p.ht, p.Kg, r0, tr, p.dzt, p.Kg, c0, tc);
-        Core::template gemm<GUARD>(p.ht, p.Kg, p.H, p.dzt, p.Kg, p.Vp, Tkc, r0, c0, smem, acc, warm);
+        if constexpr (std::is_same<Core, KMajorCore>::value) {
+            int64_t step;
+            const uint16_t* warm = warm_line_kmajor(4, 8, p.ht, p.H, r0, tr, p.dzt, p.Vp, c0, tc, step);
+            Core::template gemm<GUARD>(p.ht, p.H, p.H, p.dzt, p.Vp, p.Vp, Tkc, r0, c0, smem, acc, warm, step);
+        } else {
+            const uint16_t* warm = Core::kCanGuard ? nullptr
+                                                   : warm_row<4, 8>(p.ht, p.Kg, r0, tr, p.dzt, p.Kg, c0, tc);
+            Core::template gemm<GUARD>(p.ht, p.Kg, p.H, p.dzt, p.Kg, p.Vp, Tkc, r0, c0, smem, acc, warm);
+        }
     }
 
     accumulate_block_f32<Core, GUARD>(acc, p.acc, p.H, r0, c0, p.H, p.V, p.first != 0);
@@ -757,7 +779,7 @@ static int prepare_kernels() {
     acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_BWD>));
     acc(allow_big_lds(dhidden_kernel<DirectCore, false>));
     acc(allow_big_lds(dhidden_kernel<StagedCore, true>));
-    acc(allow_big_lds(dw_kernel<DirectCore, false>));
+    acc(allow_big_lds(dw_kernel<KMajorCore, false>));
     acc(allow_big_lds(dw_kernel<StagedCore, true>));
     states[dev] = rc + 1;
     return rc;
@@ -898,7 +920,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             hipLaunchKernelGGL(tile_info_kernel, dim3(1), dim3(64), 0, s, hdr, t, T, info,
                                slot ? info - 1 : nullptr);
             hipLaunchKernelGGL(gather_rows_kernel, dim3(Tr), dim3(256), 0, s, P.hidden, P.labels, H,
-                               idx_t, info, hc, yc);
+                               idx_t, info, hc, yc, L.km ? 1 : 0);
             ALST_HIP(hipGetLastError());
         }
 
@@ -910,7 +932,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
         lp.info = info;
         lp.lse_t = do_fwd ? nullptr : P.lse_in;
         lp.pm = pm; lp.ps = ps; lp.zlabel = zlabel; lp.stash = stash;
-        lp.Tp = Tp; lp.H = H; lp.V = V; lp.Vp = Vp;
+        lp.Tp = Tp; lp.H = H; lp.V = V; lp.Vp = Vp; lp.grouped = L.km ? 1 : 0;
         {
             ProfScope ps_(PROF_LOGITS, s);
             if (do_fwd && do_bwd) rc = launch_logits<MODE_FUSED>(lp, Tr, guard_logits, s);
@@ -931,15 +953,25 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
                 const int64_t nblk = (int64_t)(Vp / 256) * (Tr / 64);
                 if (nblk > 0x7fffffff) return ALST_ERR_SHAPE;
                 dim3 grid((unsigned)nblk);
-                if (do_fwd)
-                    hipLaunchKernelGGL(dz_finalize_kernel<true>, grid, dim3(256), 0, s, stash, dzt,
-                                       sc, yc, info, Tp, Vp, L.Kg);
-                else
-                    hipLaunchKernelGGL(dz_finalize_kernel<false>, grid, dim3(256), 0, s, stash, dzt,
-                                       sc, yc, info, Tp, Vp, L.Kg);
-                ALST_HIP(hipGetLastError());
-                rc = launch_transpose(hc, H, Tr, H, ht, L.Kg, Tr, info, s);
-                if (rc != ALST_OK) return rc;
+                if (L.km) {
+                    if (do_fwd)
+                        hipLaunchKernelGGL((dz_finalize_kernel<true, false>), grid, dim3(256), 0, s,
+                                           stash, dzt, sc, yc, info, Tp, Vp, L.Kg);
+                    else
+                        hipLaunchKernelGGL((dz_finalize_kernel<false, false>), grid, dim3(256), 0, s,
+                                           stash, dzt, sc, yc, info, Tp, Vp, L.Kg);
+                    ALST_HIP(hipGetLastError());
+                } else {
+                    if (do_fwd)
+                        hipLaunchKernelGGL((dz_finalize_kernel<true, true>), grid, dim3(256), 0, s,
+                                           stash, dzt, sc, yc, info, Tp, Vp, L.Kg);
+                    else
+                        hipLaunchKernelGGL((dz_finalize_kernel<false, true>), grid, dim3(256), 0, s,
+                                           stash, dzt, sc, yc, info, Tp, Vp, L.Kg);
+                    ALST_HIP(hipGetLastError());
+                    rc = launch_transpose(hc, H, Tr, H, ht, L.Kg, Tr, info, s);
+                    if (rc != ALST_OK) return rc;
+                }
             }
         }
         if (!do_bwd) continue;
@@ -952,7 +984,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             dp.Tp = Tp; dp.H = H; dp.Vp = Vp;
             dp.splits = L.splits; dp.ksteps = L.ksteps;
             const PatchGrid pg = choose_patches(Tr / kBlockR, (H + kBlockC - 1) / kBlockC);
-            dp.PR = pg.PR; dp.PC = pg.PC;
+            dp.PR = pg.PR; dp.PC = pg.PC; dp.grouped = L.km ? 1 : 0;
             const int grid = grid_for_patches((int64_t)pg.patches() * L.splits);
             ProfScope ps_(PROF_DHIDDEN, s);
             if (guard_h)
@@ -968,7 +1000,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
         }
         if (slot == L.g - 1 || t == ntiles - 1) {           // the group is complete
             DWParams wp;
-            wp.ht = ht; wp.dzt = dzt; wp.acc = acc; wp.info = info;
+            wp.ht = L.km ? hc : ht; wp.dzt = L.km ? stash : dzt; wp.acc = acc; wp.info = info;
             wp.Kg = L.Kg; wp.H = H; wp.V = V; wp.Vp = Vp; wp.first = (t < L.g);
             const int grid = grid_for_tiles<4, 8>((H + kBlockR - 1) / kBlockR, Vp / kBlockC);
             ProfScope ps_(PROF_DW, s);
@@ -976,8 +1008,8 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
                 hipLaunchKernelGGL((dw_kernel<StagedCore, true>), dim3(grid),
                                    dim3(StagedCore::kThreads), kLdsBytes, s, wp);
             else
-                hipLaunchKernelGGL((dw_kernel<DirectCore, false>), dim3(grid),
-                                   dim3(DirectCore::kThreads), kLdsBytes, s, wp);
+                hipLaunchKernelGGL((dw_kernel<KMajorCore, false>), dim3(grid),
+                                   dim3(KMajorCore::kThreads), kLdsBytes, s, wp);
             ALST_HIP(hipGetLastError());
         }
     }
