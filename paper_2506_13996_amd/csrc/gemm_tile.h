@@ -161,7 +161,33 @@ __device__ __forceinline__ const uint16_t* warm_line_kmajor(int PR, int PC, cons
 // ---------------------------------------------------------------------------------------------
 // StagedCore: 8 wavefronts, register staging, optional bounds checks
 // ---------------------------------------------------------------------------------------------
-struct StagedCore {
+// k-major LDS tiles (both cores): an LDS row is one k-row of 512 bytes = 8 granules of 64 bytes
+// (32 r or c each); granule g of k-row k lives at granule slot g ^ kswz(k).  One transposing read
+// covers k-rows {R .. R+3, R+8 .. R+11} (R % 4 == 0) at one granule: 8 different slots.
+__device__ __forceinline__ int kswz(int k) { return (k & 3) | (((k >> 3) & 1) << 2); }
+
+// MFMA operand (8 k of one column per lane) from a k-major tile: two transposing reads.  In each,
+// the 16 lanes of a quarter wave address 4 k-rows x 4 pieces of 8 bytes and lane i of the quarter
+// receives the 4 k of column i.  `at`: the lane's address for the first 4 k-rows; the next 4
+// k-rows are 2048 bytes on.
+__device__ __forceinline__ bf16x8_t read_kmajor(const unsigned char* at) {
+    typedef __attribute__((address_space(3))) i16x4_t* tptr_t;
+    typedef __attribute__((address_space(3))) void* lptr_t;
+    unsigned char* const p = const_cast<unsigned char*>(at);
+    const i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tptr_t)(lptr_t)p);
+    const i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tptr_t)(lptr_t)(p + 2048));
+    return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+// The lane's byte offset inside a k-major tile for granule `gran` (MFMA lane l: column l % 32 of
+// the granule, k = 8 (l / 32) .. + 7 of a 16-row slice; add 8192 per slice).
+__device__ __forceinline__ int kmajor_lane_offset(int lane, int gran) {
+    const int sl = lane & 15, b1 = (lane >> 4) & 1, half = lane >> 5;
+    const int f = (sl >> 2) | (half << 2);                   // kswz of the lane's k-rows
+    return (8 * half + (sl >> 2)) * 512 + ((gran ^ f) * 64) + b1 * 32 + (sl & 3) * 8;
+}
+
+template <bool KM>
+struct StagedCoreT {
     static constexpr int kThreads = 512;
     static constexpr int kMT = 4;     // 32-wide c tiles per wavefront
     static constexpr int kNT = 2;     // 32-wide r tiles per wavefront
@@ -192,33 +218,51 @@ struct StagedCore {
     // acc[mt][nt] += X-block(r0) * Y-block(c0)^T over all of K.
     // GUARD = false requires r0 + 256 <= rows_x, c0 + 256 <= rows_y and K % 64 == 0.
     // GUARD = true zero-fills rows beyond rows_x / rows_y and k beyond K (K % 8 == 0 required).
+    // KM: X is [K][ldx] and the block takes its columns r0 .. r0 + 255 (rows_x = number of
+    // columns, a multiple of 8), Y likewise; any K.
     template <bool GUARD>
     static __device__ __forceinline__ void gemm(const uint16_t* __restrict__ X, int64_t ldx,
                                                 int rows_x, const uint16_t* __restrict__ Y,
                                                 int64_t ldy, int rows_y, int K, int r0, int c0,
                                                 unsigned char* smem, f32x16_t (&acc)[kMT][kNT],
-                                                const uint16_t* /*warm*/ = nullptr) {
+                                                const uint16_t* /*warm*/ = nullptr,
+                                                int64_t /*warm_stride*/ = 0) {
         const int tid = threadIdx.x;
         const Lane lp;
-        const int lrow = tid >> 3;      // 0..63, row inside a 64-row slab of the operand tile
-        const int kc = tid & 7;         // 16-byte chunk along k
+        // row-major: thread -> (row inside a 64-row slab of the operand tile, 16-byte chunk along
+        // k), slab j;  KM: thread -> (k-row tid / 32 + 16 j, 16-byte chunk of 8 columns tid % 32)
+        const int lrow = KM ? (tid >> 5) : (tid >> 3);
+        const int kc = KM ? (tid & 31) : (tid & 7);
 
         const uint16_t* xp[4];
         const uint16_t* yp[4];
         bool xv[4], yv[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int gx = r0 + lrow + 64 * j, gy = c0 + lrow + 64 * j;
-            xv[j] = !GUARD || gx < rows_x;
-            yv[j] = !GUARD || gy < rows_y;
-            xp[j] = X + (int64_t)(xv[j] ? gx : 0) * ldx + kc * 8;
-            yp[j] = Y + (int64_t)(yv[j] ? gy : 0) * ldy + kc * 8;
+            if (KM) {
+                xv[j] = !GUARD || r0 + kc * 8 < rows_x;
+                yv[j] = !GUARD || c0 + kc * 8 < rows_y;
+                xp[j] = X + (int64_t)(lrow + 16 * j) * ldx + (xv[j] ? r0 + kc * 8 : 0);
+                yp[j] = Y + (int64_t)(lrow + 16 * j) * ldy + (yv[j] ? c0 + kc * 8 : 0);
+            } else {
+                const int gx = r0 + lrow + 64 * j, gy = c0 + lrow + 64 * j;
+                xv[j] = !GUARD || gx < rows_x;
+                yv[j] = !GUARD || gy < rows_y;
+                xp[j] = X + (int64_t)(xv[j] ? gx : 0) * ldx + kc * 8;
+                yp[j] = Y + (int64_t)(yv[j] ? gy : 0) * ldy + kc * 8;
+            }
         }
-        // 16-byte chunk kc of row `row` lives at chunk slot kc ^ (row & 7) of its 128-byte row
-        const int wofs = (lrow * 8 + (kc ^ (lrow & 7))) * 16;          // + j * 64 rows * 128 B
-        int rofs[4];
+        // row-major: 16-byte chunk kc of row `row` lives at chunk slot kc ^ (row & 7) of its
+        // 128-byte row (+ j * 64 rows * 128 B);  KM: see kswz (+ j * 16 k-rows * 512 B)
+        const int wofs = KM ? lrow * 512 + ((kc ^ (kswz(lrow) << 2)) * 16)
+                            : (lrow * 8 + (kc ^ (lrow & 7))) * 16;
+        int rofs[4], xofs[kNT], yofs[kMT];
 #pragma unroll
         for (int s = 0; s < 4; ++s) rofs[s] = ((2 * s + lp.half) ^ (lp.lane & 7)) * 16;
+#pragma unroll
+        for (int nt = 0; nt < kNT; ++nt) xofs[nt] = kmajor_lane_offset(lp.lane, lp.wr * kNT + nt);
+#pragma unroll
+        for (int mt = 0; mt < kMT; ++mt) yofs[mt] = kmajor_lane_offset(lp.lane, lp.wc * kMT + mt);
         const int xbase = (lp.wr * 64 + lp.l31) * 128;
         const int ybase = (lp.wc * kGroupC + lp.l31) * 128;
 
@@ -230,6 +274,15 @@ struct StagedCore {
 
         auto load_global = [&](int kt) {
             const int koff = kt * kBlockK;
+            if (KM) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bool kok = !GUARD || (koff + lrow + 16 * j < K);
+                    xg[j] = (xv[j] && kok) ? *reinterpret_cast<const u32x4_t*>(xp[j] + (int64_t)koff * ldx) : zero4;
+                    yg[j] = (yv[j] && kok) ? *reinterpret_cast<const u32x4_t*>(yp[j] + (int64_t)koff * ldy) : zero4;
+                }
+                return;
+            }
             const bool kok = !GUARD || (koff + kc * 8 + 8 <= K);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -261,10 +314,12 @@ struct StagedCore {
                 bf16x8_t yf[kMT], xf[kNT];
 #pragma unroll
                 for (int mt = 0; mt < kMT; ++mt)
-                    yf[mt] = *reinterpret_cast<const bf16x8_t*>(ys + mt * 4096 + rofs[s]);
+                    yf[mt] = KM ? read_kmajor(Ys + cur * kTileBytes + yofs[mt] + s * 8192)
+                                : *reinterpret_cast<const bf16x8_t*>(ys + mt * 4096 + rofs[s]);
 #pragma unroll
                 for (int nt = 0; nt < kNT; ++nt)
-                    xf[nt] = *reinterpret_cast<const bf16x8_t*>(xs + nt * 4096 + rofs[s]);
+                    xf[nt] = KM ? read_kmajor(Xs + cur * kTileBytes + xofs[nt] + s * 8192)
+                                : *reinterpret_cast<const bf16x8_t*>(xs + nt * 4096 + rofs[s]);
 #pragma unroll
                 for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
@@ -277,6 +332,8 @@ struct StagedCore {
         }
     }
 };
+typedef StagedCoreT<false> StagedCore;
+typedef StagedCoreT<true> StagedKMajorCore;
 
 // ---------------------------------------------------------------------------------------------
 // DirectCore: 4 wavefronts, global -> LDS DMA, aligned shapes only
@@ -309,11 +366,6 @@ struct DirectCoreT {
     // LDS row = 128 bytes = 8 chunks of 16 bytes; chunk kc of row `row` lives at slot
     // kc ^ ((row >> 1) & 7): sixteen consecutive rows at one kc then cover all 64 banks once.
     static __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
-
-    // k-major tiles: an LDS row is one k-row of 512 bytes = 8 granules of 64 bytes (32 r or c
-    // each); granule g of k-row k lives at granule slot g ^ kswz(k).  One transposing read covers
-    // k-rows {R .. R+3, R+8 .. R+11} (R % 4 == 0) at one granule: 8 different slots.
-    static __device__ __forceinline__ int kswz(int k) { return (k & 3) | (((k >> 3) & 1) << 2); }
 
     // Requires r0 + 256 <= rows of X, c0 + 256 <= rows of Y, K % 64 == 0, K >= 64, 16-byte
     // aligned rows.  GUARD must be false (rows_x / rows_y are unused).  KM: X is [K][ldx] and the
@@ -369,37 +421,25 @@ struct DirectCoreT {
             }
         };
 
-        // Operand reads.  Row-major tiles: one 16-byte read per operand.  KM: two transposing
-        // reads; in each, the 16 lanes of a quarter wave address 4 k-rows x 4 pieces of 8 bytes and
-        // lane i of the quarter receives the 4 k of column i (MFMA lane l: column l % 32,
-        // k = 8 (l / 32) .. + 7 of the slice: quarter = (l / 32, (l / 16) % 2)).
+        // Operand reads.  Row-major tiles: one 16-byte read per operand.  KM: read_kmajor.
         int rofs[4], xofs[4], yofs[4];
-        const int sl = lane & 15, b1 = (lane >> 4) & 1;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             rofs[s] = ((2 * s + half) ^ swz(l31)) * 16;
-            const int f = (sl >> 2) | (half << 2);              // kswz of the lane's k-rows
-            const int lane_ofs = (8 * half + (sl >> 2)) * 512 + b1 * 32 + (sl & 3) * 8;
-            xofs[s] = lane_ofs + (((wr * 4 + s) ^ f) * 64);      // s = accumulator tile here
-            yofs[s] = 2 * kTileBytes + lane_ofs + (((wc * 4 + s) ^ f) * 64);
+            xofs[s] = kmajor_lane_offset(lane, wr * 4 + s);      // s = accumulator tile here
+            yofs[s] = 2 * kTileBytes + kmajor_lane_offset(lane, wc * 4 + s);
         }
         const int xbase = (wr * 128 + l31) * 128;
         const int ybase = 2 * kTileBytes + (wc * kGroupC + l31) * 128;
 
         // MFMA operands of the four k-slices of a step: fy[s][t], fx[s][t] for slice s.
         bf16x8_t fy[4][4], fx[4][4];
-        auto read_km = [&](const unsigned char* at) {
-            typedef __attribute__((address_space(3))) i16x4_t* tptr_t;
-            const i16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tptr_t)(lptr_t)const_cast<unsigned char*>(at));
-            const i16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tptr_t)(lptr_t)const_cast<unsigned char*>(at + 2048));
-            return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-        };
         // item 0..3: the Y operand of accumulator row t = item, 4..7: the X operand of column t
         auto read_item = [&](int stage, int s, int item) {
             const unsigned char* base = smem + stage * kTileBytes;
             if (KM) {
-                if (item < 4) fy[s][item] = read_km(base + yofs[item] + s * 8192);
-                else fx[s][item - 4] = read_km(base + xofs[item - 4] + s * 8192);
+                if (item < 4) fy[s][item] = read_kmajor(base + yofs[item] + s * 8192);
+                else fx[s][item - 4] = read_kmajor(base + xofs[item - 4] + s * 8192);
             } else if (item < 4)
                 fy[s][item] = *reinterpret_cast<const bf16x8_t*>(base + ybase + item * 4096 + rofs[s]);
             else

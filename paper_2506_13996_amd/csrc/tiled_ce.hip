@@ -8,7 +8,8 @@
 //      gather_rows       once per call the valid rows are numbered densely in sequence order
 //                        (block_count / block_offsets / scatter_index, which also zero-fill the
 //                        dHidden rows and loss terms of ignored tokens), and a tile is T
-//                        consecutive dense rows, gathered into a dense [T, H] copy.  Their number
+//                        consecutive dense rows, gathered into a dense [T, H] copy (behind the
+//                        rows of the earlier tiles of its dW group).  Their number
 //                        M lives on the device: the host walks ceil(N / T) tiles and the kernels
 //                        of a tile beyond the dense rows leave at once, so nothing waits for the
 //                        host.
@@ -16,18 +17,18 @@
 //                        leave the registers: the epilogue reduces each row over the block's
 //                        columns to (max, sum exp) partials per 128-column group, picks out the
 //                        label logit, and writes e = exp(z - group max) as bf16 to a [T, V]
-//                        scratch ("stash").
+//                        scratch ("stash", also laid out per dW group).
 //   2. row_combine       partials -> lse, per-row loss, and the factor exp(group max - lse)
 //                        that turns e into the softmax probability.
-//   3. dz_finalize       dZ = e * factor - onehot as bf16, in place, plus its transpose appended to
-//                        the buffers of the tile's dW group.
+//   3. dz_finalize       dZ = e * factor - onehot as bf16, in place.
 //   4. dhidden_kernel    dH = (g/M) dZ W            (contraction over V), rows scattered back
 //   5. dw_kernel         acc += H_c^T dZ            once per group of tiles (contraction over the
 //                        group's dense rows, fp32)
 //
 // After the last tile: loss = sum(per-row loss) / M in a fixed order, dW = (g/M) acc.
-// All three contractions use the same k-contiguous block GEMM (gemm_tile.h); W^T and H_c^T are
-// made by a padded transpose so that every operand has its contraction index contiguous.
+// The contractions share the block GEMM of gemm_tile.h: logits and dHidden with k-contiguous
+// operands (W^T is made once per call by a padded transpose), dW with the k-major cores, which
+// take the group's dense hidden rows and dZ rows as they are.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <math.h>
@@ -58,10 +59,11 @@ struct TileInfo {
     int kofs;              // where the tile's dense rows start along k in the dW group buffers
 };
 
-// dW is accumulated into the fp32 [V, H] sums once per GROUP of consecutive tiles: dZ^T and H^T of
-// the group's tiles are packed side by side along k and one dW GEMM contracts over all of them,
-// so the read-modify-write of the 4*V*H-byte accumulator and the GEMM's epilogue are paid once
-// per group instead of once per tile.  The group spans about kDwGroupRows rows.
+// dW is accumulated into the fp32 [V, H] sums once per GROUP of consecutive tiles: the dense
+// hidden rows and dZ rows of the group's tiles are kept one behind the other and one dW GEMM
+// contracts over all of them, so the read-modify-write of the 4*V*H-byte accumulator and the
+// GEMM's epilogue are paid once per group instead of once per tile.  The group spans about
+// kDwGroupRows rows.
 constexpr int kDwGroupRows = 16384;
 constexpr int kDwGroupMax = 8;
 static inline int dw_group_size(int64_t Tp) {
@@ -75,10 +77,9 @@ struct Layout {
     int64_t Tp, Vp, ng;    // padded tile rows, padded vocabulary, 128-column groups
     int g;                 // tiles per dW group
     int64_t Kg;            // dense rows a group can hold: g * Tp
-    bool km;               // the dW product reads its operands k-major: no transposed copies
     int splits, ksteps;    // dHidden: ranges of the contraction over V, k-steps per range
     size_t header, tinfo, loss_rows, lse, idx, block_cnt, block_ofs, zlabel, yc, pm, ps, sc, hc,
-        stash, dzt, wt, ht, part, acc, total;
+        stash, wt, part, acc, total;
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -126,15 +127,11 @@ static Layout make_layout(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_
     L.pm = take((size_t)L.ng * L.Tp * 4);
     L.ps = take((size_t)L.ng * L.Tp * 4);
     L.sc = take((size_t)L.ng * L.Tp * 4);
-    // km: hc and stash hold the dense rows of the whole group (each tile at its k offset) and are
-    // the operands of the dW product as they are; otherwise they hold one tile and the group's
-    // rows are collected transposed in ht and dzt.
-    L.km = (H % kBlockR) == 0;
-    L.hc = take((size_t)(L.km ? L.Kg : L.Tp) * H * 2);
-    L.stash = take((size_t)(L.km ? L.Kg : L.Tp) * L.Vp * 2);
-    L.dzt = take(L.km ? 0 : (size_t)L.Vp * L.Kg * 2);
+    // hc and stash hold the dense rows of the whole group, each tile at its k offset: they are
+    // the two operands of the group's dW product as they are (k = dense row, the slow index)
+    L.hc = take((size_t)L.Kg * H * 2);
+    L.stash = take((size_t)L.Kg * L.Vp * 2);
     L.wt = take((size_t)H * L.Vp * 2);
-    L.ht = take(L.km ? 0 : (size_t)H * L.Kg * 2);
     dhidden_splits(L.Tp, H, L.Vp, L.splits, L.ksteps);
     L.part = take(L.splits > 1 ? (size_t)L.splits * L.Tp * H * 4 : 0);
     const bool acc_in_dw = (flags & ALST_FLAG_DW_FP32) && !(flags & ALST_FLAG_DW_ACCUMULATE);
@@ -273,16 +270,16 @@ __global__ void tile_info_kernel(const Header* __restrict__ h, int64_t t, int64_
 }
 
 // Block b: dense row b of the tile.  Copies the hidden row of token idx_t[b] into the dense
-// matrix Hc and its label into yc; rows Tc <= b < Trc of Hc are zero padding.  grouped: Hc holds
-// the whole dW group and the tile's rows start at its k offset.
+// matrix Hc and its label into yc; rows Tc <= b < Trc are zero padding.  Hc holds the whole dW
+// group and the tile's rows start at its k offset.
 __global__ __launch_bounds__(256) void gather_rows_kernel(
     const uint16_t* __restrict__ hidden, const int32_t* __restrict__ labels, int H,
     const int32_t* __restrict__ idx_t, const TileInfo* __restrict__ info,
-    uint16_t* __restrict__ Hc, int32_t* __restrict__ yc, int grouped) {
+    uint16_t* __restrict__ Hc, int32_t* __restrict__ yc) {
     const int b = blockIdx.x;
     const int chunks = H / 8;
     if (b >= info->Trc) return;
-    if (grouped) Hc += (int64_t)info->kofs * H;
+    Hc += (int64_t)info->kofs * H;
     u32x4_t* dst = reinterpret_cast<u32x4_t*>(Hc + (int64_t)b * H);
     if (b < info->Tc) {
         const int64_t row = idx_t[b];
@@ -339,21 +336,17 @@ __global__ __launch_bounds__(kCombineRows * kCombineLanes) void row_combine_kern
     }
 }
 
-// dZ = e * factor - onehot for the tile's dense rows, bf16, written over the stash and transposed
-// into dzt.  Rows Tc .. Trc and columns >= V come out as exact zeros, which is what pads the k
-// dimension of the two gradient GEMMs.  One wavefront owns a 64 (rows) x 64 (columns) patch, one lane an 8 x 8
-// block of it: lanes run along v for the row-major reads and in-place writes (8 lanes = one
-// 128-byte line) and along i for the transposed writes, and the 8 x 8 transpose is done in
-// registers with byte permutes, so every global access is a full line and no LDS is used.
-// TRANSPOSED = false: in place only; the stash holds the whole dW group, the tile's rows start
-// at its k offset, and the dW product reads it as it is.
-template <bool FUSED, bool TRANSPOSED>
+// dZ = e * factor - onehot for the tile's dense rows, bf16, in place over the stash (which holds
+// the whole dW group; the tile's rows start at its k offset).  Rows Tc .. Trc and columns >= V
+// come out as exact zeros, which is what pads the k dimension of the two gradient GEMMs.  One
+// wavefront owns a 64 (rows) x 64 (columns) patch, one lane 8 rows x 8 columns of it: the 8 lanes
+// along v cover one 128-byte line per row.
+template <bool FUSED>
 __global__ __launch_bounds__(256) void dz_finalize_kernel(uint16_t* __restrict__ stash,
-                                                          uint16_t* __restrict__ dzt,
                                                           const float* __restrict__ sc,
                                                           const int32_t* __restrict__ yc,
                                                           const TileInfo* __restrict__ info,
-                                                          int Tp, int Vp, int64_t Kg) {
+                                                          int Tp, int Vp) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     // one-dimensional grid (the row-block count can exceed the limit of gridDim.y):
     // block -> (column block bx of 256 columns, row block by of 64 rows), bx fastest
@@ -363,9 +356,7 @@ __global__ __launch_bounds__(256) void dz_finalize_kernel(uint16_t* __restrict__
     const int i0 = by * 64 + (lane >> 3) * 8;                         // first of this lane's 8 rows
     if (by * 64 >= info->Trc) return;
     const int T_cur = info->Tc;
-    if (TRANSPOSED) dzt += info->kofs;                   // dzt is [Vp, Kg]
-    else stash += (int64_t)info->kofs * Vp;
-    uint32_t in[8][4];
+    stash += (int64_t)info->kofs * Vp;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const int i = i0 + j;
@@ -383,23 +374,6 @@ __global__ __launch_bounds__(256) void dz_finalize_kernel(uint16_t* __restrict__
             d[x] = (__bf16)val;
         }
         *reinterpret_cast<bf16x8_t*>(p) = d;
-        const u32x4_t du = __builtin_bit_cast(u32x4_t, d);
-#pragma unroll
-        for (int x = 0; x < 4; ++x) in[j][x] = du[x];
-    }
-    if (!TRANSPOSED) return;
-    // out[x] = column v0 + x for rows i0 .. i0 + 7: halfword x of each input row
-#pragma unroll
-    for (int x = 0; x < 8; ++x) {
-        u32x4_t o;
-#pragma unroll
-        for (int pr = 0; pr < 4; ++pr) {
-            const uint32_t lo = in[2 * pr][x >> 1], hi = in[2 * pr + 1][x >> 1];
-            // v_perm_b32 selector bytes index {hi (4..7), lo (0..3)}
-            o[pr] = (x & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u)
-                            : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-        }
-        *reinterpret_cast<u32x4_t*>(dzt + (int64_t)(v0 + x) * Kg + i0) = o;
     }
 }
 
@@ -471,7 +445,8 @@ __global__ void shift_labels_kernel(const int32_t* __restrict__ labels, int32_t*
 enum { MODE_FWD = 0, MODE_FUSED = 1, MODE_BWD = 2 };
 
 struct LogitsParams {
-    const uint16_t* hidden_t;   // [Tp, H]      the tile's dense (valid) rows, zero padded to Trc
+    const uint16_t* hidden_t;   // [Kg, H]      dense (valid) rows of the dW group; the tile's rows
+                                //              start at its k offset and are zero padded to Trc
     const uint16_t* W;          // [V, H]
     const int32_t* labels_t;    // [Tp]         labels of the dense rows
     const int32_t* idx;         // [Tp]         dense row of the tile -> row of the sequence
@@ -480,9 +455,8 @@ struct LogitsParams {
     float* pm;                  // [ng, Tp]     MODE_FWD / MODE_FUSED
     float* ps;                  // [ng, Tp]
     float* zlabel;              // [Tp]
-    uint16_t* stash;            // [Tp, Vp]     MODE_FUSED / MODE_BWD
+    uint16_t* stash;            // [Kg, Vp]     MODE_FUSED / MODE_BWD; rows as in hidden_t
     int Tp, H, V, Vp;           // Tp = row stride of the per-tile arrays
-    int grouped;                // hidden_t and stash hold the dW group: the tile starts at its k offset
 };
 
 // r = token row of the tile (MFMA lane dimension), c = vocabulary id (register dimension).
@@ -504,7 +478,7 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
-    const int kofs = p.grouped ? p.info->kofs : 0;
+    const int kofs = p.info->kofs;
     const uint16_t* const hidden_t = p.hidden_t + (int64_t)kofs * p.H;
     const uint16_t* warm = Core::kCanGuard ? nullptr
                                            : warm_row<4, 8>(hidden_t, p.H, r0, tr, p.W, p.H, c0, tc);
@@ -601,7 +575,7 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
 }
 
 struct DHiddenParams {
-    const uint16_t* dz;      // [Tp, Vp]     dense rows
+    const uint16_t* dz;      // [Kg, Vp]     dense rows of the dW group; the tile starts at its k offset
     const uint16_t* wt;      // [H, Vp]
     uint16_t* dH_t;          // [N, H]       whole dHidden; dense row i goes to row idx[i]
     const int32_t* idx;
@@ -612,7 +586,6 @@ struct DHiddenParams {
     int splits;              // the contraction over V is cut into this many ranges
     int ksteps;              // k-steps of 64 per range (the last range may be shorter)
     int PR, PC;              // patch shape of the block -> tile mapping
-    int grouped;             // dz holds the dW group: the tile starts at its k offset
 };
 
 // r = token row (lane dimension), c = hidden index (register dimension), k = vocabulary.
@@ -646,7 +619,7 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
-    const uint16_t* const dz = p.dz + (p.grouped ? (int64_t)p.info->kofs * p.Vp : 0) + k0;
+    const uint16_t* const dz = p.dz + (int64_t)p.info->kofs * p.Vp + k0;
     const uint16_t* warm = Core::kCanGuard ? nullptr
                                            : warm_row(p.PR, p.PC, dz, p.Vp, r0, tr, p.wt + k0,
                                                       p.Vp, c0, tc);
@@ -715,18 +688,17 @@ __global__ __launch_bounds__(256) void dhidden_reduce_kernel(const float* __rest
 }
 
 struct DWParams {
-    const uint16_t* ht;      // [H, Kg]      dense rows of the group's tiles, transposed;
-    const uint16_t* dzt;     // [Vp, Kg]     KMajorCore: as they are, [Kg, H] and [Kg, Vp]
+    const uint16_t* hg;      // [Kg, H]      dense hidden rows of the group's tiles
+    const uint16_t* dzg;     // [Kg, Vp]     their dZ rows
     float* acc;              // [V, H]
     const TileInfo* info;    // of the group's last tile: k extent = kofs + Tkc
-    int64_t Kg;
     int H, V, Vp;
     int first;               // first group: store instead of add
 };
 
-// r = hidden index (lane dimension), c = vocabulary id (register dimension), k = dense token row.
-// With the hidden index along the lanes the accumulate moves full 128-byte lines of acc
-// (accumulate_block_f32).
+// r = hidden index (lane dimension), c = vocabulary id (register dimension), k = dense token row:
+// both operands have k as the slow index (k-major cores).  With the hidden index along the lanes
+// the accumulate moves full 128-byte lines of acc (accumulate_block_f32).
 template <class Core, bool GUARD>
 __global__ __launch_bounds__(Core::kThreads) void dw_kernel(const DWParams p) {
     constexpr int kMT = Core::kMT, kNT = Core::kNT;
@@ -747,15 +719,11 @@ __global__ __launch_bounds__(Core::kThreads) void dw_kernel(const DWParams p) {
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
     if (Tkc > 0) {
-        if constexpr (std::is_same<Core, KMajorCore>::value) {
-            int64_t step;
-            const uint16_t* warm = warm_line_kmajor(4, 8, p.ht, p.H, r0, tr, p.dzt, p.Vp, c0, tc, step);
-            Core::template gemm<GUARD>(p.ht, p.H, p.H, p.dzt, p.Vp, p.Vp, Tkc, r0, c0, smem, acc, warm, step);
-        } else {
-            const uint16_t* warm = Core::kCanGuard ? nullptr
-                                                   : warm_row<4, 8>(p.ht, p.Kg, r0, tr, p.dzt, p.Kg, c0, tc);
-            Core::template gemm<GUARD>(p.ht, p.Kg, p.H, p.dzt, p.Kg, p.Vp, Tkc, r0, c0, smem, acc, warm);
-        }
+        int64_t step = 0;
+        const uint16_t* warm = Core::kCanGuard ? nullptr
+                                               : warm_line_kmajor(4, 8, p.hg, p.H, r0, tr, p.dzg, p.Vp,
+                                                                  c0, tc, step);
+        Core::template gemm<GUARD>(p.hg, p.H, p.H, p.dzg, p.Vp, p.Vp, Tkc, r0, c0, smem, acc, warm, step);
     }
 
     accumulate_block_f32<Core, GUARD>(acc, p.acc, p.H, r0, c0, p.H, p.V, p.first != 0);
@@ -780,7 +748,7 @@ static int prepare_kernels() {
     acc(allow_big_lds(dhidden_kernel<DirectCore, false>));
     acc(allow_big_lds(dhidden_kernel<StagedCore, true>));
     acc(allow_big_lds(dw_kernel<KMajorCore, false>));
-    acc(allow_big_lds(dw_kernel<StagedCore, true>));
+    acc(allow_big_lds(dw_kernel<StagedKMajorCore, true>));
     states[dev] = rc + 1;
     return rc;
 }
@@ -830,10 +798,10 @@ static int validate(const Problem& P, size_t workspace_bytes, bool need_fwd_out,
 }
 
 static int launch_transpose(const uint16_t* in, int64_t ld_in, int R, int C, uint16_t* out,
-                            int64_t ld_out, int Rpad, const TileInfo* info, hipStream_t s) {
+                            int64_t ld_out, int Rpad, hipStream_t s) {
     dim3 grid((Rpad + 63) / 64, (C + 63) / 64);
     hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, s, in, ld_in, R, C, out, ld_out,
-                       Rpad, info ? &info->Trc : nullptr, info ? &info->kofs : nullptr);
+                       Rpad, (const int*)nullptr, (const int*)nullptr);
     return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
 }
 
@@ -871,9 +839,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
     float* sc = reinterpret_cast<float*>(P.ws + L.sc);
     uint16_t* hc = reinterpret_cast<uint16_t*>(P.ws + L.hc);
     uint16_t* stash = reinterpret_cast<uint16_t*>(P.ws + L.stash);
-    uint16_t* dzt = reinterpret_cast<uint16_t*>(P.ws + L.dzt);
     uint16_t* wt = reinterpret_cast<uint16_t*>(P.ws + L.wt);
-    uint16_t* ht = reinterpret_cast<uint16_t*>(P.ws + L.ht);
     const bool acc_in_dw = (P.flags & ALST_FLAG_DW_FP32) && !(P.flags & ALST_FLAG_DW_ACCUMULATE);
     float* acc = acc_in_dw ? reinterpret_cast<float*>(P.dW) : reinterpret_cast<float*>(P.ws + L.acc);
 
@@ -896,7 +862,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
     ALST_HIP(hipGetLastError());
 
     if (do_bwd) {
-        rc = launch_transpose(P.W, H, V, H, wt, Vp, Vp, nullptr, s);
+        rc = launch_transpose(P.W, H, V, H, wt, Vp, Vp, s);
         if (rc != ALST_OK) return rc;
     }
 
@@ -920,7 +886,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             hipLaunchKernelGGL(tile_info_kernel, dim3(1), dim3(64), 0, s, hdr, t, T, info,
                                slot ? info - 1 : nullptr);
             hipLaunchKernelGGL(gather_rows_kernel, dim3(Tr), dim3(256), 0, s, P.hidden, P.labels, H,
-                               idx_t, info, hc, yc, L.km ? 1 : 0);
+                               idx_t, info, hc, yc);
             ALST_HIP(hipGetLastError());
         }
 
@@ -932,7 +898,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
         lp.info = info;
         lp.lse_t = do_fwd ? nullptr : P.lse_in;
         lp.pm = pm; lp.ps = ps; lp.zlabel = zlabel; lp.stash = stash;
-        lp.Tp = Tp; lp.H = H; lp.V = V; lp.Vp = Vp; lp.grouped = L.km ? 1 : 0;
+        lp.Tp = Tp; lp.H = H; lp.V = V; lp.Vp = Vp;
         {
             ProfScope ps_(PROF_LOGITS, s);
             if (do_fwd && do_bwd) rc = launch_logits<MODE_FUSED>(lp, Tr, guard_logits, s);
@@ -953,25 +919,13 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
                 const int64_t nblk = (int64_t)(Vp / 256) * (Tr / 64);
                 if (nblk > 0x7fffffff) return ALST_ERR_SHAPE;
                 dim3 grid((unsigned)nblk);
-                if (L.km) {
-                    if (do_fwd)
-                        hipLaunchKernelGGL((dz_finalize_kernel<true, false>), grid, dim3(256), 0, s,
-                                           stash, dzt, sc, yc, info, Tp, Vp, L.Kg);
-                    else
-                        hipLaunchKernelGGL((dz_finalize_kernel<false, false>), grid, dim3(256), 0, s,
-                                           stash, dzt, sc, yc, info, Tp, Vp, L.Kg);
-                    ALST_HIP(hipGetLastError());
-                } else {
-                    if (do_fwd)
-                        hipLaunchKernelGGL((dz_finalize_kernel<true, true>), grid, dim3(256), 0, s,
-                                           stash, dzt, sc, yc, info, Tp, Vp, L.Kg);
-                    else
-                        hipLaunchKernelGGL((dz_finalize_kernel<false, true>), grid, dim3(256), 0, s,
-                                           stash, dzt, sc, yc, info, Tp, Vp, L.Kg);
-                    ALST_HIP(hipGetLastError());
-                    rc = launch_transpose(hc, H, Tr, H, ht, L.Kg, Tr, info, s);
-                    if (rc != ALST_OK) return rc;
-                }
+                if (do_fwd)
+                    hipLaunchKernelGGL(dz_finalize_kernel<true>, grid, dim3(256), 0, s, stash, sc, yc,
+                                       info, Tp, Vp);
+                else
+                    hipLaunchKernelGGL(dz_finalize_kernel<false>, grid, dim3(256), 0, s, stash, sc,
+                                       yc, info, Tp, Vp);
+                ALST_HIP(hipGetLastError());
             }
         }
         if (!do_bwd) continue;
@@ -984,7 +938,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             dp.Tp = Tp; dp.H = H; dp.Vp = Vp;
             dp.splits = L.splits; dp.ksteps = L.ksteps;
             const PatchGrid pg = choose_patches(Tr / kBlockR, (H + kBlockC - 1) / kBlockC);
-            dp.PR = pg.PR; dp.PC = pg.PC; dp.grouped = L.km ? 1 : 0;
+            dp.PR = pg.PR; dp.PC = pg.PC;
             const int grid = grid_for_patches((int64_t)pg.patches() * L.splits);
             ProfScope ps_(PROF_DHIDDEN, s);
             if (guard_h)
@@ -1000,13 +954,13 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
         }
         if (slot == L.g - 1 || t == ntiles - 1) {           // the group is complete
             DWParams wp;
-            wp.ht = L.km ? hc : ht; wp.dzt = L.km ? stash : dzt; wp.acc = acc; wp.info = info;
-            wp.Kg = L.Kg; wp.H = H; wp.V = V; wp.Vp = Vp; wp.first = (t < L.g);
+            wp.hg = hc; wp.dzg = stash; wp.acc = acc; wp.info = info;
+            wp.H = H; wp.V = V; wp.Vp = Vp; wp.first = (t < L.g);
             const int grid = grid_for_tiles<4, 8>((H + kBlockR - 1) / kBlockR, Vp / kBlockC);
             ProfScope ps_(PROF_DW, s);
             if (guard_h)
-                hipLaunchKernelGGL((dw_kernel<StagedCore, true>), dim3(grid),
-                                   dim3(StagedCore::kThreads), kLdsBytes, s, wp);
+                hipLaunchKernelGGL((dw_kernel<StagedKMajorCore, true>), dim3(grid),
+                                   dim3(StagedKMajorCore::kThreads), kLdsBytes, s, wp);
             else
                 hipLaunchKernelGGL((dw_kernel<KMajorCore, false>), dim3(grid),
                                    dim3(KMajorCore::kThreads), kLdsBytes, s, wp);
