@@ -10,13 +10,15 @@
 //              a  = silu(g) * u               swiglu_fwd_kernel
 //              y  = a Wd^T
 //   backward   gu as above (recomputed), da = dy (Wd^T)^T with Wd^T made once per call
-//              a, [dg | du]                   swiglu_bwd_kernel
+//              a, [dg | du]                   swiglu_bwd_kernel, into the rows of the tile's group
 //              dx = [dg | du] [Wg^T | Wu^T]^T one launch, K = 2I, the transposed weights made once
-//              x^T, dy^T, a^T, [dg | du]^T    appended along k to the buffers of the tile's group
 //   per group  dWg += dg^T x, dWu += du^T x, dWd += dy^T a   (fp32, contraction over the group's rows)
 //
 // As in the cross-entropy path the weight gradients are accumulated once per group of tiles
-// (about 16384 rows), so the read-modify-write of the fp32 sums is paid once per group.
+// (about 16384 rows), so the read-modify-write of the fp32 sums is paid once per group.  Their
+// operands have the contraction index (the token row) as the slow index and are read as they are
+// by the k-major cores: x and dy straight from the caller's arrays, a and [dg | du] from the
+// group's buffers.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <math.h>
@@ -32,9 +34,9 @@ constexpr int kMlpGroupRows = 16384;
 constexpr int kMlpGroupMax = 8;
 
 struct MlpLayout {
-    int64_t Tp, Kg;        // tile rows rounded up to 256; row stride of the transposed group buffers
+    int64_t Tp, Kg;        // tile rows rounded up to 256; rows a weight-gradient group can hold
     int g;                 // tiles per weight-gradient group
-    size_t gu, a, da, dgu, wdt, wgut, xt, dyt, at, dgut, acc_g, acc_u, acc_d, total;
+    size_t gu, a, da, dgu, wdt, wgut, acc_g, acc_u, acc_d, total;
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -50,16 +52,13 @@ static MlpLayout make_mlp_layout(int64_t N, int64_t H, int64_t I, int64_t tile, 
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     L.gu = take((size_t)L.Tp * 2 * I * 2);
-    L.a = take((size_t)L.Tp * I * 2);
+    // backward keeps a and [dg | du] of the whole group, each tile behind the one before
+    L.a = take((size_t)(backward ? L.Kg : L.Tp) * I * 2);
     if (backward) {
         L.da = take((size_t)L.Tp * I * 2);
-        L.dgu = take((size_t)L.Tp * 2 * I * 2);
+        L.dgu = take((size_t)L.Kg * 2 * I * 2);
         L.wdt = take((size_t)I * H * 2);
         L.wgut = take((size_t)H * 2 * I * 2);
-        L.xt = take((size_t)H * L.Kg * 2);
-        L.dyt = take((size_t)H * L.Kg * 2);
-        L.at = take((size_t)I * L.Kg * 2);
-        L.dgut = take((size_t)2 * I * L.Kg * 2);
         // fp32 overwrite outputs hold the sums themselves
         const bool in_out = (flags & ALST_FLAG_DW_FP32) && !(flags & ALST_FLAG_DW_ACCUMULATE);
         L.acc_g = take(in_out ? 0 : (size_t)I * H * 4);
@@ -133,10 +132,10 @@ __global__ __launch_bounds__(Core::kThreads) void linear_kernel(const LinearBatc
 }
 
 struct WgradParams {
-    const uint16_t* X;       // [rows_x, ldk]   r: the contiguous index of `out`
-    const uint16_t* Y;       // [rows_y, ldk]   c: the row index of `out`
-    float* out;              // [rows_y, ld]    out[c][r] (+)= sum_k X[r][k] Y[c][k]
-    int64_t ldk, ld;
+    const uint16_t* X;       // [K, ldx]        r (columns 0 .. rows_x): the contiguous index of `out`
+    const uint16_t* Y;       // [K, ldy]        c (columns 0 .. rows_y): the row index of `out`
+    float* out;              // [rows_y, ld]    out[c][r] (+)= sum_k X[k][r] Y[k][c]
+    int64_t ldx, ldy, ld;
     int rows_x, rows_y, K;
     int first;               // store instead of add
 };
@@ -163,9 +162,12 @@ __global__ __launch_bounds__(Core::kThreads) void wgrad_kernel(const WgradBatch 
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
+    int64_t step = 0;
     const uint16_t* warm = Core::kCanGuard ? nullptr
-                                           : warm_row(PR, PC, p.X, p.ldk, r0, tr, p.Y, p.ldk, c0, tc);
-    Core::template gemm<GUARD>(p.X, p.ldk, p.rows_x, p.Y, p.ldk, p.rows_y, p.K, r0, c0, smem, acc, warm);
+                                           : warm_line_kmajor(PR, PC, p.X, p.ldx, r0, tr, p.Y, p.ldy,
+                                                              c0, tc, step);
+    Core::template gemm<GUARD>(p.X, p.ldx, p.rows_x, p.Y, p.ldy, p.rows_y, p.K, r0, c0, smem, acc, warm,
+                               step);
     accumulate_block_f32<Core, GUARD>(acc, p.out, p.ld, r0, c0, p.rows_x, p.rows_y, p.first != 0);
 }
 
@@ -265,8 +267,8 @@ static int prepare_mlp_kernels() {
     auto acc = [&](int r) { if (r != ALST_OK) rc = r; };
     acc(allow_big_lds(linear_kernel<DirectCore, false>));
     acc(allow_big_lds(linear_kernel<StagedCore, true>));
-    acc(allow_big_lds(wgrad_kernel<DirectCore, false>));
-    acc(allow_big_lds(wgrad_kernel<StagedCore, true>));
+    acc(allow_big_lds(wgrad_kernel<KMajorCore, false>));
+    acc(allow_big_lds(wgrad_kernel<StagedKMajorCore, true>));
     states[dev] = rc + 1;
     return rc;
 }
@@ -305,10 +307,9 @@ static int launch_linear(const LinearParams* ps, int n, hipStream_t s) {
 
 static int launch_linear(const LinearParams& p, hipStream_t s) { return launch_linear(&p, 1, s); }
 
-static int launch_wgrad(const WgradParams* ps, int n, hipStream_t s) {
+static int launch_wgrad_batch(const WgradParams* ps, int n, bool direct, hipStream_t s) {
     WgradBatch b = {};
     b.map.n = n;
-    bool direct = true;
     int64_t patches = 0;
     for (int i = 0; i < n; ++i) {
         const WgradParams& p = ps[i];
@@ -317,20 +318,40 @@ static int launch_wgrad(const WgradParams* ps, int n, hipStream_t s) {
         const int tiles_r = (p.rows_x + kBlockR - 1) / kBlockR, tiles_c = (p.rows_y + kBlockC - 1) / kBlockC;
         b.map.g[i] = choose_patches(tiles_r, tiles_c);
         patches += b.map.g[i].patches();
-        direct = direct && p.rows_x % kBlockR == 0 && p.rows_y % kBlockC == 0 && p.K % kBlockK == 0 &&
-                 p.K >= kBlockK;
     }
     if (patches * 32 > 0x7fffff00) return ALST_ERR_SHAPE;
     for (int i = n; i <= kMaxBatch; ++i) b.map.first_patch[i] = (int)patches;
     const int blocks = grid_for_patches(patches);
     ProfScope pr(PROF_MLP_WGRAD, s);
     if (direct)
-        hipLaunchKernelGGL((wgrad_kernel<DirectCore, false>), dim3((unsigned)blocks),
-                           dim3(DirectCore::kThreads), kLdsBytes, s, b);
+        hipLaunchKernelGGL((wgrad_kernel<KMajorCore, false>), dim3((unsigned)blocks),
+                           dim3(KMajorCore::kThreads), kLdsBytes, s, b);
     else
-        hipLaunchKernelGGL((wgrad_kernel<StagedCore, true>), dim3((unsigned)blocks),
-                           dim3(StagedCore::kThreads), kLdsBytes, s, b);
+        hipLaunchKernelGGL((wgrad_kernel<StagedKMajorCore, true>), dim3((unsigned)blocks),
+                           dim3(StagedKMajorCore::kThreads), kLdsBytes, s, b);
     return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
+}
+
+// The n weight-gradient products (n <= kMaxBatch, all with the same K) in one launch.  The
+// unguarded core needs block-aligned output extents and K in whole k-steps: with aligned
+// extents, the whole k-steps go to it and the K % 64 rows left over to a second, guarded launch.
+static int launch_wgrad(const WgradParams* ps, int n, hipStream_t s) {
+    bool aligned = true;
+    for (int i = 0; i < n; ++i)
+        aligned = aligned && ps[i].rows_x % kBlockR == 0 && ps[i].rows_y % kBlockC == 0;
+    const int K = ps[0].K, K_whole = K / kBlockK * kBlockK;
+    if (!aligned || K_whole == 0) return launch_wgrad_batch(ps, n, false, s);
+    WgradParams part[kMaxBatch];
+    for (int i = 0; i < n; ++i) { part[i] = ps[i]; part[i].K = K_whole; }
+    int rc = launch_wgrad_batch(part, n, true, s);
+    if (rc != ALST_OK || K_whole == K) return rc;
+    for (int i = 0; i < n; ++i) {
+        part[i].X += (int64_t)K_whole * ps[i].ldx;
+        part[i].Y += (int64_t)K_whole * ps[i].ldy;
+        part[i].K = K - K_whole;
+        part[i].first = 0;
+    }
+    return launch_wgrad_batch(part, n, false, s);
 }
 
 static int launch_wgrad(const WgradParams& p, hipStream_t s) { return launch_wgrad(&p, 1, s); }
@@ -445,10 +466,6 @@ static int run_mlp_backward(const MlpProblem& P) {
     uint16_t* dgu = reinterpret_cast<uint16_t*>(P.ws + L.dgu);
     uint16_t* wdt = reinterpret_cast<uint16_t*>(P.ws + L.wdt);
     uint16_t* wgut = reinterpret_cast<uint16_t*>(P.ws + L.wgut);
-    uint16_t* xt = reinterpret_cast<uint16_t*>(P.ws + L.xt);
-    uint16_t* dyt = reinterpret_cast<uint16_t*>(P.ws + L.dyt);
-    uint16_t* at = reinterpret_cast<uint16_t*>(P.ws + L.at);
-    uint16_t* dgut = reinterpret_cast<uint16_t*>(P.ws + L.dgut);
     const bool f32 = P.flags & ALST_FLAG_DW_FP32, accum = P.flags & ALST_FLAG_DW_ACCUMULATE;
     const bool in_out = f32 && !accum;
     float* acc_g = in_out ? reinterpret_cast<float*>(P.dWg) : reinterpret_cast<float*>(P.ws + L.acc_g);
@@ -467,16 +484,20 @@ static int run_mlp_backward(const MlpProblem& P) {
 
     const int64_t T = P.tile < P.N ? P.tile : P.N;
     const int64_t ntiles = (P.N + T - 1) / T;
-    int kofs = 0;                                   // rows of the group appended so far (x 64)
+    int kofs = 0;                                   // rows of the group so far
+    int64_t group_row0 = 0;                         // first row of the group in x and dy
     for (int64_t t = 0; t < ntiles; ++t) {
         const int64_t i0 = t * T;
         const int T_cur = (int)((P.N - i0) < T ? (P.N - i0) : T);
         const int Tr = (T_cur + kBlockR - 1) / kBlockR * kBlockR;
-        const int Tk = (T_cur + kBlockK - 1) / kBlockK * kBlockK;
         const int slot = (int)(t % L.g);
-        if (slot == 0) kofs = 0;
+        if (slot == 0) { kofs = 0; group_row0 = i0; }
         const uint16_t* x_t = P.x + i0 * P.H;
         const uint16_t* dy_t = P.dy + i0 * P.H;
+        // the tile's rows of a and [dg | du] sit behind those of the group's earlier tiles (rows
+        // T_cur .. Tr come out as zeros and are overwritten by the next tile)
+        uint16_t* a_t = a + (int64_t)kofs * I;
+        uint16_t* dgu_t = dgu + (int64_t)kofs * I2;
 
         {   // g, u again, and da = dy_t Wd (contraction over H), one launch
             LinearParams lp = {};
@@ -489,37 +510,31 @@ static int run_mlp_backward(const MlpProblem& P) {
         {
             ProfScope ps(PROF_MLP_OTHER, s);
             hipLaunchKernelGGL(swiglu_bwd_kernel, dim3(elementwise_blocks((int64_t)Tr * I / 8)),
-                               dim3(256), 0, s, gu, da, a, dgu, (int64_t)Tr, I);
+                               dim3(256), 0, s, gu, da, a_t, dgu_t, (int64_t)Tr, I);
             ALST_HIP(hipGetLastError());
         }
         {   // dx = [dg | du] [Wg^T | Wu^T]^T: contraction over 2I
             LinearParams lp = {};
-            lp.X = dgu; lp.ldx = I2; lp.rows_x = Tr; lp.K = (int)I2;
+            lp.X = dgu_t; lp.ldx = I2; lp.rows_x = Tr; lp.K = (int)I2;
             lp.Y = wgut; lp.ldy = I2; lp.rows_y = H;
             lp.D = P.dx + i0 * P.H; lp.ldd = H; lp.rows_out = T_cur; lp.cols_out = H;
             rc = launch_linear(lp, s);
             if (rc != ALST_OK) return rc;
         }
-        {   // the tile's rows go behind those already in the group's transposed buffers
-            ProfScope ps(PROF_MLP_OTHER, s);
-            rc = launch_transpose(x_t, H, T_cur, H, xt + kofs, L.Kg, Tk, s);
-            if (rc == ALST_OK) rc = launch_transpose(dy_t, H, T_cur, H, dyt + kofs, L.Kg, Tk, s);
-            if (rc == ALST_OK) rc = launch_transpose(a, I, T_cur, I, at + kofs, L.Kg, Tk, s);
-            if (rc == ALST_OK) rc = launch_transpose(dgu, I2, T_cur, (int)I2, dgut + kofs, L.Kg, Tk, s);
-            if (rc != ALST_OK) return rc;
-        }
-        kofs += Tk;
+        kofs += T_cur;
         if (slot == L.g - 1 || t == ntiles - 1) {       // the group is complete
             const int first = t < L.g;
+            const uint16_t* x_g = P.x + group_row0 * P.H;
+            const uint16_t* dy_g = P.dy + group_row0 * P.H;
             WgradParams wp[kMaxBatch] = {};
-            wp[0].ldk = L.Kg; wp[0].K = kofs; wp[0].first = first;
-            wp[0].X = xt; wp[0].rows_x = H; wp[0].ld = H; wp[0].rows_y = I;
-            wp[0].Y = dgut; wp[0].out = acc_g;                                       // dWg[i][h]
+            wp[0].K = kofs; wp[0].first = first;
+            wp[0].X = x_g; wp[0].ldx = H; wp[0].rows_x = H; wp[0].ld = H;
+            wp[0].Y = dgu; wp[0].ldy = I2; wp[0].rows_y = I; wp[0].out = acc_g;      // dWg[i][h]
             wp[1] = wp[0];
-            wp[1].Y = dgut + (int64_t)I * L.Kg; wp[1].out = acc_u;                   // dWu[i][h]
+            wp[1].Y = dgu + I; wp[1].out = acc_u;                                    // dWu[i][h]
             wp[2] = wp[0];
-            wp[2].X = at; wp[2].rows_x = I; wp[2].ld = I; wp[2].Y = dyt; wp[2].rows_y = H;
-            wp[2].out = acc_d;                                                       // dWd[h][i]
+            wp[2].X = a; wp[2].ldx = I; wp[2].rows_x = I; wp[2].ld = I;
+            wp[2].Y = dy_g; wp[2].ldy = H; wp[2].rows_y = H; wp[2].out = acc_d;      // dWd[h][i]
             rc = launch_wgrad(wp, 3, s);                                             // one launch
             if (rc != ALST_OK) return rc;
         }
@@ -543,9 +558,9 @@ static int run_mlp_backward(const MlpProblem& P) {
 // the single tiled linear layer: y = x W^T, dx = dy W, dW = dy^T x
 // ---------------------------------------------------------------------------------------------
 struct LinLayout {
-    int64_t Tp, Kg;
-    int g;
-    size_t wt, xt, dyt, acc, total;
+    int64_t Tp;
+    int g;                 // tiles per weight-gradient group
+    size_t wt, acc, total;
 };
 
 static LinLayout make_lin_layout(int64_t N, int64_t K, int64_t M, int64_t tile, bool backward,
@@ -555,13 +570,10 @@ static LinLayout make_lin_layout(int64_t N, int64_t K, int64_t M, int64_t tile, 
     L.Tp = (T + 255) / 256 * 256;
     int64_t g = kMlpGroupRows / L.Tp;
     L.g = (int)(g < 1 ? 1 : (g > kMlpGroupMax ? kMlpGroupMax : g));
-    L.Kg = (int64_t)L.g * L.Tp;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     if (backward) {
         L.wt = take((size_t)K * M * 2);
-        L.xt = take((size_t)K * L.Kg * 2);
-        L.dyt = take((size_t)M * L.Kg * 2);
         const bool in_out = (flags & ALST_FLAG_DW_FP32) && !(flags & ALST_FLAG_DW_ACCUMULATE);
         L.acc = take(in_out ? 0 : (size_t)M * K * 4);
     }
@@ -623,8 +635,6 @@ static int run_lin_backward(const LinProblem& P) {
     const LinLayout L = make_lin_layout(P.N, P.K, P.M, P.tile, true, P.flags);
     hipStream_t s = P.stream;
     uint16_t* wt = reinterpret_cast<uint16_t*>(P.ws + L.wt);
-    uint16_t* xt = reinterpret_cast<uint16_t*>(P.ws + L.xt);
-    uint16_t* dyt = reinterpret_cast<uint16_t*>(P.ws + L.dyt);
     const bool f32 = P.flags & ALST_FLAG_DW_FP32, accum = P.flags & ALST_FLAG_DW_ACCUMULATE;
     const bool in_out = f32 && !accum;
     float* acc = in_out ? reinterpret_cast<float*>(P.dW) : reinterpret_cast<float*>(P.ws + L.acc);
@@ -636,32 +646,27 @@ static int run_lin_backward(const LinProblem& P) {
     }
     const int64_t T = P.tile < P.N ? P.tile : P.N;
     const int64_t ntiles = (P.N + T - 1) / T;
-    int kofs = 0;
+    int kofs = 0;                                   // rows of the group so far
+    int64_t group_row0 = 0;
     for (int64_t t = 0; t < ntiles; ++t) {
         const int64_t i0 = t * T;
         const int T_cur = (int)((P.N - i0) < T ? (P.N - i0) : T);
-        const int Tk = (T_cur + kBlockK - 1) / kBlockK * kBlockK;
         const int slot = (int)(t % L.g);
-        if (slot == 0) kofs = 0;
-        const uint16_t* x_t = P.x + i0 * P.K;
-        const uint16_t* dy_t = P.dy + i0 * P.M;
+        if (slot == 0) { kofs = 0; group_row0 = i0; }
         LinearParams lp = {};
-        lp.X = dy_t; lp.ldx = M; lp.rows_x = T_cur; lp.K = M;
+        lp.X = P.dy + i0 * P.M; lp.ldx = M; lp.rows_x = T_cur; lp.K = M;
         lp.Y = wt; lp.ldy = M; lp.rows_y = K;
         lp.D = P.dx + i0 * P.K; lp.ldd = K; lp.rows_out = T_cur; lp.cols_out = K;
         rc = launch_linear(lp, s);
         if (rc != ALST_OK) return rc;
-        {
-            ProfScope ps(PROF_MLP_OTHER, s);
-            rc = launch_transpose(x_t, K, T_cur, K, xt + kofs, L.Kg, Tk, s);
-            if (rc == ALST_OK) rc = launch_transpose(dy_t, M, T_cur, M, dyt + kofs, L.Kg, Tk, s);
-            if (rc != ALST_OK) return rc;
-        }
-        kofs += Tk;
+        kofs += T_cur;
         if (slot == L.g - 1 || t == ntiles - 1) {
+            // dW[m][k] += sum over the group's rows of dy[t][m] x[t][k]: both operands are read
+            // from the caller's arrays as they are
             WgradParams wp = {};
-            wp.X = xt; wp.rows_x = K; wp.Y = dyt; wp.rows_y = M; wp.ldk = L.Kg; wp.K = kofs;
-            wp.out = acc; wp.ld = K; wp.first = t < L.g;
+            wp.X = P.x + group_row0 * P.K; wp.ldx = K; wp.rows_x = K;
+            wp.Y = P.dy + group_row0 * P.M; wp.ldy = M; wp.rows_y = M;
+            wp.K = kofs; wp.out = acc; wp.ld = K; wp.first = t < L.g;
             rc = launch_wgrad(wp, s);
             if (rc != ALST_OK) return rc;
         }

@@ -43,6 +43,10 @@ CASES = [
     ("ragged", 700, 136, 200, 300),
     ("tile_gt_n", 130, 64, 72, 4096),
     ("wide_output", 512, 256, 4096, 512),       # an LM-head-like projection
+    # block-aligned K and M, rows not a whole number of k-steps: dW = whole k-steps on the
+    # unguarded core + the 12 rows left over on the guarded one
+    ("aligned_ragged_rows", 1100, 256, 512, 512),
+    ("aligned_few_rows", 40, 256, 256, 64),
 ]
 
 

@@ -43,6 +43,10 @@ CASES = [
     ("ragged", 700, 136, 200, 300),               # H % 64 != 0, I % 256 != 0, ragged tiles
     ("tile_gt_n", 200, 64, 96, 4096),
     ("one_row_tiles", 5, 64, 64, 1),
+    # block-aligned H and I, a row count that is not a whole number of k-steps: the weight
+    # gradients take the whole k-steps on the unguarded core and the 12 rows left over on the other
+    ("aligned_ragged_rows", 1100, 256, 512, 512),
+    ("aligned_few_rows", 40, 256, 256, 64),       # fewer rows than one k-step
 ]
 
 
