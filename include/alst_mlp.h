@@ -15,9 +15,9 @@
  *   da = dy Wd,  dg = da * u * silu'(g),  du = da * silu(g)
  *   dx = dg Wg + du Wu,  dWg = dg^T x,  dWu = du^T x,  dWd = dy^T a
  *
- * Products are bf16 x bf16 with fp32 accumulation; g, u, a, da, dg, du are rounded to bf16 between
- * the contractions (as a bf16 framework would); weight gradients are accumulated over the tiles
- * in fp32.
+ * Products are bf16 x bf16 with fp32 accumulation; g and u enter the SwiGLU as fp32 accumulators
+ * and never reach memory; a, da, dg, du are rounded to bf16 between the contractions (as a bf16
+ * framework would); weight gradients are accumulated over the tiles in fp32.
  *
  * Conventions are those of alst.h: device pointers unless marked host, dense row-major without
  * strides, bf16 = upper half of an IEEE binary32, H and I multiples of 8 and base pointers 16-byte

@@ -107,6 +107,20 @@ __device__ __forceinline__ bool tile_in_patch(const PatchGrid& g, int P, int w, 
     return tr < g.tiles_r && tc < g.tiles_c;
 }
 
+// Gated pair of Y operands: with Y2 given, the 256 Y rows of the block at c0 are four runs of 64
+// rows, run q = rows c0 / 2 + (q / 2) * 64 .. + 63 of Y (q even) or of Y2 (q odd): the 128 rows of
+// a wavefront are 64 rows of Y followed by the same 64 rows of Y2, so a lane that holds the
+// product with row j of Y in accumulator tile mt holds the one with row j of Y2 in tile mt + 2.
+// br = row inside the block; valid = the source row exists (the pointer is then usable anyway).
+__device__ __forceinline__ const uint16_t* paired_row(const uint16_t* Y, const uint16_t* Y2,
+                                                      int64_t ldy, int c0, int br, int rows_y,
+                                                      bool& valid) {
+    const int run = br >> 6;
+    const int src = (c0 >> 1) + (run >> 1) * 64 + (br & 63);
+    valid = src < rows_y;
+    return ((run & 1) ? Y2 : Y) + (int64_t)(valid ? src : 0) * ldy;
+}
+
 // L2 warm-up.  The blocks of a patch that share an operand tile walk k in step, so each of them
 // would meet every line of the tile as an L2 miss at the same moment.  Instead the sharers split
 // the tile's rows between them and each touches one dword per line of its share kWarmAhead
@@ -128,12 +142,16 @@ __device__ __forceinline__ const uint16_t* warm_row(const uint16_t* X, int64_t l
 // The same for a patch shape chosen at run time (2x16, 4x8, 8x4 or 16x2).
 __device__ __forceinline__ const uint16_t* warm_row(int PR, int PC, const uint16_t* X, int64_t ldx,
                                                     int r0, int tr, const uint16_t* Y, int64_t ldy,
-                                                    int c0, int tc) {
+                                                    int c0, int tc, const uint16_t* Y2 = nullptr) {
     const int nx = kBlockR / PC, ny = kBlockC / PR, total = nx + ny, per = (total + 3) / 4;   // per <= 36
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     int l = w * per + (lane < per ? lane : per - 1);
     if (l > total - 1) l = total - 1;
     if (l < nx) return X + (int64_t)(r0 + (tc % PC) * nx + l) * ldx;
+    if (Y2) {
+        bool valid;
+        return paired_row(Y, Y2, ldy, c0, (tr % PR) * ny + (l - nx), 0x7fffffff, valid);
+    }
     return Y + (int64_t)(c0 + (tr % PR) * ny + (l - nx)) * ldy;
 }
 
@@ -226,7 +244,8 @@ struct StagedCoreT {
                                                 int64_t ldy, int rows_y, int K, int r0, int c0,
                                                 unsigned char* smem, f32x16_t (&acc)[kMT][kNT],
                                                 const uint16_t* /*warm*/ = nullptr,
-                                                int64_t /*warm_stride*/ = 0) {
+                                                int64_t /*warm_stride*/ = 0,
+                                                const uint16_t* Y2 = nullptr) {
         const int tid = threadIdx.x;
         const Lane lp;
         // row-major: thread -> (row inside a 64-row slab of the operand tile, 16-byte chunk along
@@ -247,9 +266,15 @@ struct StagedCoreT {
             } else {
                 const int gx = r0 + lrow + 64 * j, gy = c0 + lrow + 64 * j;
                 xv[j] = !GUARD || gx < rows_x;
-                yv[j] = !GUARD || gy < rows_y;
                 xp[j] = X + (int64_t)(xv[j] ? gx : 0) * ldx + kc * 8;
-                yp[j] = Y + (int64_t)(yv[j] ? gy : 0) * ldy + kc * 8;
+                if (Y2) {                           // gated pair (row-major only)
+                    bool valid;
+                    yp[j] = paired_row(Y, Y2, ldy, c0, lrow + 64 * j, rows_y, valid) + kc * 8;
+                    yv[j] = !GUARD || valid;
+                } else {
+                    yv[j] = !GUARD || gy < rows_y;
+                    yp[j] = Y + (int64_t)(yv[j] ? gy : 0) * ldy + kc * 8;
+                }
             }
         }
         // row-major: 16-byte chunk kc of row `row` lives at chunk slot kc ^ (row & 7) of its
@@ -376,7 +401,8 @@ struct DirectCoreT {
                                                 int /*rows_x*/, const uint16_t* __restrict__ Y,
                                                 int64_t ldy, int /*rows_y*/, int K, int r0, int c0,
                                                 unsigned char* smem, f32x16_t (&acc)[kMT][kNT],
-                                                const uint16_t* warm, int64_t warm_stride = kBlockK) {
+                                                const uint16_t* warm, int64_t warm_stride = kBlockK,
+                                                const uint16_t* Y2 = nullptr) {
         static_assert(!GUARD, "DirectCore has no bounds checks");
         typedef const __attribute__((address_space(1))) void* gptr_t;
         typedef __attribute__((address_space(3))) void* lptr_t;
@@ -404,7 +430,12 @@ struct DirectCoreT {
                 const int row = (w * 8 + q) * 8 + lr;
                 const int kc = pc ^ swz(row);
                 xg[q] = X + (int64_t)(r0 + row) * ldx + kc * 8;
-                yg[q] = Y + (int64_t)(c0 + row) * ldy + kc * 8;
+                if (Y2) {                           // gated pair (row-major only)
+                    bool valid;
+                    yg[q] = paired_row(Y, Y2, ldy, c0, row, 0x7fffffff, valid) + kc * 8;
+                } else {
+                    yg[q] = Y + (int64_t)(c0 + row) * ldy + kc * 8;
+                }
             }
         }
         // elements from one k-step's tile to the next

@@ -6,11 +6,12 @@
 // them.  Per tile of T rows, all contractions on the block GEMM of gemm_tile.h (operands with the
 // contraction index contiguous):
 //
-//   forward    gu = [x Wg^T | x Wu^T]         two launches into the halves of a [T, 2I] buffer
-//              a  = silu(g) * u               swiglu_fwd_kernel
+//   forward    a  = silu(x Wg^T) * (x Wu^T)   gated_kernel: both products in one block, SwiGLU in
+//                                             the epilogue, g and u never reach memory
 //              y  = a Wd^T
-//   backward   gu as above (recomputed), da = dy (Wd^T)^T with Wd^T made once per call
-//              a, [dg | du]                   swiglu_bwd_kernel, into the rows of the tile's group
+//   backward   da = dy (Wd^T)^T               Wd^T made once per call
+//              a, [dg | du]                   gated_kernel again (g and u recomputed), its epilogue
+//                                             reads da; written into the rows of the tile's group
 //              dx = [dg | du] [Wg^T | Wu^T]^T one launch, K = 2I, the transposed weights made once
 //   per group  dWg += dg^T x, dWu += du^T x, dWd += dy^T a   (fp32, contraction over the group's rows)
 //
@@ -36,7 +37,7 @@ constexpr int kMlpGroupMax = 8;
 struct MlpLayout {
     int64_t Tp, Kg;        // tile rows rounded up to 256; rows a weight-gradient group can hold
     int g;                 // tiles per weight-gradient group
-    size_t gu, a, da, dgu, wdt, wgut, acc_g, acc_u, acc_d, total;
+    size_t a, da, dgu, wdt, wgut, acc_g, acc_u, acc_d, total;
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -51,7 +52,6 @@ static MlpLayout make_mlp_layout(int64_t N, int64_t H, int64_t I, int64_t tile, 
     L.Kg = (int64_t)L.g * L.Tp;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
-    L.gu = take((size_t)L.Tp * 2 * I * 2);
     // backward keeps a and [dg | du] of the whole group, each tile behind the one before
     L.a = take((size_t)(backward ? L.Kg : L.Tp) * I * 2);
     if (backward) {
@@ -131,6 +131,118 @@ __global__ __launch_bounds__(Core::kThreads) void linear_kernel(const LinearBatc
     store_block_bf16<Core, GUARD>(acc, p.D, p.ldd, r0, c0, p.rows_out, p.cols_out, smem);
 }
 
+// Gate and up projections of a tile with the SwiGLU in the epilogue: the block's Y rows are the
+// gated pair (Wg, Wu) of gemm_tile.h, so every lane holds g and u of the same elements and neither
+// reaches memory.
+//   forward   a = silu(g) * u
+//   backward  also reads da and writes dg = da * u * silu'(g), du = da * silu(g) as [dg | du]
+// g and u enter the SwiGLU as the fp32 accumulators.
+struct GatedParams {
+    const uint16_t* X;       // [rows_x, ldx]   the tile's rows of x
+    const uint16_t* Wg;      // [I, ldw]
+    const uint16_t* Wu;      // [I, ldw]
+    const uint16_t* da;      // [rows_out, I]   backward
+    uint16_t* a;             // [rows_out, I]
+    uint16_t* dgu;           // [rows_out, 2I]  backward
+    int64_t ldx, ldw;
+    int rows_x, I, K;
+    int rows_out;            // rows written; those from rows_x on come out as zeros
+    PatchGrid grid;
+};
+
+template <class Core, bool GUARD, bool BWD>
+__global__ __launch_bounds__(Core::kThreads) void gated_kernel(const GatedParams p) {
+    constexpr int kMT = Core::kMT, kNT = Core::kNT;
+    static_assert(kMT == 4, "two accumulator tiles of g and two of u per wavefront");
+    extern __shared__ __align__(16) unsigned char smem[];
+    int P, w, tr, tc;
+    patch_of_block(blockIdx.x, P, w);
+    if (P >= p.grid.patches() || !tile_in_patch(p.grid, P, w, tr, tc)) return;
+    const int r0 = tr * kBlockR, c0 = tc * kBlockC;      // c0 / 2 = first of the block's 128 columns of I
+
+    f32x16_t acc[kMT][kNT];
+#pragma unroll
+    for (int mt = 0; mt < kMT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < kNT; ++nt)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
+
+    const uint16_t* warm = Core::kCanGuard ? nullptr
+                                           : warm_row(p.grid.PR, p.grid.PC, p.X, p.ldx, r0, tr, p.Wg,
+                                                      p.ldw, c0, tc, p.Wu);
+    Core::template gemm<GUARD>(p.X, p.ldx, p.rows_x, p.Wg, p.ldw, p.I, p.K, r0, c0, smem, acc, warm,
+                               kBlockK, p.Wu);
+
+    // Per wavefront and accumulator column nt: 32 rows x 64 columns of I.  Everything that goes to
+    // or comes from memory is turned around in the wavefront's own LDS region (as in
+    // store_block_bf16) so that global accesses are whole 128-byte row segments.
+    const typename Core::Lane lp;
+    unsigned char* const tw = smem + (threadIdx.x >> 6) * (32 * kTurnPitch);
+    const int lrow = lp.lane >> 3, lcol = lp.lane & 7;             // 8 rows x 8 chunks of 16 B
+    const int gc = (c0 >> 1) + lp.wc * 64 + lcol * 8;              // this lane's 8 columns of I
+    const bool col_ok = !GUARD || gc + 8 <= p.I;
+    const u32x4_t zero4 = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int nt = 0; nt < kNT; ++nt) {
+        const int row0 = r0 + lp.rbase(nt);
+        // the lane's own elements: row l31, columns (mt & 1) * 32 + q * 8 + half * 4 + x
+        auto own = [&](int mt, int q) {
+            return tw + lp.l31 * kTurnPitch + (mt * 32 + q * 8 + lp.half * 4) * 2;
+        };
+        auto store_rows = [&](const bf16x4_t (&v)[2][4], uint16_t* dst, int64_t ld) {
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) *reinterpret_cast<bf16x4_t*>(own(mt, q)) = v[mt][q];
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const int row = it * 8 + lrow;
+                const u32x4_t val = *reinterpret_cast<const u32x4_t*>(tw + row * kTurnPitch + lcol * 16);
+                if (!GUARD || (row0 + row < p.rows_out && col_ok))
+                    *reinterpret_cast<u32x4_t*>(dst + (int64_t)(row0 + row) * ld + gc) = val;
+            }
+        };
+        bf16x4_t d[2][4];
+        if (BWD) {
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const int row = it * 8 + lrow;
+                const bool ok = !GUARD || (row0 + row < p.rows_out && col_ok);
+                const u32x4_t val = ok ? *reinterpret_cast<const u32x4_t*>(p.da + (int64_t)(row0 + row) * p.I + gc)
+                                       : zero4;
+                *reinterpret_cast<u32x4_t*>(tw + row * kTurnPitch + lcol * 16) = val;
+            }
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) d[mt][q] = *reinterpret_cast<const bf16x4_t*>(own(mt, q));
+        }
+        bf16x4_t oa[2][4], og[2][4], ou[2][4];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const float g = acc[mt][nt][q * 4 + x], u = acc[mt + 2][nt][q * 4 + x];
+                    const float sg = 1.f / (1.f + __expf(-g));
+                    const float silu = g * sg;
+                    oa[mt][q][x] = (__bf16)(silu * u);
+                    if (BWD) {
+                        const float dd = (float)d[mt][q][x];
+                        og[mt][q][x] = (__bf16)(dd * u * (sg * (1.f + g * (1.f - sg))));
+                        ou[mt][q][x] = (__bf16)(dd * silu);
+                    }
+                }
+        store_rows(oa, p.a, p.I);
+        if (BWD) {
+            store_rows(og, p.dgu, 2 * (int64_t)p.I);
+            store_rows(ou, p.dgu + p.I, 2 * (int64_t)p.I);
+        }
+    }
+}
+
 struct WgradParams {
     const uint16_t* X;       // [K, ldx]        r (columns 0 .. rows_x): the contiguous index of `out`
     const uint16_t* Y;       // [K, ldy]        c (columns 0 .. rows_y): the row index of `out`
@@ -171,65 +283,6 @@ __global__ __launch_bounds__(Core::kThreads) void wgrad_kernel(const WgradBatch 
     accumulate_block_f32<Core, GUARD>(acc, p.out, p.ld, r0, c0, p.rows_x, p.rows_y, p.first != 0);
 }
 
-__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
-
-// a = silu(g) * u over `rows` rows; gu is [rows, 2I] with g in the first I columns, u in the last.
-__global__ __launch_bounds__(256) void swiglu_fwd_kernel(const uint16_t* __restrict__ gu,
-                                                         uint16_t* __restrict__ a, int64_t rows,
-                                                         int I) {
-    const int64_t chunks_per_row = I / 8, n = rows * chunks_per_row;
-    for (int64_t ch = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; ch < n;
-         ch += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t row = ch / chunks_per_row;
-        const int col = (int)(ch % chunks_per_row) * 8;
-        const u32x4_t gv = *reinterpret_cast<const u32x4_t*>(gu + row * 2 * I + col);
-        const u32x4_t uv = *reinterpret_cast<const u32x4_t*>(gu + row * 2 * I + I + col);
-        const uint16_t* ge = reinterpret_cast<const uint16_t*>(&gv);
-        const uint16_t* ue = reinterpret_cast<const uint16_t*>(&uv);
-        bf16x8_t o;
-#pragma unroll
-        for (int x = 0; x < 8; ++x) {
-            const float g = bf16_to_f32(ge[x]), u = bf16_to_f32(ue[x]);
-            const float s = 1.f / (1.f + __expf(-g));
-            o[x] = (__bf16)(g * s * u);
-        }
-        *reinterpret_cast<bf16x8_t*>(a + row * I + col) = o;
-    }
-}
-
-// a = silu(g) * u,  dg = da * u * silu'(g),  du = da * silu(g);  dgu is [rows, 2I] = [dg | du].
-__global__ __launch_bounds__(256) void swiglu_bwd_kernel(const uint16_t* __restrict__ gu,
-                                                         const uint16_t* __restrict__ da,
-                                                         uint16_t* __restrict__ a,
-                                                         uint16_t* __restrict__ dgu, int64_t rows,
-                                                         int I) {
-    const int64_t chunks_per_row = I / 8, n = rows * chunks_per_row;
-    for (int64_t ch = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; ch < n;
-         ch += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t row = ch / chunks_per_row;
-        const int col = (int)(ch % chunks_per_row) * 8;
-        const u32x4_t gv = *reinterpret_cast<const u32x4_t*>(gu + row * 2 * I + col);
-        const u32x4_t uv = *reinterpret_cast<const u32x4_t*>(gu + row * 2 * I + I + col);
-        const u32x4_t dv = *reinterpret_cast<const u32x4_t*>(da + row * I + col);
-        const uint16_t* ge = reinterpret_cast<const uint16_t*>(&gv);
-        const uint16_t* ue = reinterpret_cast<const uint16_t*>(&uv);
-        const uint16_t* de = reinterpret_cast<const uint16_t*>(&dv);
-        bf16x8_t oa, og, ou;
-#pragma unroll
-        for (int x = 0; x < 8; ++x) {
-            const float g = bf16_to_f32(ge[x]), u = bf16_to_f32(ue[x]), d = bf16_to_f32(de[x]);
-            const float s = 1.f / (1.f + __expf(-g));
-            const float sg = g * s;
-            oa[x] = (__bf16)(sg * u);
-            og[x] = (__bf16)(d * u * (s * (1.f + g * (1.f - s))));
-            ou[x] = (__bf16)(d * sg);
-        }
-        *reinterpret_cast<bf16x8_t*>(a + row * I + col) = oa;
-        *reinterpret_cast<bf16x8_t*>(dgu + row * 2 * I + col) = og;
-        *reinterpret_cast<bf16x8_t*>(dgu + row * 2 * I + I + col) = ou;
-    }
-}
-
 // out = sums (bf16 or fp32, overwrite or +=).  `sums` may alias `out` (fp32 overwrite mode).
 template <bool OUT_F32, bool ACCUM>
 __global__ void convert_sums_kernel(const float* sums, void* out, int64_t n4) {
@@ -267,6 +320,10 @@ static int prepare_mlp_kernels() {
     auto acc = [&](int r) { if (r != ALST_OK) rc = r; };
     acc(allow_big_lds(linear_kernel<DirectCore, false>));
     acc(allow_big_lds(linear_kernel<StagedCore, true>));
+    acc(allow_big_lds(gated_kernel<DirectCore, false, false>));
+    acc(allow_big_lds(gated_kernel<StagedCore, true, false>));
+    acc(allow_big_lds(gated_kernel<DirectCore, false, true>));
+    acc(allow_big_lds(gated_kernel<StagedCore, true, true>));
     acc(allow_big_lds(wgrad_kernel<KMajorCore, false>));
     acc(allow_big_lds(wgrad_kernel<StagedKMajorCore, true>));
     states[dev] = rc + 1;
@@ -365,11 +422,6 @@ static int launch_transpose(const uint16_t* in, int64_t ld_in, int R, int C, uin
     return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
 }
 
-static int elementwise_blocks(int64_t chunks) {
-    int64_t b = (chunks + 255) / 256;
-    return (int)(b > 16384 ? 16384 : (b < 1 ? 1 : b));
-}
-
 struct MlpProblem {
     const uint16_t *x, *Wg, *Wu, *Wd, *dy;
     uint16_t *y, *dx;
@@ -400,19 +452,31 @@ static int validate_mlp(const MlpProblem& P, size_t workspace_bytes, bool backwa
     return ALST_OK;
 }
 
-// gu = [x_t Wg^T | x_t Wu^T] for the tile's T_cur rows (rows up to Tr come out as zeros), in one
-// launch together with `extra` (backward: da = dy_t Wd), if given.
-static int gate_up(const MlpProblem& P, const uint16_t* x_t, int T_cur, int Tr, uint16_t* gu,
-                   const LinearParams* extra, hipStream_t s) {
-    const int H = (int)P.H, I = (int)P.I;
-    LinearParams lp[kMaxBatch] = {};
-    lp[0].X = x_t; lp[0].ldx = H; lp[0].rows_x = T_cur; lp[0].K = H;
-    lp[0].ldy = H; lp[0].rows_y = I; lp[0].ldd = 2 * (int64_t)I; lp[0].rows_out = Tr; lp[0].cols_out = I;
-    lp[0].Y = P.Wg; lp[0].D = gu;
-    lp[1] = lp[0];
-    lp[1].Y = P.Wu; lp[1].D = gu + I;
-    if (extra) lp[2] = *extra;
-    return launch_linear(lp, extra ? 3 : 2, s);
+// a = silu(x_t Wg^T) * (x_t Wu^T) for the tile's T_cur rows (rows up to Tr come out as zeros);
+// backward (da given): also [dg | du].
+static int launch_gated(const MlpProblem& P, const uint16_t* x_t, int T_cur, int Tr,
+                        const uint16_t* da, uint16_t* a, uint16_t* dgu, hipStream_t s) {
+    GatedParams gp = {};
+    gp.X = x_t; gp.ldx = P.H; gp.rows_x = T_cur; gp.K = (int)P.H;
+    gp.Wg = P.Wg; gp.Wu = P.Wu; gp.ldw = P.H; gp.I = (int)P.I;
+    gp.da = da; gp.a = a; gp.dgu = dgu; gp.rows_out = Tr;
+    gp.grid = choose_patches(Tr / kBlockR, (int)((P.I + 127) / 128));
+    const int blocks = grid_for_patches(gp.grid.patches());
+    const bool direct = T_cur % kBlockR == 0 && P.I % 128 == 0 && P.H % kBlockK == 0;
+    ProfScope pr(PROF_MLP_LINEAR, s);
+    if (direct && da)
+        hipLaunchKernelGGL((gated_kernel<DirectCore, false, true>), dim3((unsigned)blocks),
+                           dim3(DirectCore::kThreads), kLdsBytes, s, gp);
+    else if (direct)
+        hipLaunchKernelGGL((gated_kernel<DirectCore, false, false>), dim3((unsigned)blocks),
+                           dim3(DirectCore::kThreads), kLdsBytes, s, gp);
+    else if (da)
+        hipLaunchKernelGGL((gated_kernel<StagedCore, true, true>), dim3((unsigned)blocks),
+                           dim3(StagedCore::kThreads), kLdsBytes, s, gp);
+    else
+        hipLaunchKernelGGL((gated_kernel<StagedCore, true, false>), dim3((unsigned)blocks),
+                           dim3(StagedCore::kThreads), kLdsBytes, s, gp);
+    return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
 }
 
 static int run_mlp_forward(const MlpProblem& P) {
@@ -420,7 +484,6 @@ static int run_mlp_forward(const MlpProblem& P) {
     if (rc != ALST_OK) return rc;
     const MlpLayout L = make_mlp_layout(P.N, P.H, P.I, P.tile, false, P.flags);
     hipStream_t s = P.stream;
-    uint16_t* gu = reinterpret_cast<uint16_t*>(P.ws + L.gu);
     uint16_t* a = reinterpret_cast<uint16_t*>(P.ws + L.a);
     const int H = (int)P.H, I = (int)P.I;
     const int64_t T = P.tile < P.N ? P.tile : P.N;
@@ -429,14 +492,8 @@ static int run_mlp_forward(const MlpProblem& P) {
         const int64_t i0 = t * T;
         const int T_cur = (int)((P.N - i0) < T ? (P.N - i0) : T);
         const int Tr = (T_cur + kBlockR - 1) / kBlockR * kBlockR;
-        rc = gate_up(P, P.x + i0 * P.H, T_cur, Tr, gu, nullptr, s);
+        rc = launch_gated(P, P.x + i0 * P.H, T_cur, Tr, nullptr, a, nullptr, s);
         if (rc != ALST_OK) return rc;
-        {
-            ProfScope ps(PROF_MLP_OTHER, s);
-            hipLaunchKernelGGL(swiglu_fwd_kernel, dim3(elementwise_blocks((int64_t)Tr * I / 8)),
-                               dim3(256), 0, s, gu, a, (int64_t)Tr, I);
-            ALST_HIP(hipGetLastError());
-        }
         LinearParams lp = {};
         lp.X = a; lp.ldx = I; lp.rows_x = Tr; lp.K = I;
         lp.Y = P.Wd; lp.ldy = I; lp.rows_y = H;
@@ -460,7 +517,6 @@ static int run_mlp_backward(const MlpProblem& P) {
     if (rc != ALST_OK) return rc;
     const MlpLayout L = make_mlp_layout(P.N, P.H, P.I, P.tile, true, P.flags);
     hipStream_t s = P.stream;
-    uint16_t* gu = reinterpret_cast<uint16_t*>(P.ws + L.gu);
     uint16_t* a = reinterpret_cast<uint16_t*>(P.ws + L.a);
     uint16_t* da = reinterpret_cast<uint16_t*>(P.ws + L.da);
     uint16_t* dgu = reinterpret_cast<uint16_t*>(P.ws + L.dgu);
@@ -499,19 +555,14 @@ static int run_mlp_backward(const MlpProblem& P) {
         uint16_t* a_t = a + (int64_t)kofs * I;
         uint16_t* dgu_t = dgu + (int64_t)kofs * I2;
 
-        {   // g, u again, and da = dy_t Wd (contraction over H), one launch
+        {   // da = dy_t Wd (contraction over H), then g and u again with a, dg, du made in the epilogue
             LinearParams lp = {};
             lp.X = dy_t; lp.ldx = H; lp.rows_x = T_cur; lp.K = H;
             lp.Y = wdt; lp.ldy = H; lp.rows_y = I;
             lp.D = da; lp.ldd = I; lp.rows_out = Tr; lp.cols_out = I;
-            rc = gate_up(P, x_t, T_cur, Tr, gu, &lp, s);
+            rc = launch_linear(lp, s);
+            if (rc == ALST_OK) rc = launch_gated(P, x_t, T_cur, Tr, da, a_t, dgu_t, s);
             if (rc != ALST_OK) return rc;
-        }
-        {
-            ProfScope ps(PROF_MLP_OTHER, s);
-            hipLaunchKernelGGL(swiglu_bwd_kernel, dim3(elementwise_blocks((int64_t)Tr * I / 8)),
-                               dim3(256), 0, s, gu, da, a_t, dgu_t, (int64_t)Tr, I);
-            ALST_HIP(hipGetLastError());
         }
         {   // dx = [dg | du] [Wg^T | Wu^T]^T: contraction over 2I
             LinearParams lp = {};
