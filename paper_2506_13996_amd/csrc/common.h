@@ -33,14 +33,11 @@ struct ProfScope {
 };
 
 // out[c][r] = in[r][c] for r < R, 0 for R <= r < Rpad; c < C.  16-byte accesses on both sides.
-// With `dyn_rows` the row extent (both R and Rpad) is read from the device instead, and with
-// `dyn_ofs` the output starts that many elements further along its rows.
+// (The weights of the products that contract over their row index, once per call.)
 static __global__ __launch_bounds__(256) void transpose_pad_kernel(
     const uint16_t* __restrict__ in, int64_t ld_in, int R, int C, uint16_t* __restrict__ out,
-    int64_t ld_out, int Rpad, const int* __restrict__ dyn_rows, const int* __restrict__ dyn_ofs) {
+    int64_t ld_out, int Rpad) {
     __shared__ uint16_t t[64][66];
-    if (dyn_rows) R = Rpad = *dyn_rows;
-    if (dyn_ofs) out += *dyn_ofs;
     const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
     if (r0 >= Rpad) return;
     const int tid = threadIdx.x;

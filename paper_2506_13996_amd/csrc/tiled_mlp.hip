@@ -418,7 +418,7 @@ static int launch_transpose(const uint16_t* in, int64_t ld_in, int R, int C, uin
     dim3 grid((Rpad + 63) / 64, (C + 63) / 64);
     if (grid.y > 65535u) return ALST_ERR_SHAPE;
     hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, s, in, ld_in, R, C, out, ld_out,
-                       Rpad, (const int*)nullptr, (const int*)nullptr);
+                       Rpad);
     return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
 }
 
