@@ -1,0 +1,73 @@
+"""How much of the 2e-2 gradient bar does storing dZ as bfloat16 use up?  (CPU study.)
+
+The HIP path keeps a tile's softmax in a bf16 [T, V] scratch: e = bf16(exp(z - group max)) and then
+dZ = bf16(e * factor - onehot), which is the operand of both gradient products; the products
+accumulate in fp32 and the gradients are returned as bf16.  This test emulates those roundings on
+top of the fp64 oracle's logits (numpy only, nothing of the HIP library) and compares the
+gradients with the oracle's, against the same measure the GPU parity tests use
+(max |got - ref| / max |ref|):
+
+  * fp32 dZ, bf16 outputs      -- the floor set by rounding the returned gradients
+  * bf16 e and bf16 dZ, bf16 outputs  -- what the library stores
+
+Both must stay an order of magnitude inside the 2e-2 bar, and the bf16 storage may not cost more
+than a small multiple of the output-rounding floor: there is no accuracy reason to spend twice the
+HBM bytes on an fp32 dZ.
+"""
+import numpy as np
+import pytest
+
+from oracle import tiled_ce_oracle as orc
+from paper_2506_13996_amd import synth
+
+BAR = 2e-2
+
+
+def _bf16(x):
+    """Round float64 values to bfloat16 (round to nearest even), returned as float64."""
+    return orc.bf16_bits_to_f64(synth.f32_to_bf16_bits(np.asarray(x, dtype=np.float32)))
+
+
+def _err(got, ref):
+    return float(np.max(np.abs(got - ref)) / np.max(np.abs(ref)))
+
+
+def _grads(h, W, dz):
+    return dz @ W, dz.T @ h
+
+
+@pytest.mark.parametrize("w_std", [0.02, 0.5], ids=["flat_softmax", "peaked_softmax"])
+def test_bf16_dz_costs_little_against_the_bar(w_std):
+    N, H, V = 384, 256, 2048
+    wl = synth.custom("dzstudy", N, H, V, 128, ignore_frac=0.1, seed=11)
+    h_bits, _, labels = synth.make_inputs(wl)
+    W_bits = synth.normal_bf16(V, H, w_std, 11, synth.STREAM_W)
+    h, W = orc.bf16_bits_to_f64(h_bits), orc.bf16_bits_to_f64(W_bits)
+    ref_dh, ref_dw = orc.backward(h_bits, W_bits, labels)[:2]
+
+    z = orc.logits(h_bits, W_bits)
+    lse = orc.row_lse(z)
+    valid = labels != -100
+    M = int(valid.sum())
+    onehot = np.zeros_like(z)
+    onehot[np.nonzero(valid)[0], labels[valid]] = 1.0
+
+    # (1) dZ kept in fp32, gradients rounded to bf16 on output
+    dz32 = (np.exp(z - lse[:, None]) - onehot).astype(np.float32).astype(np.float64) * valid[:, None]
+    dh, dw = _grads(h, W, dz32)
+    floor = max(_err(_bf16(dh / M), ref_dh), _err(_bf16(dw / M), ref_dw))
+
+    # (2) what the library stores: e relative to the max of its 128-column group as bf16, then
+    #     dZ = bf16(e * exp(group max - lse) - onehot)
+    zg = z.reshape(N, V // 128, 128)
+    gmax = zg.max(axis=2, keepdims=True)
+    e = _bf16(np.exp(zg - gmax))
+    factor = np.exp(gmax - lse[:, None, None]).astype(np.float32).astype(np.float64)
+    dz16 = _bf16((e * factor).reshape(N, V) - onehot) * valid[:, None]
+    dh, dw = _grads(h, W, dz16)
+    stored = max(_err(_bf16(dh / M), ref_dh), _err(_bf16(dw / M), ref_dw))
+
+    print(f"w_std {w_std}: fp32 dZ {floor:.2e}   bf16 e + bf16 dZ {stored:.2e}   bar {BAR:.0e}")
+    assert floor < BAR / 5
+    assert stored < BAR / 5
+    assert stored < 3 * floor + 1e-3
