@@ -11,8 +11,10 @@
  *
  * bf16 operands, fp32 accumulation; dW is accumulated over the tiles in fp32.  Conventions are
  * those of alst.h (device pointers, dense row-major, K and M multiples of 8, 16-byte aligned base
- * pointers, caller-owned workspace, asynchronous on `stream`, alst_status return values).  The
- * forward pass needs no workspace (`workspace` may be NULL).
+ * pointers, caller-owned workspace, asynchronous on `stream`, alst_status return values).  x, W
+ * and dy are read as they are by every product (nothing is copied or transposed), so the forward
+ * pass needs no workspace and the backward pass only the fp32 dW sums (4 M K bytes; none with
+ * fp32 overwrite output, whose sums live in dW).  `workspace` may be NULL when none is needed.
  */
 #ifndef ALST_LINEAR_H
 #define ALST_LINEAR_H
@@ -24,7 +26,7 @@ extern "C" {
 #endif
 
 /* Bytes of device scratch for forward (backward = 0: always 0) or backward (backward = 1);
- * independent of N.  Pure host arithmetic; 0 also for an invalid shape. */
+ * independent of N and of the tile.  Pure host arithmetic; 0 also for an invalid shape. */
 size_t alst_tiled_linear_workspace_bytes(int64_t N, int64_t K, int64_t M, int64_t tile, int backward,
                                          uint32_t flags);
 

@@ -38,7 +38,7 @@ extern "C" {
 /*
  * Bytes of device scratch alst_tiled_mlp_forward (backward = 0) or alst_tiled_mlp_backward
  * (backward = 1) needs, 0 if the shape is invalid.  Pure host arithmetic.  Independent of N:
- * O(tile * I) for the tile's activations, plus O(H * I) for transposed weights and fp32
+ * O(tile * I) for the activations of the tiles in flight, plus O(H * I) for the fp32
  * weight-gradient sums in backward.
  */
 size_t alst_tiled_mlp_workspace_bytes(int64_t N, int64_t H, int64_t I, int64_t tile, int backward,

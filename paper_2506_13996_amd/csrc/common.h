@@ -1,5 +1,4 @@
-// Pieces shared by the translation units of libalst: error macro, per-kernel timing, the padded
-// transpose.
+// Pieces shared by the translation units of libalst: error macro, per-kernel timing, launch helpers.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -31,42 +30,6 @@ struct ProfScope {
     ProfScope(int kind, hipStream_t stream);
     ~ProfScope();
 };
-
-// out[c][r] = in[r][c] for r < R, 0 for R <= r < Rpad; c < C.  16-byte accesses on both sides.
-// (The weights of the products that contract over their row index, once per call.)
-static __global__ __launch_bounds__(256) void transpose_pad_kernel(
-    const uint16_t* __restrict__ in, int64_t ld_in, int R, int C, uint16_t* __restrict__ out,
-    int64_t ld_out, int Rpad) {
-    __shared__ uint16_t t[64][66];
-    const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-    if (r0 >= Rpad) return;
-    const int tid = threadIdx.x;
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int chunk = tid + 256 * q;
-        const int row = chunk >> 3, cc = chunk & 7;
-        const int r = r0 + row, c = c0 + cc * 8;
-        u32x4_t v = {0u, 0u, 0u, 0u};
-        if (r < R && c + 8 <= C) v = *reinterpret_cast<const u32x4_t*>(in + (int64_t)r * ld_in + c);
-        const uint16_t* e = reinterpret_cast<const uint16_t*>(&v);
-#pragma unroll
-        for (int x = 0; x < 8; ++x) t[row][cc * 8 + x] = e[x];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        const int chunk = tid + 256 * q;
-        const int crow = chunk >> 3, rc = chunk & 7;
-        const int c = c0 + crow, r = r0 + rc * 8;
-        if (c < C && r + 8 <= Rpad) {
-            u32x4_t v;
-            uint16_t* e = reinterpret_cast<uint16_t*>(&v);
-#pragma unroll
-            for (int x = 0; x < 8; ++x) e[x] = t[rc * 8 + x][crow];
-            *reinterpret_cast<u32x4_t*>(out + (int64_t)c * ld_out + r) = v;
-        }
-    }
-}
 
 // The attribute below is per device: the first call on each device (up to kMaxDevices) sets it.
 constexpr int kMaxDevices = 64;

@@ -21,6 +21,8 @@
 //               which is how the weight-gradient products meet their operands (k = token row):
 //               the DMA lands k-rows in LDS as they are and the MFMA operands are formed by the
 //               transposing LDS read (ds_read_b64_tr_b16), so no transposed copy is ever written.
+//   MixedCore   X k-contiguous, Y k-major: D[r][c] = sum_k X[r][k] * Y[k][c], a product with a
+//               weight matrix over its row index (dH = dZ W, da = dy Wd, dx = dg Wg + du Wu).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -176,6 +178,24 @@ __device__ __forceinline__ const uint16_t* warm_line_kmajor(int PR, int PC, cons
     return Y + (int64_t)(L >> 2) * ldy + c0 + (L & 3) * 64;
 }
 
+// X k-contiguous (its lines are rows), Y k-major.
+__device__ __forceinline__ const uint16_t* warm_line_mixed(int PR, int PC, const uint16_t* X,
+                                                           int64_t ldx, int r0, int tr,
+                                                           const uint16_t* Y, int64_t ldy, int c0,
+                                                           int tc, int64_t& step) {
+    const int nx = kBlockR / PC, ny = kBlockC / PR, total = nx + ny, per = (total + 3) / 4;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int l = w * per + (lane < per ? lane : per - 1);
+    if (l > total - 1) l = total - 1;
+    if (l < nx) {
+        step = kBlockK;
+        return X + (int64_t)(r0 + (tc % PC) * nx + l) * ldx;
+    }
+    const int L = (tr % PR) * ny + (l - nx);
+    step = ldy * kBlockK;
+    return Y + (int64_t)(L >> 2) * ldy + c0 + (L & 3) * 64;
+}
+
 // ---------------------------------------------------------------------------------------------
 // StagedCore: 8 wavefronts, register staging, optional bounds checks
 // ---------------------------------------------------------------------------------------------
@@ -204,7 +224,8 @@ __device__ __forceinline__ int kmajor_lane_offset(int lane, int gran) {
     return (8 * half + (sl >> 2)) * 512 + ((gran ^ f) * 64) + b1 * 32 + (sl & 3) * 8;
 }
 
-template <bool KM>
+// XK / YK: that operand is k-major.
+template <bool XK, bool YK>
 struct StagedCoreT {
     static constexpr int kThreads = 512;
     static constexpr int kMT = 4;     // 32-wide c tiles per wavefront
@@ -235,9 +256,12 @@ struct StagedCoreT {
 
     // acc[mt][nt] += X-block(r0) * Y-block(c0)^T over all of K.
     // GUARD = false requires r0 + 256 <= rows_x, c0 + 256 <= rows_y and K % 64 == 0.
-    // GUARD = true zero-fills rows beyond rows_x / rows_y and k beyond K (K % 8 == 0 required).
-    // KM: X is [K][ldx] and the block takes its columns r0 .. r0 + 255 (rows_x = number of
-    // columns, a multiple of 8), Y likewise; any K.
+    // GUARD = true zero-fills outside the operands.  A k-contiguous operand is [rows][ld] with
+    // its rows beyond rows_x / rows_y and its k beyond K read as zero (K % 8 == 0 required); a
+    // k-major operand is [K][ld], the block takes its columns r0 .. r0 + 255 (c0 ..), rows_x
+    // (rows_y) is its number of columns (a multiple of 8), and any K goes.  K_y, if given, is the
+    // k extent of Y where that is shorter than the loop's K (X zero-padded along k, Y not).
+    // Y2: gated pair, see paired_row (k-contiguous Y only).
     template <bool GUARD>
     static __device__ __forceinline__ void gemm(const uint16_t* __restrict__ X, int64_t ldx,
                                                 int rows_x, const uint16_t* __restrict__ Y,
@@ -245,42 +269,48 @@ struct StagedCoreT {
                                                 unsigned char* smem, f32x16_t (&acc)[kMT][kNT],
                                                 const uint16_t* /*warm*/ = nullptr,
                                                 int64_t /*warm_stride*/ = 0,
-                                                const uint16_t* Y2 = nullptr) {
+                                                const uint16_t* Y2 = nullptr, int K_y = -1) {
         const int tid = threadIdx.x;
         const Lane lp;
-        // row-major: thread -> (row inside a 64-row slab of the operand tile, 16-byte chunk along
-        // k), slab j;  KM: thread -> (k-row tid / 32 + 16 j, 16-byte chunk of 8 columns tid % 32)
-        const int lrow = KM ? (tid >> 5) : (tid >> 3);
-        const int kc = KM ? (tid & 31) : (tid & 7);
+        if (K_y < 0) K_y = K;
+        // k-contiguous operand: thread -> (row tid / 8 inside a 64-row slab of the tile, 16-byte
+        // chunk tid % 8 along k), slab j = 0..3;  k-major operand: thread -> (k-row tid / 32 + 16 j,
+        // 16-byte chunk of 8 columns tid % 32)
+        const int xrow = XK ? (tid >> 5) : (tid >> 3), xch = XK ? (tid & 31) : (tid & 7);
+        const int yrow = YK ? (tid >> 5) : (tid >> 3), ych = YK ? (tid & 31) : (tid & 7);
 
         const uint16_t* xp[4];
         const uint16_t* yp[4];
         bool xv[4], yv[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            if (KM) {
-                xv[j] = !GUARD || r0 + kc * 8 < rows_x;
-                yv[j] = !GUARD || c0 + kc * 8 < rows_y;
-                xp[j] = X + (int64_t)(lrow + 16 * j) * ldx + (xv[j] ? r0 + kc * 8 : 0);
-                yp[j] = Y + (int64_t)(lrow + 16 * j) * ldy + (yv[j] ? c0 + kc * 8 : 0);
+            if (XK) {
+                xv[j] = !GUARD || r0 + xch * 8 < rows_x;
+                xp[j] = X + (int64_t)(xrow + 16 * j) * ldx + (xv[j] ? r0 + xch * 8 : 0);
             } else {
-                const int gx = r0 + lrow + 64 * j, gy = c0 + lrow + 64 * j;
+                const int gx = r0 + xrow + 64 * j;
                 xv[j] = !GUARD || gx < rows_x;
-                xp[j] = X + (int64_t)(xv[j] ? gx : 0) * ldx + kc * 8;
-                if (Y2) {                           // gated pair (row-major only)
-                    bool valid;
-                    yp[j] = paired_row(Y, Y2, ldy, c0, lrow + 64 * j, rows_y, valid) + kc * 8;
-                    yv[j] = !GUARD || valid;
-                } else {
-                    yv[j] = !GUARD || gy < rows_y;
-                    yp[j] = Y + (int64_t)(yv[j] ? gy : 0) * ldy + kc * 8;
-                }
+                xp[j] = X + (int64_t)(xv[j] ? gx : 0) * ldx + xch * 8;
+            }
+            if (YK) {
+                yv[j] = !GUARD || c0 + ych * 8 < rows_y;
+                yp[j] = Y + (int64_t)(yrow + 16 * j) * ldy + (yv[j] ? c0 + ych * 8 : 0);
+            } else if (Y2) {
+                bool valid;
+                yp[j] = paired_row(Y, Y2, ldy, c0, yrow + 64 * j, rows_y, valid) + ych * 8;
+                yv[j] = !GUARD || valid;
+            } else {
+                const int gy = c0 + yrow + 64 * j;
+                yv[j] = !GUARD || gy < rows_y;
+                yp[j] = Y + (int64_t)(yv[j] ? gy : 0) * ldy + ych * 8;
             }
         }
-        // row-major: 16-byte chunk kc of row `row` lives at chunk slot kc ^ (row & 7) of its
-        // 128-byte row (+ j * 64 rows * 128 B);  KM: see kswz (+ j * 16 k-rows * 512 B)
-        const int wofs = KM ? lrow * 512 + ((kc ^ (kswz(lrow) << 2)) * 16)
-                            : (lrow * 8 + (kc ^ (lrow & 7))) * 16;
+        // k-contiguous tile: 16-byte chunk kc of row `row` lives at chunk slot kc ^ (row & 7) of
+        // its 128-byte row (+ j * 64 rows * 128 B);  k-major tile: see kswz (+ j * 16 k-rows * 512 B)
+        const int xwofs = XK ? xrow * 512 + ((xch ^ (kswz(xrow) << 2)) * 16)
+                             : (xrow * 8 + (xch ^ (xrow & 7))) * 16;
+        const int ywofs = YK ? yrow * 512 + ((ych ^ (kswz(yrow) << 2)) * 16)
+                             : (yrow * 8 + (ych ^ (yrow & 7))) * 16;
         int rofs[4], xofs[kNT], yofs[kMT];
 #pragma unroll
         for (int s = 0; s < 4; ++s) rofs[s] = ((2 * s + lp.half) ^ (lp.lane & 7)) * 16;
@@ -299,27 +329,29 @@ struct StagedCoreT {
 
         auto load_global = [&](int kt) {
             const int koff = kt * kBlockK;
-            if (KM) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const bool kok = !GUARD || (koff + lrow + 16 * j < K);
-                    xg[j] = (xv[j] && kok) ? *reinterpret_cast<const u32x4_t*>(xp[j] + (int64_t)koff * ldx) : zero4;
-                    yg[j] = (yv[j] && kok) ? *reinterpret_cast<const u32x4_t*>(yp[j] + (int64_t)koff * ldy) : zero4;
-                }
-                return;
-            }
-            const bool kok = !GUARD || (koff + kc * 8 + 8 <= K);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                xg[j] = (xv[j] && kok) ? *reinterpret_cast<const u32x4_t*>(xp[j] + koff) : zero4;
-                yg[j] = (yv[j] && kok) ? *reinterpret_cast<const u32x4_t*>(yp[j] + koff) : zero4;
+                if (XK) {
+                    const bool kok = !GUARD || (koff + xrow + 16 * j < K);
+                    xg[j] = (xv[j] && kok) ? *reinterpret_cast<const u32x4_t*>(xp[j] + (int64_t)koff * ldx) : zero4;
+                } else {
+                    const bool kok = !GUARD || (koff + xch * 8 + 8 <= K);
+                    xg[j] = (xv[j] && kok) ? *reinterpret_cast<const u32x4_t*>(xp[j] + koff) : zero4;
+                }
+                if (YK) {
+                    const bool kok = !GUARD || (koff + yrow + 16 * j < K_y);
+                    yg[j] = (yv[j] && kok) ? *reinterpret_cast<const u32x4_t*>(yp[j] + (int64_t)koff * ldy) : zero4;
+                } else {
+                    const bool kok = !GUARD || (koff + ych * 8 + 8 <= K_y);
+                    yg[j] = (yv[j] && kok) ? *reinterpret_cast<const u32x4_t*>(yp[j] + koff) : zero4;
+                }
             }
         };
         auto store_lds = [&](int stage) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                *reinterpret_cast<u32x4_t*>(Xs + stage * kTileBytes + wofs + j * 8192) = xg[j];
-                *reinterpret_cast<u32x4_t*>(Ys + stage * kTileBytes + wofs + j * 8192) = yg[j];
+                *reinterpret_cast<u32x4_t*>(Xs + stage * kTileBytes + xwofs + j * 8192) = xg[j];
+                *reinterpret_cast<u32x4_t*>(Ys + stage * kTileBytes + ywofs + j * 8192) = yg[j];
             }
         };
 
@@ -339,11 +371,11 @@ struct StagedCoreT {
                 bf16x8_t yf[kMT], xf[kNT];
 #pragma unroll
                 for (int mt = 0; mt < kMT; ++mt)
-                    yf[mt] = KM ? read_kmajor(Ys + cur * kTileBytes + yofs[mt] + s * 8192)
+                    yf[mt] = YK ? read_kmajor(Ys + cur * kTileBytes + yofs[mt] + s * 8192)
                                 : *reinterpret_cast<const bf16x8_t*>(ys + mt * 4096 + rofs[s]);
 #pragma unroll
                 for (int nt = 0; nt < kNT; ++nt)
-                    xf[nt] = KM ? read_kmajor(Xs + cur * kTileBytes + xofs[nt] + s * 8192)
+                    xf[nt] = XK ? read_kmajor(Xs + cur * kTileBytes + xofs[nt] + s * 8192)
                                 : *reinterpret_cast<const bf16x8_t*>(xs + nt * 4096 + rofs[s]);
 #pragma unroll
                 for (int mt = 0; mt < kMT; ++mt)
@@ -357,13 +389,15 @@ struct StagedCoreT {
         }
     }
 };
-typedef StagedCoreT<false> StagedCore;
-typedef StagedCoreT<true> StagedKMajorCore;
+typedef StagedCoreT<false, false> StagedCore;
+typedef StagedCoreT<true, true> StagedKMajorCore;
+typedef StagedCoreT<false, true> StagedMixedCore;
 
 // ---------------------------------------------------------------------------------------------
 // DirectCore: 4 wavefronts, global -> LDS DMA, aligned shapes only
 // ---------------------------------------------------------------------------------------------
-template <bool KM>
+// XK / YK: that operand is k-major.
+template <bool XK, bool YK>
 struct DirectCoreT {
     static constexpr int kThreads = 256;
     static constexpr int kMT = 4;
@@ -393,8 +427,8 @@ struct DirectCoreT {
     static __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
     // Requires r0 + 256 <= rows of X, c0 + 256 <= rows of Y, K % 64 == 0, K >= 64, 16-byte
-    // aligned rows.  GUARD must be false (rows_x / rows_y are unused).  KM: X is [K][ldx] and the
-    // block takes its columns r0 .. r0 + 255, Y is [K][ldy] with columns c0 .. c0 + 255.
+    // aligned rows.  GUARD must be false (rows_x / rows_y are unused).  A k-major X is [K][ldx]
+    // and the block takes its columns r0 .. r0 + 255; a k-major Y is [K][ldy], columns c0 .. + 255.
     // warm_stride = elements between the lane's warm-up line of one k-step and the next.
     template <bool GUARD>
     static __device__ __forceinline__ void gemm(const uint16_t* __restrict__ X, int64_t ldx,
@@ -402,7 +436,7 @@ struct DirectCoreT {
                                                 int64_t ldy, int /*rows_y*/, int K, int r0, int c0,
                                                 unsigned char* smem, f32x16_t (&acc)[kMT][kNT],
                                                 const uint16_t* warm, int64_t warm_stride = kBlockK,
-                                                const uint16_t* Y2 = nullptr) {
+                                                const uint16_t* Y2 = nullptr, int /*K_y*/ = -1) {
         static_assert(!GUARD, "DirectCore has no bounds checks");
         typedef const __attribute__((address_space(1))) void* gptr_t;
         typedef __attribute__((address_space(3))) void* lptr_t;
@@ -414,32 +448,30 @@ struct DirectCoreT {
         // One DMA instruction moves 8 rows x 128 bytes: lane -> (row = lane / 8, LDS chunk slot =
         // lane % 8); the lane fetches the global chunk that belongs in its slot.  Wave w owns rows
         // [64 w, 64 w + 64) of both operand tiles: 8 instructions per operand per k-step.
-        // KM: one DMA instruction moves 2 k-rows x 512 bytes: lane -> (k-row = lane / 32, chunk
-        // slot = lane % 32); wave w owns k-rows [16 w, 16 w + 16) of both tiles.
+        // k-major: one DMA instruction moves 2 k-rows x 512 bytes: lane -> (k-row = lane / 32, chunk
+        // slot = lane % 32); wave w owns k-rows [16 w, 16 w + 16) of the tile.
         const int lr = lane >> 3, pc = lane & 7;
         const uint16_t* xg[8];
         const uint16_t* yg[8];
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-            if (KM) {
-                const int krow = w * 16 + q * 2 + (lane >> 5);
-                const int ch = (lane & 31) ^ (kswz(krow) << 2);
-                xg[q] = X + (int64_t)krow * ldx + r0 + ch * 8;
+            const int krow = w * 16 + q * 2 + (lane >> 5);
+            const int ch = (lane & 31) ^ (kswz(krow) << 2);
+            const int row = (w * 8 + q) * 8 + lr;
+            const int kc = pc ^ swz(row);
+            if (XK) xg[q] = X + (int64_t)krow * ldx + r0 + ch * 8;
+            else xg[q] = X + (int64_t)(r0 + row) * ldx + kc * 8;
+            if (YK) {
                 yg[q] = Y + (int64_t)krow * ldy + c0 + ch * 8;
+            } else if (Y2) {                        // gated pair (k-contiguous only)
+                bool valid;
+                yg[q] = paired_row(Y, Y2, ldy, c0, row, 0x7fffffff, valid) + kc * 8;
             } else {
-                const int row = (w * 8 + q) * 8 + lr;
-                const int kc = pc ^ swz(row);
-                xg[q] = X + (int64_t)(r0 + row) * ldx + kc * 8;
-                if (Y2) {                           // gated pair (row-major only)
-                    bool valid;
-                    yg[q] = paired_row(Y, Y2, ldy, c0, row, 0x7fffffff, valid) + kc * 8;
-                } else {
-                    yg[q] = Y + (int64_t)(c0 + row) * ldy + kc * 8;
-                }
+                yg[q] = Y + (int64_t)(c0 + row) * ldy + kc * 8;
             }
         }
         // elements from one k-step's tile to the next
-        const int64_t xstep = KM ? ldx * kBlockK : kBlockK, ystep = KM ? ldy * kBlockK : kBlockK;
+        const int64_t xstep = XK ? ldx * kBlockK : kBlockK, ystep = YK ? ldy * kBlockK : kBlockK;
         auto issue_loads = [&](int stage, int kt) {
             unsigned char* xs = smem + stage * kTileBytes + w * 8192;
             unsigned char* ys = smem + 2 * kTileBytes + stage * kTileBytes + w * 8192;
@@ -452,7 +484,7 @@ struct DirectCoreT {
             }
         };
 
-        // Operand reads.  Row-major tiles: one 16-byte read per operand.  KM: read_kmajor.
+        // Operand reads.  k-contiguous tiles: one 16-byte read per operand.  k-major: read_kmajor.
         int rofs[4], xofs[4], yofs[4];
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
@@ -468,14 +500,13 @@ struct DirectCoreT {
         // item 0..3: the Y operand of accumulator row t = item, 4..7: the X operand of column t
         auto read_item = [&](int stage, int s, int item) {
             const unsigned char* base = smem + stage * kTileBytes;
-            if (KM) {
-                if (item < 4) fy[s][item] = read_kmajor(base + yofs[item] + s * 8192);
-                else fx[s][item - 4] = read_kmajor(base + xofs[item - 4] + s * 8192);
-            } else if (item < 4)
-                fy[s][item] = *reinterpret_cast<const bf16x8_t*>(base + ybase + item * 4096 + rofs[s]);
+            if (item < 4)
+                fy[s][item] = YK ? read_kmajor(base + yofs[item] + s * 8192)
+                                 : *reinterpret_cast<const bf16x8_t*>(base + ybase + item * 4096 + rofs[s]);
             else
                 fx[s][item - 4] =
-                    *reinterpret_cast<const bf16x8_t*>(base + xbase + (item - 4) * 4096 + rofs[s]);
+                    XK ? read_kmajor(base + xofs[item - 4] + s * 8192)
+                       : *reinterpret_cast<const bf16x8_t*>(base + xbase + (item - 4) * 4096 + rofs[s]);
         };
         // the two MFMAs of slot i (0..7) of a quarter step on slice s
         auto mfma_pair = [&](int s, int i) {
@@ -574,8 +605,9 @@ struct DirectCoreT {
         kstep(kt, std::false_type{}, std::false_type{}, false);
     }
 };
-typedef DirectCoreT<false> DirectCore;
-typedef DirectCoreT<true> KMajorCore;
+typedef DirectCoreT<false, false> DirectCore;
+typedef DirectCoreT<true, true> KMajorCore;
+typedef DirectCoreT<false, true> MixedCore;
 
 // ---------------------------------------------------------------------------------------------
 // Epilogues shared by the kernels built on the two cores

@@ -26,9 +26,9 @@
 //                        group's dense rows, fp32)
 //
 // After the last tile: loss = sum(per-row loss) / M in a fixed order, dW = (g/M) acc.
-// The contractions share the block GEMM of gemm_tile.h: logits and dHidden with k-contiguous
-// operands (W^T is made once per call by a padded transpose), dW with the k-major cores, which
-// take the group's dense hidden rows and dZ rows as they are.
+// The contractions share the block GEMM of gemm_tile.h in its three operand layouts: logits with
+// both operands k-contiguous, dHidden with dZ k-contiguous and W k-major (as it is), dW with both
+// operands k-major (the group's dense hidden rows and dZ rows as they are).  Nothing is transposed.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <math.h>
@@ -79,7 +79,7 @@ struct Layout {
     int64_t Kg;            // dense rows a group can hold: g * Tp
     int splits, ksteps;    // dHidden: ranges of the contraction over V, k-steps per range
     size_t header, tinfo, loss_rows, lse, idx, block_cnt, block_ofs, zlabel, yc, pm, ps, sc, hc,
-        stash, wt, part, acc, total;
+        stash, part, acc, total;
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -88,9 +88,9 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 // contraction over V is cut into so that the workgroups fill the 256 compute units of the chip
 // most evenly (ties: fewest ranges), each range keeping at least 64 k-steps.
 constexpr int kComputeUnits = 256;
-static void dhidden_splits(int64_t Tp, int64_t H, int64_t Vp, int& splits, int& ksteps) {
+static void dhidden_splits(int64_t Tp, int64_t H, int64_t V, int& splits, int& ksteps) {
     const int64_t blocks = (Tp / kBlockR) * ((H + kBlockC - 1) / kBlockC);
-    const int KT = (int)(Vp / kBlockK);
+    const int KT = (int)((V + kBlockK - 1) / kBlockK);
     double best = -1.0;
     splits = 1;
     for (int sp = 1; sp <= 8; ++sp) {
@@ -131,8 +131,7 @@ static Layout make_layout(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_
     // the two operands of the group's dW product as they are (k = dense row, the slow index)
     L.hc = take((size_t)L.Kg * H * 2);
     L.stash = take((size_t)L.Kg * L.Vp * 2);
-    L.wt = take((size_t)H * L.Vp * 2);
-    dhidden_splits(L.Tp, H, L.Vp, L.splits, L.ksteps);
+    dhidden_splits(L.Tp, H, V, L.splits, L.ksteps);
     L.part = take(L.splits > 1 ? (size_t)L.splits * L.Tp * H * 4 : 0);
     const bool acc_in_dw = (flags & ALST_FLAG_DW_FP32) && !(flags & ALST_FLAG_DW_ACCUMULATE);
     L.acc = take(acc_in_dw ? 0 : (size_t)V * H * 4);
@@ -576,13 +575,13 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
 
 struct DHiddenParams {
     const uint16_t* dz;      // [Kg, Vp]     dense rows of the dW group; the tile starts at its k offset
-    const uint16_t* wt;      // [H, Vp]
+    const uint16_t* W;       // [V, H]       as it is: the k-major operand (k = vocabulary id)
     uint16_t* dH_t;          // [N, H]       whole dHidden; dense row i goes to row idx[i]
     const int32_t* idx;
     const TileInfo* info;
     const Header* hdr;
     float* part;             // [splits, Tp, H] fp32 partial products (splits > 1)
-    int Tp, H, Vp;
+    int Tp, H, V, Vp;
     int splits;              // the contraction over V is cut into this many ranges
     int ksteps;              // k-steps of 64 per range (the last range may be shorter)
     int PR, PC;              // patch shape of the block -> tile mapping
@@ -608,8 +607,9 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
     const int np = pg.patches(), split = P / np;
     if (split >= p.splits || !tile_in_patch(pg, P - split * np, w, tr, tc)) return;
     const int r0 = tr * kBlockR, c0 = tc * kBlockC;
+    // k runs over V rounded up to whole k-steps: dZ is zero there, rows of W beyond V are not read
     const int k0 = split * p.ksteps * kBlockK;
-    const int klen = min(p.ksteps * kBlockK, p.Vp - k0);        // > 0 by the host's choice of splits
+    const int klen = min(p.ksteps * kBlockK, (p.V + kBlockK - 1) / kBlockK * kBlockK - k0);   // > 0
 
     f32x16_t acc[kMT][kNT];
 #pragma unroll
@@ -620,10 +620,13 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
     const uint16_t* const dz = p.dz + (int64_t)p.info->kofs * p.Vp + k0;
+    const uint16_t* const Wk = p.W + (int64_t)k0 * p.H;
+    int64_t step = 0;
     const uint16_t* warm = Core::kCanGuard ? nullptr
-                                           : warm_row(p.PR, p.PC, dz, p.Vp, r0, tr, p.wt + k0,
-                                                      p.Vp, c0, tc);
-    Core::template gemm<GUARD>(dz, p.Vp, Trc, p.wt + k0, p.Vp, p.H, klen, r0, c0, smem, acc, warm);
+                                           : warm_line_mixed(p.PR, p.PC, dz, p.Vp, r0, tr, Wk, p.H, c0,
+                                                             tc, step);
+    Core::template gemm<GUARD>(dz, p.Vp, Trc, Wk, p.H, p.H, klen, r0, c0, smem, acc, warm, step, nullptr,
+                               p.V - k0);
 
     const typename Core::Lane lp;
     if (p.splits > 1) {
@@ -745,8 +748,8 @@ static int prepare_kernels() {
     acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_FUSED>));
     acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_BWD>));
     acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_BWD>));
-    acc(allow_big_lds(dhidden_kernel<DirectCore, false>));
-    acc(allow_big_lds(dhidden_kernel<StagedCore, true>));
+    acc(allow_big_lds(dhidden_kernel<MixedCore, false>));
+    acc(allow_big_lds(dhidden_kernel<StagedMixedCore, true>));
     acc(allow_big_lds(dw_kernel<KMajorCore, false>));
     acc(allow_big_lds(dw_kernel<StagedKMajorCore, true>));
     states[dev] = rc + 1;
@@ -797,14 +800,6 @@ static int validate(const Problem& P, size_t workspace_bytes, bool need_fwd_out,
     return ALST_OK;
 }
 
-static int launch_transpose(const uint16_t* in, int64_t ld_in, int R, int C, uint16_t* out,
-                            int64_t ld_out, int Rpad, hipStream_t s) {
-    dim3 grid((Rpad + 63) / 64, (C + 63) / 64);
-    hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, s, in, ld_in, R, C, out, ld_out,
-                       Rpad);
-    return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
-}
-
 // Grids are sized for Tr (the tile's rows rounded up to the block height); the kernels read the
 // number of rows that take part from the device and surplus blocks leave at once.
 template <int MODE>
@@ -839,7 +834,6 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
     float* sc = reinterpret_cast<float*>(P.ws + L.sc);
     uint16_t* hc = reinterpret_cast<uint16_t*>(P.ws + L.hc);
     uint16_t* stash = reinterpret_cast<uint16_t*>(P.ws + L.stash);
-    uint16_t* wt = reinterpret_cast<uint16_t*>(P.ws + L.wt);
     const bool acc_in_dw = (P.flags & ALST_FLAG_DW_FP32) && !(P.flags & ALST_FLAG_DW_ACCUMULATE);
     float* acc = acc_in_dw ? reinterpret_cast<float*>(P.dW) : reinterpret_cast<float*>(P.ws + L.acc);
 
@@ -861,15 +855,11 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
     }
     ALST_HIP(hipGetLastError());
 
-    if (do_bwd) {
-        rc = launch_transpose(P.W, H, V, H, wt, Vp, Vp, s);
-        if (rc != ALST_OK) return rc;
-    }
-
     // unguarded kernels need every extent block-aligned; the row extent always is (dense rows are
     // zero padded to a multiple of the block height)
     const bool guard_logits = (V % kBlockC) != 0 || (H % kBlockK) != 0;
     const bool guard_h = (H % kBlockC) != 0;
+    const bool guard_dh = guard_h || (V % kBlockK) != 0;      // dHidden: k = vocabulary id
 
     // The host does not know M: it walks ceil(N / T) tiles, the most there can be; the kernels of
     // a tile beyond the dense rows find Tc = 0 on the device and leave at once.
@@ -932,21 +922,21 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
 
         {
             DHiddenParams dp;
-            dp.dz = stash; dp.wt = wt; dp.dH_t = P.dHidden; dp.idx = idx_t;
+            dp.dz = stash; dp.W = P.W; dp.dH_t = P.dHidden; dp.idx = idx_t;
             dp.info = info; dp.hdr = hdr;
             dp.part = reinterpret_cast<float*>(P.ws + L.part);
-            dp.Tp = Tp; dp.H = H; dp.Vp = Vp;
+            dp.Tp = Tp; dp.H = H; dp.V = V; dp.Vp = Vp;
             dp.splits = L.splits; dp.ksteps = L.ksteps;
             const PatchGrid pg = choose_patches(Tr / kBlockR, (H + kBlockC - 1) / kBlockC);
             dp.PR = pg.PR; dp.PC = pg.PC;
             const int grid = grid_for_patches((int64_t)pg.patches() * L.splits);
             ProfScope ps_(PROF_DHIDDEN, s);
-            if (guard_h)
-                hipLaunchKernelGGL((dhidden_kernel<StagedCore, true>), dim3(grid),
-                                   dim3(StagedCore::kThreads), kLdsBytes, s, dp);
+            if (guard_dh)
+                hipLaunchKernelGGL((dhidden_kernel<StagedMixedCore, true>), dim3(grid),
+                                   dim3(StagedMixedCore::kThreads), kLdsBytes, s, dp);
             else
-                hipLaunchKernelGGL((dhidden_kernel<DirectCore, false>), dim3(grid),
-                                   dim3(DirectCore::kThreads), kLdsBytes, s, dp);
+                hipLaunchKernelGGL((dhidden_kernel<MixedCore, false>), dim3(grid),
+                                   dim3(MixedCore::kThreads), kLdsBytes, s, dp);
             if (L.splits > 1)
                 hipLaunchKernelGGL(dhidden_reduce_kernel, dim3(Tr), dim3(256), 0, s, dp.part,
                                    L.splits, Tp, H, idx_t, info, hdr, P.dHidden);

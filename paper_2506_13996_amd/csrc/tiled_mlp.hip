@@ -9,10 +9,11 @@
 //   forward    a  = silu(x Wg^T) * (x Wu^T)   gated_kernel: both products in one block, SwiGLU in
 //                                             the epilogue, g and u never reach memory
 //              y  = a Wd^T
-//   backward   da = dy (Wd^T)^T               Wd^T made once per call
+//   backward   da = dy Wd                     Wd as it is: the k-major operand (k = h)
 //              a, [dg | du]                   gated_kernel again (g and u recomputed), its epilogue
 //                                             reads da; written into the rows of the tile's group
-//              dx = [dg | du] [Wg^T | Wu^T]^T one launch, K = 2I, the transposed weights made once
+//              dx = dg Wg + du Wu             one launch, two contractions over I into the same
+//                                             accumulators, Wg and Wu as they are (k = i)
 //   per group  dWg += dg^T x, dWu += du^T x, dWd += dy^T a   (fp32, contraction over the group's rows)
 //
 // As in the cross-entropy path the weight gradients are accumulated once per group of tiles
@@ -37,7 +38,7 @@ constexpr int kMlpGroupMax = 8;
 struct MlpLayout {
     int64_t Tp, Kg;        // tile rows rounded up to 256; rows a weight-gradient group can hold
     int g;                 // tiles per weight-gradient group
-    size_t a, da, dgu, wdt, wgut, acc_g, acc_u, acc_d, total;
+    size_t a, da, dgu, acc_g, acc_u, acc_d, total;
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -57,8 +58,6 @@ static MlpLayout make_mlp_layout(int64_t N, int64_t H, int64_t I, int64_t tile, 
     if (backward) {
         L.da = take((size_t)L.Tp * I * 2);
         L.dgu = take((size_t)L.Kg * 2 * I * 2);
-        L.wdt = take((size_t)I * H * 2);
-        L.wgut = take((size_t)H * 2 * I * 2);
         // fp32 overwrite outputs hold the sums themselves
         const bool in_out = (flags & ALST_FLAG_DW_FP32) && !(flags & ALST_FLAG_DW_ACCUMULATE);
         L.acc_g = take(in_out ? 0 : (size_t)I * H * 4);
@@ -74,11 +73,17 @@ static MlpLayout make_mlp_layout(int64_t N, int64_t H, int64_t I, int64_t tile, 
 // ---------------------------------------------------------------------------------------------
 struct LinearParams {
     const uint16_t* X;       // [rows_x, ldx]   k contiguous
-    const uint16_t* Y;       // [rows_y, ldy]
-    uint16_t* D;             // [.., ldd]       D[r][c] = sum_k X[r][k] Y[c][k], bf16
+    const uint16_t* Y;       // [rows_y, ldy]   k contiguous: D[r][c] = sum_k X[r][k] Y[c][k], bf16
+                             // [K, ldy]        k-major (y_kmajor; a weight matrix contracted over its
+                             //                 row index, as it is): D[r][c] = sum_k X[r][k] Y[k][c],
+                             //                 rows_y = its number of columns
+    uint16_t* D;             // [.., ldd]
+    const uint16_t* X2;      // second product summed into the same D (y_kmajor only, same K and
+    const uint16_t* Y2;      // leading dimensions), or null
     int64_t ldx, ldy, ldd;
     int rows_x, rows_y, K;
     int rows_out, cols_out;  // guarded builds write only r < rows_out, 8-column chunks below cols_out
+    int y_kmajor;
 };
 
 // Up to three independent products in one launch: their patches of output blocks are numbered
@@ -125,9 +130,26 @@ __global__ __launch_bounds__(Core::kThreads) void linear_kernel(const LinearBatc
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
-    const uint16_t* warm = Core::kCanGuard ? nullptr
-                                           : warm_row(PR, PC, p.X, p.ldx, r0, tr, p.Y, p.ldy, c0, tc);
-    Core::template gemm<GUARD>(p.X, p.ldx, p.rows_x, p.Y, p.ldy, p.rows_y, p.K, r0, c0, smem, acc, warm);
+    constexpr bool kMixed = std::is_same<Core, MixedCore>::value || std::is_same<Core, StagedMixedCore>::value;
+    if constexpr (kMixed) {
+        int64_t step = 0;
+        const uint16_t* warm = Core::kCanGuard ? nullptr
+                                               : warm_line_mixed(PR, PC, p.X, p.ldx, r0, tr, p.Y, p.ldy,
+                                                                 c0, tc, step);
+        Core::template gemm<GUARD>(p.X, p.ldx, p.rows_x, p.Y, p.ldy, p.rows_y, p.K, r0, c0, smem, acc, warm,
+                                   step);
+        if (p.X2) {
+            __syncthreads();        // every wavefront is done with the first product's LDS stages
+            warm = Core::kCanGuard ? nullptr
+                                   : warm_line_mixed(PR, PC, p.X2, p.ldx, r0, tr, p.Y2, p.ldy, c0, tc, step);
+            Core::template gemm<GUARD>(p.X2, p.ldx, p.rows_x, p.Y2, p.ldy, p.rows_y, p.K, r0, c0, smem, acc,
+                                       warm, step);
+        }
+    } else {
+        const uint16_t* warm = Core::kCanGuard ? nullptr
+                                               : warm_row(PR, PC, p.X, p.ldx, r0, tr, p.Y, p.ldy, c0, tc);
+        Core::template gemm<GUARD>(p.X, p.ldx, p.rows_x, p.Y, p.ldy, p.rows_y, p.K, r0, c0, smem, acc, warm);
+    }
     store_block_bf16<Core, GUARD>(acc, p.D, p.ldd, r0, c0, p.rows_out, p.cols_out, smem);
 }
 
@@ -320,6 +342,8 @@ static int prepare_mlp_kernels() {
     auto acc = [&](int r) { if (r != ALST_OK) rc = r; };
     acc(allow_big_lds(linear_kernel<DirectCore, false>));
     acc(allow_big_lds(linear_kernel<StagedCore, true>));
+    acc(allow_big_lds(linear_kernel<MixedCore, false>));
+    acc(allow_big_lds(linear_kernel<StagedMixedCore, true>));
     acc(allow_big_lds(gated_kernel<DirectCore, false, false>));
     acc(allow_big_lds(gated_kernel<StagedCore, true, false>));
     acc(allow_big_lds(gated_kernel<DirectCore, false, true>));
@@ -353,9 +377,16 @@ static int launch_linear(const LinearParams* ps, int n, hipStream_t s) {
     for (int i = n; i <= kMaxBatch; ++i) b.map.first_patch[i] = (int)patches;
     const int blocks = grid_for_patches(patches);
     ProfScope pr(PROF_MLP_LINEAR, s);
-    if (direct)
+    const bool mixed = ps[0].y_kmajor != 0;           // the products of one launch are of one kind
+    if (direct && mixed)
+        hipLaunchKernelGGL((linear_kernel<MixedCore, false>), dim3((unsigned)blocks),
+                           dim3(MixedCore::kThreads), kLdsBytes, s, b);
+    else if (direct)
         hipLaunchKernelGGL((linear_kernel<DirectCore, false>), dim3((unsigned)blocks),
                            dim3(DirectCore::kThreads), kLdsBytes, s, b);
+    else if (mixed)
+        hipLaunchKernelGGL((linear_kernel<StagedMixedCore, true>), dim3((unsigned)blocks),
+                           dim3(StagedMixedCore::kThreads), kLdsBytes, s, b);
     else
         hipLaunchKernelGGL((linear_kernel<StagedCore, true>), dim3((unsigned)blocks),
                            dim3(StagedCore::kThreads), kLdsBytes, s, b);
@@ -412,15 +443,6 @@ static int launch_wgrad(const WgradParams* ps, int n, hipStream_t s) {
 }
 
 static int launch_wgrad(const WgradParams& p, hipStream_t s) { return launch_wgrad(&p, 1, s); }
-
-static int launch_transpose(const uint16_t* in, int64_t ld_in, int R, int C, uint16_t* out,
-                            int64_t ld_out, int Rpad, hipStream_t s) {
-    dim3 grid((Rpad + 63) / 64, (C + 63) / 64);
-    if (grid.y > 65535u) return ALST_ERR_SHAPE;
-    hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, s, in, ld_in, R, C, out, ld_out,
-                       Rpad);
-    return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
-}
 
 struct MlpProblem {
     const uint16_t *x, *Wg, *Wu, *Wd, *dy;
@@ -520,8 +542,6 @@ static int run_mlp_backward(const MlpProblem& P) {
     uint16_t* a = reinterpret_cast<uint16_t*>(P.ws + L.a);
     uint16_t* da = reinterpret_cast<uint16_t*>(P.ws + L.da);
     uint16_t* dgu = reinterpret_cast<uint16_t*>(P.ws + L.dgu);
-    uint16_t* wdt = reinterpret_cast<uint16_t*>(P.ws + L.wdt);
-    uint16_t* wgut = reinterpret_cast<uint16_t*>(P.ws + L.wgut);
     const bool f32 = P.flags & ALST_FLAG_DW_FP32, accum = P.flags & ALST_FLAG_DW_ACCUMULATE;
     const bool in_out = f32 && !accum;
     float* acc_g = in_out ? reinterpret_cast<float*>(P.dWg) : reinterpret_cast<float*>(P.ws + L.acc_g);
@@ -529,14 +549,6 @@ static int run_mlp_backward(const MlpProblem& P) {
     float* acc_d = in_out ? reinterpret_cast<float*>(P.dWd) : reinterpret_cast<float*>(P.ws + L.acc_d);
     const int H = (int)P.H, I = (int)P.I;
     const int64_t I2 = 2 * (int64_t)I;
-
-    {   // once per call: Wd^T [I, H] and [Wg^T | Wu^T] [H, 2I]
-        ProfScope ps(PROF_MLP_OTHER, s);
-        rc = launch_transpose(P.Wd, I, H, I, wdt, H, H, s);
-        if (rc == ALST_OK) rc = launch_transpose(P.Wg, H, I, H, wgut, I2, I, s);
-        if (rc == ALST_OK) rc = launch_transpose(P.Wu, H, I, H, wgut + I, I2, I, s);
-        if (rc != ALST_OK) return rc;
-    }
 
     const int64_t T = P.tile < P.N ? P.tile : P.N;
     const int64_t ntiles = (P.N + T - 1) / T;
@@ -558,16 +570,17 @@ static int run_mlp_backward(const MlpProblem& P) {
         {   // da = dy_t Wd (contraction over H), then g and u again with a, dg, du made in the epilogue
             LinearParams lp = {};
             lp.X = dy_t; lp.ldx = H; lp.rows_x = T_cur; lp.K = H;
-            lp.Y = wdt; lp.ldy = H; lp.rows_y = I;
+            lp.Y = P.Wd; lp.ldy = I; lp.rows_y = I; lp.y_kmajor = 1;       // Wd [H, I]: k = h
             lp.D = da; lp.ldd = I; lp.rows_out = Tr; lp.cols_out = I;
             rc = launch_linear(lp, s);
             if (rc == ALST_OK) rc = launch_gated(P, x_t, T_cur, Tr, da, a_t, dgu_t, s);
             if (rc != ALST_OK) return rc;
         }
-        {   // dx = [dg | du] [Wg^T | Wu^T]^T: contraction over 2I
+        {   // dx = dg Wg + du Wu: two contractions over I summed in the accumulators
             LinearParams lp = {};
-            lp.X = dgu_t; lp.ldx = I2; lp.rows_x = Tr; lp.K = (int)I2;
-            lp.Y = wgut; lp.ldy = I2; lp.rows_y = H;
+            lp.X = dgu_t; lp.ldx = I2; lp.rows_x = Tr; lp.K = I;
+            lp.Y = P.Wg; lp.ldy = H; lp.rows_y = H; lp.y_kmajor = 1;       // Wg [I, H]: k = i
+            lp.X2 = dgu_t + I; lp.Y2 = P.Wu;
             lp.D = P.dx + i0 * P.H; lp.ldd = H; lp.rows_out = T_cur; lp.cols_out = H;
             rc = launch_linear(lp, s);
             if (rc != ALST_OK) return rc;
@@ -611,7 +624,7 @@ static int run_mlp_backward(const MlpProblem& P) {
 struct LinLayout {
     int64_t Tp;
     int g;                 // tiles per weight-gradient group
-    size_t wt, acc, total;
+    size_t acc, total;
 };
 
 static LinLayout make_lin_layout(int64_t N, int64_t K, int64_t M, int64_t tile, bool backward,
@@ -624,7 +637,6 @@ static LinLayout make_lin_layout(int64_t N, int64_t K, int64_t M, int64_t tile, 
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     if (backward) {
-        L.wt = take((size_t)K * M * 2);
         const bool in_out = (flags & ALST_FLAG_DW_FP32) && !(flags & ALST_FLAG_DW_ACCUMULATE);
         L.acc = take(in_out ? 0 : (size_t)M * K * 4);
     }
@@ -645,18 +657,19 @@ struct LinProblem {
 static int validate_lin(const LinProblem& P, size_t workspace_bytes, bool backward) {
     if (!P.x || !P.W) return ALST_ERR_NULL;
     if (!backward && !P.y) return ALST_ERR_NULL;
-    if (backward && (!P.dy || !P.dx || !P.dW || !P.ws)) return ALST_ERR_NULL;
+    if (backward && (!P.dy || !P.dx || !P.dW)) return ALST_ERR_NULL;
     if (P.flags & ~(ALST_FLAG_DW_FP32 | ALST_FLAG_DW_ACCUMULATE)) return ALST_ERR_UNSUPPORTED;
     if (P.N < 1 || P.K < 1 || P.M < 1 || P.tile < 1) return ALST_ERR_SHAPE;
     if (P.N > (int64_t)1 << 30 || P.K > (int64_t)1 << 20 || P.M > (int64_t)1 << 24) return ALST_ERR_SHAPE;
+    // the only scratch is the fp32 dW sums, which live in dW itself for fp32 overwrite output
+    if (make_lin_layout(P.N, P.K, P.M, P.tile, backward, P.flags).total > 0 && !P.ws) return ALST_ERR_NULL;
     if (P.K % 8 != 0 || P.M % 8 != 0) return ALST_ERR_ALIGN;
     const void* ptrs[] = {P.x, P.W, P.dy, P.y, P.dx, P.dW, P.ws};
     for (const void* q : ptrs)
         if (q && !aligned16(q)) return ALST_ERR_ALIGN;
     const LinLayout L = make_lin_layout(P.N, P.K, P.M, P.tile, backward, P.flags);
     if (!checked_grid(L.Tp / kBlockR, (P.M + kBlockC - 1) / kBlockC) ||
-        !checked_grid((P.K + kBlockR - 1) / kBlockR, (P.M + kBlockC - 1) / kBlockC) ||
-        (P.M + 63) / 64 > 65535)
+        !checked_grid((P.K + kBlockR - 1) / kBlockR, (P.M + kBlockC - 1) / kBlockC))
         return ALST_ERR_SHAPE;
     if (workspace_bytes < L.total) return ALST_ERR_WORKSPACE;
     return ALST_OK;
@@ -685,16 +698,10 @@ static int run_lin_backward(const LinProblem& P) {
     if (rc != ALST_OK) return rc;
     const LinLayout L = make_lin_layout(P.N, P.K, P.M, P.tile, true, P.flags);
     hipStream_t s = P.stream;
-    uint16_t* wt = reinterpret_cast<uint16_t*>(P.ws + L.wt);
     const bool f32 = P.flags & ALST_FLAG_DW_FP32, accum = P.flags & ALST_FLAG_DW_ACCUMULATE;
     const bool in_out = f32 && !accum;
     float* acc = in_out ? reinterpret_cast<float*>(P.dW) : reinterpret_cast<float*>(P.ws + L.acc);
     const int K = (int)P.K, M = (int)P.M;
-    {   // W^T [K, M], once per call: the k-contiguous operand of dx = dy W
-        ProfScope ps(PROF_MLP_OTHER, s);
-        rc = launch_transpose(P.W, K, M, K, wt, M, M, s);
-        if (rc != ALST_OK) return rc;
-    }
     const int64_t T = P.tile < P.N ? P.tile : P.N;
     const int64_t ntiles = (P.N + T - 1) / T;
     int kofs = 0;                                   // rows of the group so far
@@ -706,7 +713,7 @@ static int run_lin_backward(const LinProblem& P) {
         if (slot == 0) { kofs = 0; group_row0 = i0; }
         LinearParams lp = {};
         lp.X = P.dy + i0 * P.M; lp.ldx = M; lp.rows_x = T_cur; lp.K = M;
-        lp.Y = wt; lp.ldy = M; lp.rows_y = K;
+        lp.Y = P.W; lp.ldy = K; lp.rows_y = K; lp.y_kmajor = 1;           // W [M, K]: k = m
         lp.D = P.dx + i0 * P.K; lp.ldd = K; lp.rows_out = T_cur; lp.cols_out = K;
         rc = launch_linear(lp, s);
         if (rc != ALST_OK) return rc;

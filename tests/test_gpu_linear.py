@@ -73,4 +73,6 @@ def test_linear_flags_and_workspace_contract():
     # forward needs no workspace; backward's is independent of N
     assert B.alst_tiled_linear_workspace_bytes(10 ** 6, 4096, 4096, 4096, False) == 0
     a = B.alst_tiled_linear_workspace_bytes(8192, 4096, 4096, 4096, True)
-    assert a == B.alst_tiled_linear_workspace_bytes(10 ** 6, 4096, 4096, 4096, True) > 0
+    assert a == B.alst_tiled_linear_workspace_bytes(10 ** 6, 4096, 4096, 4096, True) == 4 * 4096 * 4096
+    # the fp32 sums live in dW itself for fp32 overwrite output: no scratch at all
+    assert B.alst_tiled_linear_workspace_bytes(8192, 4096, 4096, 4096, True, B.ALST_FLAG_DW_FP32) == 0
