@@ -166,6 +166,17 @@ int alst_shift_labels(const int32_t* labels, int32_t* shift_labels, int64_t N,
 int alst_profile_enable(int on);
 int alst_profile_read(double* ms_total, int64_t* launches);
 
+/*
+ * Testing aid (no counterpart in the paper; host arithmetic only, no device is touched).  The block
+ * GEMM launches deal their workgroups round-robin to the 8 XCDs of the chip and give the 32
+ * workgroups resident on one XCD a compact patch of output blocks; a launch may hold several
+ * products ("parts") whose patches are numbered through.  For a launch of `parts` products of
+ * tiles_r x tiles_c blocks this returns the number of workgroups and writes, for workgroup `bid`,
+ * the part and block it computes (part = -1: the workgroup leaves at once), evaluated with the
+ * same functions the kernels use.  A negative return value is minus an alst_status.
+ */
+int alst_debug_block_tile(int tiles_r, int tiles_c, int parts, int bid, int* part, int* tr, int* tc);
+
 #ifdef __cplusplus
 }
 #endif

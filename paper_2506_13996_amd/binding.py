@@ -23,7 +23,7 @@ ALST_FLAG_REDUCE_SUM = 4
 EXPORTS = (
     "alst_status_string", "alst_version", "alst_tiled_ce_workspace_bytes", "alst_tiled_ce_forward",
     "alst_tiled_ce_backward", "alst_tiled_ce_forward_backward", "alst_last_device_status",
-    "alst_shift_labels", "alst_tiled_ce_token_losses", "alst_profile_enable", "alst_profile_read",
+    "alst_shift_labels", "alst_tiled_ce_token_losses", "alst_profile_enable", "alst_profile_read", "alst_debug_block_tile",
     "alst_tiled_mlp_workspace_bytes", "alst_tiled_mlp_forward", "alst_tiled_mlp_backward",
     "alst_tiled_linear_workspace_bytes", "alst_tiled_linear_forward", "alst_tiled_linear_backward",
 )
@@ -82,6 +82,8 @@ def load_library() -> ctypes.CDLL:
     lib.alst_profile_enable.argtypes = [c.c_int]
     lib.alst_profile_read.restype = c.c_int
     lib.alst_profile_read.argtypes = [c.POINTER(c.c_double), c.POINTER(c.c_int64)]
+    lib.alst_debug_block_tile.restype = c.c_int
+    lib.alst_debug_block_tile.argtypes = [c.c_int] * 4 + [c.POINTER(c.c_int)] * 3
     _lib = lib
     return lib
 
@@ -238,3 +240,13 @@ def alst_profile_read() -> dict:
     n = (ctypes.c_int64 * 8)()
     _check(load_library().alst_profile_read(ms, n), "alst_profile_read")
     return {k: (ms[i], int(n[i])) for i, k in enumerate(PROFILE_KINDS)}
+
+
+def alst_debug_block_tile(tiles_r: int, tiles_c: int, parts: int, bid: int):
+    """(workgroups of the launch, part, tr, tc) for workgroup `bid`; part = -1 for a padding one."""
+    part, tr, tc = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    n = load_library().alst_debug_block_tile(tiles_r, tiles_c, parts, bid, ctypes.byref(part),
+                                             ctypes.byref(tr), ctypes.byref(tc))
+    if n < 0:
+        raise AlstError(-n, "alst_debug_block_tile")
+    return n, part.value, tr.value, tc.value

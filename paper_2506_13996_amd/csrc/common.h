@@ -39,7 +39,8 @@ static inline int current_device_slot() {
     return dev;
 }
 
-// Workgroups of a launch over tiles_r x tiles_c output blocks; 0 if that does not fit a grid.
+// Upper bound of the workgroups of a launch over tiles_r x tiles_c output blocks (4 x 8 patches;
+// another patch shape is only chosen when it needs fewer); 0 if that does not fit a grid.
 static inline int64_t checked_grid(int64_t tiles_r, int64_t tiles_c) {
     const int64_t patches = ((tiles_r + 3) / 4) * ((tiles_c + 7) / 8);
     const int64_t blocks = ((patches + 7) / 8) * 8 * 32;

@@ -49,31 +49,10 @@ constexpr int kWarmAhead = 3;                           // k-steps between warm-
 
 // XCD-aware block -> tile mapping.  Workgroups are dealt round-robin to the 8 XCDs (each with its
 // own L2); the 32 workgroups that are resident together on one XCD get a compact PR x PC patch of
-// tiles so that they share operand rows through that L2.  Returns false for padding blocks.
-template <int PR, int PC>
-__device__ __forceinline__ bool tile_of_block(int bid, int tiles_r, int tiles_c, int& tr, int& tc) {
-    constexpr int kPatch = PR * PC;
-    const int xcd = bid & 7;
-    const int slot = bid >> 3;
-    const int p = slot / kPatch, w = slot % kPatch;
-    const int patches_r = (tiles_r + PR - 1) / PR;
-    const int patches_c = (tiles_c + PC - 1) / PC;
-    const int P = p * 8 + xcd;
-    if (P >= patches_r * patches_c) return false;
-    tr = (P % patches_r) * PR + (w % PR);
-    tc = (P / patches_r) * PC + (w / PR);
-    return tr < tiles_r && tc < tiles_c;
-}
-
-template <int PR, int PC>
-inline int grid_for_tiles(int tiles_r, int tiles_c) {
-    const int patches = ((tiles_r + PR - 1) / PR) * ((tiles_c + PC - 1) / PC);
-    return ((patches + 7) / 8) * 8 * PR * PC;
-}
-
-// The same mapping with the patch shape chosen at run time and several products ("parts") in one
-// launch: the patches of all parts are numbered through, and patch P goes to XCD P % 8, so the
-// XCDs stay evenly loaded whatever the number of patches of one part is.
+// output blocks so that they share operand tiles through that L2.  The patch shape is chosen per
+// launch, and a launch may hold several products ("parts"): the patches of all parts are numbered
+// through, and patch P goes to XCD P % 8, so the XCDs stay evenly loaded whatever the number of
+// patches of one part is.
 struct PatchGrid {
     int tiles_r, tiles_c;      // output blocks of one part
     int PR, PC;                // patch shape, PR * PC = 32
@@ -81,13 +60,15 @@ struct PatchGrid {
     __host__ __device__ int patches() const { return patches_r() * ((tiles_c + PC - 1) / PC); }
 };
 
-// Patch shape (of 2x16, 4x8, 8x4, 16x2) with the fewest padding blocks; ties go to the squarer one.
+// Patch shape: 4 x 8 (12 operand tiles per k-step for 32 blocks), unless 8 x 4 or one of the
+// flat shapes 2 x 16, 16 x 2 (18 tiles per k-step) pads so much less that it needs under 9/10 of
+// the patches.
 inline PatchGrid choose_patches(int tiles_r, int tiles_c) {
     const int shapes[4][2] = {{4, 8}, {8, 4}, {2, 16}, {16, 2}};
     PatchGrid best = {tiles_r, tiles_c, 4, 8};
     for (int i = 1; i < 4; ++i) {
         const PatchGrid g = {tiles_r, tiles_c, shapes[i][0], shapes[i][1]};
-        if (g.patches() < best.patches()) best = g;
+        if (10 * g.patches() < 9 * best.patches()) best = g;
     }
     return best;
 }
@@ -95,14 +76,15 @@ inline PatchGrid choose_patches(int tiles_r, int tiles_c) {
 inline int grid_for_patches(int64_t patches) { return (int)(((patches + 7) / 8) * 8 * 32); }
 
 // Workgroup -> (global patch number, position inside the patch).
-__device__ __forceinline__ void patch_of_block(int bid, int& P, int& w) {
+__host__ __device__ __forceinline__ void patch_of_block(int bid, int& P, int& w) {
     const int slot = bid >> 3;
     P = (slot >> 5) * 8 + (bid & 7);
     w = slot & 31;
 }
 
 // Block (tr, tc) of position w in local patch P of g; false if the patch sticks out there.
-__device__ __forceinline__ bool tile_in_patch(const PatchGrid& g, int P, int w, int& tr, int& tc) {
+__host__ __device__ __forceinline__ bool tile_in_patch(const PatchGrid& g, int P, int w, int& tr,
+                                                       int& tc) {
     const int pr = g.patches_r();
     tr = (P % pr) * g.PR + (w % g.PR);
     tc = (P / pr) * g.PC + (w / g.PR);
@@ -128,20 +110,8 @@ __device__ __forceinline__ const uint16_t* paired_row(const uint16_t* Y, const u
 // the tile's rows between them and each touches one dword per line of its share kWarmAhead
 // k-steps before the DMA needs it: the miss latency is paid early and once, and the sixteen DMA
 // instructions of a k-step find their lines in L2.  Returns this lane's row of X or Y (the
-// pointer to its first element); every lane gets a valid row, surplus lanes repeat one.
-template <int PR, int PC>
-__device__ __forceinline__ const uint16_t* warm_row(const uint16_t* X, int64_t ldx, int r0, int tr,
-                                                    const uint16_t* Y, int64_t ldy, int c0, int tc) {
-    constexpr int nx = kBlockR / PC, ny = kBlockC / PR, total = nx + ny, per = (total + 3) / 4;
-    static_assert(per <= 64, "one warm-up instruction per wavefront");
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    int l = w * per + (lane < per ? lane : per - 1);
-    if (l > total - 1) l = total - 1;
-    if (l < nx) return X + (int64_t)(r0 + (tc % PC) * nx + l) * ldx;
-    return Y + (int64_t)(c0 + (tr % PR) * ny + (l - nx)) * ldy;
-}
-
-// The same for a patch shape chosen at run time (2x16, 4x8, 8x4 or 16x2).
+// pointer to its first element); every lane gets a valid row, surplus lanes repeat one.  PR x PC
+// is the launch's patch shape (2 x 16, 4 x 8, 8 x 4 or 16 x 2).
 __device__ __forceinline__ const uint16_t* warm_row(int PR, int PC, const uint16_t* X, int64_t ldx,
                                                     int r0, int tr, const uint16_t* Y, int64_t ldy,
                                                     int c0, int tc, const uint16_t* Y2 = nullptr) {

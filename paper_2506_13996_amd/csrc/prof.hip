@@ -65,4 +65,25 @@ int alst_profile_read(double* ms_total, int64_t* launches) {
     return rc;
 }
 
+// The workgroup -> output block mapping of the block GEMM launches, evaluated on the host with the
+// functions the kernels use (gemm_tile.h), for a launch of `parts` products of tiles_r x tiles_c
+// blocks each.  Returns the launch's number of workgroups (< 0: alst_status); for workgroup `bid`
+// writes the part and the block it works on, part = -1 for a workgroup that leaves at once.
+int alst_debug_block_tile(int tiles_r, int tiles_c, int parts, int bid, int* part, int* tr, int* tc) {
+    if (!part || !tr || !tc) return -ALST_ERR_NULL;
+    if (tiles_r < 1 || tiles_c < 1 || parts < 1 || bid < 0) return -ALST_ERR_SHAPE;
+    const PatchGrid g = choose_patches(tiles_r, tiles_c);
+    const int64_t total = (int64_t)g.patches() * parts;
+    if (total * 32 > 0x7fffff00) return -ALST_ERR_SHAPE;
+    int P, w;
+    patch_of_block(bid, P, w);
+    *part = -1; *tr = 0; *tc = 0;
+    if (P < total) {
+        const int which = P / g.patches();
+        int r, c;
+        if (tile_in_patch(g, P - which * g.patches(), w, r, c)) { *part = which; *tr = r; *tc = c; }
+    }
+    return grid_for_patches(total);
+}
+
 }  // extern "C"

@@ -456,6 +456,7 @@ struct LogitsParams {
     float* zlabel;              // [Tp]
     uint16_t* stash;            // [Kg, Vp]     MODE_FUSED / MODE_BWD; rows as in hidden_t
     int Tp, H, V, Vp;           // Tp = row stride of the per-tile arrays
+    int PR, PC;                 // patch shape of the block -> tile mapping
 };
 
 // r = token row of the tile (MFMA lane dimension), c = vocabulary id (register dimension).
@@ -466,7 +467,12 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
     int tr, tc;
     const int T_cur = p.info->Tc, Trc = p.info->Trc;
     if (T_cur == 0) return;
-    if (!tile_of_block<4, 8>(blockIdx.x, Trc / kBlockR, p.Vp / kBlockC, tr, tc)) return;
+    {
+        const PatchGrid pg = {Trc / kBlockR, p.Vp / kBlockC, p.PR, p.PC};
+        int P, w;
+        patch_of_block(blockIdx.x, P, w);
+        if (P >= pg.patches() || !tile_in_patch(pg, P, w, tr, tc)) return;
+    }
     const int r0 = tr * kBlockR, c0 = tc * kBlockC;
 
     f32x16_t acc[kMT][kNT];
@@ -480,7 +486,7 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
     const int kofs = p.info->kofs;
     const uint16_t* const hidden_t = p.hidden_t + (int64_t)kofs * p.H;
     const uint16_t* warm = Core::kCanGuard ? nullptr
-                                           : warm_row<4, 8>(hidden_t, p.H, r0, tr, p.W, p.H, c0, tc);
+                                           : warm_row(p.PR, p.PC, hidden_t, p.H, r0, tr, p.W, p.H, c0, tc);
     Core::template gemm<GUARD>(hidden_t, p.H, Trc, p.W, p.H, p.V, p.H, r0, c0, smem, acc, warm);
 
     const typename Core::Lane lp;
@@ -697,6 +703,7 @@ struct DWParams {
     const TileInfo* info;    // of the group's last tile: k extent = kofs + Tkc
     int H, V, Vp;
     int first;               // first group: store instead of add
+    int PR, PC;              // patch shape of the block -> tile mapping
 };
 
 // r = hidden index (lane dimension), c = vocabulary id (register dimension), k = dense token row:
@@ -710,7 +717,12 @@ __global__ __launch_bounds__(Core::kThreads) void dw_kernel(const DWParams p) {
     const int tiles_r = (p.H + kBlockR - 1) / kBlockR;
     const int Tkc = p.info->kofs + p.info->Tkc;      // k extent of the whole group
     if (Tkc == 0 && !p.first) return;
-    if (!tile_of_block<4, 8>(blockIdx.x, tiles_r, p.Vp / kBlockC, tr, tc)) return;
+    {
+        const PatchGrid pg = {tiles_r, p.Vp / kBlockC, p.PR, p.PC};
+        int P, w;
+        patch_of_block(blockIdx.x, P, w);
+        if (P >= pg.patches() || !tile_in_patch(pg, P, w, tr, tc)) return;
+    }
     const int r0 = tr * kBlockR, c0 = tc * kBlockC;
 
     f32x16_t acc[kMT][kNT];
@@ -724,8 +736,8 @@ __global__ __launch_bounds__(Core::kThreads) void dw_kernel(const DWParams p) {
     if (Tkc > 0) {
         int64_t step = 0;
         const uint16_t* warm = Core::kCanGuard ? nullptr
-                                               : warm_line_kmajor(4, 8, p.hg, p.H, r0, tr, p.dzg, p.Vp,
-                                                                  c0, tc, step);
+                                               : warm_line_kmajor(p.PR, p.PC, p.hg, p.H, r0, tr, p.dzg,
+                                                                  p.Vp, c0, tc, step);
         Core::template gemm<GUARD>(p.hg, p.H, p.H, p.dzg, p.Vp, p.Vp, Tkc, r0, c0, smem, acc, warm, step);
     }
 
@@ -794,6 +806,7 @@ static int validate(const Problem& P, size_t workspace_bytes, bool need_fwd_out,
     // every launch must fit a one-dimensional grid
     if (!checked_grid(L.Tp / kBlockR, L.Vp / kBlockC) ||
         !checked_grid((P.H + kBlockR - 1) / kBlockR, L.Vp / kBlockC) ||
+        !checked_grid(L.Tp / kBlockR * 8, (P.H + kBlockC - 1) / kBlockC) ||      // dHidden, 8 ranges
         (L.Vp / 256) * (L.Tp / 64) > 0x7fffffff)
         return ALST_ERR_SHAPE;
     if (workspace_bytes < L.total) return ALST_ERR_WORKSPACE;
@@ -803,8 +816,10 @@ static int validate(const Problem& P, size_t workspace_bytes, bool need_fwd_out,
 // Grids are sized for Tr (the tile's rows rounded up to the block height); the kernels read the
 // number of rows that take part from the device and surplus blocks leave at once.
 template <int MODE>
-static int launch_logits(const LogitsParams& lp, int Tr, bool guard, hipStream_t s) {
-    const int grid = grid_for_tiles<4, 8>(Tr / kBlockR, lp.Vp / kBlockC);
+static int launch_logits(LogitsParams lp, int Tr, bool guard, hipStream_t s) {
+    const PatchGrid pg = choose_patches(Tr / kBlockR, lp.Vp / kBlockC);
+    lp.PR = pg.PR; lp.PC = pg.PC;
+    const int grid = grid_for_patches(pg.patches());
     if (guard)
         hipLaunchKernelGGL((logits_kernel<StagedCore, true, MODE>), dim3(grid),
                            dim3(StagedCore::kThreads), kLdsBytes, s, lp);
@@ -946,7 +961,9 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             DWParams wp;
             wp.hg = hc; wp.dzg = stash; wp.acc = acc; wp.info = info;
             wp.H = H; wp.V = V; wp.Vp = Vp; wp.first = (t < L.g);
-            const int grid = grid_for_tiles<4, 8>((H + kBlockR - 1) / kBlockR, Vp / kBlockC);
+            const PatchGrid pg = choose_patches((H + kBlockR - 1) / kBlockR, Vp / kBlockC);
+            wp.PR = pg.PR; wp.PC = pg.PC;
+            const int grid = grid_for_patches(pg.patches());
             ProfScope ps_(PROF_DW, s);
             if (guard_h)
                 hipLaunchKernelGGL((dw_kernel<StagedKMajorCore, true>), dim3(grid),

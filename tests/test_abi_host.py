@@ -134,3 +134,38 @@ def test_mlp_workspace_and_host_validation(lib):
     rc = lib.alst_tiled_mlp_backward(vp(0x1000), vp(0x2000), vp(0x3000), vp(0x4000), None, 16, 64, 64, 8,
                                      vp(0x5000), vp(0x6000), vp(0x7000), vp(0x8000), vp(0x9000), 1 << 40, 0, None)
     assert rc == B.ALST_ERR_NULL
+
+
+@pytest.mark.parametrize("tiles_r,tiles_c,parts", [(16, 501, 1), (16, 16, 1), (8, 16, 2), (20, 594, 1),
+                                                    (16, 56, 3), (3, 5, 4), (1, 1, 8), (17, 3, 5), (1, 40, 1)])
+def test_block_to_tile_mapping_covers_every_block_once_and_balances_the_xcds(lib, tiles_r, tiles_c, parts):
+    """Every output block of every part is computed by exactly one workgroup; workgroup b runs on
+    XCD b % 8, the 32 workgroups of a patch share one XCD, and the XCDs' loads differ by at most
+    the blocks of one patch per part boundary."""
+    n = B.alst_debug_block_tile(tiles_r, tiles_c, parts, 0)[0]
+    assert n % 256 == 0 and n >= tiles_r * tiles_c * parts
+    seen, per_xcd, patch_xcd = set(), [0] * 8, {}
+    for bid in range(n):
+        n2, part, tr, tc = B.alst_debug_block_tile(tiles_r, tiles_c, parts, bid)
+        assert n2 == n
+        if part < 0:
+            continue
+        assert 0 <= part < parts and 0 <= tr < tiles_r and 0 <= tc < tiles_c
+        assert (part, tr, tc) not in seen
+        seen.add((part, tr, tc))
+        per_xcd[bid % 8] += 1
+        patch_xcd.setdefault((bid // 8) // 32 * 8 + bid % 8, set()).add(bid % 8)
+    assert len(seen) == tiles_r * tiles_c * parts
+    assert all(len(x) == 1 for x in patch_xcd.values())
+    assert max(per_xcd) - min(per_xcd) <= 32 * 2
+    # the padding a launch carries stays below one round of patches plus the ragged patch edges
+    assert n <= 4 * tiles_r * tiles_c * parts + 256
+
+
+def test_block_to_tile_mapping_rejects_bad_arguments(lib):
+    with pytest.raises(B.AlstError):
+        B.alst_debug_block_tile(0, 4, 1, 0)
+    with pytest.raises(B.AlstError):
+        B.alst_debug_block_tile(4, 4, 1, -1)
+    with pytest.raises(B.AlstError):
+        B.alst_debug_block_tile(1 << 15, 1 << 15, 8, 0)
