@@ -26,6 +26,15 @@ MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
 }
 
 
+def mfma_sustained(B) -> dict:
+    """Sustained TFLOP/s of the bf16 matrix instruction on this device right now, from a loop that
+    touches no memory (alst_debug_mfma_rate): context for `roofline.frac`, which stays priced on
+    the published peak.  The clock under matrix load follows the power drawn, hence the operand bits."""
+    return {"random_operands_tflops": B.alst_debug_mfma_rate(1, 60000),
+            "small_integer_operands_tflops": B.alst_debug_mfma_rate(0, 60000),
+            "how": "256 workgroups x 4 wavefronts x 60000 x 64 v_mfma_f32_32x32x16_bf16, register resident"}
+
+
 def cpu_baseline(wl, h_bits, W_bits, labels, rows: int) -> dict:
     """The CPU fp64 oracle, as it stands, timed on a bounded sample of the same workload."""
     import numpy as np
@@ -122,6 +131,8 @@ def bench_mlp(args) -> int:
                      "flop_per_launch": flop_per_launch,
                      "per_kind_ms_per_step": {k: v[0] / args.steps for k, v in prof.items() if v[1]}},
     }
+    out["mfma_sustained"] = mfma_sustained(B)
+    out["roofline"]["frac_of_sustained_random"] = achieved / out["mfma_sustained"]["random_operands_tflops"]
     if not args.no_cpu_baseline:
         from oracle import tiled_mlp_oracle as morc
         rows = min(args.cpu_rows, N)
@@ -240,6 +251,8 @@ def main() -> int:
                 "avg_launch_ms": dom_ms / dom_n, "launches": dom_n,
                 "flop_per_launch": flop_per_launch,
                 "per_kind_ms_per_step": {k: v[0] / args.steps for k, v in prof.items() if v[1]}}
+    sustained = mfma_sustained(B)
+    roofline["frac_of_sustained_random"] = achieved / sustained["random_operands_tflops"]
 
     out = {
         "metric": "tokens/sec, tiled LM-head+CE fwd+bwd, H=%d V=%d" % (H, V),
@@ -257,6 +270,7 @@ def main() -> int:
         "loss": float(loss.item()), "n_valid": M, "device_status": status,
         "wall_s_timed_region": wall, "input_gen_s": t_gen,
         "roofline": roofline,
+        "mfma_sustained": sustained,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, h_bits, W_bits, labels, args.cpu_rows)

@@ -177,6 +177,17 @@ int alst_profile_read(double* ms_total, int64_t* launches);
  */
 int alst_debug_block_tile(int tiles_r, int tiles_c, int parts, int bid, int* part, int* tr, int* tc);
 
+/*
+ * Benchmarking aid (no counterpart in the paper): the sustained rate, in TFLOP/s, of the bf16
+ * matrix instruction the block GEMMs are built on, measured on the current device with a loop that
+ * touches no memory (one wavefront per SIMD of every compute unit, 64 * iters instructions each).
+ * It is the ceiling the GEMM kernels can be compared with besides the published peak: the clock
+ * under matrix load depends on the power drawn, hence on the operand bits.  data = 0: small-integer
+ * operands, 1: random operands in [-1, 1).  scratch: device, 256 * 256 floats, overwritten;
+ * tflops: HOST double.  1 <= iters <= 2^22.  Synchronises `stream`.
+ */
+int alst_debug_mfma_rate(int data, int iters, float* scratch, double* tflops, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ ALST_FLAG_REDUCE_SUM = 4
 EXPORTS = (
     "alst_status_string", "alst_version", "alst_tiled_ce_workspace_bytes", "alst_tiled_ce_forward",
     "alst_tiled_ce_backward", "alst_tiled_ce_forward_backward", "alst_last_device_status",
-    "alst_shift_labels", "alst_tiled_ce_token_losses", "alst_profile_enable", "alst_profile_read", "alst_debug_block_tile",
+    "alst_shift_labels", "alst_tiled_ce_token_losses", "alst_profile_enable", "alst_profile_read", "alst_debug_block_tile", "alst_debug_mfma_rate",
     "alst_tiled_mlp_workspace_bytes", "alst_tiled_mlp_forward", "alst_tiled_mlp_backward",
     "alst_tiled_linear_workspace_bytes", "alst_tiled_linear_forward", "alst_tiled_linear_backward",
 )
@@ -82,6 +82,8 @@ def load_library() -> ctypes.CDLL:
     lib.alst_profile_enable.argtypes = [c.c_int]
     lib.alst_profile_read.restype = c.c_int
     lib.alst_profile_read.argtypes = [c.POINTER(c.c_double), c.POINTER(c.c_int64)]
+    lib.alst_debug_mfma_rate.restype = c.c_int
+    lib.alst_debug_mfma_rate.argtypes = [c.c_int, c.c_int, c.c_void_p, c.POINTER(c.c_double), c.c_void_p]
     lib.alst_debug_block_tile.restype = c.c_int
     lib.alst_debug_block_tile.argtypes = [c.c_int] * 4 + [c.POINTER(c.c_int)] * 3
     _lib = lib
@@ -250,3 +252,12 @@ def alst_debug_block_tile(tiles_r: int, tiles_c: int, parts: int, bid: int):
     if n < 0:
         raise AlstError(-n, "alst_debug_block_tile")
     return n, part.value, tr.value, tc.value
+
+
+def alst_debug_mfma_rate(data: int, iters: int = 100000) -> float:
+    """Sustained TFLOP/s of the bf16 matrix instruction on the current device (no memory traffic)."""
+    scratch = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
+    out = ctypes.c_double()
+    _check(load_library().alst_debug_mfma_rate(data, iters, _ptr(scratch), ctypes.byref(out), _stream()),
+           "alst_debug_mfma_rate")
+    return out.value

@@ -37,6 +37,43 @@ ProfScope::~ProfScope() {
     g_prof_spans.push_back(ProfSpan{a, b, kind});
 }
 
+// Register-resident MFMA loop for alst_debug_mfma_rate: every wavefront multiplies four A and four
+// B operand registers it made itself into 16 accumulator tiles (256 accumulator registers, as the
+// block GEMMs), with no memory traffic at all.  data = 0: small integers, 1: uniform in [-1, 1).
+__device__ __forceinline__ uint32_t mix32(uint32_t x) {
+    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+    return x;
+}
+__global__ __launch_bounds__(256) void mfma_rate_kernel(float* __restrict__ out, int iters, int data) {
+    bf16x8_t a[4], b[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t ha = mix32((threadIdx.x * 8 + t) * 8 + j), hb = mix32((threadIdx.x * 8 + 4 + t + 77777) * 8 + j);
+            a[t][j] = (__bf16)(data == 0 ? (float)(ha & 3) : ((int)(ha & 0xffff) - 32768) / 32768.0f);
+            b[t][j] = (__bf16)(data == 0 ? (float)(hb & 3) : ((int)(hb & 0xffff) - 32768) / 32768.0f);
+        }
+    f32x16_t acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int rep = 0; rep < 4; ++rep)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 3], b[(i >> 2) & 3], acc[i], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s += acc[i][j];
+    out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 }  // namespace alst
 
 using namespace alst;
@@ -84,6 +121,36 @@ int alst_debug_block_tile(int tiles_r, int tiles_c, int parts, int bid, int* par
         if (tile_in_patch(g, P - which * g.patches(), w, r, c)) { *part = which; *tr = r; *tc = c; }
     }
     return grid_for_patches(total);
+}
+
+// Sustained rate of the bf16 matrix instruction the block GEMMs use, on this device now: 256
+// workgroups of 4 wavefronts (one per SIMD of every compute unit) run 64 * iters
+// v_mfma_f32_32x32x16_bf16 each out of registers.  data = 0: small-integer operands, 1: random
+// operands in [-1, 1) (the rate depends on the operand bits through the power the multipliers
+// draw).  scratch: 256 * 256 floats of device memory, overwritten.  Synchronises the stream.
+int alst_debug_mfma_rate(int data, int iters, float* scratch, double* tflops, void* stream) {
+    if (!scratch || !tflops) return ALST_ERR_NULL;
+    if (iters < 1 || iters > (1 << 22) || (data != 0 && data != 1)) return ALST_ERR_SHAPE;
+    hipStream_t s = (hipStream_t)stream;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
+        if (e0) (void)hipEventDestroy(e0);
+        return ALST_ERR_HIP;
+    }
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3(256), dim3(256), 0, s, scratch, iters < 64 ? iters : 64, data);   // warm-up
+    (void)hipEventRecord(e0, s);
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3(256), dim3(256), 0, s, scratch, iters, data);
+    (void)hipEventRecord(e1, s);
+    float ms = 0.f;
+    int rc = ALST_OK;
+    if (hipGetLastError() != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+        hipEventElapsedTime(&ms, e0, e1) != hipSuccess || ms <= 0.f)
+        rc = ALST_ERR_HIP;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    // per launch: 256 workgroups x 4 wavefronts x iters x 64 instructions x 2 * 32 * 32 * 16 flop
+    *tflops = rc == ALST_OK ? 256.0 * 4.0 * (double)iters * 64.0 * 32768.0 / ((double)ms * 1e9) : 0.0;
+    return rc;
 }
 
 }  // extern "C"

@@ -246,3 +246,15 @@ def test_large_logits_stay_finite_and_match():
     assert np.abs(orc.logits(h[:8], W)).max() > 25.0 and f["loss"] > 10.0
     r = G.run_fused(h, W, y, 256)
     _check(r, f, dH, dW, "large logits", valid=(y != IGN))
+
+
+def test_mfma_rate_aid_reports_a_plausible_rate():
+    """The benchmarking aid behind bench.py's `mfma_sustained`: a register-resident loop of the
+    matrix instruction; its rate lies between a tenth of and just above the published 2.5 PFLOP/s."""
+    for data in (0, 1):
+        r = B.alst_debug_mfma_rate(data, 5000)
+        assert 250.0 < r < 2700.0, (data, r)
+    with pytest.raises(B.AlstError):
+        B.alst_debug_mfma_rate(2, 5000)
+    with pytest.raises(B.AlstError):
+        B.alst_debug_mfma_rate(1, 0)
