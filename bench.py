@@ -164,7 +164,8 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures the one-GPU path only; run with --gpus 1 "
-              "(sharding over GPUs is described in DESIGN.md, not built)", file=sys.stderr)
+              "(the path shards along the sequence; the exchanges between GPUs are not built)",
+              file=sys.stderr)
         return 2
     if args.workload.startswith("mlp_"):
         return bench_mlp(args)
