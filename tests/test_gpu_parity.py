@@ -7,6 +7,7 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import labels_oracle as laborc
 from oracle import tiled_ce_oracle as orc
 from paper_2506_13996_amd import binding as B
 from paper_2506_13996_amd import synth
@@ -190,6 +191,44 @@ def test_shift_labels_matches_paper_example():
     B.alst_shift_labels(lab, out)
     torch.cuda.synchronize()
     assert out.cpu().tolist() == [2, 3, 4, 5, 6, 7, 8, -100]
+    # bit-exact against the label oracle on a long random sequence and a one-token one
+    g = np.random.default_rng(5)
+    for n in (1, 2, 100003):
+        y = g.integers(0, 50000, n).astype(np.int32)
+        out = torch.zeros(n, dtype=torch.int32, device="cuda")
+        B.alst_shift_labels(torch.from_numpy(y).cuda(), out, ignore_index=-7)
+        assert (out.cpu().numpy() == laborc.shift_labels(y, -7)).all()
+
+
+def test_loss_of_presharded_sequence_equals_unsharded():
+    """Section "Loss Sharding ...": shift the labels of the whole sequence, cut hidden states and
+    shifted labels into SP pieces, run the path on every piece: the summed token losses and the
+    valid counts add up to those of the whole sequence (and the naive order, cut then shift, loses
+    one label per piece)."""
+    N, H, V, SP = 1024, 128, 1536, 4
+    wl = synth.custom("sp", N, H, V, 256, ignore_frac=0.0, seed=21)
+    h, W, tokens = synth.make_inputs(wl)                       # `tokens` stand for the next-token ids
+    shifted = laborc.shift_labels(tokens, IGN)
+    whole = orc.forward(h, W, shifted, row_block=256, reduction="sum")
+    assert whole["n_valid"] == N - 1
+    flags = B.ALST_FLAG_REDUCE_SUM
+    Wd = G.bits_to_dev(W)
+    total, count = 0.0, 0
+    pieces_h = np.split(h, SP)
+    for piece_h, piece_y in zip(pieces_h, laborc.shift_then_shard(tokens, SP, IGN)):
+        n = len(piece_y)
+        ws = B.alloc_workspace(n, H, V, 128, flags)
+        loss = torch.zeros(1, device="cuda")
+        nv = torch.zeros(1, dtype=torch.int64, device="cuda")
+        B.alst_tiled_ce_forward(G.bits_to_dev(piece_h), Wd, torch.from_numpy(np.ascontiguousarray(piece_y)).cuda(),
+                                128, IGN, loss_out=loss, n_valid_out=nv, workspace=ws, flags=flags)
+        assert B.alst_last_device_status(ws) == B.ALST_OK
+        total += float(loss.item())
+        count += int(nv.item())
+    assert count == whole["n_valid"]
+    assert abs(total - whole["loss"]) / abs(whole["loss"]) <= LOSS_RTOL
+    naive = sum(int((p != IGN).sum()) for p in laborc.shard_then_shift(tokens, SP, IGN))
+    assert naive == N - SP
 
 
 def test_sum_reduction_and_token_losses():
