@@ -114,7 +114,8 @@ __device__ __forceinline__ const uint16_t* paired_row(const uint16_t* Y, const u
 // is the launch's patch shape (2 x 16, 4 x 8, 8 x 4 or 16 x 2).
 __device__ __forceinline__ const uint16_t* warm_row(int PR, int PC, const uint16_t* X, int64_t ldx,
                                                     int r0, int tr, const uint16_t* Y, int64_t ldy,
-                                                    int c0, int tc, const uint16_t* Y2 = nullptr) {
+                                                    int c0, int tc, const uint16_t* Y2 = nullptr,
+                                                    int rows_y = 0x7fffffff) {
     const int nx = kBlockR / PC, ny = kBlockC / PR, total = nx + ny, per = (total + 3) / 4;   // per <= 36
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     int l = w * per + (lane < per ? lane : per - 1);
@@ -124,7 +125,8 @@ __device__ __forceinline__ const uint16_t* warm_row(int PR, int PC, const uint16
         bool valid;
         return paired_row(Y, Y2, ldy, c0, (tr % PR) * ny + (l - nx), 0x7fffffff, valid);
     }
-    return Y + (int64_t)(c0 + (tr % PR) * ny + (l - nx)) * ldy;
+    const int row = c0 + (tr % PR) * ny + (l - nx);
+    return Y + (int64_t)(row < rows_y ? row : rows_y - 1) * ldy;      // as the DMA: clamped to Y
 }
 
 // The same for k-major operands X[k][ldx], Y[k][ldy]: the 64 k-rows x 512 bytes of a k-step's tile
@@ -396,14 +398,16 @@ struct DirectCoreT {
     // kc ^ ((row >> 1) & 7): sixteen consecutive rows at one kc then cover all 64 banks once.
     static __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
-    // Requires r0 + 256 <= rows of X, c0 + 256 <= rows of Y, K % 64 == 0, K >= 64, 16-byte
-    // aligned rows.  GUARD must be false (rows_x / rows_y are unused).  A k-major X is [K][ldx]
+    // Requires r0 + 256 <= rows of X, K % 64 == 0, K >= 64, 16-byte aligned rows.  GUARD must be
+    // false.  A k-contiguous Y (without Y2) may end inside the block: rows from rows_y on are read
+    // from row rows_y - 1 instead, and the caller discards those accumulator columns (the logits
+    // of a vocabulary that is not a multiple of the block width).  rows_x is unused.  A k-major X is [K][ldx]
     // and the block takes its columns r0 .. r0 + 255; a k-major Y is [K][ldy], columns c0 .. + 255.
     // warm_stride = elements between the lane's warm-up line of one k-step and the next.
     template <bool GUARD>
     static __device__ __forceinline__ void gemm(const uint16_t* __restrict__ X, int64_t ldx,
                                                 int /*rows_x*/, const uint16_t* __restrict__ Y,
-                                                int64_t ldy, int /*rows_y*/, int K, int r0, int c0,
+                                                int64_t ldy, int rows_y, int K, int r0, int c0,
                                                 unsigned char* smem, f32x16_t (&acc)[kMT][kNT],
                                                 const uint16_t* warm, int64_t warm_stride = kBlockK,
                                                 const uint16_t* Y2 = nullptr, int /*K_y*/ = -1) {
@@ -437,7 +441,8 @@ struct DirectCoreT {
                 bool valid;
                 yg[q] = paired_row(Y, Y2, ldy, c0, row, 0x7fffffff, valid) + kc * 8;
             } else {
-                yg[q] = Y + (int64_t)(c0 + row) * ldy + kc * 8;
+                const int yrow = c0 + row < rows_y ? c0 + row : rows_y - 1;
+                yg[q] = Y + (int64_t)yrow * ldy + kc * 8;
             }
         }
         // elements from one k-step's tile to the next

@@ -486,7 +486,8 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
     const int kofs = p.info->kofs;
     const uint16_t* const hidden_t = p.hidden_t + (int64_t)kofs * p.H;
     const uint16_t* warm = Core::kCanGuard ? nullptr
-                                           : warm_row(p.PR, p.PC, hidden_t, p.H, r0, tr, p.W, p.H, c0, tc);
+                                           : warm_row(p.PR, p.PC, hidden_t, p.H, r0, tr, p.W, p.H, c0, tc,
+                                                      nullptr, p.V);
     Core::template gemm<GUARD>(hidden_t, p.H, Trc, p.W, p.H, p.V, p.H, r0, c0, smem, acc, warm);
 
     const typename Core::Lane lp;
@@ -495,7 +496,7 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
     for (int nt = 0; nt < kNT; ++nt) {
         const int i = r0 + lp.r(nt);
         const bool rowok = i < T_cur;
-        if (GUARD) {                    // unguarded builds run on V % 256 == 0 only
+        {                               // columns beyond the vocabulary (last column block)
             if (c0 + kBlockC > p.V) {
 #pragma unroll
                 for (int mt = 0; mt < kMT; ++mt)
@@ -872,7 +873,9 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
 
     // unguarded kernels need every extent block-aligned; the row extent always is (dense rows are
     // zero padded to a multiple of the block height)
-    const bool guard_logits = (V % kBlockC) != 0 || (H % kBlockK) != 0;
+    // (a vocabulary that ends inside a column block is handled by the unguarded logits kernel:
+    // it reads the last row of W in place of the missing ones and masks those columns)
+    const bool guard_logits = (H % kBlockK) != 0;
     const bool guard_h = (H % kBlockC) != 0;
     const bool guard_dh = guard_h || (V % kBlockK) != 0;      // dHidden: k = vocabulary id
 

@@ -59,6 +59,11 @@ CASES = [
     # few dHidden output blocks and a long vocabulary: the contraction over V is cut into ranges
     ("split_v_direct", 600, 256, 16640, 256, 0.1),
     ("split_v_guarded", 520, 136, 16392, 300, 0.1),
+    # block-aligned H, a vocabulary that ends inside a column block: unguarded logits and dW kernels
+    # (the missing rows of W are masked); dHidden unguarded when V is whole k-steps, else guarded
+    ("ragged_v_whole_ksteps", 600, 256, 1088, 256, 0.1),
+    ("ragged_v", 600, 256, 1000, 256, 0.1),
+    ("ragged_v_below_one_block", 300, 256, 72, 128, 0.1),
 ]
 
 
