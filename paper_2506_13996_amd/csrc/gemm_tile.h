@@ -1,28 +1,33 @@
-// Block-tile bf16 MFMA contraction for gfx950, shared by the three GEMMs of the tiled LM-head +
-// cross-entropy path (logits of a sequence tile, dHidden of the tile, dW accumulation).
-//
-//     D[r][c] = sum_k X[r][k] * Y[c][k]          X, Y bf16 with k contiguous, fp32 accumulation
+// Block-tile bf16 MFMA contraction for gfx950, shared by every GEMM of the library: the tiled
+// LM-head + cross-entropy path (logits of a sequence tile, dHidden of the tile, dW accumulation),
+// the tiled MLP and the tiled linear layer.
 //
 // One workgroup owns a 256 (r) x 256 (c) block of D and walks k in steps of 64 through two LDS
 // stages.  The c index is the MFMA row (register) dimension and r the MFMA column (lane)
 // dimension (v_mfma_f32_32x32x16_bf16), so a lane holds, for one r, runs of 4 consecutive c:
 // reductions over c stay mostly inside a lane and stores along c are vector stores.
 //
-// Two cores with the same accumulator interface:
-//   DirectCore  4 wavefronts (one per SIMD), 128 x 128 per wavefront, operands DMA'd straight from
-//               global memory into LDS (global_load_lds_dwordx4), MFMA operands double buffered in
-//               registers, barrier placed three quarters through a k-step so that the next
-//               stage's first operands are read while the last quarter is multiplied.  Needs
-//               every extent block-aligned (no bounds checks in the DMA path).
-//   StagedCore  8 wavefronts, 64 x 128 per wavefront, operands staged through registers with
+// An operand is either k-contiguous (a matrix [rows][k]) or k-major (a matrix [k][columns], the
+// block taking 256 of its columns).  Three combinations occur:
+//     D[r][c] = sum_k X[r][k] * Y[c][k]     both k-contiguous: logits, forward projections
+//     D[r][c] = sum_k X[r][k] * Y[k][c]     "mixed": a product with a weight matrix over its row
+//                                           index (dH = dZ W, da = dy Wd, dx = dg Wg + du Wu)
+//     D[r][c] = sum_k X[k][r] * Y[k][c]     both k-major: the weight-gradient products, whose k is
+//                                           the token row
+// so that every operand is read from memory as it is and nothing is ever transposed.
+//
+// Two families of cores with the same accumulator interface, each in the three layouts:
+//   DirectCore, MixedCore, KMajorCore
+//               4 wavefronts (one per SIMD), 128 x 128 per wavefront, operands DMA'd straight from
+//               global memory into LDS (global_load_lds_dwordx4), MFMA operands of the four
+//               k-slices of a step held in registers, one barrier in the middle of a k-step so
+//               that the next stage's first operands are read while the second half is
+//               multiplied.  A k-major tile lands in LDS as 64 k-rows and the MFMA operands are
+//               formed by the transposing LDS read (ds_read_b64_tr_b16).  No bounds checks in the
+//               DMA path: every extent block-aligned (see gemm for the one exception).
+//   StagedCore, StagedMixedCore, StagedKMajorCore
+//               8 wavefronts, 64 x 128 per wavefront, operands staged through registers with
 //               zero fill outside the matrices: the fallback for ragged shapes.
-//   KMajorCore  DirectCore for operands stored with k as the slow index,
-//                   D[r][c] = sum_k X[k][r] * Y[k][c],
-//               which is how the weight-gradient products meet their operands (k = token row):
-//               the DMA lands k-rows in LDS as they are and the MFMA operands are formed by the
-//               transposing LDS read (ds_read_b64_tr_b16), so no transposed copy is ever written.
-//   MixedCore   X k-contiguous, Y k-major: D[r][c] = sum_k X[r][k] * Y[k][c], a product with a
-//               weight matrix over its row index (dH = dZ W, da = dy Wd, dx = dg Wg + du Wu).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -41,7 +46,7 @@ typedef short i16x8_t __attribute__((ext_vector_type(8)));
 constexpr int kBlockR = 256;          // rows of X per block (MFMA lane dimension)
 constexpr int kBlockC = 256;          // rows of Y per block (MFMA register dimension)
 constexpr int kBlockK = 64;           // k per main-loop step
-constexpr int kGroupC = 128;          // c extent one wavefront covers (both cores)
+constexpr int kGroupC = 128;          // c extent one wavefront covers (all cores)
 constexpr int kTileBytes = kBlockR * kBlockK * 2;       // one operand tile in LDS (32 KB)
 constexpr int kStageBytes = 4 * kTileBytes;             // X, Y, two stages each (128 KB)
 constexpr int kLdsBytes = kStageBytes + 1024;           // + landing area of the L2 warm-up loads
