@@ -294,10 +294,10 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(
 // Per dense row of the tile: combine the per-group (max, sum exp) partials into lse, the row's loss
 // term (both written to the row's original position), and (fused mode) the factor that turns the
 // stashed e into a probability.
-// Block = 64 rows x 16 group lanes: thread (x, y) owns groups y, y + 16, ... of row x; the 16
-// lanes of a row are combined through LDS in a fixed order, so lse does not depend on anything
-// but the row's partials.
-constexpr int kCombineRows = 64, kCombineLanes = 16;
+// Block = 16 rows x 64 group lanes (a tile of 4096 rows gives 256 workgroups): thread (x, y) owns
+// groups y, y + 64, ... of row x; the 64 lanes of a row are combined through LDS in a fixed order,
+// so lse does not depend on anything but the row's partials.
+constexpr int kCombineRows = 16, kCombineLanes = 64;
 __global__ __launch_bounds__(kCombineRows * kCombineLanes) void row_combine_kernel(
     const float* __restrict__ pm, const float* __restrict__ ps, const float* __restrict__ zlabel,
     const int32_t* __restrict__ idx, const TileInfo* __restrict__ info, int Tp, int ng,
