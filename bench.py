@@ -159,6 +159,9 @@ def main() -> int:
                     help="fused: alst_tiled_ce_forward_backward (the headline); split: "
                          "alst_tiled_ce_forward then alst_tiled_ce_backward, which computes the "
                          "logits twice (8 M H V executed flop)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time replays of it (the per-kind "
+                         "times and the roofline then come from one extra, eagerly launched step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=2048)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -224,17 +227,31 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    B.alst_profile_enable(True)
-    B.alst_profile_read()
+    run_step, prof_steps = step, args.steps
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run_step, prof_steps = graph.replay, 1
+        graph.replay()
+        torch.cuda.synchronize()
+    else:
+        B.alst_profile_enable(True)
+        B.alst_profile_read()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     ev0.record()
     for _ in range(args.steps):
-        step()
+        run_step()
     ev1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    if args.graph:                      # one eager step under the per-kernel timer
+        B.alst_profile_enable(True)
+        B.alst_profile_read()
+        step()
+        torch.cuda.synchronize()
     prof = B.alst_profile_read()
     B.alst_profile_enable(False)
     status = B.alst_last_device_status(ws)
@@ -256,7 +273,7 @@ def main() -> int:
     gemm = {k: v for k, v in prof.items() if k.endswith("_gemm") and v[1] > 0}
     dom = max(gemm, key=lambda k: gemm[k][0])
     dom_ms, dom_n = gemm[dom]
-    flop_per_launch = (4.0 if split and dom == "logits_gemm" else 2.0) * M * H * V * args.steps / dom_n
+    flop_per_launch = (4.0 if split and dom == "logits_gemm" else 2.0) * M * H * V * prof_steps / dom_n
     achieved = flop_per_launch / (dom_ms / dom_n * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dom, "achieved": achieved,
                 "peak": MI355X_BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -264,7 +281,7 @@ def main() -> int:
                 "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get(wl.name, {}).get(dom) if tile == wl.tile else None,
                 "avg_launch_ms": dom_ms / dom_n, "launches": dom_n,
                 "flop_per_launch": flop_per_launch,
-                "per_kind_ms_per_step": {k: v[0] / args.steps for k, v in prof.items() if v[1]}}
+                "per_kind_ms_per_step": {k: v[0] / prof_steps for k, v in prof.items() if v[1]}}
     sustained = mfma_sustained(B)
     roofline["frac_of_sustained_random"] = achieved / sustained["random_operands_tflops"]
 
@@ -276,7 +293,8 @@ def main() -> int:
         "config": {"workload": wl.name, "N": N, "H": H, "V": V, "tile": tile,
                    "ignore_frac": wl.ignore_frac,
                    "entry": "alst_tiled_ce_forward + alst_tiled_ce_backward" if split
-                   else "alst_tiled_ce_forward_backward"},
+                   else "alst_tiled_ce_forward_backward",
+                   "launch": "hip graph replay" if args.graph else "eager"},
         "tflops_useful_6NHV": tflops,
         "mfma_peak_frac": tflops / MI355X_BF16_MFMA_PEAK_TFLOPS,
         ("tflops_executed_8MHV" if split else "tflops_executed_6MHV"): tflops_exec,

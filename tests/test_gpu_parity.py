@@ -302,3 +302,37 @@ def test_mfma_rate_aid_reports_a_plausible_rate():
         B.alst_debug_mfma_rate(2, 5000)
     with pytest.raises(B.AlstError):
         B.alst_debug_mfma_rate(1, 0)
+
+
+def test_hip_graph_replays_match_eager():
+    """The entry points only enqueue kernels on the caller's stream (no allocation, no memset, no
+    host synchronisation), so a call can be captured into a HIP graph.  Every replay, with eager
+    work and synchronisations between the replays, must reproduce the eager result bit for bit."""
+    wl = synth.custom("graph", 900, 256, 1280, 256, ignore_frac=0.1, seed=31)
+    h, W, y = synth.make_inputs(wl)
+    N, H, V, tile = wl.N, wl.H, wl.V, wl.tile
+    hd, Wd, yd = G.bits_to_dev(h), G.bits_to_dev(W), torch.from_numpy(y).cuda()
+    eager = G.run_fused(h, W, y, tile, dev_inputs=(hd, Wd, yd))       # also the first-call set-up
+
+    ws = B.alloc_workspace(N, H, V, tile)
+    loss = torch.zeros(1, device="cuda")
+    lse = torch.zeros(N, device="cuda")
+    dH = torch.zeros((N, H), dtype=torch.bfloat16, device="cuda")
+    dW = torch.zeros((V, H), dtype=torch.bfloat16, device="cuda")
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.alst_tiled_ce_forward_backward(hd, Wd, yd, tile, IGN, 1.0, loss_out=loss, lse_out=lse,
+                                         dHidden=dH, dW=dW, workspace=ws)
+    for replay in range(3):
+        for t in (loss, lse, dH, dW):
+            t.fill_(float("nan"))                                   # eager work between the replays
+        ws.random_(0, 255)                                          # the workspace holds no state
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert B.alst_last_device_status(ws) == B.ALST_OK
+        assert loss.cpu().numpy().view(np.uint32)[0] == eager.loss_bits, replay
+        assert torch.equal(dH.view(torch.int16), eager.dH_t.view(torch.int16)), replay
+        assert torch.equal(dW.view(torch.int16), eager.dW_t.view(torch.int16)), replay
+        assert np.array_equal(lse.cpu().numpy(), eager.lse), replay
