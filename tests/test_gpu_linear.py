@@ -76,3 +76,21 @@ def test_linear_flags_and_workspace_contract():
     assert a == B.alst_tiled_linear_workspace_bytes(10 ** 6, 4096, 4096, 4096, True) == 4 * 4096 * 4096
     # the fp32 sums live in dW itself for fp32 overwrite output: no scratch at all
     assert B.alst_tiled_linear_workspace_bytes(8192, 4096, 4096, 4096, True, B.ALST_FLAG_DW_FP32) == 0
+
+
+def test_linear_random_shapes_against_oracle():
+    """A seeded sweep of odd and block-aligned shapes (guarded and unguarded kernels, ragged tiles,
+    row counts that are not whole k-steps)."""
+    g = np.random.default_rng(78)
+    for case in range(10):
+        N = int(g.integers(1, 900))
+        K = int(g.choice([256, 512])) if case % 2 == 0 else int(g.integers(1, 40)) * 8
+        M = int(g.choice([256, 768, 1024])) if case % 3 != 2 else int(g.integers(1, 150)) * 8
+        tile = int(g.choice([1, 64, 100, 256, 300, 512]))
+        x, W, dy = _inputs(N, K, M, 400 + case)
+        y, dx, dW = _run(x, W, dy, tile)
+        ry = orc.forward(x, W)
+        rx, rW = orc.backward(x, W, dy)
+        tag = f"case {case}: N={N} K={K} M={M} tile={tile}"
+        for e in (G.grad_err(y, ry), G.grad_err(dx, rx), G.grad_err(dW, rW)):
+            assert e <= TOL, (tag, e)

@@ -206,3 +206,24 @@ def test_mlp_hip_graph_replays_match_eager():
         torch.cuda.synchronize()
         for a, b in zip(out, eager):
             assert torch.equal(a.view(torch.int16), b.view(torch.int16)), replay
+
+
+def test_mlp_random_shapes_against_oracle():
+    """A seeded sweep of odd and block-aligned shapes: every combination of guarded and unguarded
+    kernels, ragged tiles and row counts that are not whole k-steps."""
+    g = np.random.default_rng(77)
+    for case in range(10):
+        N = int(g.integers(1, 800))
+        H = int(g.choice([256, 512])) if case % 2 == 0 else int(g.integers(1, 40)) * 8
+        I = int(g.choice([128, 256, 384, 512])) if case % 3 != 2 else int(g.integers(1, 70)) * 8
+        tile = int(g.choice([1, 64, 100, 256, 300, 512]))
+        wl = synth.MlpWorkload(f"rnd{case}", N, H, I, tile, seed=300 + case)
+        x, Wg, Wu, Wd, dy = synth.make_mlp_inputs(wl)
+        Wg = synth.normal_bf16(I, H, 0.25, 300 + case, synth.STREAM_MLP_WG)
+        yr = orc.forward(x, Wg, Wu, Wd, row_block=256)
+        ref = orc.backward(x, Wg, Wu, Wd, dy, row_block=256)
+        y, dx, gW = _run(x, Wg, Wu, Wd, dy, tile)
+        errs = [G.grad_err(y, yr), G.grad_err(dx, ref[0])] + [G.grad_err(a, b) for a, b in zip(gW, ref[1:])]
+        tag = f"case {case}: N={N} H={H} I={I} tile={tile}"
+        for e in errs:
+            assert e <= TOL, (tag, errs)

@@ -281,6 +281,26 @@ def test_random_shapes_against_oracle():
         assert (r.dH[y == IGN] == 0.0).all(), tag
 
 
+def test_random_shapes_with_block_aligned_hidden_size():
+    """The same sweep with H a multiple of the block width, so that the unguarded kernels meet
+    vocabularies, row counts and tiles of every alignment (V a multiple of 64 in half the cases,
+    which also takes dHidden off the guarded core)."""
+    g = np.random.default_rng(2025)
+    for case in range(10):
+        N = int(g.integers(1, 1200))
+        H = int(g.choice([256, 512]))
+        V = int(g.integers(1, 30)) * 64 if case % 2 == 0 else int(g.integers(2, 2000))
+        tile = int(g.choice([1, 64, 100, 256, 300, 512, 1000]))
+        frac = float(g.choice([0.0, 0.1, 0.5]))
+        wl = synth.custom(f"rnda{case}", N, H, V, tile, ignore_frac=frac, seed=200 + case)
+        h, W, y = synth.make_inputs(wl)
+        f, dH, dW = _oracle(h, W, y, grad_loss=0.75)
+        r = G.run_fused(h, W, y, tile, grad_loss=0.75)
+        tag = f"case {case}: N={N} H={H} V={V} tile={tile} ignored={frac}"
+        _check(r, f, dH, dW, tag, valid=(y != IGN))
+        assert (r.dH[y == IGN] == 0.0).all(), tag
+
+
 def test_large_logits_stay_finite_and_match():
     """Weights 30x the workload law: logits of several tens, a peaked softmax, losses up to ~100."""
     wl = synth.custom("big", 512, 256, 2048, 256, ignore_frac=0.05, seed=13)
