@@ -163,7 +163,7 @@ def main() -> int:
                     help="capture one step into a HIP graph and time replays of it (the per-kind "
                          "times and the roofline then come from one extra, eagerly launched step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=2048)
+    ap.add_argument("--cpu-rows", type=int, default=4096)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy before the timed region, so "
                          "that a rocprofv3 --pmc run holds a kernel of known traffic to scale "
