@@ -356,3 +356,19 @@ def test_hip_graph_replays_match_eager():
         assert torch.equal(dH.view(torch.int16), eager.dH_t.view(torch.int16)), replay
         assert torch.equal(dW.view(torch.int16), eager.dW_t.view(torch.int16)), replay
         assert np.array_equal(lse.cpu().numpy(), eager.lse), replay
+
+
+def test_runs_on_the_callers_stream():
+    """Everything is enqueued on the stream handed in (here a second, non-default stream of default
+    priority): results are complete once that stream is synchronised, and match the default-stream run."""
+    wl = synth.custom("stream", 700, 256, 1536, 256, ignore_frac=0.1, seed=41)
+    h, W, y = synth.make_inputs(wl)
+    base = G.run_fused(h, W, y, wl.tile)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        r = G.run_fused(h, W, y, wl.tile)
+    side.synchronize()
+    assert r.status == B.ALST_OK and r.loss_bits == base.loss_bits
+    assert torch.equal(r.dH_t.view(torch.int16), base.dH_t.view(torch.int16))
+    assert torch.equal(r.dW_t.view(torch.int16), base.dW_t.view(torch.int16))
