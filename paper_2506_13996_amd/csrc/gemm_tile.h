@@ -140,7 +140,9 @@ __device__ __forceinline__ const uint16_t* warm_row(int PR, int PC, const uint16
 __device__ __forceinline__ const uint16_t* warm_line_kmajor(int PR, int PC, const uint16_t* X,
                                                             int64_t ldx, int r0, int tr,
                                                             const uint16_t* Y, int64_t ldy, int c0,
-                                                            int tc, int64_t& step) {
+                                                            int tc, int64_t& step,
+                                                            int cols_x = 0x7fffffff,
+                                                            int cols_y = 0x7fffffff) {
     const int nx = kBlockR / PC, ny = kBlockC / PR, total = nx + ny, per = (total + 3) / 4;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     int l = w * per + (lane < per ? lane : per - 1);
@@ -148,18 +150,21 @@ __device__ __forceinline__ const uint16_t* warm_line_kmajor(int PR, int PC, cons
     if (l < nx) {
         const int L = (tc % PC) * nx + l;
         step = ldx * kBlockK;
-        return X + (int64_t)(L >> 2) * ldx + r0 + (L & 3) * 64;
+        const int col = r0 + (L & 3) * 64;
+        return X + (int64_t)(L >> 2) * ldx + (col < cols_x ? col : cols_x - 8);
     }
     const int L = (tr % PR) * ny + (l - nx);
     step = ldy * kBlockK;
-    return Y + (int64_t)(L >> 2) * ldy + c0 + (L & 3) * 64;
+    const int col = c0 + (L & 3) * 64;
+    return Y + (int64_t)(L >> 2) * ldy + (col < cols_y ? col : cols_y - 8);
 }
 
 // X k-contiguous (its lines are rows), Y k-major.
 __device__ __forceinline__ const uint16_t* warm_line_mixed(int PR, int PC, const uint16_t* X,
                                                            int64_t ldx, int r0, int tr,
                                                            const uint16_t* Y, int64_t ldy, int c0,
-                                                           int tc, int64_t& step) {
+                                                           int tc, int64_t& step,
+                                                           int cols_y = 0x7fffffff) {
     const int nx = kBlockR / PC, ny = kBlockC / PR, total = nx + ny, per = (total + 3) / 4;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     int l = w * per + (lane < per ? lane : per - 1);
@@ -170,7 +175,8 @@ __device__ __forceinline__ const uint16_t* warm_line_mixed(int PR, int PC, const
     }
     const int L = (tr % PR) * ny + (l - nx);
     step = ldy * kBlockK;
-    return Y + (int64_t)(L >> 2) * ldy + c0 + (L & 3) * 64;
+    const int col = c0 + (L & 3) * 64;
+    return Y + (int64_t)(L >> 2) * ldy + (col < cols_y ? col : cols_y - 8);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -403,15 +409,18 @@ struct DirectCoreT {
     // kc ^ ((row >> 1) & 7): sixteen consecutive rows at one kc then cover all 64 banks once.
     static __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
-    // Requires r0 + 256 <= rows of X, K % 64 == 0, K >= 64, 16-byte aligned rows.  GUARD must be
-    // false.  A k-contiguous Y (without Y2) may end inside the block: rows from rows_y on are read
-    // from row rows_y - 1 instead, and the caller discards those accumulator columns (the logits
-    // of a vocabulary that is not a multiple of the block width).  rows_x is unused.  A k-major X is [K][ldx]
+    // Requires K % 64 == 0, K >= 64, 16-byte aligned rows, and a k-contiguous X with r0 + 256 <= its
+    // rows.  GUARD must be false.  The other operands may end inside the block, and the caller
+    // discards the accumulator rows / columns that lie outside: a k-contiguous Y (without Y2) is
+    // read from its row rows_y - 1 in place of the rows from rows_y on (the logits of a vocabulary
+    // that is not a multiple of the block width); a k-major X or Y with rows_x / rows_y columns (a
+    // multiple of 8) is read from its last 8 columns in place of those beyond (a hidden size that
+    // is not a multiple of the block width).  What is read instead is finite data of the operand.  A k-major X is [K][ldx]
     // and the block takes its columns r0 .. r0 + 255; a k-major Y is [K][ldy], columns c0 .. + 255.
     // warm_stride = elements between the lane's warm-up line of one k-step and the next.
     template <bool GUARD>
     static __device__ __forceinline__ void gemm(const uint16_t* __restrict__ X, int64_t ldx,
-                                                int /*rows_x*/, const uint16_t* __restrict__ Y,
+                                                int rows_x, const uint16_t* __restrict__ Y,
                                                 int64_t ldy, int rows_y, int K, int r0, int c0,
                                                 unsigned char* smem, f32x16_t (&acc)[kMT][kNT],
                                                 const uint16_t* warm, int64_t warm_stride = kBlockK,
@@ -438,10 +447,11 @@ struct DirectCoreT {
             const int ch = (lane & 31) ^ (kswz(krow) << 2);
             const int row = (w * 8 + q) * 8 + lr;
             const int kc = pc ^ swz(row);
-            if (XK) xg[q] = X + (int64_t)krow * ldx + r0 + ch * 8;
+            // (the clamps: see the comment of this function)
+            if (XK) xg[q] = X + (int64_t)krow * ldx + (r0 + ch * 8 < rows_x ? r0 + ch * 8 : rows_x - 8);
             else xg[q] = X + (int64_t)(r0 + row) * ldx + kc * 8;
             if (YK) {
-                yg[q] = Y + (int64_t)krow * ldy + c0 + ch * 8;
+                yg[q] = Y + (int64_t)krow * ldy + (c0 + ch * 8 < rows_y ? c0 + ch * 8 : rows_y - 8);
             } else if (Y2) {                        // gated pair (k-contiguous only)
                 bool valid;
                 yg[q] = paired_row(Y, Y2, ldy, c0, row, 0x7fffffff, valid) + kc * 8;
@@ -637,7 +647,7 @@ __device__ __forceinline__ void store_block_bf16(const f32x16_t (&acc)[Core::kMT
 // covers 32 consecutive floats of one row of `out` and the accumulate is one fire-and-forget fp32
 // atomic add per register on full 128-byte lines (a plain store when `first`).  Each element
 // belongs to exactly one lane per launch; launches on one stream are ordered, so the sums are
-// formed in launch order: deterministic.  Rows r >= r_valid (GUARD) and c >= c_valid are skipped.
+// formed in launch order: deterministic.  Rows r >= r_valid and c >= c_valid are skipped.
 template <class Core, bool GUARD>
 __device__ __forceinline__ void accumulate_block_f32(const f32x16_t (&acc)[Core::kMT][Core::kNT],
                                                      float* __restrict__ out, int64_t ld, int r0,
@@ -646,7 +656,7 @@ __device__ __forceinline__ void accumulate_block_f32(const f32x16_t (&acc)[Core:
 #pragma unroll
     for (int nt = 0; nt < Core::kNT; ++nt) {
         const int r = r0 + lp.r(nt);
-        if (GUARD && r >= r_valid) continue;
+        if (r >= r_valid) continue;
 #pragma unroll
         for (int mt = 0; mt < Core::kMT; ++mt)
 #pragma unroll

@@ -631,7 +631,7 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
     int64_t step = 0;
     const uint16_t* warm = Core::kCanGuard ? nullptr
                                            : warm_line_mixed(p.PR, p.PC, dz, p.Vp, r0, tr, Wk, p.H, c0,
-                                                             tc, step);
+                                                             tc, step, p.H);
     Core::template gemm<GUARD>(dz, p.Vp, Trc, Wk, p.H, p.H, klen, r0, c0, smem, acc, warm, step, nullptr,
                                p.V - k0);
 
@@ -646,7 +646,7 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int h = c0 + lp.c(mt, q);
-                    if (GUARD && h >= p.H) continue;
+                    if (h >= p.H) continue;             // last column block of a ragged H
                     f32x4_t o;
 #pragma unroll
                     for (int x = 0; x < 4; ++x) o[x] = acc[mt][nt][q * 4 + x];
@@ -666,7 +666,7 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int h = c0 + lp.c(mt, q);
-                if (GUARD && h >= p.H) continue;
+                if (h >= p.H) continue;             // last column block of a ragged H
                 bf16x4_t o;
 #pragma unroll
                 for (int x = 0; x < 4; ++x) o[x] = (__bf16)(acc[mt][nt][q * 4 + x] * inv);
@@ -738,7 +738,7 @@ __global__ __launch_bounds__(Core::kThreads) void dw_kernel(const DWParams p) {
         int64_t step = 0;
         const uint16_t* warm = Core::kCanGuard ? nullptr
                                                : warm_line_kmajor(p.PR, p.PC, p.hg, p.H, r0, tr, p.dzg,
-                                                                  p.Vp, c0, tc, step);
+                                                                  p.Vp, c0, tc, step, p.H, p.Vp);
         Core::template gemm<GUARD>(p.hg, p.H, p.H, p.dzg, p.Vp, p.Vp, Tkc, r0, c0, smem, acc, warm, step);
     }
 
@@ -764,7 +764,6 @@ static int prepare_kernels() {
     acc(allow_big_lds(dhidden_kernel<MixedCore, false>));
     acc(allow_big_lds(dhidden_kernel<StagedMixedCore, true>));
     acc(allow_big_lds(dw_kernel<KMajorCore, false>));
-    acc(allow_big_lds(dw_kernel<StagedKMajorCore, true>));
     states[dev] = rc + 1;
     return rc;
 }
@@ -876,8 +875,10 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
     // (a vocabulary that ends inside a column block is handled by the unguarded logits kernel:
     // it reads the last row of W in place of the missing ones and masks those columns)
     const bool guard_logits = (H % kBlockK) != 0;
-    const bool guard_h = (H % kBlockC) != 0;
-    const bool guard_dh = guard_h || (V % kBlockK) != 0;      // dHidden: k = vocabulary id
+    // dHidden contracts over the vocabulary and needs it in whole k-steps; a hidden size that ends
+    // inside a block is handled by the unguarded dHidden and dW kernels (the missing columns of W
+    // and of the dense hidden rows are read from the last ones and the results discarded)
+    const bool guard_dh = (V % kBlockK) != 0;
 
     // The host does not know M: it walks ceil(N / T) tiles, the most there can be; the kernels of
     // a tile beyond the dense rows find Tc = 0 on the device and leave at once.
@@ -968,12 +969,8 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             wp.PR = pg.PR; wp.PC = pg.PC;
             const int grid = grid_for_patches(pg.patches());
             ProfScope ps_(PROF_DW, s);
-            if (guard_h)
-                hipLaunchKernelGGL((dw_kernel<StagedKMajorCore, true>), dim3(grid),
-                                   dim3(StagedKMajorCore::kThreads), kLdsBytes, s, wp);
-            else
-                hipLaunchKernelGGL((dw_kernel<KMajorCore, false>), dim3(grid),
-                                   dim3(KMajorCore::kThreads), kLdsBytes, s, wp);
+            hipLaunchKernelGGL((dw_kernel<KMajorCore, false>), dim3(grid), dim3(KMajorCore::kThreads),
+                               kLdsBytes, s, wp);
             ALST_HIP(hipGetLastError());
         }
     }

@@ -299,7 +299,7 @@ __global__ __launch_bounds__(Core::kThreads) void wgrad_kernel(const WgradBatch 
     int64_t step = 0;
     const uint16_t* warm = Core::kCanGuard ? nullptr
                                            : warm_line_kmajor(PR, PC, p.X, p.ldx, r0, tr, p.Y, p.ldy,
-                                                              c0, tc, step);
+                                                              c0, tc, step, p.rows_x, p.rows_y);
     Core::template gemm<GUARD>(p.X, p.ldx, p.rows_x, p.Y, p.ldy, p.rows_y, p.K, r0, c0, smem, acc, warm,
                                step);
     accumulate_block_f32<Core, GUARD>(acc, p.out, p.ld, r0, c0, p.rows_x, p.rows_y, p.first != 0);
@@ -421,14 +421,11 @@ static int launch_wgrad_batch(const WgradParams* ps, int n, bool direct, hipStre
 }
 
 // The n weight-gradient products (n <= kMaxBatch, all with the same K) in one launch.  The
-// unguarded core needs block-aligned output extents and K in whole k-steps: with aligned
-// extents, the whole k-steps go to it and the K % 64 rows left over to a second, guarded launch.
+// unguarded core needs K in whole k-steps (output extents that end inside a block are its
+// business): the whole k-steps go to it and the K % 64 rows left over to a second, guarded launch.
 static int launch_wgrad(const WgradParams* ps, int n, hipStream_t s) {
-    bool aligned = true;
-    for (int i = 0; i < n; ++i)
-        aligned = aligned && ps[i].rows_x % kBlockR == 0 && ps[i].rows_y % kBlockC == 0;
     const int K = ps[0].K, K_whole = K / kBlockK * kBlockK;
-    if (!aligned || K_whole == 0) return launch_wgrad_batch(ps, n, false, s);
+    if (K_whole == 0) return launch_wgrad_batch(ps, n, false, s);
     WgradParams part[kMaxBatch];
     for (int i = 0; i < n; ++i) { part[i] = ps[i]; part[i].K = K_whole; }
     int rc = launch_wgrad_batch(part, n, true, s);
