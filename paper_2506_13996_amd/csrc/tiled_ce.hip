@@ -57,6 +57,8 @@ struct TileInfo {
     int Trc;               // Tc rounded up to the block height (256)
     int Tkc;               // Tc rounded up to the k-step (64)
     int kofs;              // where the tile's dense rows start along k in the dW group buffers
+    int splits;            // dHidden: ranges the contraction over V is cut into for this tile
+    int ksteps;            //          k-steps of 64 per range (the last range may be shorter)
 };
 
 // dW is accumulated into the fp32 [V, H] sums once per GROUP of consecutive tiles: the dense
@@ -77,28 +79,37 @@ struct Layout {
     int64_t Tp, Vp, ng;    // padded tile rows, padded vocabulary, 128-column groups
     int g;                 // tiles per dW group
     int64_t Kg;            // dense rows a group can hold: g * Tp
-    int splits, ksteps;    // dHidden: ranges of the contraction over V, k-steps per range
+    int dh_PR, dh_PC;      // dHidden: patch shape of the block -> tile mapping
+    int64_t dh_patches;    //          most patches (over all ranges) a tile of any number of rows needs
+    int64_t dh_part_rows;  //          most rows of fp32 partial products (0: never cut)
     size_t header, tinfo, loss_rows, lse, idx, block_cnt, block_ofs, zlabel, yc, pm, ps, sc, hc,
         stash, part, acc, total;
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// dHidden has (Tp / 256) * (H / 256) output blocks.  Picks the number of ranges (1..8) the
-// contraction over V is cut into so that the workgroups fill the 256 compute units of the chip
-// most evenly (ties: fewest ranges), each range keeping at least 64 k-steps.
+// dHidden has (rows / 256) * (H / 256) output blocks for a tile of `rows` dense rows (a multiple
+// of 256).  Picks the number of ranges (1..8) the contraction over V is cut into so that the
+// workgroups fill the 256 compute units of the chip most evenly (ties: fewest ranges), each range
+// keeping at least 64 k-steps.  The tile's row count is known on the device only, so
+// tile_info_kernel makes the choice; the host evaluates the same function for every possible row
+// count to size the launch and the buffer of partial products.
 constexpr int kComputeUnits = 256;
-static void dhidden_splits(int64_t Tp, int64_t H, int64_t V, int& splits, int& ksteps) {
-    const int64_t blocks = (Tp / kBlockR) * ((H + kBlockC - 1) / kBlockC);
+// part_rows_cap: the ranges' fp32 partial products (splits * rows rows) must fit that many rows
+// (0: no limit).
+__host__ __device__ inline void dhidden_splits(int64_t rows, int64_t H, int64_t V, int64_t part_rows_cap,
+                                               int& splits, int& ksteps) {
+    const int64_t blocks = (rows / kBlockR) * ((H + kBlockC - 1) / kBlockC);
     const int KT = (int)((V + kBlockK - 1) / kBlockK);
-    double best = -1.0;
+    int64_t best_wg = 0, best_slots = 1;               // fill = best_wg / best_slots
     splits = 1;
     for (int sp = 1; sp <= 8; ++sp) {
         const int per = (KT + sp - 1) / sp;
         if (sp > 1 && (per < 64 || (int64_t)(sp - 1) * per >= KT)) break;
-        const int64_t wg = blocks * sp, rounds = (wg + kComputeUnits - 1) / kComputeUnits;
-        const double fill = (double)wg / (double)(rounds * kComputeUnits);
-        if (fill > best + 1e-9) { best = fill; splits = sp; }
+        if (sp > 1 && part_rows_cap > 0 && sp * rows > part_rows_cap) break;
+        const int64_t wg = blocks * sp;
+        const int64_t slots = (wg + kComputeUnits - 1) / kComputeUnits * kComputeUnits;
+        if (wg * best_slots > best_wg * slots) { best_wg = wg; best_slots = slots; splits = sp; }
     }
     ksteps = (KT + splits - 1) / splits;
 }
@@ -131,8 +142,27 @@ static Layout make_layout(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_
     // the two operands of the group's dW product as they are (k = dense row, the slow index)
     L.hc = take((size_t)L.Kg * H * 2);
     L.stash = take((size_t)L.Kg * L.Vp * 2);
-    dhidden_splits(L.Tp, H, V, L.splits, L.ksteps);
-    L.part = take(L.splits > 1 ? (size_t)L.splits * L.Tp * H * 4 : 0);
+    {   // dHidden: the launch and the partial products are sized for the worst tile
+        const PatchGrid pg = choose_patches((int)(L.Tp / kBlockR), (int)((H + kBlockC - 1) / kBlockC));
+        L.dh_PR = pg.PR; L.dh_PC = pg.PC;
+        // partial products: what a full tile needs, and no less than one tile's rows, so that a
+        // smaller last tile may be cut into more ranges than a full one
+        int sp_full, ks;
+        dhidden_splits(L.Tp, H, V, 0, sp_full, ks);
+        L.dh_part_rows = (int64_t)sp_full * L.Tp;
+        L.dh_patches = 0;
+        // (beyond 4096 row blocks per tile only the full tile is looked at; tile_info_kernel then
+        // keeps a smaller tile's choice within these bounds)
+        const int64_t rb_max = L.Tp / kBlockR, rb_lo = rb_max > 4096 ? rb_max : 1;
+        for (int64_t rb = rb_lo; rb <= rb_max; ++rb) {
+            int sp;
+            dhidden_splits(rb * kBlockR, H, V, L.dh_part_rows, sp, ks);
+            const PatchGrid g = {(int)rb, pg.tiles_c, pg.PR, pg.PC};
+            const int64_t patches = (int64_t)g.patches() * sp;
+            if (patches > L.dh_patches) L.dh_patches = patches;
+        }
+    }
+    L.part = take((size_t)L.dh_part_rows * H * 4);
     const bool acc_in_dw = (flags & ALST_FLAG_DW_FP32) && !(flags & ALST_FLAG_DW_ACCUMULATE);
     L.acc = take(acc_in_dw ? 0 : (size_t)V * H * 4);
     L.total = o;
@@ -258,14 +288,32 @@ __global__ __launch_bounds__(kScanThreads) void scatter_index_kernel(
 
 // The counts of tile t (dense rows [t T, t T + T) cut at M) and its k offset inside its dW group.
 __global__ void tile_info_kernel(const Header* __restrict__ h, int64_t t, int64_t T,
-                                 TileInfo* __restrict__ info, const TileInfo* __restrict__ prev) {
+                                 TileInfo* __restrict__ info, const TileInfo* __restrict__ prev,
+                                 int64_t H, int64_t V, int64_t Tp, int64_t dh_patches,
+                                 int64_t dh_part_rows, int PR, int PC) {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     long long left = h->n_valid - t * T;
     const int Tc = (int)(left < 0 ? 0 : (left > T ? T : left));
+    const int Trc = (Tc + kBlockR - 1) / kBlockR * kBlockR;
     info->Tc = Tc;
-    info->Trc = (Tc + kBlockR - 1) / kBlockR * kBlockR;
+    info->Trc = Trc;
     info->Tkc = (Tc + kBlockK - 1) / kBlockK * kBlockK;
     info->kofs = prev ? prev->kofs + prev->Tkc : 0;     // prev: the tile before, same dW group
+    // dHidden of this tile: as many ranges of V as fill the chip best for its Trc rows, within
+    // what the launch and the buffer of partial products were sized for
+    int sp = 1, ks = (int)((V + kBlockK - 1) / kBlockK);
+    if (Trc > 0) {
+        dhidden_splits(Trc, H, V, dh_part_rows, sp, ks);
+        const PatchGrid g = {Trc / kBlockR, (int)((H + kBlockC - 1) / kBlockC), PR, PC};
+        if ((int64_t)g.patches() * sp > dh_patches || (sp > 1 && (int64_t)sp * Trc > dh_part_rows))
+            dhidden_splits(Tp, H, V, 0, sp, ks);        // the full tile's choice always fits
+        if ((int64_t)g.patches() * sp > dh_patches || (sp > 1 && (int64_t)sp * Trc > dh_part_rows)) {
+            sp = 1;
+            ks = (int)((V + kBlockK - 1) / kBlockK);
+        }
+    }
+    info->splits = sp;
+    info->ksteps = ks;
 }
 
 // Block b: dense row b of the tile.  Copies the hidden row of token idx_t[b] into the dense
@@ -587,10 +635,9 @@ struct DHiddenParams {
     const int32_t* idx;
     const TileInfo* info;
     const Header* hdr;
-    float* part;             // [splits, Tp, H] fp32 partial products (splits > 1)
+    float* part;             // [splits, Trc, H] fp32 partial products (splits > 1); the number
+                             // of ranges and their length are the tile's (TileInfo)
     int Tp, H, V, Vp;
-    int splits;              // the contraction over V is cut into this many ranges
-    int ksteps;              // k-steps of 64 per range (the last range may be shorter)
     int PR, PC;              // patch shape of the block -> tile mapping
 };
 
@@ -612,11 +659,12 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
     int P, w;
     patch_of_block(blockIdx.x, P, w);
     const int np = pg.patches(), split = P / np;
-    if (split >= p.splits || !tile_in_patch(pg, P - split * np, w, tr, tc)) return;
+    const int splits = p.info->splits, ksteps = p.info->ksteps;
+    if (split >= splits || !tile_in_patch(pg, P - split * np, w, tr, tc)) return;
     const int r0 = tr * kBlockR, c0 = tc * kBlockC;
     // k runs over V rounded up to whole k-steps: dZ is zero there, rows of W beyond V are not read
-    const int k0 = split * p.ksteps * kBlockK;
-    const int klen = min(p.ksteps * kBlockK, (p.V + kBlockK - 1) / kBlockK * kBlockK - k0);   // > 0
+    const int k0 = split * ksteps * kBlockK;
+    const int klen = min(ksteps * kBlockK, (p.V + kBlockK - 1) / kBlockK * kBlockK - k0);     // > 0
 
     f32x16_t acc[kMT][kNT];
 #pragma unroll
@@ -636,8 +684,8 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
                                p.V - k0);
 
     const typename Core::Lane lp;
-    if (p.splits > 1) {
-        float* const part = p.part + (int64_t)split * p.Tp * p.H;
+    if (splits > 1) {
+        float* const part = p.part + (int64_t)split * Trc * p.H;
 #pragma unroll
         for (int nt = 0; nt < kNT; ++nt) {
             float* row = part + (int64_t)(r0 + lp.r(nt)) * p.H;
@@ -676,20 +724,21 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
 }
 
 // dH[idx[i]] = (g/M) * sum over the ranges of the partial products of dense row i, in range order.
-__global__ __launch_bounds__(256) void dhidden_reduce_kernel(const float* __restrict__ part,
-                                                             int splits, int Tp, int H,
+// Tiles whose contraction was not cut were written by dhidden_kernel itself.
+__global__ __launch_bounds__(256) void dhidden_reduce_kernel(const float* __restrict__ part, int H,
                                                              const int32_t* __restrict__ idx,
                                                              const TileInfo* __restrict__ info,
                                                              const Header* __restrict__ hdr,
                                                              uint16_t* __restrict__ dH) {
     const int i = blockIdx.x;
-    if (i >= info->Tc) return;
+    const int splits = info->splits, Trc = info->Trc;
+    if (i >= info->Tc || splits <= 1) return;
     const float inv = hdr->inv;
     uint16_t* out = dH + (int64_t)idx[i] * H;
     for (int c = threadIdx.x * 4; c < H; c += 256 * 4) {
         f32x4_t a = *reinterpret_cast<const f32x4_t*>(part + (int64_t)i * H + c);
         for (int sp = 1; sp < splits; ++sp)
-            a += *reinterpret_cast<const f32x4_t*>(part + ((int64_t)sp * Tp + i) * H + c);
+            a += *reinterpret_cast<const f32x4_t*>(part + ((int64_t)sp * Trc + i) * H + c);
         bf16x4_t o;
 #pragma unroll
         for (int x = 0; x < 4; ++x) o[x] = (__bf16)(a[x] * inv);
@@ -806,7 +855,7 @@ static int validate(const Problem& P, size_t workspace_bytes, bool need_fwd_out,
     // every launch must fit a one-dimensional grid
     if (!checked_grid(L.Tp / kBlockR, L.Vp / kBlockC) ||
         !checked_grid((P.H + kBlockR - 1) / kBlockR, L.Vp / kBlockC) ||
-        !checked_grid(L.Tp / kBlockR * 8, (P.H + kBlockC - 1) / kBlockC) ||      // dHidden, 8 ranges
+        L.dh_patches * 32 > 0x7fffff00 ||                                        // dHidden
         (L.Vp / 256) * (L.Tp / 64) > 0x7fffffff)
         return ALST_ERR_SHAPE;
     if (workspace_bytes < L.total) return ALST_ERR_WORKSPACE;
@@ -893,7 +942,8 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
         {
             ProfScope small_(PROF_OTHER, s);
             hipLaunchKernelGGL(tile_info_kernel, dim3(1), dim3(64), 0, s, hdr, t, T, info,
-                               slot ? info - 1 : nullptr);
+                               slot ? info - 1 : nullptr, P.H, P.V, L.Tp, L.dh_patches, L.dh_part_rows,
+                               L.dh_PR, L.dh_PC);
             hipLaunchKernelGGL(gather_rows_kernel, dim3(Tr), dim3(256), 0, s, P.hidden, P.labels, H,
                                idx_t, info, hc, yc);
             ALST_HIP(hipGetLastError());
@@ -945,10 +995,9 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             dp.info = info; dp.hdr = hdr;
             dp.part = reinterpret_cast<float*>(P.ws + L.part);
             dp.Tp = Tp; dp.H = H; dp.V = V; dp.Vp = Vp;
-            dp.splits = L.splits; dp.ksteps = L.ksteps;
-            const PatchGrid pg = choose_patches(Tr / kBlockR, (H + kBlockC - 1) / kBlockC);
-            dp.PR = pg.PR; dp.PC = pg.PC;
-            const int grid = grid_for_patches((int64_t)pg.patches() * L.splits);
+            dp.PR = L.dh_PR; dp.PC = L.dh_PC;
+            // enough workgroups for whatever number of rows and ranges the tile turns out to have
+            const int grid = grid_for_patches(L.dh_patches);
             ProfScope ps_(PROF_DHIDDEN, s);
             if (guard_dh)
                 hipLaunchKernelGGL((dhidden_kernel<StagedMixedCore, true>), dim3(grid),
@@ -956,9 +1005,9 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             else
                 hipLaunchKernelGGL((dhidden_kernel<MixedCore, false>), dim3(grid),
                                    dim3(MixedCore::kThreads), kLdsBytes, s, dp);
-            if (L.splits > 1)
-                hipLaunchKernelGGL(dhidden_reduce_kernel, dim3(Tr), dim3(256), 0, s, dp.part,
-                                   L.splits, Tp, H, idx_t, info, hdr, P.dHidden);
+            if (L.dh_part_rows > 0)
+                hipLaunchKernelGGL(dhidden_reduce_kernel, dim3(Tr), dim3(256), 0, s, dp.part, H, idx_t,
+                                   info, hdr, P.dHidden);
             ALST_HIP(hipGetLastError());
         }
         if (slot == L.g - 1 || t == ntiles - 1) {           // the group is complete

@@ -59,6 +59,9 @@ CASES = [
     # few dHidden output blocks and a long vocabulary: the contraction over V is cut into ranges
     ("split_v_direct", 600, 256, 16640, 256, 0.1),
     ("split_v_guarded", 520, 136, 16392, 300, 0.1),
+    # a full tile of 64 output blocks is cut into 4 ranges, the last tile (2 row blocks) into 8: the
+    # number of ranges is chosen per tile on the device
+    ("split_v_last_tile_differs", 8500, 512, 33280, 8192, 0.0),
     # block-aligned H, a vocabulary that ends inside a column block: unguarded logits and dW kernels
     # (the missing rows of W are masked); dHidden unguarded when V is whole k-steps, else guarded
     ("ragged_v_whole_ksteps", 600, 256, 1088, 256, 0.1),
