@@ -23,8 +23,9 @@
  *   - Layout: dense row-major, no strides: hidden[N,H], W[V,H], dHidden[N,H], dW[V,H].
  *     bf16 = bfloat16 (upper half of an IEEE binary32).  H must be a multiple of 8 and every
  *     base pointer 16-byte aligned, else ALST_ERR_ALIGN.  Any V >= 1 is accepted.  The fastest
- *     kernels are used when H and V are multiples of 64 (neither has to be a multiple of the
- *     256-wide blocks the kernels work in); other sizes run on slower, bounds-checked kernels.
+ *     kernels are used for every V and every H that is a multiple of 64 (neither has to be a
+ *     multiple of the 256-wide blocks the kernels work in); with another H the logits run on a
+ *     slower, bounds-checked kernel.
  *   - Ownership: the caller owns every buffer, including `workspace`; the library allocates and
  *     frees no device memory and keeps no state between calls, so peak device memory is
  *     inputs + outputs + alst_tiled_ce_workspace_bytes().  Calls that share a workspace must be

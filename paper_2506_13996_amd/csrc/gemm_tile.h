@@ -164,7 +164,8 @@ __device__ __forceinline__ const uint16_t* warm_line_mixed(int PR, int PC, const
                                                            int64_t ldx, int r0, int tr,
                                                            const uint16_t* Y, int64_t ldy, int c0,
                                                            int tc, int64_t& step,
-                                                           int cols_y = 0x7fffffff) {
+                                                           int cols_y = 0x7fffffff,
+                                                           int krows_y = 0x7fffffff) {
     const int nx = kBlockR / PC, ny = kBlockC / PR, total = nx + ny, per = (total + 3) / 4;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     int l = w * per + (lane < per ? lane : per - 1);
@@ -176,7 +177,8 @@ __device__ __forceinline__ const uint16_t* warm_line_mixed(int PR, int PC, const
     const int L = (tr % PR) * ny + (l - nx);
     step = ldy * kBlockK;
     const int col = c0 + (L & 3) * 64;
-    return Y + (int64_t)(L >> 2) * ldy + (col < cols_y ? col : cols_y - 8);
+    const int krow = (L >> 2) < krows_y ? (L >> 2) : krows_y - 1;
+    return Y + (int64_t)krow * ldy + (col < cols_y ? col : cols_y - 8);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -415,7 +417,10 @@ struct DirectCoreT {
     // read from its row rows_y - 1 in place of the rows from rows_y on (the logits of a vocabulary
     // that is not a multiple of the block width); a k-major X or Y with rows_x / rows_y columns (a
     // multiple of 8) is read from its last 8 columns in place of those beyond (a hidden size that
-    // is not a multiple of the block width).  What is read instead is finite data of the operand.  A k-major X is [K][ldx]
+    // is not a multiple of the block width).  What is read instead is finite data of the operand.
+    // MixedCore only: K_y (if >= 0 and < K) is the number of k-rows Y has when X is zero-padded
+    // along k beyond it (W in dH = dZ W for a vocabulary that is not whole k-steps): the k-rows of
+    // the last step that Y lacks are read from its last row, and meet zeros of X.  A k-major X is [K][ldx]
     // and the block takes its columns r0 .. r0 + 255; a k-major Y is [K][ldy], columns c0 .. + 255.
     // warm_stride = elements between the lane's warm-up line of one k-step and the next.
     template <bool GUARD>
@@ -424,7 +429,7 @@ struct DirectCoreT {
                                                 int64_t ldy, int rows_y, int K, int r0, int c0,
                                                 unsigned char* smem, f32x16_t (&acc)[kMT][kNT],
                                                 const uint16_t* warm, int64_t warm_stride = kBlockK,
-                                                const uint16_t* Y2 = nullptr, int /*K_y*/ = -1) {
+                                                const uint16_t* Y2 = nullptr, int K_y = -1) {
         static_assert(!GUARD, "DirectCore has no bounds checks");
         typedef const __attribute__((address_space(1))) void* gptr_t;
         typedef __attribute__((address_space(3))) void* lptr_t;
@@ -462,6 +467,24 @@ struct DirectCoreT {
         }
         // elements from one k-step's tile to the next
         const int64_t xstep = XK ? ldx * kBlockK : kBlockK, ystep = YK ? ldy * kBlockK : kBlockK;
+        // MixedCore, Y shorter than the loop's K: the lane's sources in the last k-step, clamped
+        constexpr bool kTail = YK && !XK;
+        const int KT_ = K / kBlockK;
+        const bool ytail = kTail && K_y >= 0 && K_y < K;
+        const uint16_t* yg_tail[8];
+        if (kTail) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int krow = (KT_ - 1) * kBlockK + w * 16 + q * 2 + (lane >> 5);
+                const int ch = (lane & 31) ^ (kswz(krow) << 2);
+                const int kr = ytail && krow >= K_y ? K_y - 1 : krow;
+                yg_tail[q] = Y + (int64_t)kr * ldy + (c0 + ch * 8 < rows_y ? c0 + ch * 8 : rows_y - 8);
+            }
+        }
+        auto ysrc = [&](int q, int kt) -> const uint16_t* {
+            if (kTail) return (ytail && kt == KT_ - 1) ? yg_tail[q] : yg[q] + kt * ystep;
+            return yg[q] + kt * ystep;
+        };
         auto issue_loads = [&](int stage, int kt) {
             unsigned char* xs = smem + stage * kTileBytes + w * 8192;
             unsigned char* ys = smem + 2 * kTileBytes + stage * kTileBytes + w * 8192;
@@ -469,8 +492,7 @@ struct DirectCoreT {
             for (int q = 0; q < 8; ++q) {
                 __builtin_amdgcn_global_load_lds((gptr_t)(xg[q] + kt * xstep),
                                                  (lptr_t)(xs + q * 1024), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds((gptr_t)(yg[q] + kt * ystep),
-                                                 (lptr_t)(ys + q * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((gptr_t)ysrc(q, kt), (lptr_t)(ys + q * 1024), 16, 0, 0);
             }
         };
 
@@ -513,7 +535,10 @@ struct DirectCoreT {
         constexpr bool warming = true;
         unsigned char* const dump = smem + kStageBytes + w * 256;
         auto warm_step = [&](int kt) {
-            const int kk = kt < KT ? kt : KT - 1;
+            // (with a Y that lacks k-rows of the last step, that step is not warmed: the lane's
+            // line may be one of them)
+            const int last = ytail && KT > 1 ? KT - 2 : KT - 1;
+            const int kk = kt < last ? kt : last;
             __builtin_amdgcn_global_load_lds((gptr_t)(warm + kk * warm_stride), (lptr_t)dump, 4, 0, 0);
         };
         // Joins the wavefronts once this wavefront's DMA of the next stage has landed.  The warm-up
@@ -578,8 +603,8 @@ struct DirectCoreT {
             for (int i = 0; i < 8; ++i) {
                 mfma_pair(3, i);
                 if (LOADS)
-                    __builtin_amdgcn_global_load_lds((gptr_t)(yg[i] + (kt + 2) * ystep),
-                                                     (lptr_t)(ys + i * 1024), 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds((gptr_t)ysrc(i, kt + 2), (lptr_t)(ys + i * 1024), 16,
+                                                     0, 0);
                 if (NEXT) read_item(cur ^ 1, 1, i);
                 __builtin_amdgcn_sched_barrier(0);
             }

@@ -679,7 +679,7 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
     int64_t step = 0;
     const uint16_t* warm = Core::kCanGuard ? nullptr
                                            : warm_line_mixed(p.PR, p.PC, dz, p.Vp, r0, tr, Wk, p.H, c0,
-                                                             tc, step, p.H);
+                                                             tc, step, p.H, p.V - k0);
     Core::template gemm<GUARD>(dz, p.Vp, Trc, Wk, p.H, p.H, klen, r0, c0, smem, acc, warm, step, nullptr,
                                p.V - k0);
 
@@ -811,7 +811,6 @@ static int prepare_kernels() {
     acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_BWD>));
     acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_BWD>));
     acc(allow_big_lds(dhidden_kernel<MixedCore, false>));
-    acc(allow_big_lds(dhidden_kernel<StagedMixedCore, true>));
     acc(allow_big_lds(dw_kernel<KMajorCore, false>));
     states[dev] = rc + 1;
     return rc;
@@ -924,10 +923,10 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
     // (a vocabulary that ends inside a column block is handled by the unguarded logits kernel:
     // it reads the last row of W in place of the missing ones and masks those columns)
     const bool guard_logits = (H % kBlockK) != 0;
-    // dHidden contracts over the vocabulary and needs it in whole k-steps; a hidden size that ends
-    // inside a block is handled by the unguarded dHidden and dW kernels (the missing columns of W
-    // and of the dense hidden rows are read from the last ones and the results discarded)
-    const bool guard_dh = (V % kBlockK) != 0;
+    // (a hidden size that ends inside a block is handled by the unguarded dHidden and dW kernels:
+    // the missing columns of W and of the dense hidden rows are read from the last ones and the
+    // results discarded; a vocabulary that is not whole k-steps by the unguarded dHidden kernel:
+    // the rows W lacks in the last k-step are read from its last row and meet zeros of dZ)
 
     // The host does not know M: it walks ceil(N / T) tiles, the most there can be; the kernels of
     // a tile beyond the dense rows find Tc = 0 on the device and leave at once.
@@ -999,12 +998,8 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             // enough workgroups for whatever number of rows and ranges the tile turns out to have
             const int grid = grid_for_patches(L.dh_patches);
             ProfScope ps_(PROF_DHIDDEN, s);
-            if (guard_dh)
-                hipLaunchKernelGGL((dhidden_kernel<StagedMixedCore, true>), dim3(grid),
-                                   dim3(StagedMixedCore::kThreads), kLdsBytes, s, dp);
-            else
-                hipLaunchKernelGGL((dhidden_kernel<MixedCore, false>), dim3(grid),
-                                   dim3(MixedCore::kThreads), kLdsBytes, s, dp);
+            hipLaunchKernelGGL((dhidden_kernel<MixedCore, false>), dim3(grid), dim3(MixedCore::kThreads),
+                               kLdsBytes, s, dp);
             if (L.dh_part_rows > 0)
                 hipLaunchKernelGGL(dhidden_reduce_kernel, dim3(Tr), dim3(256), 0, s, dp.part, H, idx_t,
                                    info, hdr, P.dHidden);
