@@ -121,3 +121,56 @@ def test_full_size_workload(name):
     assert colsum <= 2e-2 * gmax * np.sqrt(V) / 16, (colsum, gmax)
     print(f"[{name}] loss {lg:.6f} (oracle {gold['loss']:.6f})  dH err {eh:.2e}  dW err {ew:.2e}  "
           f"colsum {colsum:.2e}  peak {peak / 2**30:.2f} GiB", flush=True)
+
+
+@pytest.mark.timeout(600)
+def test_row_offsets_beyond_32_bits():
+    """A sequence whose hidden states hold more than 2^32 elements (N * H = 4.5e9; element offsets of
+    the last rows do not fit 32 bits) with a small vocabulary: sampled rows from both ends against the
+    oracle, rows of ignored tokens exact zeros, columns of dW summing to zero.  The inputs are drawn on
+    the device (the oracle sees the same bits for the rows it checks)."""
+    N, H, V, tile = 1_100_000, 4096, 512, 4096
+    g = torch.Generator(device="cuda").manual_seed(7)
+    hd = torch.empty((N, H), dtype=torch.bfloat16, device="cuda")
+    for lo in range(0, N, 100_000):                          # in pieces: bounded temporaries
+        hi = min(lo + 100_000, N)
+        hd[lo:hi] = torch.randn((hi - lo, H), device="cuda", generator=g).bfloat16()
+    Wd = (torch.randn((V, H), device="cuda", generator=g) * 0.02).bfloat16()
+    yd = torch.randint(0, V, (N,), device="cuda", generator=g, dtype=torch.int32)
+    ign = torch.rand((N,), device="cuda", generator=g) < 0.1
+    yd[ign] = IGN
+    n_valid = int((~ign).sum().item())
+
+    ws = B.alloc_workspace(N, H, V, tile)
+    loss = torch.zeros(1, device="cuda")
+    lse = torch.zeros(N, device="cuda")
+    nv = torch.zeros(1, dtype=torch.int64, device="cuda")
+    dH = torch.full((N, H), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((V, H), dtype=torch.float32, device="cuda")
+    B.alst_tiled_ce_forward_backward(hd, Wd, yd, tile, IGN, 1.0, loss_out=loss, lse_out=lse, n_valid_out=nv,
+                                     dHidden=dH, dW=dW, workspace=ws, flags=B.ALST_FLAG_DW_FP32)
+    assert B.alst_last_device_status(ws) == B.ALST_OK
+    torch.cuda.synchronize()
+    assert int(nv.item()) == n_valid
+
+    rows = np.unique(np.concatenate([np.arange(0, 40), np.arange(N - 40, N),
+                                     np.random.default_rng(1).integers(0, N, 60)]))
+    rt = torch.from_numpy(rows).cuda()
+    bits = lambda t: t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    h_sub, W_all, y_sub = bits(hd[rt]), bits(Wd), yd[rt].cpu().numpy()
+    ref, lse_r, loss_r = orc.dhidden_rows(h_sub, W_all, y_sub, np.arange(len(rows)), n_valid, ignore_index=IGN)
+    got = dH[rt].float().cpu().numpy().astype(np.float64)
+    assert G.grad_err(got, ref) <= 2e-2
+    vr = y_sub != IGN
+    assert np.abs(lse[rt].cpu().numpy().astype(np.float64)[vr] - lse_r[vr]).max() <= 1e-3 * np.log(V)
+    # every row was written: ignored ones as exact zeros, none left at the NaN it was filled with
+    assert bool((dH[ign].view(torch.int16) == 0).all())
+    assert bool(torch.isfinite(dH.float().abs().max()))
+    # the mean loss is the mean of (lse - label logit) over the valid rows; the logits are
+    # ~ N(0, 0.0004 H), so it is close to ln V + 0.0002 H, and the sampled rows' mean agrees with it
+    # within their spread
+    lg = float(loss.item())
+    assert abs(lg - (np.log(V) + 0.0002 * H)) < 0.02 * lg
+    assert abs(lg - loss_r[vr].mean()) < 5 * loss_r[vr].std() / np.sqrt(vr.sum()) + 1e-3
+    gmax = float(dW.abs().max().item())
+    assert float(dW.double().sum(dim=0).abs().max().item()) <= 1e-3 * gmax * V
