@@ -174,3 +174,49 @@ def test_row_offsets_beyond_32_bits():
     assert abs(lg - loss_r[vr].mean()) < 5 * loss_r[vr].std() / np.sqrt(vr.sum()) + 1e-3
     gmax = float(dW.abs().max().item())
     assert float(dW.double().sum(dim=0).abs().max().item()) <= 1e-3 * gmax * V
+
+
+@pytest.mark.timeout(600)
+def test_scratch_offsets_beyond_32_bits():
+    """A vocabulary wide enough that the dZ scratch of one dW group (16384 rows x V) holds more than
+    2^32 elements, with a small hidden size: rows from the end of a group (whose scratch offsets do
+    not fit 32 bits) and from the other tiles against the oracle, plus the zero-sum property of dW."""
+    N, H, V, tile = 17_000, 256, 270_336, 4096
+    assert 4 * tile * V > 2 ** 32
+    g = torch.Generator(device="cuda").manual_seed(8)
+    hd = torch.randn((N, H), device="cuda", generator=g).bfloat16()
+    Wd = (torch.randn((V, H), device="cuda", generator=g) * 0.05).bfloat16()
+    yd = torch.randint(0, V, (N,), device="cuda", generator=g, dtype=torch.int32)
+    n_valid = N
+
+    ws = B.alloc_workspace(N, H, V, tile)
+    loss = torch.zeros(1, device="cuda")
+    lse = torch.zeros(N, device="cuda")
+    dH = torch.full((N, H), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((V, H), dtype=torch.float32, device="cuda")
+    B.alst_tiled_ce_forward_backward(hd, Wd, yd, tile, IGN, 1.0, loss_out=loss, lse_out=lse, dHidden=dH, dW=dW,
+                                     workspace=ws, flags=B.ALST_FLAG_DW_FP32)
+    assert B.alst_last_device_status(ws) == B.ALST_OK
+    torch.cuda.synchronize()
+
+    rows = np.unique(np.concatenate([np.arange(0, 8), np.arange(4 * tile - 24, 4 * tile + 8),
+                                     np.arange(N - 16, N), np.random.default_rng(2).integers(0, N, 24)]))
+    rt = torch.from_numpy(rows).cuda()
+    bits = lambda t: t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    ref, lse_r, loss_r = orc.dhidden_rows(bits(hd[rt]), bits(Wd), yd[rt].cpu().numpy(), np.arange(len(rows)),
+                                          n_valid, ignore_index=IGN)
+    got = dH[rt].float().cpu().numpy().astype(np.float64)
+    assert G.grad_err(got, ref) <= 2e-2
+    assert np.abs(lse[rt].cpu().numpy().astype(np.float64) - lse_r).max() <= 1e-3 * np.log(V)
+    assert bool(torch.isfinite(dH.float().abs().max()))
+    lg = float(loss.item())
+    assert abs(lg - loss_r.mean()) < 5 * loss_r.std() / np.sqrt(len(rows)) + 1e-3
+    gmax = float(dW.abs().max().item())
+    assert float(dW.double().sum(dim=0).abs().max().item()) <= 1e-3 * gmax * np.sqrt(V)
+    # the label rows of dW carry -h/M: check a few of them (no other token shares these labels)
+    lab, cnt = torch.unique(yd, return_counts=True)
+    single = lab[cnt == 1][:8]
+    for v in single.tolist():
+        i = int((yd == v).nonzero()[0].item())
+        expect = -hd[i].float() / n_valid                 # the softmax part is ~1/V of it
+        assert float((dW[v] - expect).abs().max().item()) <= 0.05 * float(expect.abs().max().item())
