@@ -11,6 +11,9 @@ outputs it can compute exactly, plus properties that hold at any size:
 Bars as in test_gpu_parity.py: loss 1e-3 relative, gradients 2e-2 of max |oracle gradient| (the
 maximum is taken over the sampled oracle entries, a lower bound of the true one, so the check is
 stricter than the stated bar).
+
+Two further cases push single dimensions past 32-bit element offsets (hidden states of more than
+2^32 elements; a dZ scratch of more than 2^32 elements) and check sampled rows and closed forms.
 """
 import json
 import os
