@@ -471,15 +471,18 @@ struct DirectCoreT {
         constexpr bool kTail = YK && !XK;
         const int KT_ = K / kBlockK;
         const bool ytail = kTail && K_y >= 0 && K_y < K;
-        auto ysrc = [&](int q, int kt) -> const uint16_t* {
-            if (kTail) {
-                if (ytail && kt == KT_ - 1) {           // once per block: recomputed, not kept
-                    const int krow = kt * kBlockK + w * 16 + q * 2 + (lane >> 5);
-                    const int ch = (lane & 31) ^ (kswz(krow) << 2);
-                    const int kr = krow < K_y ? krow : K_y - 1;
-                    return Y + (int64_t)kr * ldy + (c0 + ch * 8 < rows_y ? c0 + ch * 8 : rows_y - 8);
-                }
+        const uint16_t* yg_tail[8];
+        if (kTail) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int krow = (KT_ - 1) * kBlockK + w * 16 + q * 2 + (lane >> 5);
+                const int ch = (lane & 31) ^ (kswz(krow) << 2);
+                const int kr = ytail && krow >= K_y ? K_y - 1 : krow;
+                yg_tail[q] = Y + (int64_t)kr * ldy + (c0 + ch * 8 < rows_y ? c0 + ch * 8 : rows_y - 8);
             }
+        }
+        auto ysrc = [&](int q, int kt) -> const uint16_t* {
+            if (kTail) return (ytail && kt == KT_ - 1) ? yg_tail[q] : yg[q] + kt * ystep;
             return yg[q] + kt * ystep;
         };
         auto issue_loads = [&](int stage, int kt) {
