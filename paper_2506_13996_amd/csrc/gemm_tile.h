@@ -418,12 +418,12 @@ struct DirectCoreT {
     // that is not a multiple of the block width); a k-major X or Y with rows_x / rows_y columns (a
     // multiple of 8) is read from its last 8 columns in place of those beyond (a hidden size that
     // is not a multiple of the block width).  What is read instead is finite data of the operand.
-    // MixedCore only: K_y (if >= 0 and < K) is the number of k-rows Y has when X is zero-padded
+    // MixedCore with YTAIL only: K_y (if >= 0 and < K) is the number of k-rows Y has when X is zero-padded
     // along k beyond it (W in dH = dZ W for a vocabulary that is not whole k-steps): the k-rows of
     // the last step that Y lacks are read from its last row, and meet zeros of X.  A k-major X is [K][ldx]
     // and the block takes its columns r0 .. r0 + 255; a k-major Y is [K][ldy], columns c0 .. + 255.
     // warm_stride = elements between the lane's warm-up line of one k-step and the next.
-    template <bool GUARD>
+    template <bool GUARD, bool YTAIL = false>
     static __device__ __forceinline__ void gemm(const uint16_t* __restrict__ X, int64_t ldx,
                                                 int rows_x, const uint16_t* __restrict__ Y,
                                                 int64_t ldy, int rows_y, int K, int r0, int c0,
@@ -468,7 +468,7 @@ struct DirectCoreT {
         // elements from one k-step's tile to the next
         const int64_t xstep = XK ? ldx * kBlockK : kBlockK, ystep = YK ? ldy * kBlockK : kBlockK;
         // MixedCore, Y shorter than the loop's K: the lane's sources in the last k-step, clamped
-        constexpr bool kTail = YK && !XK;
+        constexpr bool kTail = YTAIL && YK && !XK;
         const int KT_ = K / kBlockK;
         const bool ytail = kTail && K_y >= 0 && K_y < K;
         const uint16_t* yg_tail[8];

@@ -646,7 +646,7 @@ struct DHiddenParams {
 // number does not fill the compute units evenly, the contraction is cut into `splits` ranges, each
 // range's blocks write fp32 partial products, and dhidden_reduce_kernel adds them in a fixed
 // order.
-template <class Core, bool GUARD>
+template <class Core, bool GUARD, bool YTAIL>
 __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenParams p) {
     constexpr int kMT = Core::kMT, kNT = Core::kNT;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -680,8 +680,9 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
     const uint16_t* warm = Core::kCanGuard ? nullptr
                                            : warm_line_mixed(p.PR, p.PC, dz, p.Vp, r0, tr, Wk, p.H, c0,
                                                              tc, step, p.H, p.V - k0);
-    Core::template gemm<GUARD>(dz, p.Vp, Trc, Wk, p.H, p.H, klen, r0, c0, smem, acc, warm, step, nullptr,
-                               p.V - k0);
+    // YTAIL: the vocabulary is not whole k-steps and the last range's last step lacks rows of W
+    Core::template gemm<GUARD, YTAIL>(dz, p.Vp, Trc, Wk, p.H, p.H, klen, r0, c0, smem, acc, warm, step,
+                                      nullptr, p.V - k0);
 
     const typename Core::Lane lp;
     if (splits > 1) {
@@ -810,7 +811,8 @@ static int prepare_kernels() {
     acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_FUSED>));
     acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_BWD>));
     acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_BWD>));
-    acc(allow_big_lds(dhidden_kernel<MixedCore, false>));
+    acc(allow_big_lds(dhidden_kernel<MixedCore, false, false>));
+    acc(allow_big_lds(dhidden_kernel<MixedCore, false, true>));
     acc(allow_big_lds(dw_kernel<KMajorCore, false>));
     states[dev] = rc + 1;
     return rc;
@@ -998,8 +1000,12 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             // enough workgroups for whatever number of rows and ranges the tile turns out to have
             const int grid = grid_for_patches(L.dh_patches);
             ProfScope ps_(PROF_DHIDDEN, s);
-            hipLaunchKernelGGL((dhidden_kernel<MixedCore, false>), dim3(grid), dim3(MixedCore::kThreads),
-                               kLdsBytes, s, dp);
+            if (V % kBlockK != 0)
+                hipLaunchKernelGGL((dhidden_kernel<MixedCore, false, true>), dim3(grid),
+                                   dim3(MixedCore::kThreads), kLdsBytes, s, dp);
+            else
+                hipLaunchKernelGGL((dhidden_kernel<MixedCore, false, false>), dim3(grid),
+                                   dim3(MixedCore::kThreads), kLdsBytes, s, dp);
             if (L.dh_part_rows > 0)
                 hipLaunchKernelGGL(dhidden_reduce_kernel, dim3(Tr), dim3(256), 0, s, dp.part, H, idx_t,
                                    info, hdr, P.dHidden);
