@@ -22,7 +22,7 @@ MI355X_BF16_MFMA_PEAK_TFLOPS = 2500.0      # dense bf16, vendor figure
 # Memory-side bytes per launch (calibrated FETCH_SIZE + WRITE_SIZE from two `rocprofv3 --pmc` runs of
 # this script on llama8b_128k, see profiles/bench_llama8b_128k_hbm_traffic.txt); other workloads: None.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
-    "llama8b_128k": {"logits_gemm": 6.806e9, "dhidden_gemm": 5.839e9, "dw_gemm": 25.232e9},
+    "llama8b_128k": {"logits_gemm": 6.806e9, "dhidden_gemm": 5.843e9, "dw_gemm": 25.259e9},
 }
 
 
