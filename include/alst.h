@@ -29,7 +29,10 @@
  *   - Ownership: the caller owns every buffer, including `workspace`; the library allocates and
  *     frees no device memory and keeps no state between calls, so peak device memory is
  *     inputs + outputs + alst_tiled_ce_workspace_bytes().  Calls that share a workspace must be
- *     ordered on one stream.
+ *     ordered on one stream; calls on different workspaces may come from different host threads.
+ *     The one thing remembered is that a device's kernels have been given their LDS size
+ *     attribute: the first compute call on each device sets it (once, behind a lock) and must
+ *     therefore be made outside a HIP graph capture.
  *   - The functions validate on the host, enqueue work on `stream` and return without
  *     synchronising.  Outputs are valid once the stream has been synchronised.
  *   - Errors: an alst_status value is returned; host-detectable errors are returned before
@@ -62,7 +65,7 @@ typedef enum {
     ALST_ERR_WORKSPACE = 4,   /* workspace_bytes smaller than alst_tiled_ce_workspace_bytes() */
     ALST_ERR_LABEL_RANGE = 5, /* device: a label outside [0,V) that is not ignore_index */
     ALST_ERR_HIP = 6,         /* a HIP runtime call or kernel launch failed */
-    ALST_ERR_UNSUPPORTED = 7, /* unknown flag bits */
+    ALST_ERR_UNSUPPORTED = 7, /* unknown flag bits, or a flag the entry point does not take */
     ALST_ERR_NONFINITE = 8    /* device: the loss is not finite */
 } alst_status;
 
@@ -74,6 +77,19 @@ typedef enum {
  * the gradients are those of that sum (scaled by grad_loss instead of grad_loss / M). */
 #define ALST_FLAG_REDUCE_SUM 4u
 
+/* The dW sums are updated after EVERY tile instead of once per group of tiles, so the scratch holds
+ * the bf16 dZ rows and the dense hidden rows of one tile only: workspace = O(tile * V) + O(V * H)
+ * with the constant 1 (2 bytes per logit of one tile), the memory contract of Sequence Tiling to
+ * the letter.  Without the flag the scratch holds a group of tiles (about 16384 rows: 8 tiles of
+ * up to 2048 rows, 4 of 4096, 2 of 8192, 1 beyond), which saves the read-modify-write of the fp32
+ * dW sums and the dW GEMM's start-up on all but the group's last tile.  Results agree to fp32
+ * summation order. */
+#define ALST_FLAG_TILE_SCRATCH 8u
+/* alst_tiled_ce_workspace_bytes() / alst_tiled_ce_forward() / alst_tiled_ce_token_losses() only:
+ * the workspace is sized for the forward pass alone (no dZ scratch, no dW sums); the entry points
+ * that compute gradients return ALST_ERR_UNSUPPORTED for it. */
+#define ALST_FLAG_FORWARD_ONLY 16u
+
 /* Static, NUL-terminated description of a status value.  Host only. */
 const char* alst_status_string(int status);
 
@@ -82,10 +98,15 @@ int alst_version(void);
 
 /*
  * Bytes of device scratch the three compute entry points need for this problem, 0 if the
- * shape is invalid.  Pure host arithmetic, no device access.  The value is independent of N
- * except for about 12 * N bytes (per-row loss term, lse and dense-row index): this is the
- * memory contract of Sequence Tiling, peak = O(N * H) for the activations and their gradients
- * + O(tile * V) + O(V * H).
+ * shape or the flags are invalid.  Pure host arithmetic, no device access.  The value is
+ * independent of N except for about 12 * N bytes (per-row loss term, lse and dense-row index):
+ * this is the memory contract of Sequence Tiling, peak = O(N * H) for the activations and their
+ * gradients + O(tile * V) + O(V * H).  With Tp, Vp = tile and V rounded up to 256 the large terms are
+ *   2 * Kg * (Vp + H)   bf16 dZ rows and dense hidden rows of the Kg rows in flight: Kg = Tp with
+ *                       ALST_FLAG_TILE_SCRATCH, else Tp * clamp(16384 / Tp, 1, 8) (a group of tiles)
+ *   4 * V * H           fp32 dW sums (absent for fp32 overwrite output, whose sums live in dW)
+ *   12 * (Vp / 128) * Tp  softmax partials of one tile
+ * and with ALST_FLAG_FORWARD_ONLY only the last one and 2 * Tp * H remain.
  */
 size_t alst_tiled_ce_workspace_bytes(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_t flags);
 
@@ -118,9 +139,10 @@ int alst_tiled_ce_backward(const void* hidden, const void* W, const int32_t* lab
                            void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
 
 /*
- * Forward and backward of every tile in one sweep, as the paper's method does it ("compute the
- * forward and backward passes on each shard independently"): 6NHV flop, each tile's logits are
- * computed once.  Arguments as in the two calls above; lse_out and n_valid_out may be NULL.
+ * Forward and backward of every tile in one sweep, as the paper's method does it (section
+ * "Sequence Tiling for Reducing Activation Memory Footprint": forward and backward of a logits
+ * shard are done together, shard by shard): 6NHV flop, each tile's logits are computed once.
+ * Arguments as in the two calls above; lse_out and n_valid_out may be NULL.
  */
 int alst_tiled_ce_forward_backward(const void* hidden, const void* W, const int32_t* labels,
                                    int64_t N, int64_t H, int64_t V, int64_t tile,
@@ -142,10 +164,12 @@ int alst_last_device_status(void* workspace, void* stream);
  * for ignored ones, [N] fp32, as left in `workspace` by the last alst_tiled_ce_forward or
  * alst_tiled_ce_forward_backward call on it with the same N, H, V, tile and flags (the per-token
  * loss computations the paper's section "Sequence Tiling ..." lists among the operations without
- * cross-sequence dependency).  Enqueued on `stream` after that call.
+ * cross-sequence dependency).  Enqueued on `stream` after that call.  workspace_bytes is checked
+ * against alst_tiled_ce_workspace_bytes() of the same arguments (ALST_ERR_WORKSPACE).
  */
-int alst_tiled_ce_token_losses(const void* workspace, int64_t N, int64_t H, int64_t V, int64_t tile,
-                               uint32_t flags, float* token_loss_out, void* stream);
+int alst_tiled_ce_token_losses(const void* workspace, size_t workspace_bytes, int64_t N, int64_t H,
+                               int64_t V, int64_t tile, uint32_t flags, float* token_loss_out,
+                               void* stream);
 
 /*
  * Label utility for the boundary convention above (section "Loss Sharding in Hugging Face
@@ -155,41 +179,6 @@ int alst_tiled_ce_token_losses(const void* workspace, int64_t N, int64_t H, int6
  */
 int alst_shift_labels(const int32_t* labels, int32_t* shift_labels, int64_t N,
                       int32_t ignore_index, void* stream);
-
-/*
- * Benchmarking aid (no counterpart in the paper).  While enabled, every launch of a block GEMM and
- * each group of small kernels between them is bracketed by a pair of HIP events on the launch
- * stream.  alst_profile_read() waits for the recorded events, writes per kind the summed
- * milliseconds and the number of spans into the HOST arrays ms_total[8] and launches[8], and
- * forgets the spans.  Kinds: 0 logits GEMM, 1 dHidden GEMM, 2 dW GEMM, 3 the small kernels of a
- * cross-entropy tile; 4 the projection GEMMs of the tiled MLP (alst_mlp.h), 5 its weight-gradient
- * GEMMs, 6 its small kernels; 7 unused.  This is the only state the library keeps between calls;
- * it is process-wide and not thread-safe.
- */
-int alst_profile_enable(int on);
-int alst_profile_read(double* ms_total, int64_t* launches);
-
-/*
- * Testing aid (no counterpart in the paper; host arithmetic only, no device is touched).  The block
- * GEMM launches deal their workgroups round-robin to the 8 XCDs of the chip and give the 32
- * workgroups resident on one XCD a compact patch of output blocks; a launch may hold several
- * products ("parts") whose patches are numbered through.  For a launch of `parts` products of
- * tiles_r x tiles_c blocks this returns the number of workgroups and writes, for workgroup `bid`,
- * the part and block it computes (part = -1: the workgroup leaves at once), evaluated with the
- * same functions the kernels use.  A negative return value is minus an alst_status.
- */
-int alst_debug_block_tile(int tiles_r, int tiles_c, int parts, int bid, int* part, int* tr, int* tc);
-
-/*
- * Benchmarking aid (no counterpart in the paper): the sustained rate, in TFLOP/s, of the bf16
- * matrix instruction the block GEMMs are built on, measured on the current device with a loop that
- * touches no memory (one wavefront per SIMD of every compute unit, 64 * iters instructions each).
- * It is the ceiling the GEMM kernels can be compared with besides the published peak: the clock
- * under matrix load depends on the power drawn, hence on the operand bits.  data = 0: small-integer
- * operands, 1: random operands in [-1, 1).  scratch: device, 256 * 256 floats, overwritten;
- * tflops: HOST double.  1 <= iters <= 2^22.  Synchronises `stream`.
- */
-int alst_debug_mfma_rate(int data, int iters, float* scratch, double* tflops, void* stream);
 
 #ifdef __cplusplus
 }

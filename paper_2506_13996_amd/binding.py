@@ -19,11 +19,14 @@ ALST_ERR_LABEL_RANGE, ALST_ERR_HIP, ALST_ERR_UNSUPPORTED, ALST_ERR_NONFINITE = 5
 ALST_FLAG_DW_FP32 = 1
 ALST_FLAG_DW_ACCUMULATE = 2
 ALST_FLAG_REDUCE_SUM = 4
+ALST_FLAG_TILE_SCRATCH = 8
+ALST_FLAG_FORWARD_ONLY = 16
 
 EXPORTS = (
     "alst_status_string", "alst_version", "alst_tiled_ce_workspace_bytes", "alst_tiled_ce_forward",
     "alst_tiled_ce_backward", "alst_tiled_ce_forward_backward", "alst_last_device_status",
-    "alst_shift_labels", "alst_tiled_ce_token_losses", "alst_profile_enable", "alst_profile_read", "alst_debug_block_tile", "alst_debug_mfma_rate",
+    "alst_shift_labels", "alst_tiled_ce_token_losses",
+    "alst_profile_enable", "alst_profile_read", "alst_debug_block_tile", "alst_debug_mfma_rate",
     "alst_tiled_mlp_workspace_bytes", "alst_tiled_mlp_forward", "alst_tiled_mlp_backward",
     "alst_tiled_linear_workspace_bytes", "alst_tiled_linear_forward", "alst_tiled_linear_backward",
 )
@@ -64,7 +67,7 @@ def load_library() -> ctypes.CDLL:
     lib.alst_shift_labels.restype = c.c_int
     lib.alst_shift_labels.argtypes = [vp, vp, i64, i32, vp]
     lib.alst_tiled_ce_token_losses.restype = c.c_int
-    lib.alst_tiled_ce_token_losses.argtypes = [vp, i64, i64, i64, i64, u32, vp, vp]
+    lib.alst_tiled_ce_token_losses.argtypes = [vp, sz, i64, i64, i64, i64, u32, vp, vp]
     lib.alst_tiled_mlp_workspace_bytes.restype = sz
     lib.alst_tiled_mlp_workspace_bytes.argtypes = [i64, i64, i64, i64, c.c_int, u32]
     lib.alst_tiled_mlp_forward.restype = c.c_int
@@ -106,6 +109,48 @@ def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
+def _want(t, name: str, dtype, shape=None, optional: bool = False):
+    """The C ABI sees only addresses: a tensor of another dtype, a strided view or a host tensor
+    would be reinterpreted silently, so the binding refuses them here."""
+    if t is None and optional:
+        return
+    why = None
+    if t is None:
+        why = "a tensor is required"
+    elif not isinstance(t, torch.Tensor):
+        why = f"expected a torch.Tensor, got {type(t).__name__}"
+    elif t.dtype != dtype:
+        why = f"must be {dtype}, got {t.dtype}"
+    elif not t.is_contiguous():
+        why = "must be contiguous (dense row-major, no strides)"
+    elif shape is not None and tuple(t.shape) != tuple(shape):
+        why = f"expected shape {tuple(shape)}, got {tuple(t.shape)}"
+    if why:
+        raise TypeError(f"{name}: {why}")
+
+
+def _on_device(**tensors) -> None:
+    """Last check of a wrapper, after every dtype / shape / contiguity check has passed: all the
+    tensors it hands to the library live on a GPU."""
+    for name, t in tensors.items():
+        if t is not None and not t.is_cuda:
+            raise TypeError(f"{name}: must be a device tensor, got device {t.device}")
+
+
+def _want_ce_inputs(hidden, W, labels):
+    _want(hidden, "hidden", torch.bfloat16)
+    _want(W, "W", torch.bfloat16)
+    if hidden.dim() != 2 or W.dim() != 2 or hidden.shape[1] != W.shape[1]:
+        raise TypeError(f"hidden [N,H] and W [V,H] must share H, got {tuple(hidden.shape)} and {tuple(W.shape)}")
+    N, H = hidden.shape
+    _want(labels, "labels", torch.int32, (N,))
+    return N, H, W.shape[0]
+
+
+def _want_dw(dW, V: int, H: int, flags: int, name: str = "dW"):
+    _want(dW, name, torch.float32 if flags & ALST_FLAG_DW_FP32 else torch.bfloat16, (V, H))
+
+
 def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -127,8 +172,12 @@ def alst_tiled_ce_forward(hidden, W, labels, tile: int, ignore_index: int = -100
     """hidden [N,H] bf16, W [V,H] bf16, labels [N] int32 (device tensors); results are written
     into loss_out [1] f32, lse_out [N] f32, n_valid_out [1] int64.  Asynchronous on the current
     stream."""
-    N, H = hidden.shape
-    V = W.shape[0]
+    N, H, V = _want_ce_inputs(hidden, W, labels)
+    _want(loss_out, "loss_out", torch.float32, (1,))
+    _want(lse_out, "lse_out", torch.float32, (N,), optional=True)
+    _want(n_valid_out, "n_valid_out", torch.int64, (1,), optional=True)
+    _want(workspace, "workspace", torch.uint8)
+    _on_device(hidden=hidden, W=W, labels=labels, loss_out=loss_out, lse_out=lse_out, n_valid_out=n_valid_out, workspace=workspace)
     st = load_library().alst_tiled_ce_forward(
         _ptr(hidden), _ptr(W), _ptr(labels), N, H, V, tile, ignore_index, _ptr(loss_out),
         _ptr(lse_out), _ptr(n_valid_out), _ptr(workspace), workspace.numel(), flags, _stream())
@@ -137,8 +186,12 @@ def alst_tiled_ce_forward(hidden, W, labels, tile: int, ignore_index: int = -100
 
 def alst_tiled_ce_backward(hidden, W, labels, lse, tile: int, ignore_index: int = -100,
                            grad_loss: float = 1.0, *, dHidden, dW, workspace, flags: int = 0) -> None:
-    N, H = hidden.shape
-    V = W.shape[0]
+    N, H, V = _want_ce_inputs(hidden, W, labels)
+    _want(lse, "lse", torch.float32, (N,))
+    _want(dHidden, "dHidden", torch.bfloat16, (N, H))
+    _want_dw(dW, V, H, flags)
+    _want(workspace, "workspace", torch.uint8)
+    _on_device(hidden=hidden, W=W, labels=labels, lse=lse, dHidden=dHidden, dW=dW, workspace=workspace)
     st = load_library().alst_tiled_ce_backward(
         _ptr(hidden), _ptr(W), _ptr(labels), _ptr(lse), N, H, V, tile, ignore_index, grad_loss,
         _ptr(dHidden), _ptr(dW), _ptr(workspace), workspace.numel(), flags, _stream())
@@ -148,8 +201,15 @@ def alst_tiled_ce_backward(hidden, W, labels, lse, tile: int, ignore_index: int 
 def alst_tiled_ce_forward_backward(hidden, W, labels, tile: int, ignore_index: int = -100,
                                    grad_loss: float = 1.0, *, loss_out, lse_out=None,
                                    n_valid_out=None, dHidden, dW, workspace, flags: int = 0) -> None:
-    N, H = hidden.shape
-    V = W.shape[0]
+    N, H, V = _want_ce_inputs(hidden, W, labels)
+    _want(loss_out, "loss_out", torch.float32, (1,))
+    _want(lse_out, "lse_out", torch.float32, (N,), optional=True)
+    _want(n_valid_out, "n_valid_out", torch.int64, (1,), optional=True)
+    _want(dHidden, "dHidden", torch.bfloat16, (N, H))
+    _want_dw(dW, V, H, flags)
+    _want(workspace, "workspace", torch.uint8)
+    _on_device(hidden=hidden, W=W, labels=labels, loss_out=loss_out, lse_out=lse_out, n_valid_out=n_valid_out,
+               dHidden=dHidden, dW=dW, workspace=workspace)
     st = load_library().alst_tiled_ce_forward_backward(
         _ptr(hidden), _ptr(W), _ptr(labels), N, H, V, tile, ignore_index, grad_loss,
         _ptr(loss_out), _ptr(lse_out), _ptr(n_valid_out), _ptr(dHidden), _ptr(dW),
@@ -162,6 +222,9 @@ def alst_last_device_status(workspace) -> int:
 
 
 def alst_shift_labels(labels, shift_labels, ignore_index: int = -100) -> None:
+    _want(labels, "labels", torch.int32)
+    _want(shift_labels, "shift_labels", torch.int32, tuple(labels.shape))
+    _on_device(labels=labels, shift_labels=shift_labels)
     st = load_library().alst_shift_labels(_ptr(labels), _ptr(shift_labels), labels.numel(),
                                           ignore_index, _stream())
     _check(st, "alst_shift_labels")
@@ -169,8 +232,11 @@ def alst_shift_labels(labels, shift_labels, ignore_index: int = -100) -> None:
 
 def alst_tiled_ce_token_losses(workspace, N: int, H: int, V: int, tile: int, token_loss_out,
                                flags: int = 0) -> None:
-    st = load_library().alst_tiled_ce_token_losses(_ptr(workspace), N, H, V, tile, flags,
-                                                   _ptr(token_loss_out), _stream())
+    _want(workspace, "workspace", torch.uint8)
+    _want(token_loss_out, "token_loss_out", torch.float32, (N,))
+    _on_device(workspace=workspace, token_loss_out=token_loss_out)
+    st = load_library().alst_tiled_ce_token_losses(_ptr(workspace), workspace.numel(), N, H, V, tile,
+                                                   flags, _ptr(token_loss_out), _stream())
     _check(st, "alst_tiled_ce_token_losses")
 
 
@@ -186,10 +252,24 @@ def alloc_mlp_workspace(N: int, H: int, I: int, tile: int, backward: bool, flags
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
 
 
-def alst_tiled_mlp_forward(x, Wg, Wu, Wd, tile: int, *, y, workspace, flags: int = 0) -> None:
-    """x [N,H], Wg/Wu [I,H], Wd [H,I] bf16 device tensors; y [N,H] bf16 is overwritten."""
+def _want_mlp_inputs(x, Wg, Wu, Wd):
+    _want(x, "x", torch.bfloat16)
+    if x.dim() != 2 or Wg.dim() != 2:
+        raise TypeError("x must be [N,H] and Wg [I,H]")
     N, H = x.shape
     I = Wg.shape[0]
+    _want(Wg, "Wg", torch.bfloat16, (I, H))
+    _want(Wu, "Wu", torch.bfloat16, (I, H))
+    _want(Wd, "Wd", torch.bfloat16, (H, I))
+    return N, H, I
+
+
+def alst_tiled_mlp_forward(x, Wg, Wu, Wd, tile: int, *, y, workspace, flags: int = 0) -> None:
+    """x [N,H], Wg/Wu [I,H], Wd [H,I] bf16 device tensors; y [N,H] bf16 is overwritten."""
+    N, H, I = _want_mlp_inputs(x, Wg, Wu, Wd)
+    _want(y, "y", torch.bfloat16, (N, H))
+    _want(workspace, "workspace", torch.uint8)
+    _on_device(x=x, Wg=Wg, Wu=Wu, Wd=Wd, y=y, workspace=workspace)
     st = load_library().alst_tiled_mlp_forward(_ptr(x), _ptr(Wg), _ptr(Wu), _ptr(Wd), N, H, I, tile,
                                                _ptr(y), _ptr(workspace), workspace.numel(), flags,
                                                _stream())
@@ -198,8 +278,14 @@ def alst_tiled_mlp_forward(x, Wg, Wu, Wd, tile: int, *, y, workspace, flags: int
 
 def alst_tiled_mlp_backward(x, Wg, Wu, Wd, dy, tile: int, *, dx, dWg, dWu, dWd, workspace,
                             flags: int = 0) -> None:
-    N, H = x.shape
-    I = Wg.shape[0]
+    N, H, I = _want_mlp_inputs(x, Wg, Wu, Wd)
+    _want(dy, "dy", torch.bfloat16, (N, H))
+    _want(dx, "dx", torch.bfloat16, (N, H))
+    _want_dw(dWg, I, H, flags, "dWg")
+    _want_dw(dWu, I, H, flags, "dWu")
+    _want_dw(dWd, H, I, flags, "dWd")
+    _want(workspace, "workspace", torch.uint8)
+    _on_device(x=x, Wg=Wg, Wu=Wu, Wd=Wd, dy=dy, dx=dx, dWg=dWg, dWu=dWu, dWd=dWd, workspace=workspace)
     st = load_library().alst_tiled_mlp_backward(_ptr(x), _ptr(Wg), _ptr(Wu), _ptr(Wd), _ptr(dy), N, H,
                                                 I, tile, _ptr(dx), _ptr(dWg), _ptr(dWu), _ptr(dWd),
                                                 _ptr(workspace), workspace.numel(), flags, _stream())
@@ -212,19 +298,31 @@ def alst_tiled_linear_workspace_bytes(N: int, K: int, M: int, tile: int, backwar
 
 def alst_tiled_linear_forward(x, W, tile: int, *, y) -> None:
     """y [N,M] = x [N,K] W[M,K]^T (bf16 device tensors)."""
+    _want(x, "x", torch.bfloat16)
     N, K = x.shape
     M = W.shape[0]
+    _want(W, "W", torch.bfloat16, (M, K))
+    _want(y, "y", torch.bfloat16, (N, M))
+    _on_device(x=x, W=W, y=y)
     st = load_library().alst_tiled_linear_forward(_ptr(x), _ptr(W), N, K, M, tile, _ptr(y), None, 0, 0,
                                                   _stream())
     _check(st, "alst_tiled_linear_forward")
 
 
 def alst_tiled_linear_backward(x, W, dy, tile: int, *, dx, dW, workspace, flags: int = 0) -> None:
+    _want(x, "x", torch.bfloat16)
     N, K = x.shape
     M = W.shape[0]
+    _want(W, "W", torch.bfloat16, (M, K))
+    _want(dy, "dy", torch.bfloat16, (N, M))
+    _want(dx, "dx", torch.bfloat16, (N, K))
+    _want_dw(dW, M, K, flags)
+    _want(workspace, "workspace", torch.uint8, optional=True)
+    _on_device(x=x, W=W, dy=dy, dx=dx, dW=dW, workspace=workspace)
     st = load_library().alst_tiled_linear_backward(_ptr(x), _ptr(W), _ptr(dy), N, K, M, tile, _ptr(dx),
-                                                   _ptr(dW), _ptr(workspace), workspace.numel(), flags,
-                                                   _stream())
+                                                   _ptr(dW), _ptr(workspace),
+                                                   0 if workspace is None else workspace.numel(),
+                                                   flags, _stream())
     _check(st, "alst_tiled_linear_backward")
 
 

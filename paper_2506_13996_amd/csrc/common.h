@@ -15,7 +15,7 @@ namespace alst {
 
 // Optional per-kernel timing (alst_profile_*): while enabled, each launch of a block GEMM (and each
 // group of small kernels between them) is bracketed by a pair of HIP events on the launch stream.
-// A benchmarking aid; it is the only state the library keeps between calls and is not thread-safe.
+// A benchmarking aid; its list of spans is process-wide and guarded by a lock.
 // The kinds are the indices of alst_profile_read().
 enum {
     PROF_LOGITS = 0, PROF_DHIDDEN = 1, PROF_DW = 2, PROF_OTHER = 3,

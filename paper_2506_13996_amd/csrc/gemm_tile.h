@@ -62,7 +62,10 @@ struct PatchGrid {
     int tiles_r, tiles_c;      // output blocks of one part
     int PR, PC;                // patch shape, PR * PC = 32
     __host__ __device__ int patches_r() const { return (tiles_r + PR - 1) / PR; }
+    // (int: the launches are checked to fit a one-dimensional grid before any kernel sees this)
     __host__ __device__ int patches() const { return patches_r() * ((tiles_c + PC - 1) / PC); }
+    // for the host-side sizing, which also meets shapes no launch can hold
+    int64_t patches64() const { return (int64_t)patches_r() * ((tiles_c + PC - 1) / PC); }
 };
 
 // Patch shape: 4 x 8 (12 operand tiles per k-step for 32 blocks), unless 8 x 4 or one of the
@@ -73,7 +76,7 @@ inline PatchGrid choose_patches(int tiles_r, int tiles_c) {
     PatchGrid best = {tiles_r, tiles_c, 4, 8};
     for (int i = 1; i < 4; ++i) {
         const PatchGrid g = {tiles_r, tiles_c, shapes[i][0], shapes[i][1]};
-        if (10 * g.patches() < 9 * best.patches()) best = g;
+        if (10 * g.patches64() < 9 * best.patches64()) best = g;
     }
     return best;
 }

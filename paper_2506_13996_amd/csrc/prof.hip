@@ -1,29 +1,38 @@
-// Per-kernel timing aid of libalst (alst_profile_enable / alst_profile_read): HIP event pairs around
-// kernel launches, recorded on the launch stream.  Process-wide state, not thread-safe.
+// Benchmarking and testing aids of libalst (alst_debug.h).  Per-kernel timing (alst_profile_enable /
+// alst_profile_read): HIP event pairs around kernel launches, recorded on the launch stream; the
+// list of spans and the pool of events are process-wide and guarded by one lock.
 #include <hip/hip_runtime.h>
+#include <atomic>
+#include <mutex>
 #include <vector>
 
+#include "../../include/alst_debug.h"
 #include "common.h"
 
 namespace alst {
 
 struct ProfSpan { hipEvent_t a, b; int kind; };
-static bool g_prof_on = false;
+static std::atomic<bool> g_prof_on{false};
+static std::mutex g_prof_lock;                  // guards the two vectors
 static std::vector<ProfSpan> g_prof_spans;
 static std::vector<hipEvent_t> g_prof_pool;
 
 static hipEvent_t prof_event() {
-    if (!g_prof_pool.empty()) {
-        hipEvent_t e = g_prof_pool.back();
-        g_prof_pool.pop_back();
-        return e;
+    {
+        std::lock_guard<std::mutex> hold(g_prof_lock);
+        if (!g_prof_pool.empty()) {
+            hipEvent_t e = g_prof_pool.back();
+            g_prof_pool.pop_back();
+            return e;
+        }
     }
     hipEvent_t e = nullptr;
     if (hipEventCreate(&e) != hipSuccess) return nullptr;
     return e;
 }
 
-ProfScope::ProfScope(int kind_, hipStream_t stream) : a(nullptr), b(nullptr), kind(kind_), s(stream), on(g_prof_on) {
+ProfScope::ProfScope(int kind_, hipStream_t stream)
+    : a(nullptr), b(nullptr), kind(kind_), s(stream), on(g_prof_on.load(std::memory_order_relaxed)) {
     if (!on) return;
     a = prof_event();
     b = prof_event();
@@ -34,6 +43,7 @@ ProfScope::ProfScope(int kind_, hipStream_t stream) : a(nullptr), b(nullptr), ki
 ProfScope::~ProfScope() {
     if (!on) return;
     (void)hipEventRecord(b, s);
+    std::lock_guard<std::mutex> hold(g_prof_lock);
     g_prof_spans.push_back(ProfSpan{a, b, kind});
 }
 
@@ -81,7 +91,7 @@ using namespace alst;
 extern "C" {
 
 int alst_profile_enable(int on) {
-    g_prof_on = on != 0;
+    g_prof_on.store(on != 0, std::memory_order_relaxed);
     return ALST_OK;
 }
 
@@ -89,16 +99,23 @@ int alst_profile_read(double* ms_total, int64_t* launches) {
     if (!ms_total || !launches) return ALST_ERR_NULL;
     for (int k = 0; k < PROF_KINDS; ++k) { ms_total[k] = 0.0; launches[k] = 0; }
     int rc = ALST_OK;
-    for (const ProfSpan& sp : g_prof_spans) {
+    std::vector<ProfSpan> spans;
+    {
+        std::lock_guard<std::mutex> hold(g_prof_lock);
+        spans.swap(g_prof_spans);
+    }
+    for (const ProfSpan& sp : spans) {              // waits for the GPU: outside the lock
         float ms = 0.f;
         if (hipEventSynchronize(sp.b) != hipSuccess ||
             hipEventElapsedTime(&ms, sp.a, sp.b) != hipSuccess) rc = ALST_ERR_HIP;
         ms_total[sp.kind] += ms;
         launches[sp.kind] += 1;
+    }
+    std::lock_guard<std::mutex> hold(g_prof_lock);
+    for (const ProfSpan& sp : spans) {
         g_prof_pool.push_back(sp.a);
         g_prof_pool.push_back(sp.b);
     }
-    g_prof_spans.clear();
     return rc;
 }
 

@@ -32,6 +32,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <math.h>
+#include <mutex>
 
 #include "../../include/alst.h"
 #include "gemm_tile.h"
@@ -68,10 +69,14 @@ struct TileInfo {
 // kDwGroupRows rows.
 constexpr int kDwGroupRows = 16384;
 constexpr int kDwGroupMax = 8;
-static inline int dw_group_size(int64_t Tp) {
+// ALST_FLAG_TILE_SCRATCH (and the forward-only layout, which keeps no dZ at all): groups of one tile.
+static inline int dw_group_size(int64_t Tp, uint32_t flags) {
+    if (flags & (ALST_FLAG_TILE_SCRATCH | ALST_FLAG_FORWARD_ONLY)) return 1;
     int64_t g = kDwGroupRows / Tp;
     return (int)(g < 1 ? 1 : (g > kDwGroupMax ? kDwGroupMax : g));
 }
+constexpr uint32_t kKnownFlags = ALST_FLAG_DW_FP32 | ALST_FLAG_DW_ACCUMULATE | ALST_FLAG_REDUCE_SUM |
+                                 ALST_FLAG_TILE_SCRATCH | ALST_FLAG_FORWARD_ONLY;
 
 constexpr int kScanThreads = 1024;   // rows per block of the compaction kernels
 
@@ -103,7 +108,10 @@ __host__ __device__ inline void dhidden_splits(int64_t rows, int64_t H, int64_t 
     const int KT = (int)((V + kBlockK - 1) / kBlockK);
     int64_t best_wg = 0, best_slots = 1;               // fill = best_wg / best_slots
     splits = 1;
-    for (int sp = 1; sp <= 8; ++sp) {
+    // with 16 or more rounds of workgroups the chip is filled to 16/17 or better as it is (and the
+    // products below stay small)
+    const int sp_max = blocks >= 16 * kComputeUnits ? 1 : 8;
+    for (int sp = 1; sp <= sp_max; ++sp) {
         const int per = (KT + sp - 1) / sp;
         if (sp > 1 && (per < 64 || (int64_t)(sp - 1) * per >= KT)) break;
         if (sp > 1 && part_rows_cap > 0 && sp * rows > part_rows_cap) break;
@@ -120,8 +128,9 @@ static Layout make_layout(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_
     L.Tp = (T + 255) / 256 * 256;
     L.Vp = (V + 255) / 256 * 256;
     L.ng = L.Vp / 128;
-    L.g = dw_group_size(L.Tp);
+    L.g = dw_group_size(L.Tp, flags);
     L.Kg = (int64_t)L.g * L.Tp;
+    const bool fwd_only = flags & ALST_FLAG_FORWARD_ONLY;     // no dZ rows, partial products, dW sums
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     L.header = take(sizeof(Header));
@@ -137,11 +146,11 @@ static Layout make_layout(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_
     L.yc = take((size_t)L.Tp * 4);
     L.pm = take((size_t)L.ng * L.Tp * 4);
     L.ps = take((size_t)L.ng * L.Tp * 4);
-    L.sc = take((size_t)L.ng * L.Tp * 4);
+    L.sc = take(fwd_only ? 0 : (size_t)L.ng * L.Tp * 4);
     // hc and stash hold the dense rows of the whole group, each tile at its k offset: they are
     // the two operands of the group's dW product as they are (k = dense row, the slow index)
     L.hc = take((size_t)L.Kg * H * 2);
-    L.stash = take((size_t)L.Kg * L.Vp * 2);
+    L.stash = take(fwd_only ? 0 : (size_t)L.Kg * L.Vp * 2);
     {   // dHidden: the launch and the partial products are sized for the worst tile
         const PatchGrid pg = choose_patches((int)(L.Tp / kBlockR), (int)((H + kBlockC - 1) / kBlockC));
         L.dh_PR = pg.PR; L.dh_PC = pg.PC;
@@ -158,13 +167,13 @@ static Layout make_layout(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_
             int sp;
             dhidden_splits(rb * kBlockR, H, V, L.dh_part_rows, sp, ks);
             const PatchGrid g = {(int)rb, pg.tiles_c, pg.PR, pg.PC};
-            const int64_t patches = (int64_t)g.patches() * sp;
+            const int64_t patches = g.patches64() * sp;
             if (patches > L.dh_patches) L.dh_patches = patches;
         }
     }
-    L.part = take((size_t)L.dh_part_rows * H * 4);
+    L.part = take(fwd_only ? 0 : (size_t)L.dh_part_rows * H * 4);
     const bool acc_in_dw = (flags & ALST_FLAG_DW_FP32) && !(flags & ALST_FLAG_DW_ACCUMULATE);
-    L.acc = take(acc_in_dw ? 0 : (size_t)V * H * 4);
+    L.acc = take(acc_in_dw || fwd_only ? 0 : (size_t)V * H * 4);
     L.total = o;
     return L;
 }
@@ -798,11 +807,7 @@ __global__ __launch_bounds__(Core::kThreads) void dw_kernel(const DWParams p) {
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
-static int prepare_kernels() {
-    static int states[kMaxDevices];         // 0 = not yet prepared on that device, else status + 1
-    const int dev = current_device_slot();
-    if (dev < 0) return ALST_ERR_HIP;
-    if (states[dev] > 0) return states[dev] - 1;
+static int prepare_kernels_on_current_device() {
     int rc = ALST_OK;
     auto acc = [&](int r) { if (r != ALST_OK) rc = r; };
     acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_FWD>));
@@ -814,8 +819,16 @@ static int prepare_kernels() {
     acc(allow_big_lds(dhidden_kernel<MixedCore, false, false>));
     acc(allow_big_lds(dhidden_kernel<MixedCore, false, true>));
     acc(allow_big_lds(dw_kernel<KMajorCore, false>));
-    states[dev] = rc + 1;
     return rc;
+}
+// Once per device, whatever the number of host threads that make their first call together.
+static int prepare_kernels() {
+    static std::once_flag once[kMaxDevices];
+    static int results[kMaxDevices];
+    const int dev = current_device_slot();
+    if (dev < 0) return ALST_ERR_HIP;
+    std::call_once(once[dev], [dev] { results[dev] = prepare_kernels_on_current_device(); });
+    return results[dev];
 }
 
 struct Problem {
@@ -844,8 +857,8 @@ static int validate(const Problem& P, size_t workspace_bytes, bool need_fwd_out,
     if (need_fwd_out && !P.loss_out) return ALST_ERR_NULL;
     if (need_bwd_out && (!P.dHidden || !P.dW)) return ALST_ERR_NULL;
     if (need_lse_in && !P.lse_in) return ALST_ERR_NULL;
-    if (P.flags & ~(ALST_FLAG_DW_FP32 | ALST_FLAG_DW_ACCUMULATE | ALST_FLAG_REDUCE_SUM))
-        return ALST_ERR_UNSUPPORTED;
+    if (P.flags & ~kKnownFlags) return ALST_ERR_UNSUPPORTED;
+    if (need_bwd_out && (P.flags & ALST_FLAG_FORWARD_ONLY)) return ALST_ERR_UNSUPPORTED;
     if (P.N < 1 || P.H < 1 || P.V < 1 || P.tile < 1) return ALST_ERR_SHAPE;
     if (P.N > (int64_t)1 << 30 || P.H > (int64_t)1 << 20 || P.V > (int64_t)1 << 24)
         return ALST_ERR_SHAPE;
@@ -1066,7 +1079,7 @@ const char* alst_status_string(int status) {
         case ALST_ERR_WORKSPACE: return "workspace is smaller than alst_tiled_ce_workspace_bytes()";
         case ALST_ERR_LABEL_RANGE: return "a label is neither ignore_index nor inside [0, V)";
         case ALST_ERR_HIP: return "a HIP runtime call or kernel launch failed";
-        case ALST_ERR_UNSUPPORTED: return "unknown flag bits";
+        case ALST_ERR_UNSUPPORTED: return "unknown flag bits, or a flag this entry point does not take";
         case ALST_ERR_NONFINITE: return "the loss is not finite";
         default: return "unknown status";
     }
@@ -1077,6 +1090,7 @@ int alst_version(void) { return 100; }
 size_t alst_tiled_ce_workspace_bytes(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_t flags) {
     if (N < 1 || H < 1 || V < 1 || tile < 1) return 0;
     if (N > (int64_t)1 << 30 || H > (int64_t)1 << 20 || V > (int64_t)1 << 24) return 0;
+    if (flags & ~kKnownFlags) return 0;
     return make_layout(N, H, V, tile, flags).total;
 }
 
@@ -1141,12 +1155,15 @@ int alst_last_device_status(void* workspace, void* stream) {
     return st;
 }
 
-int alst_tiled_ce_token_losses(const void* workspace, int64_t N, int64_t H, int64_t V, int64_t tile,
-                               uint32_t flags, float* token_loss_out, void* stream) {
+int alst_tiled_ce_token_losses(const void* workspace, size_t workspace_bytes, int64_t N, int64_t H,
+                               int64_t V, int64_t tile, uint32_t flags, float* token_loss_out,
+                               void* stream) {
     if (!workspace || !token_loss_out) return ALST_ERR_NULL;
+    if (flags & ~kKnownFlags) return ALST_ERR_UNSUPPORTED;
     if (N < 1 || H < 1 || V < 1 || tile < 1) return ALST_ERR_SHAPE;
     if (N > (int64_t)1 << 30 || H > (int64_t)1 << 20 || V > (int64_t)1 << 24) return ALST_ERR_SHAPE;
     const Layout L = make_layout(N, H, V, tile, flags);
+    if (workspace_bytes < L.total) return ALST_ERR_WORKSPACE;
     const float* rows = reinterpret_cast<const float*>((const unsigned char*)workspace + L.loss_rows);
     int blocks = (int)((N + 255) / 256);
     if (blocks > 4096) blocks = 4096;

@@ -22,6 +22,7 @@
 // by the k-major cores: x and dy straight from the caller's arrays, a and [dg | du] from the
 // group's buffers.
 #include <hip/hip_runtime.h>
+#include <mutex>
 #include <stdint.h>
 #include <math.h>
 
@@ -333,11 +334,7 @@ __global__ void convert_sums_kernel(const float* sums, void* out, int64_t n4) {
 // ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
-static int prepare_mlp_kernels() {
-    static int states[kMaxDevices];         // 0 = not yet prepared on that device, else status + 1
-    const int dev = current_device_slot();
-    if (dev < 0) return ALST_ERR_HIP;
-    if (states[dev] > 0) return states[dev] - 1;
+static int prepare_mlp_kernels_on_current_device() {
     int rc = ALST_OK;
     auto acc = [&](int r) { if (r != ALST_OK) rc = r; };
     acc(allow_big_lds(linear_kernel<DirectCore, false>));
@@ -350,8 +347,16 @@ static int prepare_mlp_kernels() {
     acc(allow_big_lds(gated_kernel<StagedCore, true, true>));
     acc(allow_big_lds(wgrad_kernel<KMajorCore, false>));
     acc(allow_big_lds(wgrad_kernel<StagedKMajorCore, true>));
-    states[dev] = rc + 1;
     return rc;
+}
+// Once per device, whatever the number of host threads that make their first call together.
+static int prepare_mlp_kernels() {
+    static std::once_flag once[kMaxDevices];
+    static int results[kMaxDevices];
+    const int dev = current_device_slot();
+    if (dev < 0) return ALST_ERR_HIP;
+    std::call_once(once[dev], [dev] { results[dev] = prepare_mlp_kernels_on_current_device(); });
+    return results[dev];
 }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

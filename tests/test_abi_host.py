@@ -23,6 +23,7 @@ def test_every_declared_symbol_is_exported(lib):
     hdr = open(os.path.join(ROOT, "include", "alst.h")).read()
     hdr += open(os.path.join(ROOT, "include", "alst_mlp.h")).read()
     hdr += open(os.path.join(ROOT, "include", "alst_linear.h")).read()
+    hdr += open(os.path.join(ROOT, "include", "alst_debug.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     declared = set(re.findall(r"\b(alst_[a-z_0-9]+)\s*\(", hdr))
     assert declared == set(B.EXPORTS)
@@ -59,6 +60,38 @@ def test_workspace_is_independent_of_n_beyond_12_bytes_per_row(lib):
     assert B.alst_tiled_ce_workspace_bytes(0, H, V, T) == 0
     assert B.alst_tiled_ce_workspace_bytes(10, H, 0, T) == 0
     assert B.alst_tiled_ce_workspace_bytes(10, H, V, 0) == 0
+
+
+def test_workspace_follows_the_tile_as_documented(lib):
+    """The large terms of the workspace (alst.h): 2 Kg (Vp + H) bytes of dZ and dense hidden rows,
+    4 V H of dW sums, 12 (Vp / 128) Tp of softmax partials; Kg is one tile under
+    ALST_FLAG_TILE_SCRATCH and a group of tiles (about 16384 rows) without it."""
+    H, V, N = 4096, 128256, 131072
+    Vp = (V + 255) // 256 * 256
+    small = 12 * N + 12 * N // 1024 + 64 * 1024          # the O(N) part and the roundings to 256 bytes
+
+    def expect(T, kg, acc=True, part_rows=0):
+        Tp = (T + 255) // 256 * 256
+        return 2 * kg * (Vp + H) + (4 * V * H if acc else 0) + 12 * (Vp // 128) * Tp + 8 * Tp + 4 * part_rows * H
+
+    for T, g in ((128, 8), (2048, 8), (4096, 4), (8192, 2), (16384, 1), (32768, 1)):
+        Tp = (T + 255) // 256 * 256
+        # dHidden partial products: a tile of fewer than 256 output blocks may be cut along V
+        w1 = B.alst_tiled_ce_workspace_bytes(N, H, V, T, B.ALST_FLAG_TILE_SCRATCH)
+        wg = B.alst_tiled_ce_workspace_bytes(N, H, V, T)
+        assert wg - w1 == 2 * (g - 1) * Tp * (Vp + H), (T, g)
+        lo = expect(T, Tp)
+        assert lo <= w1 <= lo + 4 * 8 * Tp * H + small, T       # at most 8 ranges of partial products
+        # the tile bounds the dZ scratch: no more than 2 bytes per logit of ONE tile
+        assert w1 - 4 * V * H - 4 * 8 * Tp * H - small <= 2 * Tp * Vp + 2 * Tp * H + 12 * (Vp // 128) * Tp + 8 * Tp
+    # halving the tile halves everything but the dW sums and the O(N) part
+    a = B.alst_tiled_ce_workspace_bytes(N, H, V, 4096, B.ALST_FLAG_TILE_SCRATCH | B.ALST_FLAG_DW_FP32)
+    b = B.alst_tiled_ce_workspace_bytes(N, H, V, 2048, B.ALST_FLAG_TILE_SCRATCH | B.ALST_FLAG_DW_FP32)
+    assert abs((a - 12 * N) - 2 * (b - 12 * N)) <= 4 * 8 * 2048 * H + small
+    # forward only: no dZ rows, no dW sums, no partial products
+    f = B.alst_tiled_ce_workspace_bytes(N, H, V, 4096, B.ALST_FLAG_FORWARD_ONLY)
+    assert f <= 2 * 4096 * H + 8 * (Vp // 128) * 4096 + 8 * 4096 + small
+    assert B.alst_tiled_ce_workspace_bytes(N, H, V, 4096, 1 << 9) == 0       # unknown flag
 
 
 def test_paper_memory_arithmetic():
@@ -99,6 +132,19 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
                                             vp(0x4000), None, None, None, vp(0x7000), vp(0x5000),
                                             1 << 40, 0, None)
     assert rc == B.ALST_ERR_NULL
+    # a forward-only workspace cannot serve the entry points that compute gradients
+    rc = lib.alst_tiled_ce_forward_backward(vp(0x1000), vp(0x2000), vp(0x3000), 16, 64, 32, 8, -100, 1.0,
+                                            vp(0x4000), None, None, vp(0x6000), vp(0x7000), vp(0x5000),
+                                            1 << 40, B.ALST_FLAG_FORWARD_ONLY, None)
+    assert rc == B.ALST_ERR_UNSUPPORTED
+    assert _call_forward(lib, flags=B.ALST_FLAG_FORWARD_ONLY, ws_bytes=1024) == B.ALST_ERR_WORKSPACE
+    # the unreduced losses live in the workspace: its size is checked like everywhere else
+    rc = lib.alst_tiled_ce_token_losses(vp(0x5000), 1024, 16, 64, 32, 8, 0, vp(0x8000), None)
+    assert rc == B.ALST_ERR_WORKSPACE
+    rc = lib.alst_tiled_ce_token_losses(None, 1 << 40, 16, 64, 32, 8, 0, vp(0x8000), None)
+    assert rc == B.ALST_ERR_NULL
+    rc = lib.alst_tiled_ce_token_losses(vp(0x5000), 1 << 40, 16, 64, 32, 8, 1 << 9, vp(0x8000), None)
+    assert rc == B.ALST_ERR_UNSUPPORTED
     assert lib.alst_last_device_status(None, None) == B.ALST_ERR_NULL
     assert lib.alst_shift_labels(None, vp(0x1000), 4, -100, None) == B.ALST_ERR_NULL
     assert lib.alst_shift_labels(vp(0x1000), vp(0x2000), 0, -100, None) == B.ALST_ERR_SHAPE
@@ -169,3 +215,61 @@ def test_block_to_tile_mapping_rejects_bad_arguments(lib):
         B.alst_debug_block_tile(4, 4, 1, -1)
     with pytest.raises(B.AlstError):
         B.alst_debug_block_tile(1 << 15, 1 << 15, 8, 0)
+
+
+def test_binding_refuses_tensors_the_abi_would_reinterpret():
+    """The C ABI sees addresses only; the binding checks dtype, shape, contiguity and device."""
+    import torch
+    N, H, V = 8, 16, 12
+    bf = lambda *sh: torch.zeros(sh, dtype=torch.bfloat16)
+    h, W = bf(N, H), bf(V, H)
+    y32 = torch.zeros(N, dtype=torch.int32)
+    loss = torch.zeros(1)
+    ws = torch.zeros(64, dtype=torch.uint8)
+    kw = dict(loss_out=loss, workspace=ws)
+    with pytest.raises(TypeError, match="labels: must be torch.int32"):
+        B.alst_tiled_ce_forward(h, W, torch.zeros(N, dtype=torch.int64), 4, **kw)
+    with pytest.raises(TypeError, match="hidden: must be torch.bfloat16"):
+        B.alst_tiled_ce_forward(h.to(torch.float16), W, y32, 4, **kw)
+    with pytest.raises(TypeError, match="W: must be contiguous"):
+        B.alst_tiled_ce_forward(h, bf(H, V).t(), y32, 4, **kw)
+    with pytest.raises(TypeError, match="share H"):
+        B.alst_tiled_ce_forward(h, bf(V, H + 8), y32, 4, **kw)
+    with pytest.raises(TypeError, match="labels: expected shape"):
+        B.alst_tiled_ce_forward(h, W, torch.zeros(N + 1, dtype=torch.int32), 4, **kw)
+    with pytest.raises(TypeError, match="lse_out: must be torch.float32"):
+        B.alst_tiled_ce_forward(h, W, y32, 4, lse_out=torch.zeros(N, dtype=torch.float64), **kw)
+    with pytest.raises(TypeError, match="dW: must be torch.float32"):
+        B.alst_tiled_ce_forward_backward(h, W, y32, 4, dHidden=bf(N, H), dW=bf(V, H),
+                                         flags=B.ALST_FLAG_DW_FP32, **kw)
+    with pytest.raises(TypeError, match="dHidden: expected shape"):
+        B.alst_tiled_ce_backward(h, W, y32, torch.zeros(N), 4, dHidden=bf(N, H + 8), dW=bf(V, H), workspace=ws)
+    # everything else right: a host tensor is refused (nothing is launched)
+    with pytest.raises(TypeError, match="hidden: must be a device tensor"):
+        B.alst_tiled_ce_forward(h, W, y32, 4, **kw)
+    with pytest.raises(TypeError, match="Wd: expected shape"):
+        B.alst_tiled_mlp_forward(h, bf(24, H), bf(24, H), bf(24, H), 4, y=bf(N, H), workspace=ws)
+
+
+def test_host_logic_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The library's own sources, rebuilt with ASan + UBSan on the host pass, driven by
+    tests/host_sanitize_main.cpp: workspace layout, choice of dHidden ranges, patch mapping and
+    argument validation over a sweep of shapes (no kernel is launched, so this runs without a GPU)."""
+    import subprocess
+    from paper_2506_13996_amd.build import CSRC, hipcc_path
+    exe = str(tmp_path / "host_sanitize")
+    srcs = [os.path.join(ROOT, "tests", "host_sanitize_main.cpp")]
+    srcs += [os.path.join(CSRC, f) for f in ("tiled_ce.hip", "tiled_mlp.hip", "prof.hip")]
+    cmd = [hipcc_path(), "--offload-arch=gfx950", "-O1", "-g", "-std=c++17",
+           "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-I", os.path.join(ROOT, "include"), *srcs, "-o", exe]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr[-4000:]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    env.pop("LD_PRELOAD", None)
+    run = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=600)
+    assert run.returncode == 0, (run.stdout[-2000:], run.stderr[-4000:])
+    assert "runtime error" not in run.stderr and "AddressSanitizer" not in run.stderr, run.stderr[-4000:]
+    assert "0 failures" in run.stdout

@@ -63,7 +63,8 @@ CASES = [
     # number of ranges is chosen per tile on the device
     ("split_v_last_tile_differs", 8500, 512, 33280, 8192, 0.0),
     # block-aligned H, a vocabulary that ends inside a column block: unguarded logits and dW kernels
-    # (the missing rows of W are masked); dHidden unguarded when V is whole k-steps, else guarded
+    # (the missing rows of W are masked); dHidden unguarded too, a vocabulary that is not whole
+    # k-steps taking the kernel variant that clamps the last k-step's rows of W
     ("ragged_v_whole_ksteps", 600, 256, 1088, 256, 0.1),
     ("ragged_v", 600, 256, 1000, 256, 0.1),
     ("ragged_v_below_one_block", 300, 256, 72, 128, 0.1),
@@ -170,6 +171,74 @@ def test_dw_fp32_and_accumulate_flags():
     r = G.run_fused(h, W, y, 256, flags=B.ALST_FLAG_DW_ACCUMULATE, dW_init=base16)
     ref = base16.float().cpu().numpy().astype(np.float64) + dW
     assert G.grad_err(r.dW, ref) <= GRAD_TOL
+
+
+def test_tile_scratch_flag_keeps_one_tile_of_dz_and_matches_oracle():
+    """ALST_FLAG_TILE_SCRATCH: the dW sums are updated after every tile (5 tiles here, the last one
+    ragged) instead of once per group; same loss bits, gradients within the bar."""
+    wl = synth.custom("tile_scratch", 1200, 256, 1500, 256, ignore_frac=0.1, seed=13)
+    h, W, y = synth.make_inputs(wl)
+    f, dH, dW = _oracle(h, W, y)
+    assert (B.alst_tiled_ce_workspace_bytes(1200, 256, 1500, 256, B.ALST_FLAG_TILE_SCRATCH)
+            < 0.5 * B.alst_tiled_ce_workspace_bytes(1200, 256, 1500, 256))
+    for flags in (B.ALST_FLAG_TILE_SCRATCH, B.ALST_FLAG_TILE_SCRATCH | B.ALST_FLAG_DW_FP32):
+        r = G.run_fused(h, W, y, 256, flags=flags)
+        _check(r, f, dH, dW, f"tile scratch flags={flags}", valid=(y != IGN))
+        r0 = G.run_fused(h, W, y, 256, flags=flags & ~B.ALST_FLAG_TILE_SCRATCH)
+        assert r.loss_bits == r0.loss_bits
+        assert torch.equal(r.dH_t.view(torch.int16), r0.dH_t.view(torch.int16))   # dHidden is per tile anyway
+    r = G.run_split(h, W, y, 256, flags=B.ALST_FLAG_TILE_SCRATCH)
+    assert r.status_bwd == B.ALST_OK
+    _check(r, f, dH, dW, "tile scratch, split entry points", valid=(y != IGN))
+
+
+def test_forward_only_workspace():
+    """ALST_FLAG_FORWARD_ONLY: a workspace without dZ rows and dW sums serves the forward entry
+    point and the unreduced losses, with the bits of the full-size workspace."""
+    N, H, V, T = 900, 192, 2100, 256
+    wl = synth.custom("fwd_only", N, H, V, T, ignore_frac=0.1, seed=14)
+    h, W, y = synth.make_inputs(wl)
+    f = orc.forward(h, W, y, row_block=256)
+    hd, Wd, yd = G.bits_to_dev(h), G.bits_to_dev(W), torch.from_numpy(y).cuda()
+    out = []
+    for flags in (B.ALST_FLAG_FORWARD_ONLY, 0):
+        ws = B.alloc_workspace(N, H, V, T, flags)
+        loss = torch.full((1,), float("nan"), device="cuda")
+        lse = torch.full((N,), float("nan"), device="cuda")
+        tok = torch.full((N,), float("nan"), device="cuda")
+        B.alst_tiled_ce_forward(hd, Wd, yd, T, IGN, loss_out=loss, lse_out=lse, workspace=ws, flags=flags)
+        B.alst_tiled_ce_token_losses(ws, N, H, V, T, tok, flags=flags)
+        assert B.alst_last_device_status(ws) == B.ALST_OK
+        out.append((ws.numel(), loss.cpu().numpy().view(np.uint32)[0], lse.cpu().numpy(), tok.cpu().numpy()))
+    assert out[0][0] < 0.2 * out[1][0]
+    assert out[0][1] == out[1][1]
+    assert (out[0][2].view(np.uint32) == out[1][2].view(np.uint32)).all()
+    assert (out[0][3].view(np.uint32) == out[1][3].view(np.uint32)).all()
+    assert abs(float(np.array(out[0][1], dtype=np.uint32).view(np.float32)) - f["loss"]) / f["loss"] <= LOSS_RTOL
+    assert np.abs(out[0][3] - f["loss_rows"]).max() <= 1e-3 * np.abs(f["loss_rows"]).max()
+    ws = B.alloc_workspace(N, H, V, T, B.ALST_FLAG_FORWARD_ONLY)
+    with pytest.raises(B.AlstError) as e:
+        B.alst_tiled_ce_forward_backward(hd, Wd, yd, T, IGN, 1.0, loss_out=torch.zeros(1, device="cuda"),
+                                         dHidden=torch.empty((N, H), dtype=torch.bfloat16, device="cuda"),
+                                         dW=torch.empty((V, H), dtype=torch.bfloat16, device="cuda"),
+                                         workspace=ws, flags=B.ALST_FLAG_FORWARD_ONLY)
+    assert e.value.status == B.ALST_ERR_UNSUPPORTED
+
+
+def test_vocabulary_of_one():
+    """V = 1: the only logit is the label's, so every token loss is 0 and both gradients vanish
+    (softmax = 1 = one-hot)."""
+    wl = synth.custom("v1", 300, 64, 1, 128, ignore_frac=0.1, seed=15)
+    h, W, y = synth.make_inputs(wl)
+    assert set(np.unique(y)) <= {0, IGN}
+    f, dH, dW = _oracle(h, W, y)
+    assert f["loss"] == 0.0 and not dH.any() and not dW.any()
+    r = G.run_fused(h, W, y, 128)
+    assert r.status == B.ALST_OK and r.n_valid == f["n_valid"]
+    assert abs(r.loss) <= 1e-6
+    assert np.abs(r.lse - np.where(y != IGN, f["lse"], 0.0)).max() <= 1e-3 * max(1.0, np.abs(f["lse"]).max())
+    # e = exp(0) = 1 exactly, dZ = 1 * 1 - 1 = 0 exactly
+    assert (r.dH == 0).all() and (r.dW == 0).all()
 
 
 def test_label_out_of_range_is_flagged_and_treated_as_ignored():
