@@ -66,7 +66,9 @@ typedef enum {
     ALST_ERR_LABEL_RANGE = 5, /* device: a label outside [0,V) that is not ignore_index */
     ALST_ERR_HIP = 6,         /* a HIP runtime call or kernel launch failed */
     ALST_ERR_UNSUPPORTED = 7, /* unknown flag bits, or a flag the entry point does not take */
-    ALST_ERR_NONFINITE = 8    /* device: the loss is not finite */
+    ALST_ERR_NONFINITE = 8,   /* device: the loss is not finite */
+    ALST_ERR_NOALLOC_LIMIT = 9 /* alst_tiled_ce_forward_backward_noalloc: the problem needs more
+                                 scratch than ALST_NOALLOC_SCRATCH_BYTES */
 } alst_status;
 
 /* dW is written as fp32 instead of bf16. */
@@ -151,6 +153,36 @@ int alst_tiled_ce_forward_backward(const void* hidden, const void* W, const int3
                                    void* dHidden, void* dW,
                                    void* workspace, size_t workspace_bytes, uint32_t flags,
                                    void* stream);
+
+/*
+ * For callers that cannot allocate device memory and therefore cannot bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same computation
+ * and same results, bit for bit, as alst_tiled_ce_forward_backward, with the workspace taken from
+ * a buffer of ALST_NOALLOC_SCRATCH_BYTES that is part of the library's device code (every GPU the
+ * library's kernels are loaded on holds one until the process ends).  The call allocates and
+ * frees nothing, on the device or through any library.
+ *   - A problem whose alst_tiled_ce_workspace_bytes(N, H, V, tile, flags) exceeds
+ *     ALST_NOALLOC_SCRATCH_BYTES is refused with ALST_ERR_NOALLOC_LIMIT before anything is
+ *     enqueued (ALST_FLAG_TILE_SCRATCH and ALST_FLAG_DW_FP32 lower the need; the LM-head
+ *     workloads with V * H in the hundreds of millions do not fit: they need the caller's
+ *     workspace for the fp32 dW sums alone).
+ *   - device_status_out [1] int32, device, may be NULL: receives the status word the kernels
+ *     leave (ALST_OK, ALST_ERR_LABEL_RANGE or ALST_ERR_NONFINITE), since the caller has no
+ *     workspace to hand to alst_last_device_status.
+ *   - All calls on one GPU share that GPU's buffer: calls that overlap in time on one GPU (two
+ *     streams, two host threads) race and give wrong results; order them on one stream.  The
+ *     buffer keeps the last call's contents; every call resets what it needs.
+ *   - As for the other entry points, the first compute call on a device must be made outside a
+ *     graph capture.
+ * ALST_FLAG_FORWARD_ONLY is refused (ALST_ERR_UNSUPPORTED).
+ */
+#define ALST_NOALLOC_SCRATCH_BYTES ((size_t)64 << 20)
+int alst_tiled_ce_forward_backward_noalloc(const void* hidden, const void* W, const int32_t* labels,
+                                           int64_t N, int64_t H, int64_t V, int64_t tile,
+                                           int32_t ignore_index, float grad_loss,
+                                           float* loss_out, float* lse_out, int64_t* n_valid_out,
+                                           void* dHidden, void* dW, int32_t* device_status_out,
+                                           uint32_t flags, void* stream);
 
 /*
  * Synchronises `stream`, then reads and clears the device status word that the last call on this

@@ -16,6 +16,8 @@ LIB_PATH = os.path.join(_PKG_DIR, "libalst.so")
 ALST_OK = 0
 ALST_ERR_NULL, ALST_ERR_SHAPE, ALST_ERR_ALIGN, ALST_ERR_WORKSPACE = 1, 2, 3, 4
 ALST_ERR_LABEL_RANGE, ALST_ERR_HIP, ALST_ERR_UNSUPPORTED, ALST_ERR_NONFINITE = 5, 6, 7, 8
+ALST_ERR_NOALLOC_LIMIT = 9
+ALST_NOALLOC_SCRATCH_BYTES = 64 << 20
 ALST_FLAG_DW_FP32 = 1
 ALST_FLAG_DW_ACCUMULATE = 2
 ALST_FLAG_REDUCE_SUM = 4
@@ -24,7 +26,8 @@ ALST_FLAG_FORWARD_ONLY = 16
 
 EXPORTS = (
     "alst_status_string", "alst_version", "alst_tiled_ce_workspace_bytes", "alst_tiled_ce_forward",
-    "alst_tiled_ce_backward", "alst_tiled_ce_forward_backward", "alst_last_device_status",
+    "alst_tiled_ce_backward", "alst_tiled_ce_forward_backward",
+    "alst_tiled_ce_forward_backward_noalloc", "alst_last_device_status",
     "alst_shift_labels", "alst_tiled_ce_token_losses",
     "alst_profile_enable", "alst_profile_read", "alst_debug_block_tile", "alst_debug_mfma_rate",
     "alst_tiled_mlp_workspace_bytes", "alst_tiled_mlp_forward", "alst_tiled_mlp_backward",
@@ -62,6 +65,9 @@ def load_library() -> ctypes.CDLL:
     lib.alst_tiled_ce_backward.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, i32, f32, vp, vp, vp, sz, u32, vp]
     lib.alst_tiled_ce_forward_backward.restype = c.c_int
     lib.alst_tiled_ce_forward_backward.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, f32, vp, vp, vp, vp, vp, vp, sz, u32, vp]
+    lib.alst_tiled_ce_forward_backward_noalloc.restype = c.c_int
+    lib.alst_tiled_ce_forward_backward_noalloc.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, f32, vp, vp, vp,
+                                                           vp, vp, vp, u32, vp]
     lib.alst_last_device_status.restype = c.c_int
     lib.alst_last_device_status.argtypes = [vp, vp]
     lib.alst_shift_labels.restype = c.c_int
@@ -215,6 +221,28 @@ def alst_tiled_ce_forward_backward(hidden, W, labels, tile: int, ignore_index: i
         _ptr(loss_out), _ptr(lse_out), _ptr(n_valid_out), _ptr(dHidden), _ptr(dW),
         _ptr(workspace), workspace.numel(), flags, _stream())
     _check(st, "alst_tiled_ce_forward_backward")
+
+
+def alst_tiled_ce_forward_backward_noalloc(hidden, W, labels, tile: int, ignore_index: int = -100,
+                                           grad_loss: float = 1.0, *, loss_out, lse_out=None,
+                                           n_valid_out=None, dHidden, dW, device_status_out=None,
+                                           flags: int = 0) -> None:
+    """alst_tiled_ce_forward_backward on the library's own static scratch (no workspace argument);
+    device_status_out [1] int32 receives the device status word."""
+    N, H, V = _want_ce_inputs(hidden, W, labels)
+    _want(loss_out, "loss_out", torch.float32, (1,))
+    _want(lse_out, "lse_out", torch.float32, (N,), optional=True)
+    _want(n_valid_out, "n_valid_out", torch.int64, (1,), optional=True)
+    _want(dHidden, "dHidden", torch.bfloat16, (N, H))
+    _want_dw(dW, V, H, flags)
+    _want(device_status_out, "device_status_out", torch.int32, (1,), optional=True)
+    _on_device(hidden=hidden, W=W, labels=labels, loss_out=loss_out, lse_out=lse_out, n_valid_out=n_valid_out,
+               dHidden=dHidden, dW=dW, device_status_out=device_status_out)
+    st = load_library().alst_tiled_ce_forward_backward_noalloc(
+        _ptr(hidden), _ptr(W), _ptr(labels), N, H, V, tile, ignore_index, grad_loss,
+        _ptr(loss_out), _ptr(lse_out), _ptr(n_valid_out), _ptr(dHidden), _ptr(dW),
+        _ptr(device_status_out), flags, _stream())
+    _check(st, "alst_tiled_ce_forward_backward_noalloc")
 
 
 def alst_last_device_status(workspace) -> int:

@@ -851,9 +851,11 @@ struct Problem {
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// own_scratch: the workspace is the library's own static buffer of workspace_bytes (P.ws is not
+// looked at).
 static int validate(const Problem& P, size_t workspace_bytes, bool need_fwd_out, bool need_bwd_out,
-                    bool need_lse_in) {
-    if (!P.hidden || !P.W || !P.labels || !P.ws) return ALST_ERR_NULL;
+                    bool need_lse_in, bool own_scratch = false) {
+    if (!P.hidden || !P.W || !P.labels || (!own_scratch && !P.ws)) return ALST_ERR_NULL;
     if (need_fwd_out && !P.loss_out) return ALST_ERR_NULL;
     if (need_bwd_out && (!P.dHidden || !P.dW)) return ALST_ERR_NULL;
     if (need_lse_in && !P.lse_in) return ALST_ERR_NULL;
@@ -863,7 +865,8 @@ static int validate(const Problem& P, size_t workspace_bytes, bool need_fwd_out,
     if (P.N > (int64_t)1 << 30 || P.H > (int64_t)1 << 20 || P.V > (int64_t)1 << 24)
         return ALST_ERR_SHAPE;
     if (P.H % 8 != 0) return ALST_ERR_ALIGN;
-    if (!aligned16(P.hidden) || !aligned16(P.W) || !aligned16(P.ws)) return ALST_ERR_ALIGN;
+    if (!aligned16(P.hidden) || !aligned16(P.W) || (!own_scratch && !aligned16(P.ws)))
+        return ALST_ERR_ALIGN;
     if (need_bwd_out && (!aligned16(P.dHidden) || !aligned16(P.dW))) return ALST_ERR_ALIGN;
     const Layout L = make_layout(P.N, P.H, P.V, P.tile, P.flags);
     // every launch must fit a one-dimensional grid
@@ -872,7 +875,7 @@ static int validate(const Problem& P, size_t workspace_bytes, bool need_fwd_out,
         L.dh_patches * 32 > 0x7fffff00 ||                                        // dHidden
         (L.Vp / 256) * (L.Tp / 64) > 0x7fffffff)
         return ALST_ERR_SHAPE;
-    if (workspace_bytes < L.total) return ALST_ERR_WORKSPACE;
+    if (workspace_bytes < L.total) return own_scratch ? ALST_ERR_NOALLOC_LIMIT : ALST_ERR_WORKSPACE;
     return ALST_OK;
 }
 
@@ -1061,6 +1064,35 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
     return ALST_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// the entry point that allocates nothing
+// ---------------------------------------------------------------------------------------------
+// The workspace of alst_tiled_ce_forward_backward_noalloc: one array per GPU, held from the moment
+// the library's code is loaded on it until the process ends.  In host code the name `scratch` is
+// only a handle for hipGetSymbolAddress; what the kernels get is the address that call returns
+// for the current device (each GPU has its own copy at its own address).
+static __device__ __align__(256) unsigned char scratch[ALST_NOALLOC_SCRATCH_BYTES];
+
+// The device address of `scratch` on the current device, looked up once per device.
+static int noalloc_scratch(unsigned char** out) {
+    static std::mutex lock;
+    static unsigned char* ptrs[kMaxDevices];
+    const int dev = current_device_slot();
+    if (dev < 0) return ALST_ERR_HIP;
+    std::lock_guard<std::mutex> hold(lock);
+    if (!ptrs[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return ALST_ERR_HIP;
+        ptrs[dev] = static_cast<unsigned char*>(p);
+    }
+    *out = ptrs[dev];
+    return ALST_OK;
+}
+
+__global__ void copy_status_kernel(const Header* __restrict__ h, int32_t* __restrict__ out) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *out = h->status;
+}
+
 }  // namespace alst
 
 // ---------------------------------------------------------------------------------------------
@@ -1081,6 +1113,9 @@ const char* alst_status_string(int status) {
         case ALST_ERR_HIP: return "a HIP runtime call or kernel launch failed";
         case ALST_ERR_UNSUPPORTED: return "unknown flag bits, or a flag this entry point does not take";
         case ALST_ERR_NONFINITE: return "the loss is not finite";
+        case ALST_ERR_NOALLOC_LIMIT:
+            return "the problem needs more scratch than the static buffer of "
+                   "alst_tiled_ce_forward_backward_noalloc holds";
         default: return "unknown status";
     }
 }
@@ -1138,6 +1173,34 @@ int alst_tiled_ce_forward_backward(const void* hidden, const void* W, const int3
     const int rc = validate(P, workspace_bytes, true, true, false);
     if (rc != ALST_OK) return rc;
     return run(P, true, true);
+}
+
+int alst_tiled_ce_forward_backward_noalloc(const void* hidden, const void* W, const int32_t* labels,
+                                           int64_t N, int64_t H, int64_t V, int64_t tile,
+                                           int32_t ignore_index, float grad_loss, float* loss_out,
+                                           float* lse_out, int64_t* n_valid_out, void* dHidden,
+                                           void* dW, int32_t* device_status_out, uint32_t flags,
+                                           void* stream) {
+    Problem P = {};
+    P.hidden = (const uint16_t*)hidden; P.W = (const uint16_t*)W; P.labels = labels;
+    P.N = N; P.H = H; P.V = V; P.tile = tile; P.ignore_index = ignore_index;
+    P.grad_loss = grad_loss; P.loss_out = loss_out; P.lse_out = lse_out;
+    P.n_valid_out = n_valid_out; P.dHidden = (uint16_t*)dHidden; P.dW = dW;
+    P.flags = flags; P.stream = (hipStream_t)stream;
+    int rc = validate(P, ALST_NOALLOC_SCRATCH_BYTES, true, true, false, /*own_scratch=*/true);
+    if (rc != ALST_OK) return rc;
+    rc = noalloc_scratch(&P.ws);
+    if (rc != ALST_OK) return rc;
+    // run() starts by resetting the header and writes every other region of the workspace before
+    // it reads it, so what the last call left in the array does not matter
+    rc = run(P, true, true);
+    if (rc != ALST_OK) return rc;
+    if (device_status_out) {
+        hipLaunchKernelGGL(copy_status_kernel, dim3(1), dim3(64), 0, P.stream,
+                           reinterpret_cast<const Header*>(P.ws), device_status_out);
+        if (hipGetLastError() != hipSuccess) return ALST_ERR_HIP;
+    }
+    return ALST_OK;
 }
 
 int alst_last_device_status(void* workspace, void* stream) {

@@ -34,11 +34,11 @@ def test_every_declared_symbol_is_exported(lib):
 def test_version_and_status_strings(lib):
     assert B.alst_version() >= 100
     seen = set()
-    for s in range(0, 9):
+    for s in range(0, 10):
         msg = B.alst_status_string(s)
         assert msg and msg != "unknown status"
         seen.add(msg)
-    assert len(seen) == 9
+    assert len(seen) == 10
     assert B.alst_status_string(99) == "unknown status"
 
 
@@ -146,6 +146,19 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     rc = lib.alst_tiled_ce_token_losses(vp(0x5000), 1 << 40, 16, 64, 32, 8, 1 << 9, vp(0x8000), None)
     assert rc == B.ALST_ERR_UNSUPPORTED
     assert lib.alst_last_device_status(None, None) == B.ALST_ERR_NULL
+    # the entry point without a workspace argument: host validation as above, and a problem beyond
+    # its static scratch is refused before any device is touched
+    def noalloc(hidden=0x1000, N=16, H=64, V=32, tile=8, flags=0):
+        return lib.alst_tiled_ce_forward_backward_noalloc(
+            vp(hidden), vp(0x2000), vp(0x3000), N, H, V, tile, -100, 1.0, vp(0x4000), None, None,
+            vp(0x6000), vp(0x7000), None, flags, None)
+    assert noalloc(hidden=None) == B.ALST_ERR_NULL
+    assert noalloc(H=60) == B.ALST_ERR_ALIGN
+    assert noalloc(flags=B.ALST_FLAG_FORWARD_ONLY) == B.ALST_ERR_UNSUPPORTED
+    assert noalloc(N=131072, H=4096, V=128256, tile=4096) == B.ALST_ERR_NOALLOC_LIMIT
+    assert B.alst_tiled_ce_workspace_bytes(4096, 1024, 8192, 256, B.ALST_FLAG_TILE_SCRATCH) <= B.ALST_NOALLOC_SCRATCH_BYTES
+    assert B.alst_tiled_ce_workspace_bytes(4096, 1024, 8192, 2048) > B.ALST_NOALLOC_SCRATCH_BYTES
+    assert noalloc(N=4096, H=1024, V=8192, tile=2048) == B.ALST_ERR_NOALLOC_LIMIT
     assert lib.alst_shift_labels(None, vp(0x1000), 4, -100, None) == B.ALST_ERR_NULL
     assert lib.alst_shift_labels(vp(0x1000), vp(0x2000), 0, -100, None) == B.ALST_ERR_SHAPE
 
