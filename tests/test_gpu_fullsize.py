@@ -32,16 +32,88 @@ GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 IGN = synth.IGNORE_INDEX
 
 
+DW_GROUP_ROWS = 16384       # dense rows of one dW group at the workloads' tile sizes
+
+
 def _sample_rows(wl, y):
+    """Sequence rows whose dHidden is compared with the oracle.  The library cuts its tiles from
+    the DENSE numbering of the rows with a valid label, so the edges of its tiles and of its dW
+    groups are dense rows k * tile and k * 16384: those are mapped back to sequence positions
+    here.  Sequence positions at multiples of the tile, ignored rows, both ends of ignore runs
+    and a few random rows are kept as well."""
     ign = (y == IGN)
+    valid_pos = np.flatnonzero(~ign)                       # dense row -> sequence row
+    M = len(valid_pos)
+    dense = [0, M - 1, M // 2]
+    tiles = list(range(wl.tile, M, wl.tile))
+    for k in tiles[:2] + tiles[len(tiles) // 2: len(tiles) // 2 + 1] + tiles[-2:]:
+        dense += [k - 1, k]                                # last row of a tile, first of the next
+    groups = list(range(DW_GROUP_ROWS, M, DW_GROUP_ROWS))
+    for k in groups[:1] + groups[-1:]:
+        dense += [k - 1, k]                                # the same at dW group boundaries
+    dense += [(M - 1) // 256 * 256 - 1, (M - 1) // 256 * 256]     # the last (ragged) row block
+    picks = valid_pos[np.clip(np.array(dense, dtype=np.int64), 0, M - 1)].tolist()
+    picks += [0, 1, wl.tile - 1, wl.tile, wl.N - wl.tile, wl.N - 1, wl.N // 2]
     edges = np.flatnonzero(np.diff(ign.astype(np.int8)) != 0)
-    picks = [0, 1, wl.tile - 1, wl.tile, wl.N - wl.tile, wl.N - 1, wl.N // 2]
     for e in edges[:3].tolist() + edges[-2:].tolist():
         picks += [e, e + 1]
     picks += np.flatnonzero(ign)[:2].tolist()
     g = np.random.default_rng(4321)
     picks += g.integers(0, wl.N, 6).tolist()
     return np.unique(np.clip(np.array(picks, dtype=np.int64), 0, wl.N - 1))
+
+
+def _check_against_golden(name, wl, gold, h, W, y, loss, lse, nv, dH, dW, oracle_rows=None, tag=""):
+    """loss, count, lse, sampled dHidden rows and the stored dW entries of one run against the
+    oracle's values; returns the oracle's (rows, dHidden rows, lse, token losses) for reuse."""
+    N, H, V = wl.N, wl.H, wl.V
+    # ---- loss, count, lse ---------------------------------------------------------------------
+    assert int(nv.item()) == gold["n_valid"]
+    lg = float(loss.item())
+    assert abs(lg - gold["loss"]) / abs(gold["loss"]) <= 1e-3, (lg, gold["loss"])
+    lse_h = lse.cpu().numpy().astype(np.float64)
+    # lse is defined for the tokens that take part; rows of ignored tokens are skipped and read 0
+    rows_g = np.array(gold["lse_rows"])
+    vg = y[rows_g] != IGN
+    assert np.abs(lse_h[rows_g][vg] - np.array(gold["lse_values"])[vg]).max() <= 1e-3 * 12.0
+    assert (lse_h[y == IGN] == 0.0).all()
+    assert abs(lse_h.sum() - gold["lse_sum_valid"]) / abs(gold["lse_sum_valid"]) <= 1e-5
+    # closed-form sanity: logits ~ N(0, 0.0004 H), so E[loss] ~ ln V + 0.0002 H
+    assert abs(lg - (np.log(V) + 0.0002 * H)) < 0.02 * lg
+
+    # ---- dHidden: sampled rows against the oracle ------------------------------------------------
+    if oracle_rows is None:
+        rows = _sample_rows(wl, y)
+        print(f"[{name}] oracle dHidden for {len(rows)} rows", flush=True)
+        ref, lse_r, loss_r = orc.dhidden_rows(h, W, y, rows, gold["n_valid"], ignore_index=IGN)
+        oracle_rows = (rows, ref, lse_r, loss_r)
+    rows, ref, lse_r, loss_r = oracle_rows
+    got = dH[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+    eh = G.grad_err(got, ref)
+    assert eh <= 2e-2, ("dHidden", eh)
+    vr = y[rows] != IGN
+    assert np.abs(lse_h[rows][vr] - lse_r[vr]).max() <= 1e-3 * 12.0
+    ign = torch.from_numpy(y == IGN).cuda()
+    assert bool((dH[ign].view(torch.int16) == 0).all()), "rows of ignored tokens must be exact zeros"
+    assert bool(torch.isfinite(dH.float().abs().max())) and bool(torch.isfinite(dW.float().abs().max()))
+
+    # ---- dW: stored oracle entries ------------------------------------------------------------------
+    ids = torch.tensor(gold["dw_ids"], device="cuda")
+    cols = torch.tensor(gold["dw_cols"], device="cuda")
+    got_w = dW[ids][:, cols].float().cpu().numpy().astype(np.float64)
+    ref_w = np.array(gold["dw_values"])
+    den = max(gold["dw_row_maxabs"])
+    ew = np.abs(got_w - ref_w).max() / den
+    assert ew <= 2e-2, ("dW", ew)
+    # the GPU's own maximum is of the same order as the sampled oracle maximum (label rows dominate)
+    gmax = float(dW.float().abs().max().item())
+    assert 0.5 * den <= gmax <= 50 * den, (gmax, den)
+    # sum_v dz[i, v] = 0  =>  every column of dW sums to zero over the vocabulary
+    colsum = dW.double().sum(dim=0).abs().max().item()
+    assert colsum <= 2e-2 * gmax * np.sqrt(V) / 16, (colsum, gmax)
+    print(f"[{name}{tag}] loss {lg:.6f} (oracle {gold['loss']:.6f})  dH err {eh:.2e}  dW err {ew:.2e}  "
+          f"colsum {colsum:.2e}", flush=True)
+    return oracle_rows
 
 
 @pytest.mark.timeout(600)
@@ -81,49 +153,86 @@ def test_full_size_workload(name):
     grow = ws.numel() - B.alst_tiled_ce_workspace_bytes(wl.tile, H, V, wl.tile)
     assert 0 <= grow - 12 * (N - wl.tile) <= 12 * N // 1024 + 512
 
-    # ---- loss, count, lse ---------------------------------------------------------------------
-    assert int(nv.item()) == gold["n_valid"]
-    lg = float(loss.item())
-    assert abs(lg - gold["loss"]) / abs(gold["loss"]) <= 1e-3, (lg, gold["loss"])
-    lse_h = lse.cpu().numpy().astype(np.float64)
-    # lse is defined for the tokens that take part; rows of ignored tokens are skipped and read 0
-    rows_g = np.array(gold["lse_rows"])
-    vg = y[rows_g] != IGN
-    assert np.abs(lse_h[rows_g][vg] - np.array(gold["lse_values"])[vg]).max() <= 1e-3 * 12.0
-    assert (lse_h[y == IGN] == 0.0).all()
-    assert abs(lse_h.sum() - gold["lse_sum_valid"]) / abs(gold["lse_sum_valid"]) <= 1e-5
-    # closed-form sanity: logits ~ N(0, 0.0004 H), so E[loss] ~ ln V + 0.0002 H
-    assert abs(lg - (np.log(V) + 0.0002 * H)) < 0.02 * lg
+    print(f"[{name}] peak {peak / 2**30:.2f} GiB", flush=True)
+    _check_against_golden(name, wl, gold, h, W, y, loss, lse, nv, dH, dW)
 
-    # ---- dHidden: sampled rows against the oracle ------------------------------------------------
-    rows = _sample_rows(wl, y)
-    print(f"[{name}] oracle dHidden for {len(rows)} rows", flush=True)
-    ref, lse_r, _ = orc.dhidden_rows(h, W, y, rows, gold["n_valid"], ignore_index=IGN)
-    got = dH[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
-    eh = G.grad_err(got, ref)
-    assert eh <= 2e-2, ("dHidden", eh)
+
+@pytest.mark.timeout(600)
+def test_other_entry_points_and_one_tile_scratch_at_full_size():
+    """llama8b_32k through the launch configurations the benchmark line does not time: the fused
+    entry point with the dZ scratch of ONE tile (ALST_FLAG_TILE_SCRATCH: peak memory to the
+    letter of the tiling contract), the split entry points (forward, then backward from the saved
+    lse, which recomputes the logits), and the forward pass on a forward-only workspace with the
+    unreduced token losses.  Same golden values and the same sampled rows as the fused case."""
+    name = "llama8b_32k"
+    gold = json.load(open(os.path.join(GOLDEN, name + ".json")))
+    wl = synth.WORKLOADS[name]
+    N, H, V, T = wl.N, wl.H, wl.V, wl.tile
+    print(f"[{name}] generating inputs", flush=True)
+    h, W, y = synth.make_inputs(wl)
+    torch.cuda.empty_cache()
+    torch.cuda.reset_peak_memory_stats()
+    base = torch.cuda.memory_allocated()
+    hd, Wd, yd = G.bits_to_dev(h), G.bits_to_dev(W), torch.from_numpy(y).cuda()
+
+    def outputs():
+        return (torch.zeros(1, device="cuda"), torch.zeros(N, device="cuda"),
+                torch.zeros(1, dtype=torch.int64, device="cuda"),
+                torch.full((N, H), float("nan"), dtype=torch.bfloat16, device="cuda"),
+                torch.full((V, H), float("nan"), dtype=torch.bfloat16, device="cuda"))
+
+    # ---- one tile of dZ scratch -----------------------------------------------------------------
+    flags = B.ALST_FLAG_TILE_SCRATCH
+    ws = B.alloc_workspace(N, H, V, T, flags)
+    loss, lse, nv, dH, dW = outputs()
+    print(f"[{name}] fused pass, one-tile scratch", flush=True)
+    B.alst_tiled_ce_forward_backward(hd, Wd, yd, T, IGN, 1.0, loss_out=loss, lse_out=lse, n_valid_out=nv,
+                                     dHidden=dH, dW=dW, workspace=ws, flags=flags)
+    assert B.alst_last_device_status(ws) == B.ALST_OK
+    torch.cuda.synchronize()
+    peak = torch.cuda.max_memory_allocated() - base
+    # the scratch is 2 bytes per logit of one tile (+ the tile's hidden rows, the softmax partials,
+    # the dHidden partial products and the 12 N bytes of per-row state), beside the fp32 dW sums
+    Vp, Tp = (V + 255) // 256 * 256, (T + 255) // 256 * 256
+    assert ws.numel() <= 2 * Tp * (Vp + H) + 4 * V * H + 12 * (Vp // 128) * Tp + 4 * 8 * Tp * H + 13 * N + (1 << 20)
+    assert peak < 0.6 * 4 * N * V, (peak, 4 * N * V)
+    assert peak < 0.4 * 4 * N * V, (peak, 4 * N * V)          # measured: about a third
+    oracle_rows = _check_against_golden(name, wl, gold, h, W, y, loss, lse, nv, dH, dW, tag=" tile scratch")
+    lse_fused = lse.clone()
+    del ws
+
+    # ---- split entry points -----------------------------------------------------------------------
+    ws = B.alloc_workspace(N, H, V, T)
+    loss, lse, nv, dH, dW = outputs()
+    print(f"[{name}] forward, then backward", flush=True)
+    B.alst_tiled_ce_forward(hd, Wd, yd, T, IGN, loss_out=loss, lse_out=lse, n_valid_out=nv, workspace=ws)
+    assert B.alst_last_device_status(ws) == B.ALST_OK
+    B.alst_tiled_ce_backward(hd, Wd, yd, lse, T, IGN, 1.0, dHidden=dH, dW=dW, workspace=ws)
+    assert B.alst_last_device_status(ws) == B.ALST_OK
+    torch.cuda.synchronize()
+    _check_against_golden(name, wl, gold, h, W, y, loss, lse, nv, dH, dW, oracle_rows, tag=" split")
+    assert torch.equal(lse.view(torch.int32), lse_fused.view(torch.int32))   # lse bits: one definition
+    del ws, dH, dW
+
+    # ---- forward on a forward-only workspace, unreduced token losses ------------------------------
+    flags = B.ALST_FLAG_FORWARD_ONLY
+    ws = B.alloc_workspace(N, H, V, T, flags)
+    assert ws.numel() < 0.05 * B.alst_tiled_ce_workspace_bytes(N, H, V, T)
+    loss2, lse2 = torch.zeros(1, device="cuda"), torch.zeros(N, device="cuda")
+    tok = torch.full((N,), float("nan"), device="cuda")
+    B.alst_tiled_ce_forward(hd, Wd, yd, T, IGN, loss_out=loss2, lse_out=lse2, workspace=ws, flags=flags)
+    B.alst_tiled_ce_token_losses(ws, N, H, V, T, tok, flags=flags)
+    assert B.alst_last_device_status(ws) == B.ALST_OK
+    torch.cuda.synchronize()
+    assert torch.equal(loss2.view(torch.int32), loss.view(torch.int32))
+    assert torch.equal(lse2.view(torch.int32), lse.view(torch.int32))
+    rows, _, _, loss_r = oracle_rows
+    t = tok.cpu().numpy().astype(np.float64)
     vr = y[rows] != IGN
-    assert np.abs(lse_h[rows][vr] - lse_r[vr]).max() <= 1e-3 * 12.0
-    ign = torch.from_numpy(y == IGN).cuda()
-    assert bool((dH[ign].view(torch.int16) == 0).all()), "rows of ignored tokens must be exact zeros"
-    assert bool(torch.isfinite(dH.float().abs().max())) and bool(torch.isfinite(dW.float().abs().max()))
-
-    # ---- dW: stored oracle entries ------------------------------------------------------------------
-    ids = torch.tensor(gold["dw_ids"], device="cuda")
-    cols = torch.tensor(gold["dw_cols"], device="cuda")
-    got_w = dW[ids][:, cols].float().cpu().numpy().astype(np.float64)
-    ref_w = np.array(gold["dw_values"])
-    den = max(gold["dw_row_maxabs"])
-    ew = np.abs(got_w - ref_w).max() / den
-    assert ew <= 2e-2, ("dW", ew)
-    # the GPU's own maximum is of the same order as the sampled oracle maximum (label rows dominate)
-    gmax = float(dW.float().abs().max().item())
-    assert 0.5 * den <= gmax <= 50 * den, (gmax, den)
-    # sum_v dz[i, v] = 0  =>  every column of dW sums to zero over the vocabulary
-    colsum = dW.double().sum(dim=0).abs().max().item()
-    assert colsum <= 2e-2 * gmax * np.sqrt(V) / 16, (colsum, gmax)
-    print(f"[{name}] loss {lg:.6f} (oracle {gold['loss']:.6f})  dH err {eh:.2e}  dW err {ew:.2e}  "
-          f"colsum {colsum:.2e}  peak {peak / 2**30:.2f} GiB", flush=True)
+    assert (t[y == IGN] == 0.0).all()
+    assert np.abs(t[rows][vr] - loss_r[vr]).max() <= 1e-3 * 12.0
+    # their mean over the valid tokens is the loss
+    assert abs(t.sum() / gold["n_valid"] - gold["loss"]) / gold["loss"] <= 1e-5
 
 
 @pytest.mark.timeout(600)
