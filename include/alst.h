@@ -107,7 +107,7 @@ int alst_version(void);
  *   2 * Kg * (Vp + H)   bf16 dZ rows and dense hidden rows of the Kg rows in flight: Kg = Tp with
  *                       ALST_FLAG_TILE_SCRATCH, else Tp * clamp(16384 / Tp, 1, 8) (a group of tiles)
  *   4 * V * H           fp32 dW sums (absent for fp32 overwrite output, whose sums live in dW)
- *   12 * (Vp / 128) * Tp  softmax partials of one tile
+ *   8 * (Vp / 128) * Tp   softmax partials of one tile
  * and with ALST_FLAG_FORWARD_ONLY only the last one and 2 * Tp * H remain.
  */
 size_t alst_tiled_ce_workspace_bytes(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_t flags);

@@ -14,16 +14,22 @@
 //                        of a tile beyond the dense rows leave at once, so nothing waits for the
 //                        host.
 //   1. logits_kernel     Z = H_c W^T in 256x256 blocks, fp32 accumulators.  The logits never
-//                        leave the registers: the epilogue reduces each row over the block's
-//                        columns to (max, sum exp) partials per 128-column group, picks out the
-//                        label logit, and writes e = exp(z - group max) as bf16 to a [T, V]
-//                        scratch ("stash", also laid out per dW group).
-//   2. row_combine       partials -> lse, per-row loss, and the factor exp(group max - lse)
-//                        that turns e into the softmax probability.
-//   3. dz_finalize       dZ = e * factor - onehot as bf16, in place.
-//   4. dhidden_kernel    dH = (g/M) dZ W            (contraction over V), rows scattered back
-//   5. dw_kernel         acc += H_c^T dZ            once per group of tiles (contraction over the
-//                        group's dense rows, fp32)
+//                        leave the registers: the epilogue picks out the label logit, writes
+//                        e = exp(z - ref_i) as bf16 to a [T, V] scratch ("stash", also laid out
+//                        per dW group) and reduces each row over the block's columns to
+//                        (max, sum e) partials per 128-column group.  ref_i is ONE reference per
+//                        row (0 to begin with), so a row's softmax is e / S_i with S_i = sum_v e:
+//                        the scale is a per-row scalar that the consumers of the stash apply.
+//   2. row_finish        partials -> S_i, lse_i = ref_i + log S_i, per-row loss; the label entry of
+//                        the stash becomes e - S_i (so that e' / S_i = p - onehot), and the row's
+//                        dense hidden row is scaled by 1 / S_i in place (the dW operand).  A row
+//                        whose S_i left the safe range of the bf16 / fp32 exponents (logits
+//                        beyond about +-40) is redone with ref_i = its exact maximum: a second,
+//                        conditional launch of 1. and 2. whose workgroups leave at once when no
+//                        row of the tile asked for it.
+//   3. dhidden_kernel    dH_i = (g/M) (1/S_i) e'_i W   (contraction over V), rows scattered back
+//   4. dw_kernel         acc += (H_c / S)^T e'         once per group of tiles (contraction over
+//                        the group's dense rows, fp32)
 //
 // After the last tile: loss = sum(per-row loss) / M in a fixed order, dW = (g/M) acc.
 // The contractions share the block GEMM of gemm_tile.h in its three operand layouts: logits with
@@ -60,6 +66,8 @@ struct TileInfo {
     int kofs;              // where the tile's dense rows start along k in the dW group buffers
     int splits;            // dHidden: ranges the contraction over V is cut into for this tile
     int ksteps;            //          k-steps of 64 per range (the last range may be shorter)
+    int redo;              // set by row_finish: some row of the tile needs the second logits pass
+    int pad;
 };
 
 // dW is accumulated into the fp32 [V, H] sums once per GROUP of consecutive tiles: the dense
@@ -87,8 +95,8 @@ struct Layout {
     int dh_PR, dh_PC;      // dHidden: patch shape of the block -> tile mapping
     int64_t dh_patches;    //          most patches (over all ranges) a tile of any number of rows needs
     int64_t dh_part_rows;  //          most rows of fp32 partial products (0: never cut)
-    size_t header, tinfo, loss_rows, lse, idx, block_cnt, block_ofs, zlabel, yc, pm, ps, sc, hc,
-        stash, part, acc, total;
+    size_t header, tinfo, loss_rows, lse, idx, block_cnt, block_ofs, zlabel, yc, ref, frow, rowstate,
+        pm, ps, hc, stash, part, acc, total;
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -144,9 +152,11 @@ static Layout make_layout(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_
     L.block_ofs = take(nblocks * 8);
     L.zlabel = take((size_t)L.Tp * 4);
     L.yc = take((size_t)L.Tp * 4);
+    L.ref = take((size_t)L.Tp * 4);
+    L.frow = take((size_t)L.Tp * 4);
+    L.rowstate = take((size_t)L.Tp * 4);
     L.pm = take((size_t)L.ng * L.Tp * 4);
     L.ps = take((size_t)L.ng * L.Tp * 4);
-    L.sc = take(fwd_only ? 0 : (size_t)L.ng * L.Tp * 4);
     // hc and stash hold the dense rows of the whole group, each tile at its k offset: they are
     // the two operands of the group's dW product as they are (k = dense row, the slow index)
     L.hc = take((size_t)L.Kg * H * 2);
@@ -323,15 +333,19 @@ __global__ void tile_info_kernel(const Header* __restrict__ h, int64_t t, int64_
     }
     info->splits = sp;
     info->ksteps = ks;
+    info->redo = 0;
 }
 
 // Block b: dense row b of the tile.  Copies the hidden row of token idx_t[b] into the dense
 // matrix Hc and its label into yc; rows Tc <= b < Trc are zero padding.  Hc holds the whole dW
-// group and the tile's rows start at its k offset.
+// group and the tile's rows start at its k offset.  Also sets the row's softmax reference for the
+// first logits pass (0; backward from a saved lse: that lse, so that e is the probability itself)
+// and marks the row as taking part in that pass.
 __global__ __launch_bounds__(256) void gather_rows_kernel(
     const uint16_t* __restrict__ hidden, const int32_t* __restrict__ labels, int H,
     const int32_t* __restrict__ idx_t, const TileInfo* __restrict__ info,
-    uint16_t* __restrict__ Hc, int32_t* __restrict__ yc) {
+    const float* __restrict__ lse_in, uint16_t* __restrict__ Hc, int32_t* __restrict__ yc,
+    float* __restrict__ ref, int32_t* __restrict__ rowstate) {
     const int b = blockIdx.x;
     const int chunks = H / 8;
     if (b >= info->Trc) return;
@@ -341,95 +355,144 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(
         const int64_t row = idx_t[b];
         const u32x4_t* src = reinterpret_cast<const u32x4_t*>(hidden + row * H);
         for (int c = threadIdx.x; c < chunks; c += 256) dst[c] = src[c];
-        if (threadIdx.x == 0) yc[b] = labels[row];
+        if (threadIdx.x == 0) {
+            yc[b] = labels[row];
+            ref[b] = lse_in ? lse_in[row] : 0.f;
+            rowstate[b] = 1;
+        }
     } else {
         const u32x4_t zero4 = {0u, 0u, 0u, 0u};
         for (int c = threadIdx.x; c < chunks; c += 256) dst[c] = zero4;
+        if (threadIdx.x == 0) {
+            yc[b] = -1;
+            ref[b] = 0.f;
+            rowstate[b] = 1;
+        }
     }
 }
 
-// Per dense row of the tile: combine the per-group (max, sum exp) partials into lse, the row's loss
-// term (both written to the row's original position), and (fused mode) the factor that turns the
-// stashed e into a probability.
-// Block = 16 rows x 64 group lanes (a tile of 4096 rows gives 256 workgroups): thread (x, y) owns
-// groups y, y + 64, ... of row x; the 64 lanes of a row are combined through LDS in a fixed order,
-// so lse does not depend on anything but the row's partials.
+enum { MODE_FWD = 0, MODE_FUSED = 1, MODE_BWD = 2 };
+
+// A row's e = exp(z - ref) live in bf16 (the stash) and in fp32 sums; both have 8 exponent bits.
+// With S = sum_v e inside [kSumLo, kSumHi] no e of weight overflows, the ones that underflow are
+// below 2^-66 of the row's mass, and the fp32 products S * |w| of the dHidden contraction stay far
+// from overflow.  A row outside is redone with ref = its exact maximum (then 1 <= S <= V).
+constexpr float kSumLo = 8.673617379884035e-19f;      // 2^-60
+constexpr float kSumHi = 1.2676506002282294e30f;      // 2^100
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct RowFinishParams {
+    const float* pm;         // [ng, Tp]  per 128-column group: max z          (first pass only)
+    const float* ps;         // [ng, Tp]  per 128-column group: sum of e
+    const float* zlabel;     // [Tp]      label logit of each dense row
+    const int32_t* yc;       // [Tp]      label of each dense row
+    const int32_t* idx;      // [Tp]      dense row -> row of the sequence
+    TileInfo* info;
+    float* ref;              // [Tp]      the row's reference; rewritten for a row that is redone
+    float* frow;             // [Tp]      1 / S of a finished row (MODE_FUSED), 1 (MODE_BWD)
+    int32_t* rowstate;       // [Tp]      1: the row takes part in the next logits pass, 0: finished
+    float* lse_t;            // [N]       by row of the sequence
+    float* loss_rows_t;      // [N]
+    uint16_t* hc;            // [Kg, H]   dense hidden rows of the group (scaled in place, MODE_FUSED)
+    uint16_t* stash;         // [Kg, Vp]
+    int Tp, ng, H, Vp;
+};
+
+// Per dense row of the tile, after a logits pass: S = sum of the per-group sums of e (fixed order,
+// so a row's lse depends on nothing but its own partials), lse = ref + log S, the row's loss term
+// (both written to the row's original position) and, when gradients follow,
+//   * the stash entry of the label becomes e_label - S (MODE_FUSED) or p_label - 1 (MODE_BWD),
+//     formed in fp32 from the label logit, so that (stash * f)[v] = p[v] - [v = label] with the
+//     relative precision of bf16 in every entry;
+//   * frow = f = 1 / S (adjusted by the rounding of the label entry, see below), which dHidden
+//     applies to its output rows;
+//   * the row's dense hidden row is multiplied by f in place: it is the other operand of the
+//     dW product, whose contraction index is the row.
+// First pass (REDO = false): a row whose S is outside [kSumLo, kSumHi] is not finished; its
+// reference becomes its exact maximum, it stays marked, and the tile is flagged for the second
+// pass.  Second pass (REDO = true): leaves at once unless flagged; finishes the marked rows.
+// MODE_BWD has no sums to combine (e is the probability itself): label entries only.
+// Block = 16 rows x 64 lanes: thread (x, y) owns groups y, y + 64, ... of row x; the 64 lanes of a
+// row are combined through LDS in a fixed order.
 constexpr int kCombineRows = 16, kCombineLanes = 64;
-__global__ __launch_bounds__(kCombineRows * kCombineLanes) void row_combine_kernel(
-    const float* __restrict__ pm, const float* __restrict__ ps, const float* __restrict__ zlabel,
-    const int32_t* __restrict__ idx, const TileInfo* __restrict__ info, int Tp, int ng,
-    float* __restrict__ lse_t, float* __restrict__ loss_rows_t, float* __restrict__ sc) {
+template <int MODE, bool REDO>
+__global__ __launch_bounds__(kCombineRows * kCombineLanes) void row_finish_kernel(const RowFinishParams p) {
     __shared__ float red[kCombineLanes][kCombineRows];
     const int x = threadIdx.x, y = threadIdx.y;
-    if ((int)blockIdx.x * kCombineRows >= info->Trc) return;
+    if ((int)blockIdx.x * kCombineRows >= p.info->Trc) return;
+    if (REDO && !p.info->redo) return;
     const int i = blockIdx.x * kCombineRows + x;          // dense row; Trc is a multiple of 256
-    const bool inrow = i < info->Tc;                      // every dense row below Tc is valid
-    float m = -INFINITY;
-    for (int g = y; g < ng; g += kCombineLanes) m = fmaxf(m, pm[(int64_t)g * Tp + i]);
-    red[y][x] = m;
-    __syncthreads();
-    float M = red[0][x];
+    const bool inrow = i < p.info->Tc;                    // every dense row below Tc is valid
+    const bool marked = p.rowstate[i] != 0;
+    __syncthreads();                                      // every thread of a row has read its mark
+    const int Tp = p.Tp, ng = p.ng;
+    float S = 1.f, M = 0.f;
+    if (MODE != MODE_BWD) {
+        float sum = 0.f;
+        for (int g = y; g < ng; g += kCombineLanes) sum += p.ps[(int64_t)g * Tp + i];
+        red[y][x] = sum;
+        __syncthreads();
+        S = red[0][x];
 #pragma unroll
-    for (int l = 1; l < kCombineLanes; ++l) M = fmaxf(M, red[l][x]);
-    __syncthreads();
-    float sum = 0.f;
-    for (int g = y; g < ng; g += kCombineLanes)
-        sum += ps[(int64_t)g * Tp + i] * __expf(pm[(int64_t)g * Tp + i] - M);
-    red[y][x] = sum;
-    __syncthreads();
-    float S = red[0][x];
+        for (int l = 1; l < kCombineLanes; ++l) S += red[l][x];
+        __syncthreads();
+        if (!REDO) {
+            float m = -INFINITY;
+            for (int g = y; g < ng; g += kCombineLanes) m = fmaxf(m, p.pm[(int64_t)g * Tp + i]);
+            red[y][x] = m;
+            __syncthreads();
+            M = red[0][x];
 #pragma unroll
-    for (int l = 1; l < kCombineLanes; ++l) S += red[l][x];
-    const float lse = M + __logf(S);
-    if (inrow && y == 0) {
-        const int orig = idx[i];
-        lse_t[orig] = lse;
-        loss_rows_t[orig] = lse - zlabel[i];
-    }
-    if (sc) {
-        for (int g = y; g < ng; g += kCombineLanes)
-            sc[(int64_t)g * Tp + i] = inrow ? __expf(pm[(int64_t)g * Tp + i] - lse) : 0.f;
-    }
-}
-
-// dZ = e * factor - onehot for the tile's dense rows, bf16, in place over the stash (which holds
-// the whole dW group; the tile's rows start at its k offset).  Rows Tc .. Trc and columns >= V
-// come out as exact zeros, which is what pads the k dimension of the two gradient GEMMs.  One
-// wavefront owns a 64 (rows) x 64 (columns) patch, one lane 8 rows x 8 columns of it: the 8 lanes
-// along v cover one 128-byte line per row.
-template <bool FUSED>
-__global__ __launch_bounds__(256) void dz_finalize_kernel(uint16_t* __restrict__ stash,
-                                                          const float* __restrict__ sc,
-                                                          const int32_t* __restrict__ yc,
-                                                          const TileInfo* __restrict__ info,
-                                                          int Tp, int Vp) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    // one-dimensional grid (the row-block count can exceed the limit of gridDim.y):
-    // block -> (column block bx of 256 columns, row block by of 64 rows), bx fastest
-    const int nbx = Vp / 256;
-    const int bx = blockIdx.x % nbx, by = blockIdx.x / nbx;
-    const int v0 = (bx * 4 + wave) * 64 + (lane & 7) * 8;             // first of this lane's 8 columns
-    const int i0 = by * 64 + (lane >> 3) * 8;                         // first of this lane's 8 rows
-    if (by * 64 >= info->Trc) return;
-    const int T_cur = info->Tc;
-    stash += (int64_t)info->kofs * Vp;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int i = i0 + j;
-        uint16_t* p = stash + (int64_t)i * Vp + v0;
-        const bf16x8_t e = *reinterpret_cast<const bf16x8_t*>(p);
-        const bool valid = i < T_cur;                   // dense rows below Tc all carry a valid label
-        const int y = valid ? yc[i] : -1;
-        float f = valid ? 1.f : 0.f;
-        if (FUSED) f = valid ? sc[(int64_t)(v0 >> 7) * Tp + i] : 0.f;
-        bf16x8_t d;
-#pragma unroll
-        for (int x = 0; x < 8; ++x) {
-            float val = (float)e[x] * f;
-            if (valid && v0 + x == y) val -= 1.f;
-            d[x] = (__bf16)val;
+            for (int l = 1; l < kCombineLanes; ++l) M = fmaxf(M, red[l][x]);
         }
-        *reinterpret_cast<bf16x8_t*>(p) = d;
+    }
+    // (rowstate, ref and frow of row i are written by the row's thread y == 0 only, and read above
+    // or below by the same thread or before the barriers)
+    if (!inrow) {                                         // padding rows: nothing to finish
+        if (y == 0 && !REDO) { p.rowstate[i] = 0; p.frow[i] = 0.f; }
+        return;
+    }
+    if (!marked) return;
+    const bool ok = MODE == MODE_BWD || REDO || (S >= kSumLo && S <= kSumHi);
+    if (!ok) {
+        if (y == 0) {
+            p.ref[i] = (M == -INFINITY || M != M) ? 0.f : M;
+            atomicOr(&p.info->redo, 1);
+        }
+        return;
+    }
+    const int kofs = p.info->kofs;
+    const float ref = p.ref[i], zl = p.zlabel[i];
+    // the label's e, as the logits pass formed it before rounding it to bf16, minus S (MODE_BWD:
+    // p - 1, S = 1), rounded to bf16 for the stash
+    const float el = __builtin_amdgcn_exp2f(fmaf(zl, kLog2e, -(ref * kLog2e)));
+    const __bf16 d = (__bf16)(el - S);
+    // The row's scale is chosen so that the ROUNDED label entry times the scale is p - 1 to fp32
+    // precision (the label entries carry the largest gradients); every other entry of the row then
+    // sees the scale off by the label entry's rounding, within the 2^-9 its own rounding has.
+    float f = 1.f / S;
+    if (MODE != MODE_FWD && (float)d != 0.f) f = ((el - S) / (float)d) / S;     // (d * S may overflow)
+    if (y == 0) {
+        if (MODE != MODE_BWD) {
+            const int orig = p.idx[i];
+            const float lse = ref + __logf(S);
+            p.lse_t[orig] = lse;
+            p.loss_rows_t[orig] = lse - zl;
+        }
+        if (MODE != MODE_FWD) {
+            p.stash[(int64_t)(kofs + i) * p.Vp + p.yc[i]] = __builtin_bit_cast(uint16_t, d);
+            p.frow[i] = f;
+        }
+        p.rowstate[i] = 0;
+    }
+    if (MODE == MODE_FUSED) {
+        uint16_t* row = p.hc + (int64_t)(kofs + i) * p.H;
+        for (int c = y; c < p.H / 8; c += kCombineLanes) {
+            bf16x8_t v = *reinterpret_cast<const bf16x8_t*>(row + c * 8);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) v[q] = (__bf16)((float)v[q] * f);
+            *reinterpret_cast<bf16x8_t*>(row + c * 8) = v;
+        }
     }
 }
 
@@ -498,16 +561,14 @@ __global__ void shift_labels_kernel(const int32_t* __restrict__ labels, int32_t*
 // ---------------------------------------------------------------------------------------------
 // the three block GEMMs
 // ---------------------------------------------------------------------------------------------
-enum { MODE_FWD = 0, MODE_FUSED = 1, MODE_BWD = 2 };
-
 struct LogitsParams {
     const uint16_t* hidden_t;   // [Kg, H]      dense (valid) rows of the dW group; the tile's rows
                                 //              start at its k offset and are zero padded to Trc
     const uint16_t* W;          // [V, H]
     const int32_t* labels_t;    // [Tp]         labels of the dense rows
-    const int32_t* idx;         // [Tp]         dense row of the tile -> row of the sequence
     const TileInfo* info;
-    const float* lse_t;         // [N]          MODE_BWD, indexed by the row of the sequence
+    const float* ref;           // [Tp]         reference of each dense row: e = exp(z - ref)
+    const int32_t* rowstate;    // [Tp]         second pass: rows that are redone (others keep their results)
     float* pm;                  // [ng, Tp]     MODE_FWD / MODE_FUSED
     float* ps;                  // [ng, Tp]
     float* zlabel;              // [Tp]
@@ -517,13 +578,17 @@ struct LogitsParams {
 };
 
 // r = token row of the tile (MFMA lane dimension), c = vocabulary id (register dimension).
-template <class Core, bool GUARD, int MODE>
+// REDO: the second pass over a tile, for the rows whose first-pass sums left the safe range; its
+// workgroups leave at once unless row_finish flagged the tile, and rows that are not marked keep
+// what the first pass wrote.
+template <class Core, bool GUARD, int MODE, bool REDO>
 __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsParams p) {
     constexpr int kMT = Core::kMT, kNT = Core::kNT;
     extern __shared__ __align__(16) unsigned char smem[];
     int tr, tc;
     const int T_cur = p.info->Tc, Trc = p.info->Trc;
     if (T_cur == 0) return;
+    if (REDO && !p.info->redo) return;
     {
         const PatchGrid pg = {Trc / kBlockR, p.Vp / kBlockC, p.PR, p.PC};
         int P, w;
@@ -548,11 +613,11 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
     Core::template gemm<GUARD>(hidden_t, p.H, Trc, p.W, p.H, p.V, p.H, r0, c0, smem, acc, warm);
 
     const typename Core::Lane lp;
-    constexpr float kLog2e = 1.4426950408889634f;
 #pragma unroll
     for (int nt = 0; nt < kNT; ++nt) {
         const int i = r0 + lp.r(nt);
         const bool rowok = i < T_cur;
+        const bool act = !REDO || p.rowstate[i] != 0;     // this pass writes row i's results
         {                               // columns beyond the vocabulary (last column block)
             if (c0 + kBlockC > p.V) {
 #pragma unroll
@@ -562,20 +627,20 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
                         if (c0 + lp.c(mt, j >> 2) + (j & 3) >= p.V) acc[mt][nt][j] = -INFINITY;
             }
         }
-        float ref, m = 0.f;
-        if (MODE == MODE_BWD) {
-            ref = rowok ? p.lse_t[p.idx[i]] : 0.f;
-        } else {
+        const float ref = p.ref[i];
+        float m = 0.f;
+        if (MODE != MODE_BWD && !REDO) {                  // the row's exact maximum, for a redo
             m = -INFINITY;
 #pragma unroll
             for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
                 for (int j = 0; j < 16; ++j) m = fmaxf(m, acc[mt][nt][j]);
             m = fmaxf(m, __shfl_xor(m, 32));
-            ref = (m == -INFINITY) ? 0.f : m;
+        }
+        {
             // label logit: exactly one lane of one block holds column y of row i.  Few wavefronts
             // hold any (32 rows x 128 of V columns), so the search sits behind a uniform branch.
-            const int y = rowok ? p.labels_t[i] : -1;
+            const int y = rowok && act ? p.labels_t[i] : -1;
             const unsigned d = (unsigned)(y - (c0 + lp.wc * kGroupC));
             const bool mine = y >= 0 && d < (unsigned)kGroupC && ((d >> 2) & 1u) == (unsigned)lp.half;
             if (__ballot(mine) != 0ull) {
@@ -617,20 +682,21 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
             }
         if (MODE != MODE_FWD) {
             const int lrow = lp.lane >> 4, lcol = lp.lane & 15;        // 4 rows x 16 chunks of 16 B
-            uint16_t* const out = p.stash + (int64_t)(kofs + r0 + lp.rbase(nt)) * p.Vp + c0 +
-                                  lp.wc * kGroupC + lcol * 8;
+            const int rb = r0 + lp.rbase(nt);
+            uint16_t* const out = p.stash + (int64_t)(kofs + rb) * p.Vp + c0 + lp.wc * kGroupC + lcol * 8;
 #pragma unroll
             for (int it = 0; it < 8; ++it) {
                 const int row = it * 4 + lrow;
                 const u32x4_t v = *reinterpret_cast<const u32x4_t*>(tw + row * kTurnPitch + lcol * 16);
-                *reinterpret_cast<u32x4_t*>(out + (int64_t)row * p.Vp) = v;
+                if (!REDO || p.rowstate[rb + row] != 0)
+                    *reinterpret_cast<u32x4_t*>(out + (int64_t)row * p.Vp) = v;
             }
         }
         if (MODE != MODE_BWD) {
             s += __shfl_xor(s, 32);
-            if (lp.half == 0) {
+            if (lp.half == 0 && act) {
                 const int64_t g = (c0 + lp.wc * kGroupC) >> 7;
-                p.pm[g * p.Tp + i] = m;
+                if (!REDO) p.pm[g * p.Tp + i] = m;
                 p.ps[g * p.Tp + i] = s;
             }
         }
@@ -644,6 +710,7 @@ struct DHiddenParams {
     const int32_t* idx;
     const TileInfo* info;
     const Header* hdr;
+    const float* frow;       // [Tp]         scale of each dense row's result: 1 / S of its softmax
     float* part;             // [splits, Trc, H] fp32 partial products (splits > 1); the number
                              // of ranges and their length are the tile's (TileInfo)
     int Tp, H, V, Vp;
@@ -718,6 +785,7 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
     for (int nt = 0; nt < kNT; ++nt) {
         const int i = r0 + lp.r(nt);
         if (i >= T_cur) continue;
+        const float sc = inv * p.frow[i];
         uint16_t* row = p.dH_t + (int64_t)p.idx[i] * p.H;
 #pragma unroll
         for (int mt = 0; mt < kMT; ++mt)
@@ -727,23 +795,24 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
                 if (h >= p.H) continue;             // last column block of a ragged H
                 bf16x4_t o;
 #pragma unroll
-                for (int x = 0; x < 4; ++x) o[x] = (__bf16)(acc[mt][nt][q * 4 + x] * inv);
+                for (int x = 0; x < 4; ++x) o[x] = (__bf16)(acc[mt][nt][q * 4 + x] * sc);
                 *reinterpret_cast<bf16x4_t*>(row + h) = o;
             }
     }
 }
 
-// dH[idx[i]] = (g/M) * sum over the ranges of the partial products of dense row i, in range order.
-// Tiles whose contraction was not cut were written by dhidden_kernel itself.
+// dH[idx[i]] = (g/M) (1/S_i) * sum over the ranges of the partial products of dense row i, in
+// range order.  Tiles whose contraction was not cut were written by dhidden_kernel itself.
 __global__ __launch_bounds__(256) void dhidden_reduce_kernel(const float* __restrict__ part, int H,
                                                              const int32_t* __restrict__ idx,
                                                              const TileInfo* __restrict__ info,
                                                              const Header* __restrict__ hdr,
+                                                             const float* __restrict__ frow,
                                                              uint16_t* __restrict__ dH) {
     const int i = blockIdx.x;
     const int splits = info->splits, Trc = info->Trc;
     if (i >= info->Tc || splits <= 1) return;
-    const float inv = hdr->inv;
+    const float inv = hdr->inv * frow[i];
     uint16_t* out = dH + (int64_t)idx[i] * H;
     for (int c = threadIdx.x * 4; c < H; c += 256 * 4) {
         f32x4_t a = *reinterpret_cast<const f32x4_t*>(part + (int64_t)i * H + c);
@@ -810,12 +879,16 @@ __global__ __launch_bounds__(Core::kThreads) void dw_kernel(const DWParams p) {
 static int prepare_kernels_on_current_device() {
     int rc = ALST_OK;
     auto acc = [&](int r) { if (r != ALST_OK) rc = r; };
-    acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_FWD>));
-    acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_FWD>));
-    acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_FUSED>));
-    acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_FUSED>));
-    acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_BWD>));
-    acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_BWD>));
+    acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_FWD, false>));
+    acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_FWD, false>));
+    acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_FUSED, false>));
+    acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_FUSED, false>));
+    acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_BWD, false>));
+    acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_BWD, false>));
+    acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_FWD, true>));
+    acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_FWD, true>));
+    acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_FUSED, true>));
+    acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_FUSED, true>));
     acc(allow_big_lds(dhidden_kernel<MixedCore, false, false>));
     acc(allow_big_lds(dhidden_kernel<MixedCore, false, true>));
     acc(allow_big_lds(dw_kernel<KMajorCore, false>));
@@ -881,18 +954,46 @@ static int validate(const Problem& P, size_t workspace_bytes, bool need_fwd_out,
 
 // Grids are sized for Tr (the tile's rows rounded up to the block height); the kernels read the
 // number of rows that take part from the device and surplus blocks leave at once.
-template <int MODE>
+template <int MODE, bool REDO>
 static int launch_logits(LogitsParams lp, int Tr, bool guard, hipStream_t s) {
     const PatchGrid pg = choose_patches(Tr / kBlockR, lp.Vp / kBlockC);
     lp.PR = pg.PR; lp.PC = pg.PC;
     const int grid = grid_for_patches(pg.patches());
     if (guard)
-        hipLaunchKernelGGL((logits_kernel<StagedCore, true, MODE>), dim3(grid),
+        hipLaunchKernelGGL((logits_kernel<StagedCore, true, MODE, REDO>), dim3(grid),
                            dim3(StagedCore::kThreads), kLdsBytes, s, lp);
     else
-        hipLaunchKernelGGL((logits_kernel<DirectCore, false, MODE>), dim3(grid),
+        hipLaunchKernelGGL((logits_kernel<DirectCore, false, MODE, REDO>), dim3(grid),
                            dim3(DirectCore::kThreads), kLdsBytes, s, lp);
     return hipGetLastError() == hipSuccess ? ALST_OK : ALST_ERR_HIP;
+}
+
+// The logits pass of a tile and the per-row work behind it; for the modes that form the softmax
+// sums, followed by the conditional second pass (see row_finish_kernel).
+template <int MODE>
+static int logits_and_finish(const LogitsParams& lp, const RowFinishParams& fp, int Tr, bool guard,
+                             hipStream_t s) {
+    const dim3 fgrid(Tr / kCombineRows), fblock(kCombineRows, kCombineLanes);
+    int rc;
+    {
+        ProfScope ps_(PROF_LOGITS, s);
+        rc = launch_logits<MODE, false>(lp, Tr, guard, s);
+    }
+    if (rc != ALST_OK) return rc;
+    {
+        ProfScope small_(PROF_OTHER, s);
+        hipLaunchKernelGGL((row_finish_kernel<MODE, false>), fgrid, fblock, 0, s, fp);
+        ALST_HIP(hipGetLastError());
+    }
+    if (MODE == MODE_BWD) return ALST_OK;
+    constexpr int M2 = MODE == MODE_BWD ? MODE_FUSED : MODE;      // (MODE_BWD never gets here)
+    // (timed with the small kernels: in all but pathological inputs both launches are empty)
+    ProfScope small_(PROF_OTHER, s);
+    rc = launch_logits<M2, true>(lp, Tr, guard, s);
+    if (rc != ALST_OK) return rc;
+    hipLaunchKernelGGL((row_finish_kernel<M2, true>), fgrid, fblock, 0, s, fp);
+    ALST_HIP(hipGetLastError());
+    return ALST_OK;
 }
 
 // do_fwd: produce loss / lse.  do_bwd: produce gradients.  Both: one fused sweep.
@@ -912,7 +1013,9 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
     int64_t* block_ofs = reinterpret_cast<int64_t*>(P.ws + L.block_ofs);
     float* pm = reinterpret_cast<float*>(P.ws + L.pm);
     float* ps = reinterpret_cast<float*>(P.ws + L.ps);
-    float* sc = reinterpret_cast<float*>(P.ws + L.sc);
+    float* ref = reinterpret_cast<float*>(P.ws + L.ref);
+    float* frow = reinterpret_cast<float*>(P.ws + L.frow);
+    int32_t* rowstate = reinterpret_cast<int32_t*>(P.ws + L.rowstate);
     uint16_t* hc = reinterpret_cast<uint16_t*>(P.ws + L.hc);
     uint16_t* stash = reinterpret_cast<uint16_t*>(P.ws + L.stash);
     const bool acc_in_dw = (P.flags & ALST_FLAG_DW_FP32) && !(P.flags & ALST_FLAG_DW_ACCUMULATE);
@@ -962,7 +1065,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
                                slot ? info - 1 : nullptr, P.H, P.V, L.Tp, L.dh_patches, L.dh_part_rows,
                                L.dh_PR, L.dh_PC);
             hipLaunchKernelGGL(gather_rows_kernel, dim3(Tr), dim3(256), 0, s, P.hidden, P.labels, H,
-                               idx_t, info, hc, yc);
+                               idx_t, info, do_fwd ? nullptr : P.lse_in, hc, yc, ref, rowstate);
             ALST_HIP(hipGetLastError());
         }
 
@@ -970,46 +1073,25 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
         lp.hidden_t = hc;
         lp.W = P.W;
         lp.labels_t = yc;
-        lp.idx = idx_t;
         lp.info = info;
-        lp.lse_t = do_fwd ? nullptr : P.lse_in;
+        lp.ref = ref; lp.rowstate = rowstate;
         lp.pm = pm; lp.ps = ps; lp.zlabel = zlabel; lp.stash = stash;
         lp.Tp = Tp; lp.H = H; lp.V = V; lp.Vp = Vp;
-        {
-            ProfScope ps_(PROF_LOGITS, s);
-            if (do_fwd && do_bwd) rc = launch_logits<MODE_FUSED>(lp, Tr, guard_logits, s);
-            else if (do_fwd) rc = launch_logits<MODE_FWD>(lp, Tr, guard_logits, s);
-            else rc = launch_logits<MODE_BWD>(lp, Tr, guard_logits, s);
-        }
+        RowFinishParams fp;
+        fp.pm = pm; fp.ps = ps; fp.zlabel = zlabel; fp.yc = yc; fp.idx = idx_t; fp.info = info;
+        fp.ref = ref; fp.frow = frow; fp.rowstate = rowstate;
+        fp.lse_t = lse_buf; fp.loss_rows_t = loss_rows; fp.hc = hc; fp.stash = stash;
+        fp.Tp = Tp; fp.ng = ng; fp.H = H; fp.Vp = Vp;
+        if (do_fwd && do_bwd) rc = logits_and_finish<MODE_FUSED>(lp, fp, Tr, guard_logits, s);
+        else if (do_fwd) rc = logits_and_finish<MODE_FWD>(lp, fp, Tr, guard_logits, s);
+        else rc = logits_and_finish<MODE_BWD>(lp, fp, Tr, guard_logits, s);
         if (rc != ALST_OK) return rc;
-
-        {
-            ProfScope small_(PROF_OTHER, s);
-            if (do_fwd) {
-                hipLaunchKernelGGL(row_combine_kernel, dim3(Tr / kCombineRows),
-                                   dim3(kCombineRows, kCombineLanes), 0, s, pm, ps, zlabel, idx_t,
-                                   info, Tp, ng, lse_buf, loss_rows, do_bwd ? sc : nullptr);
-                ALST_HIP(hipGetLastError());
-            }
-            if (do_bwd) {
-                const int64_t nblk = (int64_t)(Vp / 256) * (Tr / 64);
-                if (nblk > 0x7fffffff) return ALST_ERR_SHAPE;
-                dim3 grid((unsigned)nblk);
-                if (do_fwd)
-                    hipLaunchKernelGGL(dz_finalize_kernel<true>, grid, dim3(256), 0, s, stash, sc, yc,
-                                       info, Tp, Vp);
-                else
-                    hipLaunchKernelGGL(dz_finalize_kernel<false>, grid, dim3(256), 0, s, stash, sc,
-                                       yc, info, Tp, Vp);
-                ALST_HIP(hipGetLastError());
-            }
-        }
         if (!do_bwd) continue;
 
         {
             DHiddenParams dp;
             dp.dz = stash; dp.W = P.W; dp.dH_t = P.dHidden; dp.idx = idx_t;
-            dp.info = info; dp.hdr = hdr;
+            dp.info = info; dp.hdr = hdr; dp.frow = frow;
             dp.part = reinterpret_cast<float*>(P.ws + L.part);
             dp.Tp = Tp; dp.H = H; dp.V = V; dp.Vp = Vp;
             dp.PR = L.dh_PR; dp.PC = L.dh_PC;
@@ -1024,7 +1106,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
                                    dim3(MixedCore::kThreads), kLdsBytes, s, dp);
             if (L.dh_part_rows > 0)
                 hipLaunchKernelGGL(dhidden_reduce_kernel, dim3(Tr), dim3(256), 0, s, dp.part, H, idx_t,
-                                   info, hdr, P.dHidden);
+                                   info, hdr, frow, P.dHidden);
             ALST_HIP(hipGetLastError());
         }
         if (slot == L.g - 1 || t == ntiles - 1) {           // the group is complete

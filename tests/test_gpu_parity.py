@@ -384,6 +384,47 @@ def test_large_logits_stay_finite_and_match():
     _check(r, f, dH, dW, "large logits", valid=(y != IGN))
 
 
+def _redo_case(name, h, W, y, tile):
+    f, dH, dW = _oracle(h, W, y)
+    r = G.run_fused(h, W, y, tile)
+    eh, ew = _check(r, f, dH, dW, name, valid=(y != IGN))
+    rs = G.run_split(h, W, y, tile)
+    assert rs.status_bwd == B.ALST_OK
+    _check(rs, f, dH, dW, name + " split", valid=(y != IGN))
+    assert rs.loss_bits == r.loss_bits and (rs.lse.view(np.uint32) == r.lse.view(np.uint32)).all()
+    print(f"{name}: loss {r.loss:.4f}  max|z| {np.abs(orc.logits(h[:64], W)).max():.0f}  dH err {eh:.2e}  dW err {ew:.2e}")
+    return f
+
+
+def test_rows_outside_the_exponent_window_are_redone_with_their_exact_maximum():
+    """The softmax of a row is first formed as exp(z) with no shift; rows whose sum leaves the
+    safe range of the fp32 / bf16 exponents are recomputed relative to their exact maximum.
+    Logits of +-170 (overflow), logits around -100 (underflow), and a mix where only some rows
+    of each tile take the second pass; 3 tiles, the last ragged."""
+    N, H, V, tile = 640, 256, 1500, 256
+    wl = synth.custom("redo", N, H, V, tile, ignore_frac=0.1, seed=41)
+    h, _, y = synth.make_inputs(wl)
+    # overflow: logits ~ N(0, 48^2), exp(z) overflows fp32 in every row
+    W_big = synth.normal_bf16(V, H, 3.0, 41, synth.STREAM_W)
+    f = _redo_case("overflow", h, W_big, y, tile)
+    assert np.abs(f["lse"]).max() > 100.0
+    # underflow: every logit near -110 +- 10 (hidden states positive, weights negative)
+    hf = np.abs(orc.bf16_bits_to_f64(h)) + 0.5
+    h_pos = synth.f32_to_bf16_bits(hf.astype(np.float32))
+    Wf = -np.abs(orc.bf16_bits_to_f64(synth.normal_bf16(V, H, 0.1, 42, synth.STREAM_W))) - 0.25
+    W_neg = synth.f32_to_bf16_bits(Wf.astype(np.float32))
+    f = _redo_case("underflow", h_pos, W_neg, y, tile)
+    assert f["lse"][y != IGN].max() < -60.0
+    # mixed: every third row scaled by 40 (its logits overflow), the rest ordinary
+    W_ord = synth.normal_bf16(V, H, 0.1, 43, synth.STREAM_W)
+    hm = orc.bf16_bits_to_f64(h).copy()
+    hm[::3] *= 40.0
+    h_mix = synth.f32_to_bf16_bits(hm.astype(np.float32))
+    f = _redo_case("mixed", h_mix, W_ord, y, tile)
+    big = np.abs(f["lse"]) > 90.0
+    assert big[::3][(y != IGN)[::3]].all() and not big[1::3].any()
+
+
 def test_mfma_rate_aid_reports_a_plausible_rate():
     """The benchmarking aid behind bench.py's `mfma_sustained`: a register-resident loop of the
     matrix instruction; its rate lies between a tenth of and just above the published 2.5 PFLOP/s."""
