@@ -535,7 +535,9 @@ struct DirectCoreT {
         const int KT = K / kBlockK;
         // One 4-byte DMA per wavefront and k-step into a landing area nobody reads: it only pulls
         // the line into L2.  `warm` (see warm_row) must be a valid row pointer in every lane.
-        constexpr bool warming = true;
+        // Not for two k-major operands (the weight-gradient products): measured there, the extra
+        // L2 lookups cost as much as the early misses save.
+        constexpr bool warming = !(XK && YK);
         unsigned char* const dump = smem + kStageBytes + w * 256;
         auto warm_step = [&](int kt) {
             // (with a Y that lacks k-rows of the last step, that step is not warmed: the lane's

@@ -437,6 +437,45 @@ def test_mfma_rate_aid_reports_a_plausible_rate():
         B.alst_debug_mfma_rate(1, 0)
 
 
+def test_calls_from_two_host_threads_on_their_own_workspaces_and_streams():
+    """The library keeps no state between calls (the one-time kernel setup is behind a lock, the
+    timers behind another): two host threads, each with its own workspace, outputs and stream, run
+    the fused pass concurrently several times and get the bits of a single-threaded call."""
+    import threading
+    cases = [synth.custom("thr_a", 900, 256, 1280, 256, ignore_frac=0.1, seed=51),
+             synth.custom("thr_b", 700, 128, 2100, 512, ignore_frac=0.2, seed=52)]
+    inputs = [synth.make_inputs(wl) for wl in cases]
+    refs = [G.run_fused(h, W, y, wl.tile) for wl, (h, W, y) in zip(cases, inputs)]
+    results, errors = [None, None], []
+    B.alst_profile_enable(True)            # the timers' span list is shared by the threads
+
+    def worker(k):
+        try:
+            torch.cuda.set_device(0)
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                for _ in range(5):
+                    r = G.run_fused(*inputs[k], cases[k].tile)
+                results[k] = r
+        except Exception as e:             # surfaced by the assert below
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    prof = B.alst_profile_read()
+    B.alst_profile_enable(False)
+    assert not errors, errors
+    for r, ref in zip(results, refs):
+        assert r.status == B.ALST_OK and r.loss_bits == ref.loss_bits
+        assert torch.equal(r.dH_t.view(torch.int16), ref.dH_t.view(torch.int16))
+        assert torch.equal(r.dW_t.view(torch.int16), ref.dW_t.view(torch.int16))
+    # every span of both threads was recorded: 5 calls x tiles of each case, one logits span per tile
+    assert prof["logits_gemm"][1] == 5 * (4 + 2)
+
+
 def test_hip_graph_replays_match_eager():
     """The entry points only enqueue kernels on the caller's stream (no allocation, no memset, no
     host synchronisation), so a call can be captured into a HIP graph.  Every replay, with eager
