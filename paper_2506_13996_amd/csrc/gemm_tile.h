@@ -421,9 +421,12 @@ struct DirectCoreT {
     // that is not a multiple of the block width); a k-major X or Y with rows_x / rows_y columns (a
     // multiple of 8) is read from its last 8 columns in place of those beyond (a hidden size that
     // is not a multiple of the block width).  What is read instead is finite data of the operand.
-    // MixedCore with YTAIL only: K_y (if >= 0 and < K) is the number of k-rows Y has when X is zero-padded
-    // along k beyond it (W in dH = dZ W for a vocabulary that is not whole k-steps): the k-rows of
-    // the last step that Y lacks are read from its last row, and meet zeros of X.  A k-major X is [K][ldx]
+    // With YTAIL (k-contiguous X only): K_y (if >= 0 and < K) is the k extent Y has when X is
+    // zero-padded along k beyond it.  MixedCore (W in dH = dZ W for a vocabulary that is not whole
+    // k-steps): the k-rows of the last step that Y lacks are read from its last row.  DirectCore
+    // without Y2 (the logits of a hidden size that is not whole k-steps, X being the library's own
+    // zero-padded copy of the hidden rows): the chunks of a row of Y beyond K_y are read from the
+    // row's last chunk (K_y a multiple of 8).  What is read instead meets zeros of X.  A k-major X is [K][ldx]
     // and the block takes its columns r0 .. r0 + 255; a k-major Y is [K][ldy], columns c0 .. + 255.
     // warm_stride = elements between the lane's warm-up line of one k-step and the next.
     template <bool GUARD, bool YTAIL = false>
@@ -470,18 +473,28 @@ struct DirectCoreT {
         }
         // elements from one k-step's tile to the next
         const int64_t xstep = XK ? ldx * kBlockK : kBlockK, ystep = YK ? ldy * kBlockK : kBlockK;
-        // MixedCore, Y shorter than the loop's K: the lane's sources in the last k-step, clamped
-        constexpr bool kTail = YTAIL && YK && !XK;
+        // Y shorter than the loop's K (X zero-padded along k beyond K_y): the lane's sources in the
+        // last k-step, clamped.  k-major Y (MixedCore): the k-rows Y lacks are read from its last
+        // row.  k-contiguous Y (DirectCore, no Y2): the 16-byte chunks beyond K_y of a row are read
+        // from the row's last chunk.  Either way finite data of Y meets zeros of X.
+        constexpr bool kTail = YTAIL && !XK;
         const int KT_ = K / kBlockK;
         const bool ytail = kTail && K_y >= 0 && K_y < K;
         const uint16_t* yg_tail[8];
         if (kTail) {
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                const int krow = (KT_ - 1) * kBlockK + w * 16 + q * 2 + (lane >> 5);
-                const int ch = (lane & 31) ^ (kswz(krow) << 2);
-                const int kr = ytail && krow >= K_y ? K_y - 1 : krow;
-                yg_tail[q] = Y + (int64_t)kr * ldy + (c0 + ch * 8 < rows_y ? c0 + ch * 8 : rows_y - 8);
+                if (YK) {
+                    const int krow = (KT_ - 1) * kBlockK + w * 16 + q * 2 + (lane >> 5);
+                    const int ch = (lane & 31) ^ (kswz(krow) << 2);
+                    const int kr = ytail && krow >= K_y ? K_y - 1 : krow;
+                    yg_tail[q] = Y + (int64_t)kr * ldy + (c0 + ch * 8 < rows_y ? c0 + ch * 8 : rows_y - 8);
+                } else {
+                    const int row = (w * 8 + q) * 8 + lr;
+                    const int k = (KT_ - 1) * kBlockK + (pc ^ swz(row)) * 8;
+                    const int yrow = c0 + row < rows_y ? c0 + row : rows_y - 1;
+                    yg_tail[q] = Y + (int64_t)yrow * ldy + (ytail && k >= K_y ? K_y - 8 : k);
+                }
             }
         }
         auto ysrc = [&](int q, int kt) -> const uint16_t* {

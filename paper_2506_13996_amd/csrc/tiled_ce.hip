@@ -90,6 +90,7 @@ constexpr int kScanThreads = 1024;   // rows per block of the compaction kernels
 
 struct Layout {
     int64_t Tp, Vp, ng;    // padded tile rows, padded vocabulary, 128-column groups
+    int64_t Hk;            // row pitch of the dense hidden copy: H rounded up to whole k-steps
     int g;                 // tiles per dW group
     int64_t Kg;            // dense rows a group can hold: g * Tp
     int dh_PR, dh_PC;      // dHidden: patch shape of the block -> tile mapping
@@ -136,6 +137,7 @@ static Layout make_layout(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_
     L.Tp = (T + 255) / 256 * 256;
     L.Vp = (V + 255) / 256 * 256;
     L.ng = L.Vp / 128;
+    L.Hk = (H + kBlockK - 1) / kBlockK * kBlockK;
     L.g = dw_group_size(L.Tp, flags);
     L.Kg = (int64_t)L.g * L.Tp;
     const bool fwd_only = flags & ALST_FLAG_FORWARD_ONLY;     // no dZ rows, partial products, dW sums
@@ -159,7 +161,7 @@ static Layout make_layout(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_
     L.ps = take((size_t)L.ng * L.Tp * 4);
     // hc and stash hold the dense rows of the whole group, each tile at its k offset: they are
     // the two operands of the group's dW product as they are (k = dense row, the slow index)
-    L.hc = take((size_t)L.Kg * H * 2);
+    L.hc = take((size_t)L.Kg * L.Hk * 2);
     L.stash = take(fwd_only ? 0 : (size_t)L.Kg * L.Vp * 2);
     {   // dHidden: the launch and the partial products are sized for the worst tile
         const PatchGrid pg = choose_patches((int)(L.Tp / kBlockR), (int)((H + kBlockC - 1) / kBlockC));
@@ -337,24 +339,26 @@ __global__ void tile_info_kernel(const Header* __restrict__ h, int64_t t, int64_
 }
 
 // Block b: dense row b of the tile.  Copies the hidden row of token idx_t[b] into the dense
-// matrix Hc and its label into yc; rows Tc <= b < Trc are zero padding.  Hc holds the whole dW
-// group and the tile's rows start at its k offset.  Also sets the row's softmax reference for the
+// matrix Hc (row pitch Hk = H rounded up to whole k-steps, zeros behind the H elements: the logits
+// GEMM contracts over Hk) and its label into yc; rows Tc <= b < Trc are zero padding.  Hc holds
+// the whole dW group and the tile's rows start at its k offset.  Also sets the row's softmax reference for the
 // first logits pass (0; backward from a saved lse: that lse, so that e is the probability itself)
 // and marks the row as taking part in that pass.
 __global__ __launch_bounds__(256) void gather_rows_kernel(
-    const uint16_t* __restrict__ hidden, const int32_t* __restrict__ labels, int H,
+    const uint16_t* __restrict__ hidden, const int32_t* __restrict__ labels, int H, int Hk,
     const int32_t* __restrict__ idx_t, const TileInfo* __restrict__ info,
     const float* __restrict__ lse_in, uint16_t* __restrict__ Hc, int32_t* __restrict__ yc,
     float* __restrict__ ref, int32_t* __restrict__ rowstate) {
     const int b = blockIdx.x;
-    const int chunks = H / 8;
+    const int chunks = Hk / 8, src_chunks = H / 8;      // the row pitch Hk is H in whole k-steps
     if (b >= info->Trc) return;
-    Hc += (int64_t)info->kofs * H;
-    u32x4_t* dst = reinterpret_cast<u32x4_t*>(Hc + (int64_t)b * H);
+    Hc += (int64_t)info->kofs * Hk;
+    u32x4_t* dst = reinterpret_cast<u32x4_t*>(Hc + (int64_t)b * Hk);
     if (b < info->Tc) {
         const int64_t row = idx_t[b];
         const u32x4_t* src = reinterpret_cast<const u32x4_t*>(hidden + row * H);
-        for (int c = threadIdx.x; c < chunks; c += 256) dst[c] = src[c];
+        const u32x4_t zero4 = {0u, 0u, 0u, 0u};
+        for (int c = threadIdx.x; c < chunks; c += 256) dst[c] = c < src_chunks ? src[c] : zero4;
         if (threadIdx.x == 0) {
             yc[b] = labels[row];
             ref[b] = lse_in ? lse_in[row] : 0.f;
@@ -393,9 +397,9 @@ struct RowFinishParams {
     int32_t* rowstate;       // [Tp]      1: the row takes part in the next logits pass, 0: finished
     float* lse_t;            // [N]       by row of the sequence
     float* loss_rows_t;      // [N]
-    uint16_t* hc;            // [Kg, H]   dense hidden rows of the group (scaled in place, MODE_FUSED)
+    uint16_t* hc;            // [Kg, Hk]  dense hidden rows of the group (scaled in place, MODE_FUSED)
     uint16_t* stash;         // [Kg, Vp]
-    int Tp, ng, H, Vp;
+    int Tp, ng, H, Hk, Vp;
 };
 
 // Per dense row of the tile, after a logits pass: S = sum of the per-group sums of e (fixed order,
@@ -486,7 +490,7 @@ __global__ __launch_bounds__(kCombineRows * kCombineLanes) void row_finish_kerne
         p.rowstate[i] = 0;
     }
     if (MODE == MODE_FUSED) {
-        uint16_t* row = p.hc + (int64_t)(kofs + i) * p.H;
+        uint16_t* row = p.hc + (int64_t)(kofs + i) * p.Hk;
         for (int c = y; c < p.H / 8; c += kCombineLanes) {
             bf16x8_t v = *reinterpret_cast<const bf16x8_t*>(row + c * 8);
 #pragma unroll
@@ -562,7 +566,7 @@ __global__ void shift_labels_kernel(const int32_t* __restrict__ labels, int32_t*
 // the three block GEMMs
 // ---------------------------------------------------------------------------------------------
 struct LogitsParams {
-    const uint16_t* hidden_t;   // [Kg, H]      dense (valid) rows of the dW group; the tile's rows
+    const uint16_t* hidden_t;   // [Kg, Hk]     dense (valid) rows of the dW group; the tile's rows
                                 //              start at its k offset and are zero padded to Trc
     const uint16_t* W;          // [V, H]
     const int32_t* labels_t;    // [Tp]         labels of the dense rows
@@ -573,15 +577,17 @@ struct LogitsParams {
     float* ps;                  // [ng, Tp]
     float* zlabel;              // [Tp]
     uint16_t* stash;            // [Kg, Vp]     MODE_FUSED / MODE_BWD; rows as in hidden_t
-    int Tp, H, V, Vp;           // Tp = row stride of the per-tile arrays
+    int Tp, H, Hk, V, Vp;       // Tp = row stride of the per-tile arrays
     int PR, PC;                 // patch shape of the block -> tile mapping
 };
 
 // r = token row of the tile (MFMA lane dimension), c = vocabulary id (register dimension).
+// KTAIL: the hidden size is not whole k-steps; the contraction runs over Hk, the dense hidden rows
+// are zero beyond H and the chunks of W's rows beyond H are read from each row's last chunk.
 // REDO: the second pass over a tile, for the rows whose first-pass sums left the safe range; its
 // workgroups leave at once unless row_finish flagged the tile, and rows that are not marked keep
 // what the first pass wrote.
-template <class Core, bool GUARD, int MODE, bool REDO>
+template <class Core, bool KTAIL, int MODE, bool REDO>
 __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsParams p) {
     constexpr int kMT = Core::kMT, kNT = Core::kNT;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -606,11 +612,10 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
             for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
 
     const int kofs = p.info->kofs;
-    const uint16_t* const hidden_t = p.hidden_t + (int64_t)kofs * p.H;
-    const uint16_t* warm = Core::kCanGuard ? nullptr
-                                           : warm_row(p.PR, p.PC, hidden_t, p.H, r0, tr, p.W, p.H, c0, tc,
-                                                      nullptr, p.V);
-    Core::template gemm<GUARD>(hidden_t, p.H, Trc, p.W, p.H, p.V, p.H, r0, c0, smem, acc, warm);
+    const uint16_t* const hidden_t = p.hidden_t + (int64_t)kofs * p.Hk;
+    const uint16_t* warm = warm_row(p.PR, p.PC, hidden_t, p.Hk, r0, tr, p.W, p.H, c0, tc, nullptr, p.V);
+    Core::template gemm<false, KTAIL>(hidden_t, p.Hk, Trc, p.W, p.H, p.V, p.Hk, r0, c0, smem, acc, warm,
+                                      kBlockK, nullptr, p.H);
 
     const typename Core::Lane lp;
 #pragma unroll
@@ -826,11 +831,11 @@ __global__ __launch_bounds__(256) void dhidden_reduce_kernel(const float* __rest
 }
 
 struct DWParams {
-    const uint16_t* hg;      // [Kg, H]      dense hidden rows of the group's tiles
+    const uint16_t* hg;      // [Kg, Hk]     dense hidden rows of the group's tiles (H of the Hk columns used)
     const uint16_t* dzg;     // [Kg, Vp]     their dZ rows
     float* acc;              // [V, H]
     const TileInfo* info;    // of the group's last tile: k extent = kofs + Tkc
-    int H, V, Vp;
+    int H, Hk, V, Vp;
     int first;               // first group: store instead of add
     int PR, PC;              // patch shape of the block -> tile mapping
 };
@@ -865,9 +870,9 @@ __global__ __launch_bounds__(Core::kThreads) void dw_kernel(const DWParams p) {
     if (Tkc > 0) {
         int64_t step = 0;
         const uint16_t* warm = Core::kCanGuard ? nullptr
-                                               : warm_line_kmajor(p.PR, p.PC, p.hg, p.H, r0, tr, p.dzg,
+                                               : warm_line_kmajor(p.PR, p.PC, p.hg, p.Hk, r0, tr, p.dzg,
                                                                   p.Vp, c0, tc, step, p.H, p.Vp);
-        Core::template gemm<GUARD>(p.hg, p.H, p.H, p.dzg, p.Vp, p.Vp, Tkc, r0, c0, smem, acc, warm, step);
+        Core::template gemm<GUARD>(p.hg, p.Hk, p.H, p.dzg, p.Vp, p.Vp, Tkc, r0, c0, smem, acc, warm, step);
     }
 
     accumulate_block_f32<Core, GUARD>(acc, p.acc, p.H, r0, c0, p.H, p.V, p.first != 0);
@@ -880,15 +885,15 @@ static int prepare_kernels_on_current_device() {
     int rc = ALST_OK;
     auto acc = [&](int r) { if (r != ALST_OK) rc = r; };
     acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_FWD, false>));
-    acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_FWD, false>));
+    acc(allow_big_lds(logits_kernel<DirectCore, true, MODE_FWD, false>));
     acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_FUSED, false>));
-    acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_FUSED, false>));
+    acc(allow_big_lds(logits_kernel<DirectCore, true, MODE_FUSED, false>));
     acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_BWD, false>));
-    acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_BWD, false>));
+    acc(allow_big_lds(logits_kernel<DirectCore, true, MODE_BWD, false>));
     acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_FWD, true>));
-    acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_FWD, true>));
+    acc(allow_big_lds(logits_kernel<DirectCore, true, MODE_FWD, true>));
     acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_FUSED, true>));
-    acc(allow_big_lds(logits_kernel<StagedCore, true, MODE_FUSED, true>));
+    acc(allow_big_lds(logits_kernel<DirectCore, true, MODE_FUSED, true>));
     acc(allow_big_lds(dhidden_kernel<MixedCore, false, false>));
     acc(allow_big_lds(dhidden_kernel<MixedCore, false, true>));
     acc(allow_big_lds(dw_kernel<KMajorCore, false>));
@@ -955,13 +960,13 @@ static int validate(const Problem& P, size_t workspace_bytes, bool need_fwd_out,
 // Grids are sized for Tr (the tile's rows rounded up to the block height); the kernels read the
 // number of rows that take part from the device and surplus blocks leave at once.
 template <int MODE, bool REDO>
-static int launch_logits(LogitsParams lp, int Tr, bool guard, hipStream_t s) {
+static int launch_logits(LogitsParams lp, int Tr, bool ktail, hipStream_t s) {
     const PatchGrid pg = choose_patches(Tr / kBlockR, lp.Vp / kBlockC);
     lp.PR = pg.PR; lp.PC = pg.PC;
     const int grid = grid_for_patches(pg.patches());
-    if (guard)
-        hipLaunchKernelGGL((logits_kernel<StagedCore, true, MODE, REDO>), dim3(grid),
-                           dim3(StagedCore::kThreads), kLdsBytes, s, lp);
+    if (ktail)
+        hipLaunchKernelGGL((logits_kernel<DirectCore, true, MODE, REDO>), dim3(grid),
+                           dim3(DirectCore::kThreads), kLdsBytes, s, lp);
     else
         hipLaunchKernelGGL((logits_kernel<DirectCore, false, MODE, REDO>), dim3(grid),
                            dim3(DirectCore::kThreads), kLdsBytes, s, lp);
@@ -971,13 +976,13 @@ static int launch_logits(LogitsParams lp, int Tr, bool guard, hipStream_t s) {
 // The logits pass of a tile and the per-row work behind it; for the modes that form the softmax
 // sums, followed by the conditional second pass (see row_finish_kernel).
 template <int MODE>
-static int logits_and_finish(const LogitsParams& lp, const RowFinishParams& fp, int Tr, bool guard,
+static int logits_and_finish(const LogitsParams& lp, const RowFinishParams& fp, int Tr, bool ktail,
                              hipStream_t s) {
     const dim3 fgrid(Tr / kCombineRows), fblock(kCombineRows, kCombineLanes);
     int rc;
     {
         ProfScope ps_(PROF_LOGITS, s);
-        rc = launch_logits<MODE, false>(lp, Tr, guard, s);
+        rc = launch_logits<MODE, false>(lp, Tr, ktail, s);
     }
     if (rc != ALST_OK) return rc;
     {
@@ -989,7 +994,7 @@ static int logits_and_finish(const LogitsParams& lp, const RowFinishParams& fp, 
     constexpr int M2 = MODE == MODE_BWD ? MODE_FUSED : MODE;      // (MODE_BWD never gets here)
     // (timed with the small kernels: in all but pathological inputs both launches are empty)
     ProfScope small_(PROF_OTHER, s);
-    rc = launch_logits<M2, true>(lp, Tr, guard, s);
+    rc = launch_logits<M2, true>(lp, Tr, ktail, s);
     if (rc != ALST_OK) return rc;
     hipLaunchKernelGGL((row_finish_kernel<M2, true>), fgrid, fblock, 0, s, fp);
     ALST_HIP(hipGetLastError());
@@ -1039,11 +1044,13 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
     }
     ALST_HIP(hipGetLastError());
 
-    // unguarded kernels need every extent block-aligned; the row extent always is (dense rows are
-    // zero padded to a multiple of the block height)
-    // (a vocabulary that ends inside a column block is handled by the unguarded logits kernel:
-    // it reads the last row of W in place of the missing ones and masks those columns)
-    const bool guard_logits = (H % kBlockK) != 0;
+    // The GEMM cores without bounds checks serve every shape.  The row extent of a tile is always
+    // block-aligned (dense rows are zero padded to a multiple of the block height).
+    // (a vocabulary that ends inside a column block: the logits kernel reads the last row of W
+    // in place of the missing ones and masks those columns; a hidden size that is not whole
+    // k-steps: the dense hidden rows are zero padded to Hk and the chunks of W's rows beyond H
+    // are read from each row's last chunk)
+    const bool ktail_logits = (H % kBlockK) != 0;
     // (a hidden size that ends inside a block is handled by the unguarded dHidden and dW kernels:
     // the missing columns of W and of the dense hidden rows are read from the last ones and the
     // results discarded; a vocabulary that is not whole k-steps by the unguarded dHidden kernel:
@@ -1065,7 +1072,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
                                slot ? info - 1 : nullptr, P.H, P.V, L.Tp, L.dh_patches, L.dh_part_rows,
                                L.dh_PR, L.dh_PC);
             hipLaunchKernelGGL(gather_rows_kernel, dim3(Tr), dim3(256), 0, s, P.hidden, P.labels, H,
-                               idx_t, info, do_fwd ? nullptr : P.lse_in, hc, yc, ref, rowstate);
+                               (int)L.Hk, idx_t, info, do_fwd ? nullptr : P.lse_in, hc, yc, ref, rowstate);
             ALST_HIP(hipGetLastError());
         }
 
@@ -1076,15 +1083,15 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
         lp.info = info;
         lp.ref = ref; lp.rowstate = rowstate;
         lp.pm = pm; lp.ps = ps; lp.zlabel = zlabel; lp.stash = stash;
-        lp.Tp = Tp; lp.H = H; lp.V = V; lp.Vp = Vp;
+        lp.Tp = Tp; lp.H = H; lp.Hk = (int)L.Hk; lp.V = V; lp.Vp = Vp;
         RowFinishParams fp;
         fp.pm = pm; fp.ps = ps; fp.zlabel = zlabel; fp.yc = yc; fp.idx = idx_t; fp.info = info;
         fp.ref = ref; fp.frow = frow; fp.rowstate = rowstate;
         fp.lse_t = lse_buf; fp.loss_rows_t = loss_rows; fp.hc = hc; fp.stash = stash;
-        fp.Tp = Tp; fp.ng = ng; fp.H = H; fp.Vp = Vp;
-        if (do_fwd && do_bwd) rc = logits_and_finish<MODE_FUSED>(lp, fp, Tr, guard_logits, s);
-        else if (do_fwd) rc = logits_and_finish<MODE_FWD>(lp, fp, Tr, guard_logits, s);
-        else rc = logits_and_finish<MODE_BWD>(lp, fp, Tr, guard_logits, s);
+        fp.Tp = Tp; fp.ng = ng; fp.H = H; fp.Hk = (int)L.Hk; fp.Vp = Vp;
+        if (do_fwd && do_bwd) rc = logits_and_finish<MODE_FUSED>(lp, fp, Tr, ktail_logits, s);
+        else if (do_fwd) rc = logits_and_finish<MODE_FWD>(lp, fp, Tr, ktail_logits, s);
+        else rc = logits_and_finish<MODE_BWD>(lp, fp, Tr, ktail_logits, s);
         if (rc != ALST_OK) return rc;
         if (!do_bwd) continue;
 
@@ -1112,7 +1119,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
         if (slot == L.g - 1 || t == ntiles - 1) {           // the group is complete
             DWParams wp;
             wp.hg = hc; wp.dzg = stash; wp.acc = acc; wp.info = info;
-            wp.H = H; wp.V = V; wp.Vp = Vp; wp.first = (t < L.g);
+            wp.H = H; wp.Hk = (int)L.Hk; wp.V = V; wp.Vp = Vp; wp.first = (t < L.g);
             const PatchGrid pg = choose_patches((H + kBlockR - 1) / kBlockR, Vp / kBlockC);
             wp.PR = pg.PR; wp.PC = pg.PC;
             const int grid = grid_for_patches(pg.patches());

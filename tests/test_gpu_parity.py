@@ -68,6 +68,11 @@ CASES = [
     ("ragged_v_whole_ksteps", 600, 256, 1088, 256, 0.1),
     ("ragged_v", 600, 256, 1000, 256, 0.1),
     ("ragged_v_below_one_block", 300, 256, 72, 128, 0.1),
+    # hidden sizes that are not whole k-steps of 64 (below one step, just above one, odd multiples
+    # of 8): the dense hidden rows are zero padded, W's rows are read clamped in the last k-step
+    ("h_below_one_kstep", 300, 8, 500, 128, 0.1),
+    ("h_72", 520, 72, 700, 256, 0.1),
+    ("h_1000", 300, 1000, 520, 256, 0.1),
 ]
 
 
