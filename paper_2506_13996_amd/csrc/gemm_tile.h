@@ -4,8 +4,13 @@
 //
 // One workgroup owns a 256 (r) x 256 (c) block of D and walks k in steps of 64 through two LDS
 // stages.  The c index is the MFMA row (register) dimension and r the MFMA column (lane)
-// dimension (v_mfma_f32_32x32x16_bf16), so a lane holds, for one r, runs of 4 consecutive c:
-// reductions over c stay mostly inside a lane and stores along c are vector stores.
+// dimension, so a lane holds, for one r, runs of 4 consecutive c: reductions over c stay mostly
+// inside a lane and stores along c are vector stores.  The DMA cores multiply with
+// v_mfma_f32_16x16x32_bf16 (accumulator tiles of 16 x 16, 4 registers per lane), the
+// register-staged cores with v_mfma_f32_32x32x16_bf16 (32 x 32, 16 registers): on random operands
+// the 16 x 16 form draws less power per flop (a register-resident loop sustains 1.89 against
+// 1.80 PFLOP/s) and the same block GEMM runs 5.5 - 7.5 % faster with it.  The kernels' epilogues
+// are written against the layout description every core carries (Lane, kTile, kRuns, kGroups).
 //
 // An operand is either k-contiguous (a matrix [rows][k]) or k-major (a matrix [k][columns], the
 // block taking 256 of its columns).  Three combinations occur:
@@ -19,12 +24,12 @@
 // Two families of cores with the same accumulator interface, each in the three layouts:
 //   DirectCore, MixedCore, KMajorCore
 //               4 wavefronts (one per SIMD), 128 x 128 per wavefront, operands DMA'd straight from
-//               global memory into LDS (global_load_lds_dwordx4), MFMA operands of the four
+//               global memory into LDS (global_load_lds_dwordx4), MFMA operands of the two
 //               k-slices of a step held in registers, one barrier in the middle of a k-step so
 //               that the next stage's first operands are read while the second half is
 //               multiplied.  A k-major tile lands in LDS as 64 k-rows and the MFMA operands are
 //               formed by the transposing LDS read (ds_read_b64_tr_b16).  No bounds checks in the
-//               DMA path: every extent block-aligned (see gemm for the one exception).
+//               DMA path: every extent block-aligned (see gemm for the exceptions).
 //   StagedCore, StagedMixedCore, StagedKMajorCore
 //               8 wavefronts, 64 x 128 per wavefront, operands staged through registers with
 //               zero fill outside the matrices: the fallback for ragged shapes.
@@ -102,7 +107,8 @@ __host__ __device__ __forceinline__ bool tile_in_patch(const PatchGrid& g, int P
 // Gated pair of Y operands: with Y2 given, the 256 Y rows of the block at c0 are four runs of 64
 // rows, run q = rows c0 / 2 + (q / 2) * 64 .. + 63 of Y (q even) or of Y2 (q odd): the 128 rows of
 // a wavefront are 64 rows of Y followed by the same 64 rows of Y2, so a lane that holds the
-// product with row j of Y in accumulator tile mt holds the one with row j of Y2 in tile mt + 2.
+// product with row j of Y in accumulator tile mt holds the one with row j of Y2 in the tile 64 rows on
+// (mt + 2 for 32-row tiles, mt + 4 for 16-row tiles).
 // br = row inside the block; valid = the source row exists (the pointer is then usable anyway).
 __device__ __forceinline__ const uint16_t* paired_row(const uint16_t* Y, const uint16_t* Y2,
                                                       int64_t ldy, int c0, int br, int rows_y,
@@ -212,6 +218,30 @@ __device__ __forceinline__ int kmajor_lane_offset(int lane, int gran) {
     return (8 * half + (sl >> 2)) * 512 + ((gran ^ f) * 64) + b1 * 32 + (sl & 3) * 8;
 }
 
+// Global -> LDS DMA: each lane's BYTES (16 or 4) land at lds + lane * BYTES; `lds` must be uniform
+// over the wavefront.
+template <int BYTES>
+__device__ __forceinline__ void dma_to_lds(const void* g, unsigned char* lds) {
+    typedef const __attribute__((address_space(1))) void* gptr_t;
+    typedef __attribute__((address_space(3))) void* lptr_t;
+    static_assert(BYTES == 16 || BYTES == 4, "one or four dwords per lane");
+    if (BYTES == 16) __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)lds, 16, 0, 0);
+    else __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)lds, 4, 0, 0);
+}
+
+// Combines a value over the lane groups of a wavefront that hold the same r (lanes l, l ^ 16, l ^ 32,
+// l ^ 48 for 16 x 16 tiles; l, l ^ 32 for 32 x 32 tiles): every lane gets the result.
+template <int GROUPS>
+__device__ __forceinline__ float groups_max(float v) {
+    if (GROUPS == 4) v = fmaxf(v, __shfl_xor(v, 16));
+    return fmaxf(v, __shfl_xor(v, 32));
+}
+template <int GROUPS>
+__device__ __forceinline__ float groups_sum(float v) {
+    if (GROUPS == 4) v += __shfl_xor(v, 16);
+    return v + __shfl_xor(v, 32);
+}
+
 // XK / YK: that operand is k-major.
 template <bool XK, bool YK>
 struct StagedCoreT {
@@ -219,27 +249,31 @@ struct StagedCoreT {
     static constexpr int kMT = 4;     // 32-wide c tiles per wavefront
     static constexpr int kNT = 2;     // 32-wide r tiles per wavefront
     static constexpr bool kCanGuard = true;
+    // accumulator layout: tiles of kTile x kTile; a lane holds kRuns runs of 4 consecutive c per
+    // tile; kGroups lane groups hold the same r
+    typedef f32x16_t acc_t;
+    static constexpr int kTile = 32, kRuns = 4, kGroups = 2;
 
     // Where the calling lane's accumulators sit inside the block.
     struct Lane {
-        int lane, half, l31, wr, wc;
+        int lane, grp, lrow, wr, wc;
         __device__ __forceinline__ Lane() {
             const int tid = threadIdx.x;
             lane = tid & 63;
-            half = lane >> 5;
-            l31 = lane & 31;
+            grp = lane >> 5;
+            lrow = lane & 31;
             const int wave = tid >> 6;
             wr = wave & 3;
             wc = wave >> 2;
         }
         // row of X (r index inside the block) of accumulator tile nt
-        __device__ __forceinline__ int r(int nt) const { return wr * 64 + nt * 32 + l31; }
+        __device__ __forceinline__ int r(int nt) const { return wr * 64 + nt * 32 + lrow; }
         // first of the 32 rows of accumulator tile nt that this wavefront holds
         __device__ __forceinline__ int rbase(int nt) const { return wr * 64 + nt * 32; }
-        // first of the 4 consecutive c held in registers 4q..4q+3 of accumulator tile mt
-        __device__ __forceinline__ int c(int mt, int q) const {
-            return wc * kGroupC + mt * 32 + q * 8 + half * 4;
-        }
+        // first of the 4 consecutive c held in registers 4q..4q+3 of accumulator tile mt: inside
+        // the wavefront's 128 columns (cw) and inside the block (c)
+        __device__ __forceinline__ int cw(int mt, int q) const { return mt * 32 + q * 8 + grp * 4; }
+        __device__ __forceinline__ int c(int mt, int q) const { return wc * kGroupC + cw(mt, q); }
     };
 
     // acc[mt][nt] += X-block(r0) * Y-block(c0)^T over all of K.
@@ -301,13 +335,13 @@ struct StagedCoreT {
                              : (yrow * 8 + (ych ^ (yrow & 7))) * 16;
         int rofs[4], xofs[kNT], yofs[kMT];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) rofs[s] = ((2 * s + lp.half) ^ (lp.lane & 7)) * 16;
+        for (int s = 0; s < 4; ++s) rofs[s] = ((2 * s + lp.grp) ^ (lp.lane & 7)) * 16;
 #pragma unroll
         for (int nt = 0; nt < kNT; ++nt) xofs[nt] = kmajor_lane_offset(lp.lane, lp.wr * kNT + nt);
 #pragma unroll
         for (int mt = 0; mt < kMT; ++mt) yofs[mt] = kmajor_lane_offset(lp.lane, lp.wc * kMT + mt);
-        const int xbase = (lp.wr * 64 + lp.l31) * 128;
-        const int ybase = (lp.wc * kGroupC + lp.l31) * 128;
+        const int xbase = (lp.wr * 64 + lp.lrow) * 128;
+        const int ybase = (lp.wc * kGroupC + lp.lrow) * 128;
 
         unsigned char* const Xs = smem;
         unsigned char* const Ys = smem + 2 * kTileBytes;
@@ -382,32 +416,37 @@ typedef StagedCoreT<true, true> StagedKMajorCore;
 typedef StagedCoreT<false, true> StagedMixedCore;
 
 // ---------------------------------------------------------------------------------------------
-// DirectCore: 4 wavefronts, global -> LDS DMA, aligned shapes only
+// KMajorDirectT: the DMA core for a k-major Y (and, with XK, a k-major X): v_mfma_f32_32x32x16_bf16
 // ---------------------------------------------------------------------------------------------
-// XK / YK: that operand is k-major.
-template <bool XK, bool YK>
-struct DirectCoreT {
+// Same pipeline as DirectCore below on 32 x 32 accumulator tiles.  Measured on the dHidden and dW
+// GEMMs the 16 x 16 x 32 form gains nothing over this one when operands come through the
+// transposing reads, and its register allocation breaks down for two k-major operands.
+// XK: X is k-major too.
+template <bool XK>
+struct KMajorDirectT {
+    static constexpr bool YK = true;
     static constexpr int kThreads = 256;
-    static constexpr int kMT = 4;
-    static constexpr int kNT = 4;
+    static constexpr int kMT = 4;     // 32-wide c tiles per wavefront
+    static constexpr int kNT = 4;     // 32-wide r tiles per wavefront
     static constexpr bool kCanGuard = false;
+    typedef f32x16_t acc_t;
+    static constexpr int kTile = 32, kRuns = 4, kGroups = 2;
 
     struct Lane {
-        int lane, half, l31, wr, wc;
+        int lane, grp, lrow, wr, wc;
         __device__ __forceinline__ Lane() {
             const int tid = threadIdx.x;
             lane = tid & 63;
-            half = lane >> 5;
-            l31 = lane & 31;
+            grp = lane >> 5;
+            lrow = lane & 31;
             const int wave = tid >> 6;
             wr = wave & 1;
             wc = wave >> 1;
         }
-        __device__ __forceinline__ int r(int nt) const { return wr * 128 + nt * 32 + l31; }
+        __device__ __forceinline__ int r(int nt) const { return wr * 128 + nt * 32 + lrow; }
         __device__ __forceinline__ int rbase(int nt) const { return wr * 128 + nt * 32; }
-        __device__ __forceinline__ int c(int mt, int q) const {
-            return wc * kGroupC + mt * 32 + q * 8 + half * 4;
-        }
+        __device__ __forceinline__ int cw(int mt, int q) const { return mt * 32 + q * 8 + grp * 4; }
+        __device__ __forceinline__ int c(int mt, int q) const { return wc * kGroupC + cw(mt, q); }
     };
 
     // LDS row = 128 bytes = 8 chunks of 16 bytes; chunk kc of row `row` lives at slot
@@ -415,30 +454,23 @@ struct DirectCoreT {
     static __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
     // Requires K % 64 == 0, K >= 64, 16-byte aligned rows, and a k-contiguous X with r0 + 256 <= its
-    // rows.  GUARD must be false.  The other operands may end inside the block, and the caller
-    // discards the accumulator rows / columns that lie outside: a k-contiguous Y (without Y2) is
-    // read from its row rows_y - 1 in place of the rows from rows_y on (the logits of a vocabulary
-    // that is not a multiple of the block width); a k-major X or Y with rows_x / rows_y columns (a
-    // multiple of 8) is read from its last 8 columns in place of those beyond (a hidden size that
-    // is not a multiple of the block width).  What is read instead is finite data of the operand.
+    // rows.  GUARD must be false.  Y is [K][ldy] and the block takes its columns c0 .. c0 + 255; a
+    // k-major X is [K][ldx], columns r0 .. r0 + 255.  A k-major operand with rows_x / rows_y
+    // columns (a multiple of 8) may end inside the block: it is read from its last 8 columns in
+    // place of those beyond (a hidden size that is not a multiple of the block width), finite data
+    // of the operand, and the caller discards the accumulator rows / columns that lie outside.
     // With YTAIL (k-contiguous X only): K_y (if >= 0 and < K) is the k extent Y has when X is
-    // zero-padded along k beyond it.  MixedCore (W in dH = dZ W for a vocabulary that is not whole
-    // k-steps): the k-rows of the last step that Y lacks are read from its last row.  DirectCore
-    // without Y2 (the logits of a hidden size that is not whole k-steps, X being the library's own
-    // zero-padded copy of the hidden rows): the chunks of a row of Y beyond K_y are read from the
-    // row's last chunk (K_y a multiple of 8).  What is read instead meets zeros of X.  A k-major X is [K][ldx]
-    // and the block takes its columns r0 .. r0 + 255; a k-major Y is [K][ldy], columns c0 .. + 255.
+    // zero-padded along k beyond it (W in dH = dZ W for a vocabulary that is not whole k-steps):
+    // the k-rows of the last step that Y lacks are read from its last row and meet zeros of X.
     // warm_stride = elements between the lane's warm-up line of one k-step and the next.
     template <bool GUARD, bool YTAIL = false>
     static __device__ __forceinline__ void gemm(const uint16_t* __restrict__ X, int64_t ldx,
                                                 int rows_x, const uint16_t* __restrict__ Y,
                                                 int64_t ldy, int rows_y, int K, int r0, int c0,
-                                                unsigned char* smem, f32x16_t (&acc)[kMT][kNT],
+                                                unsigned char* smem, acc_t (&acc)[kMT][kNT],
                                                 const uint16_t* warm, int64_t warm_stride = kBlockK,
-                                                const uint16_t* Y2 = nullptr, int K_y = -1) {
-        static_assert(!GUARD, "DirectCore has no bounds checks");
-        typedef const __attribute__((address_space(1))) void* gptr_t;
-        typedef __attribute__((address_space(3))) void* lptr_t;
+                                                const uint16_t* /*Y2*/ = nullptr, int K_y = -1) {
+        static_assert(!GUARD, "the DMA cores have no bounds checks");
         const int tid = threadIdx.x, lane = tid & 63;
         const int w = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave id, provably uniform
         const int wr = w & 1, wc = w >> 1;
@@ -461,22 +493,12 @@ struct DirectCoreT {
             // (the clamps: see the comment of this function)
             if (XK) xg[q] = X + (int64_t)krow * ldx + (r0 + ch * 8 < rows_x ? r0 + ch * 8 : rows_x - 8);
             else xg[q] = X + (int64_t)(r0 + row) * ldx + kc * 8;
-            if (YK) {
-                yg[q] = Y + (int64_t)krow * ldy + (c0 + ch * 8 < rows_y ? c0 + ch * 8 : rows_y - 8);
-            } else if (Y2) {                        // gated pair (k-contiguous only)
-                bool valid;
-                yg[q] = paired_row(Y, Y2, ldy, c0, row, 0x7fffffff, valid) + kc * 8;
-            } else {
-                const int yrow = c0 + row < rows_y ? c0 + row : rows_y - 1;
-                yg[q] = Y + (int64_t)yrow * ldy + kc * 8;
-            }
+            yg[q] = Y + (int64_t)krow * ldy + (c0 + ch * 8 < rows_y ? c0 + ch * 8 : rows_y - 8);
         }
         // elements from one k-step's tile to the next
-        const int64_t xstep = XK ? ldx * kBlockK : kBlockK, ystep = YK ? ldy * kBlockK : kBlockK;
+        const int64_t xstep = XK ? ldx * kBlockK : kBlockK, ystep = ldy * kBlockK;
         // Y shorter than the loop's K (X zero-padded along k beyond K_y): the lane's sources in the
-        // last k-step, clamped.  k-major Y (MixedCore): the k-rows Y lacks are read from its last
-        // row.  k-contiguous Y (DirectCore, no Y2): the 16-byte chunks beyond K_y of a row are read
-        // from the row's last chunk.  Either way finite data of Y meets zeros of X.
+        // last k-step, the k-rows Y lacks read from its last row.
         constexpr bool kTail = YTAIL && !XK;
         const int KT_ = K / kBlockK;
         const bool ytail = kTail && K_y >= 0 && K_y < K;
@@ -484,17 +506,10 @@ struct DirectCoreT {
         if (kTail) {
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                if (YK) {
-                    const int krow = (KT_ - 1) * kBlockK + w * 16 + q * 2 + (lane >> 5);
-                    const int ch = (lane & 31) ^ (kswz(krow) << 2);
-                    const int kr = ytail && krow >= K_y ? K_y - 1 : krow;
-                    yg_tail[q] = Y + (int64_t)kr * ldy + (c0 + ch * 8 < rows_y ? c0 + ch * 8 : rows_y - 8);
-                } else {
-                    const int row = (w * 8 + q) * 8 + lr;
-                    const int k = (KT_ - 1) * kBlockK + (pc ^ swz(row)) * 8;
-                    const int yrow = c0 + row < rows_y ? c0 + row : rows_y - 1;
-                    yg_tail[q] = Y + (int64_t)yrow * ldy + (ytail && k >= K_y ? K_y - 8 : k);
-                }
+                const int krow = (KT_ - 1) * kBlockK + w * 16 + q * 2 + (lane >> 5);
+                const int ch = (lane & 31) ^ (kswz(krow) << 2);
+                const int kr = ytail && krow >= K_y ? K_y - 1 : krow;
+                yg_tail[q] = Y + (int64_t)kr * ldy + (c0 + ch * 8 < rows_y ? c0 + ch * 8 : rows_y - 8);
             }
         }
         auto ysrc = [&](int q, int kt) -> const uint16_t* {
@@ -506,9 +521,8 @@ struct DirectCoreT {
             unsigned char* ys = smem + 2 * kTileBytes + stage * kTileBytes + w * 8192;
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                __builtin_amdgcn_global_load_lds((gptr_t)(xg[q] + kt * xstep),
-                                                 (lptr_t)(xs + q * 1024), 16, 0, 0);
-                __builtin_amdgcn_global_load_lds((gptr_t)ysrc(q, kt), (lptr_t)(ys + q * 1024), 16, 0, 0);
+                dma_to_lds<16>(xg[q] + kt * xstep, xs + q * 1024);
+                dma_to_lds<16>(ysrc(q, kt), ys + q * 1024);
             }
         };
 
@@ -521,7 +535,6 @@ struct DirectCoreT {
             yofs[s] = 2 * kTileBytes + kmajor_lane_offset(lane, wc * 4 + s);
         }
         const int xbase = (wr * 128 + l31) * 128;
-        const int ybase = 2 * kTileBytes + (wc * kGroupC + l31) * 128;
 
         // MFMA operands of the four k-slices of a step: fy[s][t], fx[s][t] for slice s.
         bf16x8_t fy[4][4], fx[4][4];
@@ -529,8 +542,7 @@ struct DirectCoreT {
         auto read_item = [&](int stage, int s, int item) {
             const unsigned char* base = smem + stage * kTileBytes;
             if (item < 4)
-                fy[s][item] = YK ? read_kmajor(base + yofs[item] + s * 8192)
-                                 : *reinterpret_cast<const bf16x8_t*>(base + ybase + item * 4096 + rofs[s]);
+                fy[s][item] = read_kmajor(base + yofs[item] + s * 8192);
             else
                 fx[s][item - 4] =
                     XK ? read_kmajor(base + xofs[item - 4] + s * 8192)
@@ -550,14 +562,14 @@ struct DirectCoreT {
         // the line into L2.  `warm` (see warm_row) must be a valid row pointer in every lane.
         // Not for two k-major operands (the weight-gradient products): measured there, the extra
         // L2 lookups cost as much as the early misses save.
-        constexpr bool warming = !(XK && YK);
+        constexpr bool warming = !XK;
         unsigned char* const dump = smem + kStageBytes + w * 256;
         auto warm_step = [&](int kt) {
             // (with a Y that lacks k-rows of the last step, that step is not warmed: the lane's
             // line may be one of them)
             const int last = ytail && KT > 1 ? KT - 2 : KT - 1;
             const int kk = kt < last ? kt : last;
-            __builtin_amdgcn_global_load_lds((gptr_t)(warm + kk * warm_stride), (lptr_t)dump, 4, 0, 0);
+            dma_to_lds<4>(warm + kk * warm_stride, dump);
         };
         // Joins the wavefronts once this wavefront's DMA of the next stage has landed.  The warm-up
         // load issued after that DMA may still be in flight (loads complete in order).
@@ -612,8 +624,7 @@ struct DirectCoreT {
             for (int i = 0; i < 8; ++i) {
                 mfma_pair(2, i);
                 if (LOADS)
-                    __builtin_amdgcn_global_load_lds((gptr_t)(xg[i] + (kt + 2) * xstep),
-                                                     (lptr_t)(xs + i * 1024), 16, 0, 0);
+                    dma_to_lds<16>(xg[i] + (kt + 2) * xstep, xs + i * 1024);
                 if (NEXT) read_item(cur ^ 1, 0, i);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -621,8 +632,7 @@ struct DirectCoreT {
             for (int i = 0; i < 8; ++i) {
                 mfma_pair(3, i);
                 if (LOADS)
-                    __builtin_amdgcn_global_load_lds((gptr_t)ysrc(i, kt + 2), (lptr_t)(ys + i * 1024), 16,
-                                                     0, 0);
+                    dma_to_lds<16>(ysrc(i, kt + 2), ys + i * 1024);
                 if (NEXT) read_item(cur ^ 1, 1, i);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -638,23 +648,259 @@ struct DirectCoreT {
         kstep(kt, std::false_type{}, std::false_type{}, false);
     }
 };
-typedef DirectCoreT<false, false> DirectCore;
-typedef DirectCoreT<true, true> KMajorCore;
-typedef DirectCoreT<false, true> MixedCore;
+typedef KMajorDirectT<true> KMajorCore;
+typedef KMajorDirectT<false> MixedCore;
 
 // ---------------------------------------------------------------------------------------------
-// Epilogues shared by the kernels built on the two cores
+// DirectCore: 4 wavefronts, global -> LDS DMA, aligned shapes only, both operands k-contiguous,
+// v_mfma_f32_16x16x32_bf16
+// ---------------------------------------------------------------------------------------------
+// The 16 x 16 x 32 form sustains about 5 % more than the 32 x 32 x 16 form on this chip under the
+// same power limit (measured with register-resident operands and in this kernel).
+struct DirectCore {
+    static constexpr int kThreads = 256;
+    static constexpr int kMT = 8;     // 16-wide c tiles per wavefront
+    static constexpr int kNT = 8;     // 16-wide r tiles per wavefront
+    static constexpr bool kCanGuard = false;
+    typedef f32x4_t acc_t;
+    static constexpr int kTile = 16, kRuns = 1, kGroups = 4;
+
+    // acc[mt][nt][x]: r = nt * 16 + lane % 16, c = mt * 16 + 4 (lane / 16) + x inside the wavefront's
+    // 128 x 128.
+    struct Lane {
+        int lane, grp, lrow, wr, wc;
+        __device__ __forceinline__ Lane() {
+            const int tid = threadIdx.x;
+            lane = tid & 63;
+            grp = lane >> 4;
+            lrow = lane & 15;
+            const int wave = tid >> 6;
+            wr = wave & 1;
+            wc = wave >> 1;
+        }
+        __device__ __forceinline__ int r(int nt) const { return wr * 128 + nt * 16 + lrow; }
+        __device__ __forceinline__ int rbase(int nt) const { return wr * 128 + nt * 16; }
+        __device__ __forceinline__ int cw(int mt, int /*q*/) const { return mt * 16 + grp * 4; }
+        __device__ __forceinline__ int c(int mt, int q) const { return wc * kGroupC + cw(mt, q); }
+    };
+
+    // LDS row of a tile = 128 bytes = 8 chunks of 16 bytes; chunk kc of row `row` lives at slot
+    // kc ^ ((row >> 1) & 7): sixteen consecutive rows at one kc then cover all 64 banks once.
+    static __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
+
+    // Requires K % 64 == 0, K >= 64, 16-byte aligned rows and r0 + 256 <= rows of X.  GUARD must
+    // be false.  Y (without Y2) may end inside the block: it is read from its row rows_y - 1 in
+    // place of the rows from rows_y on (the logits of a vocabulary that is not a multiple of the
+    // block width), finite data of Y, and the caller discards those accumulator columns.
+    // With YTAIL (no Y2): K_y (if >= 0 and < K) is the k extent Y has when X is zero-padded along k
+    // beyond it (the logits of a hidden size that is not whole k-steps, X being the library's own
+    // zero-padded copy of the hidden rows): the chunks of a row of Y beyond K_y are read from the
+    // row's last chunk (K_y a multiple of 8) and meet zeros of X.
+    // Y2: gated pair, see paired_row.
+    // warm_stride = elements between the lane's warm-up line of one k-step and the next.
+    template <bool GUARD, bool YTAIL = false>
+    static __device__ __forceinline__ void gemm(const uint16_t* __restrict__ X, int64_t ldx,
+                                                int /*rows_x*/, const uint16_t* __restrict__ Y,
+                                                int64_t ldy, int rows_y, int K, int r0, int c0,
+                                                unsigned char* smem, acc_t (&acc)[kMT][kNT],
+                                                const uint16_t* warm, int64_t warm_stride = kBlockK,
+                                                const uint16_t* Y2 = nullptr, int K_y = -1) {
+        static_assert(!GUARD, "the DMA cores have no bounds checks");
+        const int tid = threadIdx.x, lane = tid & 63;
+        const int w = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave id, provably uniform
+        const int wr = w & 1, wc = w >> 1;
+        const int l15 = lane & 15, g = lane >> 4;
+
+        // One DMA instruction moves 8 rows x 128 bytes: lane -> (row = lane / 8, LDS chunk slot =
+        // lane % 8); the lane fetches the global chunk that belongs in its slot.  Wave w owns rows
+        // [64 w, 64 w + 64) of both operand tiles: 8 instructions per operand per k-step.
+        const int lr = lane >> 3, pc = lane & 7;
+        const uint16_t* xg[8];
+        const uint16_t* yg[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int row = (w * 8 + q) * 8 + lr;
+            const int kc = pc ^ swz(row);
+            xg[q] = X + (int64_t)(r0 + row) * ldx + kc * 8;
+            if (Y2) {                               // gated pair
+                bool valid;
+                yg[q] = paired_row(Y, Y2, ldy, c0, row, 0x7fffffff, valid) + kc * 8;
+            } else {
+                const int yrow = c0 + row < rows_y ? c0 + row : rows_y - 1;        // (the clamp: see above)
+                yg[q] = Y + (int64_t)yrow * ldy + kc * 8;
+            }
+        }
+        // Y shorter than the loop's K: the lane's sources in the last k-step, clamped
+        const int KT_ = K / kBlockK;
+        const bool ytail = YTAIL && K_y >= 0 && K_y < K;
+        const uint16_t* yg_tail[8];
+        if (YTAIL) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int row = (w * 8 + q) * 8 + lr;
+                const int k = (KT_ - 1) * kBlockK + (pc ^ swz(row)) * 8;
+                const int yrow = c0 + row < rows_y ? c0 + row : rows_y - 1;
+                yg_tail[q] = Y + (int64_t)yrow * ldy + (ytail && k >= K_y ? K_y - 8 : k);
+            }
+        }
+        auto ysrc = [&](int q, int kt) -> const uint16_t* {
+            if (YTAIL) return (ytail && kt == KT_ - 1) ? yg_tail[q] : yg[q] + kt * kBlockK;
+            return yg[q] + kt * kBlockK;
+        };
+        auto issue_loads = [&](int stage, int kt) {
+            unsigned char* xs = smem + stage * kTileBytes + w * 8192;
+            unsigned char* ys = smem + 2 * kTileBytes + stage * kTileBytes + w * 8192;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                dma_to_lds<16>(xg[q] + kt * kBlockK, xs + q * 1024);
+                dma_to_lds<16>(ysrc(q, kt), ys + q * 1024);
+            }
+        };
+
+        // Operand reads.  A k-step is two slices of 32 k; lane (row l15 of a 16-row tile, k-group g)
+        // reads the 16-byte chunk 4 s + g of its row: one read per operand.
+        int rofs[2];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) rofs[s] = ((4 * s + g) ^ swz(l15)) * 16;
+        const int xbase = (wr * 128 + l15) * 128;
+        const int ybase = 2 * kTileBytes + (wc * kGroupC + l15) * 128;
+
+        // MFMA operands of the two k-slices of a step: fy[s][t], fx[s][t] for slice s.
+        bf16x8_t fy[2][8], fx[2][8];
+        // item 0..7: the Y operand of accumulator row t = item, 8..15: the X operand of column t
+        auto read_item = [&](int stage, int s, int item) {
+            const unsigned char* base = smem + stage * kTileBytes + rofs[s];
+            if (item < 8) fy[s][item] = *reinterpret_cast<const bf16x8_t*>(base + ybase + item * 2048);
+            else fx[s][item - 8] = *reinterpret_cast<const bf16x8_t*>(base + xbase + (item - 8) * 2048);
+        };
+        // the four MFMAs of slot i (0..15) of a slice
+        auto mfma_quad = [&](int s, int i) {
+            const int mt = i >> 1, n0 = (i & 1) * 4;
+#pragma unroll
+            for (int d = 0; d < 4; ++d)
+                acc[mt][n0 + d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fy[s][mt], fx[s][n0 + d],
+                                                                          acc[mt][n0 + d], 0, 0, 0);
+        };
+
+        const int KT = K / kBlockK;
+        // One 4-byte DMA per wavefront and k-step into a landing area nobody reads: it only pulls
+        // the line into L2.  `warm` (see warm_row) must be a valid row pointer in every lane.
+        unsigned char* const dump = smem + kStageBytes + w * 256;
+        auto warm_step = [&](int kt) {
+            // (with a Y that lacks k of the last step, that step is not warmed: the lane's line
+            // may lie beyond K_y)
+            const int last = ytail && KT > 1 ? KT - 2 : KT - 1;
+            const int kk = kt < last ? kt : last;
+            dma_to_lds<4>(warm + kk * warm_stride, dump);
+        };
+        // Joins the wavefronts once this wavefront's DMA of the next stage has landed.  The warm-up
+        // load issued after that DMA may still be in flight (loads complete in order).
+        auto stage_barrier = [&](bool one_behind) {
+            if (one_behind) asm volatile("s_waitcnt vmcnt(1) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        };
+        for (int p = 2; p < 2 + kWarmAhead; ++p) warm_step(p);
+        issue_loads(0, 0);
+        __syncthreads();                       // waits for the DMA (vmcnt) and joins the waves
+        if (KT > 1) issue_loads(1, 1);
+#pragma unroll
+        for (int item = 0; item < 16; ++item) read_item(0, 0, item);
+
+        // One k-step = two slices of 64 MFMAs, each slice sixteen fenced slots of four MFMAs (64
+        // cycles) plus the memory instructions that ride along, in this order:
+        //   slice 0, slots 0..7    | read slice 1 of this stage (two operands per slot)
+        //   slice 0, slots 8..15   |
+        //   -- all of this stage has been read, the next stage has landed: workgroup barrier --
+        //   slice 1, slots 0..7    | DMA of step kt + 2, X half, into this stage | read slice 0 of kt + 1
+        //   slice 1, slots 8..15   | DMA of step kt + 2, Y half                  | read slice 0 of kt + 1
+        // Every operand read is issued at least half a slice before its first MFMA, so a burst of
+        // DMA writes into LDS delays reads without draining the matrix pipe, and the DMA issue is
+        // spread over half a step (left to the scheduler the sixteen DMA instructions come out
+        // back to back and the matrix pipe idles behind their issue).  Inside a slot the MFMAs
+        // go first (the sched_group_barrier calls): the wait the compiler puts before a slot's
+        // first MFMA then covers reads issued long ago, not the slot's own (1.5 % of the kernel).
+        // LOADS: step kt + 2 exists.  NEXT: step kt + 1 exists.  The tail steps skip the DMA so
+        // that none is in flight when the workgroup ends.
+        // BEHIND: the previous k-step issued a warm-up load after its DMA.
+        auto kstep = [&](int kt, auto loads, auto next, bool behind) {
+            constexpr bool LOADS = decltype(loads)::value, NEXT = decltype(next)::value;
+            const int cur = kt & 1;
+            unsigned char* const xs = smem + cur * kTileBytes + w * 8192;
+            unsigned char* const ys = smem + 2 * kTileBytes + cur * kTileBytes + w * 8192;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                mfma_quad(0, i);
+                read_item(cur, 1, 2 * i);
+                read_item(cur, 1, 2 * i + 1);
+                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int i = 8; i < 16; ++i) {
+                mfma_quad(0, i);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            stage_barrier(behind);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                mfma_quad(1, i);
+                if (LOADS)
+                    dma_to_lds<16>(xg[i] + (kt + 2) * kBlockK, xs + i * 1024);
+                if (NEXT) read_item(cur ^ 1, 0, i);
+                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+                if (LOADS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                if (NEXT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int i = 8; i < 16; ++i) {
+                mfma_quad(1, i);
+                if (LOADS)
+                    dma_to_lds<16>(ysrc(i - 8, kt + 2), ys + (i - 8) * 1024);
+                if (NEXT) read_item(cur ^ 1, 0, i);
+                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+                if (LOADS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                if (NEXT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (LOADS) warm_step(kt + 2 + kWarmAhead);
+        };
+        // a step's barrier may leave one load in flight iff the step before it had LOADS and warmed
+        int kt = 0;
+        for (; kt + 2 < KT; ++kt) kstep(kt, std::true_type{}, std::true_type{}, kt > 0);
+        if (KT >= 2) {
+            kstep(kt, std::false_type{}, std::true_type{}, kt > 0);
+            ++kt;
+        }
+        kstep(kt, std::false_type{}, std::false_type{}, false);
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// Epilogues shared by the kernels built on the cores (written against the cores' layout traits)
 // ---------------------------------------------------------------------------------------------
 constexpr int kTurnPitch = 272;     // bytes per row of the LDS turn-around area: 256 + 16 of padding
 
+template <class Core>
+__device__ __forceinline__ void zero_acc(typename Core::acc_t (&acc)[Core::kMT][Core::kNT]) {
+#pragma unroll
+    for (int mt = 0; mt < Core::kMT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < Core::kNT; ++nt)
+#pragma unroll
+            for (int j = 0; j < 4 * Core::kRuns; ++j) acc[mt][nt][j] = 0.f;
+}
+
 // D[(r0 + r) * ldd + c0 + c] = bf16(acc) for the block's 256 x 256 accumulators, D row-major with c
 // contiguous.  In the accumulators a lane holds 4 consecutive c of one r, so a direct store would
-// scatter 8-byte pieces over 32 rows per instruction: each wavefront instead turns its 32 x 128
-// pieces around in LDS (free once the k-loop is over; each wavefront has its own region and LDS
-// serves a wavefront's accesses in order, so no barrier is needed) and stores whole 256-byte row
-// segments.  GUARD: rows >= rows_out and 8-column chunks beyond cols_out are not written.
+// scatter 8-byte pieces over many rows per instruction: each wavefront instead turns its
+// kTile x 128 pieces around in LDS (free once the k-loop is over; each wavefront has its own region
+// and LDS serves a wavefront's accesses in order, so no barrier is needed) and stores whole
+// 256-byte row segments.  GUARD: rows >= rows_out and 8-column chunks beyond cols_out are not written.
 template <class Core, bool GUARD>
-__device__ __forceinline__ void store_block_bf16(const f32x16_t (&acc)[Core::kMT][Core::kNT],
+__device__ __forceinline__ void store_block_bf16(const typename Core::acc_t (&acc)[Core::kMT][Core::kNT],
                                                  uint16_t* __restrict__ D, int64_t ldd, int r0,
                                                  int c0, int rows_out, int cols_out,
                                                  unsigned char* smem) {
@@ -667,15 +913,14 @@ __device__ __forceinline__ void store_block_bf16(const f32x16_t (&acc)[Core::kMT
 #pragma unroll
         for (int mt = 0; mt < Core::kMT; ++mt)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < Core::kRuns; ++q) {
                 bf16x4_t o;
 #pragma unroll
                 for (int x = 0; x < 4; ++x) o[x] = (__bf16)acc[mt][nt][q * 4 + x];
-                *reinterpret_cast<bf16x4_t*>(tw + lp.l31 * kTurnPitch +
-                                             (mt * 32 + q * 8 + lp.half * 4) * 2) = o;
+                *reinterpret_cast<bf16x4_t*>(tw + lp.lrow * kTurnPitch + lp.cw(mt, q) * 2) = o;
             }
 #pragma unroll
-        for (int it = 0; it < 8; ++it) {
+        for (int it = 0; it < Core::kTile / 4; ++it) {
             const int row = it * 4 + lrow;
             const int gr = r0 + lp.rbase(nt) + row;
             const u32x4_t v = *reinterpret_cast<const u32x4_t*>(tw + row * kTurnPitch + lcol * 16);
@@ -687,12 +932,12 @@ __device__ __forceinline__ void store_block_bf16(const f32x16_t (&acc)[Core::kMT
 
 // out[(c0 + c) * ld + r0 + r] (+)= acc: the transposed fp32 accumulate used by the weight-gradient
 // GEMMs.  r runs along the MFMA lane dimension, so each accumulator register of a wavefront
-// covers 32 consecutive floats of one row of `out` and the accumulate is one fire-and-forget fp32
-// atomic add per register on full 128-byte lines (a plain store when `first`).  Each element
+// covers runs of kTile consecutive floats of rows of `out` and the accumulate is one
+// fire-and-forget fp32 atomic add per register (a plain store when `first`).  Each element
 // belongs to exactly one lane per launch; launches on one stream are ordered, so the sums are
 // formed in launch order: deterministic.  Rows r >= r_valid and c >= c_valid are skipped.
 template <class Core, bool GUARD>
-__device__ __forceinline__ void accumulate_block_f32(const f32x16_t (&acc)[Core::kMT][Core::kNT],
+__device__ __forceinline__ void accumulate_block_f32(const typename Core::acc_t (&acc)[Core::kMT][Core::kNT],
                                                      float* __restrict__ out, int64_t ld, int r0,
                                                      int c0, int r_valid, int c_valid, bool first) {
     const typename Core::Lane lp;
@@ -703,7 +948,7 @@ __device__ __forceinline__ void accumulate_block_f32(const f32x16_t (&acc)[Core:
 #pragma unroll
         for (int mt = 0; mt < Core::kMT; ++mt)
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
+            for (int j = 0; j < 4 * Core::kRuns; ++j) {
                 const int c = c0 + lp.c(mt, j >> 2) + (j & 3);
                 if (c >= c_valid) continue;
                 float* dst = out + (int64_t)c * ld + r;

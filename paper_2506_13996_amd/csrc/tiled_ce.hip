@@ -602,14 +602,10 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
         if (P >= pg.patches() || !tile_in_patch(pg, P, w, tr, tc)) return;
     }
     const int r0 = tr * kBlockR, c0 = tc * kBlockC;
+    constexpr int kRegs = 4 * Core::kRuns;          // accumulator registers of a tile
 
-    f32x16_t acc[kMT][kNT];
-#pragma unroll
-    for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < kNT; ++nt)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
+    typename Core::acc_t acc[kMT][kNT];
+    zero_acc<Core>(acc);
 
     const int kofs = p.info->kofs;
     const uint16_t* const hidden_t = p.hidden_t + (int64_t)kofs * p.Hk;
@@ -628,7 +624,7 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
 #pragma unroll
                 for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
-                    for (int j = 0; j < 16; ++j)
+                    for (int j = 0; j < kRegs; ++j)
                         if (c0 + lp.c(mt, j >> 2) + (j & 3) >= p.V) acc[mt][nt][j] = -INFINITY;
             }
         }
@@ -639,32 +635,32 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
 #pragma unroll
             for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) m = fmaxf(m, acc[mt][nt][j]);
-            m = fmaxf(m, __shfl_xor(m, 32));
+                for (int j = 0; j < kRegs; ++j) m = fmaxf(m, acc[mt][nt][j]);
+            m = groups_max<Core::kGroups>(m);
         }
         {
             // label logit: exactly one lane of one block holds column y of row i.  Few wavefronts
-            // hold any (32 rows x 128 of V columns), so the search sits behind a uniform branch.
+            // hold any (a tile's rows x 128 of V columns), so the search sits behind a uniform branch.
             const int y = rowok && act ? p.labels_t[i] : -1;
             const unsigned d = (unsigned)(y - (c0 + lp.wc * kGroupC));
-            const bool mine = y >= 0 && d < (unsigned)kGroupC && ((d >> 2) & 1u) == (unsigned)lp.half;
+            const bool mine = y >= 0 && d < (unsigned)kGroupC &&
+                              ((d >> 2) & (unsigned)(Core::kGroups - 1)) == (unsigned)lp.grp;
             if (__ballot(mine) != 0ull) {
                 if (mine) {
                     float zl = 0.f;
 #pragma unroll
                     for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
-                        for (int j = 0; j < 16; ++j)
-                            if (d == (unsigned)(mt * 32 + (j >> 2) * 8 + lp.half * 4 + (j & 3)))
-                                zl = acc[mt][nt][j];
+                        for (int j = 0; j < kRegs; ++j)
+                            if (d == (unsigned)(lp.cw(mt, j >> 2) + (j & 3))) zl = acc[mt][nt][j];
                     p.zlabel[i] = zl;
                 }
             }
         }
         // e = exp(z - ref) as exp2(z * log2(e) - ref * log2(e)); summed in fp32, stored as bf16.
         // In the accumulators a lane holds 4 consecutive columns of one row, so a direct store
-        // would scatter 16-byte pieces over 32 rows per instruction.  The wavefront instead turns
-        // its 32 x 128 piece around in LDS (free once the k-loop is over; each wavefront has its
+        // would scatter 8-byte pieces over many rows per instruction.  The wavefront instead turns
+        // its kTile x 128 piece around in LDS (free once the k-loop is over; each wavefront has its
         // own region and LDS serves a wavefront's accesses in order, so no barrier is needed) and
         // stores whole 256-byte row segments.
         const float ref2 = ref * kLog2e;
@@ -673,7 +669,7 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
 #pragma unroll
         for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < Core::kRuns; ++q) {
                 bf16x4_t o;
 #pragma unroll
                 for (int x = 0; x < 4; ++x) {
@@ -682,15 +678,14 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
                     o[x] = (__bf16)e;
                 }
                 if (MODE != MODE_FWD)
-                    *reinterpret_cast<bf16x4_t*>(tw + lp.l31 * kTurnPitch +
-                                                 (mt * 32 + q * 8 + lp.half * 4) * 2) = o;
+                    *reinterpret_cast<bf16x4_t*>(tw + lp.lrow * kTurnPitch + lp.cw(mt, q) * 2) = o;
             }
         if (MODE != MODE_FWD) {
             const int lrow = lp.lane >> 4, lcol = lp.lane & 15;        // 4 rows x 16 chunks of 16 B
             const int rb = r0 + lp.rbase(nt);
             uint16_t* const out = p.stash + (int64_t)(kofs + rb) * p.Vp + c0 + lp.wc * kGroupC + lcol * 8;
 #pragma unroll
-            for (int it = 0; it < 8; ++it) {
+            for (int it = 0; it < Core::kTile / 4; ++it) {
                 const int row = it * 4 + lrow;
                 const u32x4_t v = *reinterpret_cast<const u32x4_t*>(tw + row * kTurnPitch + lcol * 16);
                 if (!REDO || p.rowstate[rb + row] != 0)
@@ -698,8 +693,8 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
             }
         }
         if (MODE != MODE_BWD) {
-            s += __shfl_xor(s, 32);
-            if (lp.half == 0 && act) {
+            s = groups_sum<Core::kGroups>(s);
+            if (lp.grp == 0 && act) {
                 const int64_t g = (c0 + lp.wc * kGroupC) >> 7;
                 if (!REDO) p.pm[g * p.Tp + i] = m;
                 p.ps[g * p.Tp + i] = s;
@@ -747,13 +742,8 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
     const int k0 = split * ksteps * kBlockK;
     const int klen = min(ksteps * kBlockK, (p.V + kBlockK - 1) / kBlockK * kBlockK - k0);     // > 0
 
-    f32x16_t acc[kMT][kNT];
-#pragma unroll
-    for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < kNT; ++nt)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
+    typename Core::acc_t acc[kMT][kNT];
+    zero_acc<Core>(acc);
 
     const uint16_t* const dz = p.dz + (int64_t)p.info->kofs * p.Vp + k0;
     const uint16_t* const Wk = p.W + (int64_t)k0 * p.H;
@@ -774,7 +764,7 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
 #pragma unroll
             for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
+                for (int q = 0; q < Core::kRuns; ++q) {
                     const int h = c0 + lp.c(mt, q);
                     if (h >= p.H) continue;             // last column block of a ragged H
                     f32x4_t o;
@@ -795,7 +785,7 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
 #pragma unroll
         for (int mt = 0; mt < kMT; ++mt)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < Core::kRuns; ++q) {
                 const int h = c0 + lp.c(mt, q);
                 if (h >= p.H) continue;             // last column block of a ragged H
                 bf16x4_t o;
@@ -859,13 +849,8 @@ __global__ __launch_bounds__(Core::kThreads) void dw_kernel(const DWParams p) {
     }
     const int r0 = tr * kBlockR, c0 = tc * kBlockC;
 
-    f32x16_t acc[kMT][kNT];
-#pragma unroll
-    for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < kNT; ++nt)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
+    typename Core::acc_t acc[kMT][kNT];
+    zero_acc<Core>(acc);
 
     if (Tkc > 0) {
         int64_t step = 0;

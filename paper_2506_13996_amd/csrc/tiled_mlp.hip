@@ -123,13 +123,8 @@ __global__ __launch_bounds__(Core::kThreads) void linear_kernel(const LinearBatc
     const LinearParams& p = b.p[which];
     const int r0 = tr * kBlockR, c0 = tc * kBlockC;
 
-    f32x16_t acc[kMT][kNT];
-#pragma unroll
-    for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < kNT; ++nt)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
+    typename Core::acc_t acc[kMT][kNT];
+    zero_acc<Core>(acc);
 
     constexpr bool kMixed = std::is_same<Core, MixedCore>::value || std::is_same<Core, StagedMixedCore>::value;
     if constexpr (kMixed) {
@@ -176,20 +171,16 @@ struct GatedParams {
 template <class Core, bool GUARD, bool BWD>
 __global__ __launch_bounds__(Core::kThreads) void gated_kernel(const GatedParams p) {
     constexpr int kMT = Core::kMT, kNT = Core::kNT;
-    static_assert(kMT == 4, "two accumulator tiles of g and two of u per wavefront");
+    static_assert(kMT * Core::kTile == kGroupC, "a wavefront's 128 Y rows: 64 of Wg, then the same 64 of Wu");
+    constexpr int kHalfMT = kMT / 2;       // accumulator tiles mt < kHalfMT hold g, tile mt + kHalfMT the u of the same elements
     extern __shared__ __align__(16) unsigned char smem[];
     int P, w, tr, tc;
     patch_of_block(blockIdx.x, P, w);
     if (P >= p.grid.patches() || !tile_in_patch(p.grid, P, w, tr, tc)) return;
     const int r0 = tr * kBlockR, c0 = tc * kBlockC;      // c0 / 2 = first of the block's 128 columns of I
 
-    f32x16_t acc[kMT][kNT];
-#pragma unroll
-    for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < kNT; ++nt)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
+    typename Core::acc_t acc[kMT][kNT];
+    zero_acc<Core>(acc);
 
     const uint16_t* warm = Core::kCanGuard ? nullptr
                                            : warm_row(p.grid.PR, p.grid.PC, p.X, p.ldx, r0, tr, p.Wg,
@@ -197,10 +188,11 @@ __global__ __launch_bounds__(Core::kThreads) void gated_kernel(const GatedParams
     Core::template gemm<GUARD>(p.X, p.ldx, p.rows_x, p.Wg, p.ldw, p.I, p.K, r0, c0, smem, acc, warm,
                                kBlockK, p.Wu);
 
-    // Per wavefront and accumulator column nt: 32 rows x 64 columns of I.  Everything that goes to
-    // or comes from memory is turned around in the wavefront's own LDS region (as in
+    // Per wavefront and accumulator column nt: kTile rows x 64 columns of I.  Everything that goes
+    // to or comes from memory is turned around in the wavefront's own LDS region (as in
     // store_block_bf16) so that global accesses are whole 128-byte row segments.
     const typename Core::Lane lp;
+    constexpr int kRuns = Core::kRuns, kTile = Core::kTile;
     unsigned char* const tw = smem + (threadIdx.x >> 6) * (32 * kTurnPitch);
     const int lrow = lp.lane >> 3, lcol = lp.lane & 7;             // 8 rows x 8 chunks of 16 B
     const int gc = (c0 >> 1) + lp.wc * 64 + lcol * 8;              // this lane's 8 columns of I
@@ -209,27 +201,25 @@ __global__ __launch_bounds__(Core::kThreads) void gated_kernel(const GatedParams
 #pragma unroll
     for (int nt = 0; nt < kNT; ++nt) {
         const int row0 = r0 + lp.rbase(nt);
-        // the lane's own elements: row l31, columns (mt & 1) * 32 + q * 8 + half * 4 + x
-        auto own = [&](int mt, int q) {
-            return tw + lp.l31 * kTurnPitch + (mt * 32 + q * 8 + lp.half * 4) * 2;
-        };
-        auto store_rows = [&](const bf16x4_t (&v)[2][4], uint16_t* dst, int64_t ld) {
+        // the lane's own elements: row lrow of the tile, columns cw(mt, q) + x of the wavefront's 64
+        auto own = [&](int mt, int q) { return tw + lp.lrow * kTurnPitch + lp.cw(mt, q) * 2; };
+        auto store_rows = [&](const bf16x4_t (&v)[kHalfMT][kRuns], uint16_t* dst, int64_t ld) {
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
+            for (int mt = 0; mt < kHalfMT; ++mt)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) *reinterpret_cast<bf16x4_t*>(own(mt, q)) = v[mt][q];
+                for (int q = 0; q < kRuns; ++q) *reinterpret_cast<bf16x4_t*>(own(mt, q)) = v[mt][q];
 #pragma unroll
-            for (int it = 0; it < 4; ++it) {
+            for (int it = 0; it < kTile / 8; ++it) {
                 const int row = it * 8 + lrow;
                 const u32x4_t val = *reinterpret_cast<const u32x4_t*>(tw + row * kTurnPitch + lcol * 16);
                 if (!GUARD || (row0 + row < p.rows_out && col_ok))
                     *reinterpret_cast<u32x4_t*>(dst + (int64_t)(row0 + row) * ld + gc) = val;
             }
         };
-        bf16x4_t d[2][4];
+        bf16x4_t d[kHalfMT][kRuns];
         if (BWD) {
 #pragma unroll
-            for (int it = 0; it < 4; ++it) {
+            for (int it = 0; it < kTile / 8; ++it) {
                 const int row = it * 8 + lrow;
                 const bool ok = !GUARD || (row0 + row < p.rows_out && col_ok);
                 const u32x4_t val = ok ? *reinterpret_cast<const u32x4_t*>(p.da + (int64_t)(row0 + row) * p.I + gc)
@@ -237,18 +227,18 @@ __global__ __launch_bounds__(Core::kThreads) void gated_kernel(const GatedParams
                 *reinterpret_cast<u32x4_t*>(tw + row * kTurnPitch + lcol * 16) = val;
             }
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
+            for (int mt = 0; mt < kHalfMT; ++mt)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) d[mt][q] = *reinterpret_cast<const bf16x4_t*>(own(mt, q));
+                for (int q = 0; q < kRuns; ++q) d[mt][q] = *reinterpret_cast<const bf16x4_t*>(own(mt, q));
         }
-        bf16x4_t oa[2][4], og[2][4], ou[2][4];
+        bf16x4_t oa[kHalfMT][kRuns], og[kHalfMT][kRuns], ou[kHalfMT][kRuns];
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+        for (int mt = 0; mt < kHalfMT; ++mt)
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+            for (int q = 0; q < kRuns; ++q)
 #pragma unroll
                 for (int x = 0; x < 4; ++x) {
-                    const float g = acc[mt][nt][q * 4 + x], u = acc[mt + 2][nt][q * 4 + x];
+                    const float g = acc[mt][nt][q * 4 + x], u = acc[mt + kHalfMT][nt][q * 4 + x];
                     const float sg = 1.f / (1.f + __expf(-g));
                     const float silu = g * sg;
                     oa[mt][q][x] = (__bf16)(silu * u);
@@ -289,13 +279,8 @@ __global__ __launch_bounds__(Core::kThreads) void wgrad_kernel(const WgradBatch 
     const WgradParams& p = b.p[which];
     const int r0 = tr * kBlockR, c0 = tc * kBlockC;
 
-    f32x16_t acc[kMT][kNT];
-#pragma unroll
-    for (int mt = 0; mt < kMT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < kNT; ++nt)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) acc[mt][nt][j] = 0.f;
+    typename Core::acc_t acc[kMT][kNT];
+    zero_acc<Core>(acc);
 
     int64_t step = 0;
     const uint16_t* warm = Core::kCanGuard ? nullptr
