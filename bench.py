@@ -32,7 +32,7 @@ MI355X_BF16_MFMA_PEAK_TFLOPS = 2500.0      # dense bf16, vendor figure
 # and says so in `traffic_source`; for any other workload or tile the field is null.
 TRAFFIC_PROFILE = "profiles/bench_llama8b_128k_hbm_traffic.txt"
 PROFILED_TRAFFIC_BYTES_PER_LAUNCH = {
-    "llama8b_128k": {"logits_gemm": 6.806e9, "dhidden_gemm": 5.871e9, "dw_gemm": 25.513e9},
+    "llama8b_128k": {"logits_gemm": 6.806e9, "dhidden_gemm": 5.865e9, "dw_gemm": 26.727e9},
 }
 OTHER_STEPS, OTHER_WARMUP = 3, 1
 
@@ -43,7 +43,9 @@ def mfma_sustained(B) -> dict:
     the published peak.  The clock under matrix load follows the power drawn, hence the operand bits."""
     return {"random_operands_tflops": B.alst_debug_mfma_rate(1, 60000),
             "small_integer_operands_tflops": B.alst_debug_mfma_rate(0, 60000),
-            "how": "256 workgroups x 4 wavefronts x 60000 x 64 v_mfma_f32_32x32x16_bf16, register resident"}
+            "random_operands_16x16x32_tflops": B.alst_debug_mfma_rate(3, 60000),
+            "how": "256 workgroups x 4 wavefronts x 60000 x 64 v_mfma_f32_32x32x16_bf16 (or 128 "
+                   "v_mfma_f32_16x16x32_bf16), register resident"}
 
 
 def cpu_model() -> str:

@@ -38,12 +38,14 @@ int alst_debug_block_tile(int tiles_r, int tiles_c, int parts, int bid, int* par
 
 /*
  * Benchmarking aid (no counterpart in the paper): the sustained rate, in TFLOP/s, of the bf16
- * matrix instruction the block GEMMs are built on, measured on the current device with a loop that
- * touches no memory (one wavefront per SIMD of every compute unit, 64 * iters instructions each).
+ * matrix instructions the block GEMMs are built on, measured on the current device with a loop that
+ * touches no memory (one wavefront per SIMD of every compute unit, iters * 2^21 flop each).
  * It is the ceiling the GEMM kernels can be compared with besides the published peak: the clock
- * under matrix load depends on the power drawn, hence on the operand bits.  data = 0: small-integer
- * operands, 1: random operands in [-1, 1).  scratch: device, 256 * 256 floats, overwritten;
- * tflops: HOST double.  1 <= iters <= 2^22.  Synchronises `stream`.
+ * under matrix load depends on the power drawn, hence on the operand bits and the instruction form.
+ * data bit 0: 0 = small-integer operands, 1 = random operands in [-1, 1); data bit 1: 0 =
+ * v_mfma_f32_32x32x16_bf16 (the cores with a k-major operand), 1 = v_mfma_f32_16x16x32_bf16 (the
+ * k-contiguous core).  scratch: device, 256 * 256 floats, overwritten; tflops: HOST double.
+ * 1 <= iters <= 2^22; any other data is ALST_ERR_SHAPE.  Synchronises `stream`.
  */
 int alst_debug_mfma_rate(int data, int iters, float* scratch, double* tflops, void* stream);
 

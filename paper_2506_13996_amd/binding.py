@@ -381,7 +381,8 @@ def alst_debug_block_tile(tiles_r: int, tiles_c: int, parts: int, bid: int):
 
 
 def alst_debug_mfma_rate(data: int, iters: int = 100000) -> float:
-    """Sustained TFLOP/s of the bf16 matrix instruction on the current device (no memory traffic)."""
+    """Sustained TFLOP/s of a bf16 matrix instruction on the current device (no memory traffic).
+    data bit 0: small-integer (0) or random (1) operands; bit 1: 32x32x16 (0) or 16x16x32 (1) form."""
     scratch = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
     out = ctypes.c_double()
     _check(load_library().alst_debug_mfma_rate(data, iters, _ptr(scratch), ctypes.byref(out), _stream()),

@@ -1,6 +1,7 @@
 // Pieces shared by the translation units of libalst: error macro, per-kernel timing, launch helpers.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <stdint.h>
 
 #include "../../include/alst.h"
@@ -47,12 +48,30 @@ static inline int64_t checked_grid(int64_t tiles_r, int64_t tiles_c) {
     return blocks <= 0x7fffffff ? blocks : 0;
 }
 
-// Lets a kernel use the whole LDS of a compute unit.
+// Lets a kernel use the LDS of a compute unit beyond the default limit.
 template <typename K>
-static int allow_big_lds(K kernel) {
+static int allow_big_lds(K kernel, int bytes = kLdsBytes) {
     return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) == hipSuccess
+                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess
                ? ALST_OK : ALST_ERR_HIP;
+}
+
+// Workgroups of a launch of persistent workgroups (one per compute unit, each walking its share of
+// the launch's blocks): the compute units of the current device, a multiple of 8 so that the
+// workgroups dealt to one XCD keep their XCD from block to block.  Looked up once per device.
+static inline int persistent_grid() {
+    static std::atomic<int> cached[kMaxDevices];
+    const int dev = current_device_slot();
+    if (dev < 0) return 256;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        int cu = 0;
+        if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu < 8)
+            cu = 256;
+        n = cu / 8 * 8;
+        cached[dev].store(n, std::memory_order_relaxed);
+    }
+    return n;
 }
 
 }  // namespace alst

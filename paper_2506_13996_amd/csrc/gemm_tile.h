@@ -218,6 +218,19 @@ __device__ __forceinline__ int kmajor_lane_offset(int lane, int gran) {
     return (8 * half + (sl >> 2)) * 512 + ((gran ^ f) * 64) + b1 * 32 + (sl & 3) * 8;
 }
 
+// Values that are the same in every lane of a wavefront, said so to the compiler (it then keeps
+// them in scalar registers and branches on them without masking lanes).
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ int64_t uniform(int64_t v) {
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+template <class T>
+__device__ __forceinline__ const T* uniform(const T* p) {
+    return reinterpret_cast<const T*>(uniform((int64_t)reinterpret_cast<uintptr_t>(p)));
+}
+
 // Global -> LDS DMA: each lane's BYTES (16 or 4) land at lds + lane * BYTES; `lds` must be uniform
 // over the wavefront.
 template <int BYTES>
@@ -688,66 +701,106 @@ struct DirectCore {
     // kc ^ ((row >> 1) & 7): sixteen consecutive rows at one kc then cover all 64 banks once.
     static __device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
 
-    // Requires K % 64 == 0, K >= 64, 16-byte aligned rows and r0 + 256 <= rows of X.  GUARD must
-    // be false.  Y (without Y2) may end inside the block: it is read from its row rows_y - 1 in
+    // The operands of one output block: D[r0 + r][c0 + c] = sum_k X[r0 + r][k] Y[c0 + c][k].
+    // Requires K % 64 == 0, K >= 64, 16-byte aligned rows and r0 + 256 <= rows of X.
+    // Y (without Y2) may end inside the block: it is read from its row rows_y - 1 in
     // place of the rows from rows_y on (the logits of a vocabulary that is not a multiple of the
     // block width), finite data of Y, and the caller discards those accumulator columns.
-    // With YTAIL (no Y2): K_y (if >= 0 and < K) is the k extent Y has when X is zero-padded along k
+    // K_y (used with YTAIL, no Y2): if >= 0 and < K, the k extent Y has when X is zero-padded along k
     // beyond it (the logits of a hidden size that is not whole k-steps, X being the library's own
     // zero-padded copy of the hidden rows): the chunks of a row of Y beyond K_y are read from the
     // row's last chunk (K_y a multiple of 8) and meet zeros of X.
     // Y2: gated pair, see paired_row.
-    // warm_stride = elements between the lane's warm-up line of one k-step and the next.
-    template <bool GUARD, bool YTAIL = false>
-    static __device__ __forceinline__ void gemm(const uint16_t* __restrict__ X, int64_t ldx,
-                                                int /*rows_x*/, const uint16_t* __restrict__ Y,
-                                                int64_t ldy, int rows_y, int K, int r0, int c0,
-                                                unsigned char* smem, acc_t (&acc)[kMT][kNT],
-                                                const uint16_t* warm, int64_t warm_stride = kBlockK,
-                                                const uint16_t* Y2 = nullptr, int K_y = -1) {
-        static_assert(!GUARD, "the DMA cores have no bounds checks");
-        const int tid = threadIdx.x, lane = tid & 63;
-        const int w = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave id, provably uniform
-        const int wr = w & 1, wc = w >> 1;
-        const int l15 = lane & 15, g = lane >> 4;
+    // warm (see warm_row): the lane's warm-up row; warm_stride = elements between its line of one
+    // k-step and the next.
+    struct Block {
+        const uint16_t* X;
+        int64_t ldx;
+        const uint16_t* Y;
+        int64_t ldy;
+        int rows_y, K, r0, c0;
+        const uint16_t* warm;
+        int64_t warm_stride;
+        const uint16_t* Y2;
+        int K_y;
+    };
 
-        // One DMA instruction moves 8 rows x 128 bytes: lane -> (row = lane / 8, LDS chunk slot =
-        // lane % 8); the lane fetches the global chunk that belongs in its slot.  Wave w owns rows
-        // [64 w, 64 w + 64) of both operand tiles: 8 instructions per operand per k-step.
-        const int lr = lane >> 3, pc = lane & 7;
+    // The k-loop's state: the DMA sources of the block whose operands are being fetched, the LDS
+    // read offsets and the operand registers.  Used in two ways.
+    //  * One block per workgroup: gemm() below.
+    //  * A chain of blocks on one (persistent) workgroup: start(first); then for every block
+    //    run(block, the block after it, acc) followed by the caller's epilogue; finish() after
+    //    the last.  The last two k-steps of a block, which otherwise issue no DMA, fetch the
+    //    first two k-steps of the block after it into the stages they free, so the next block's
+    //    operands travel while the epilogue runs and no block but the first waits for a
+    //    prologue.  The last block of a chain names itself as the block after it (the fetch is
+    //    then wasted; finish() waits for it so that nothing is in flight when the workgroup
+    //    ends).  Every block of a chain must have the same K, a multiple of 128 (the stages
+    //    alternate: a block's step 0 must meet stage 0) and >= 256.  Between start() and
+    //    finish() the first kLdsBytes of LDS belong to the chain: an epilogue that turns data
+    //    around in LDS does it behind them.
+    template <bool YTAIL>
+    struct Pipe {
+        unsigned char* smem;
+        int w, lr, pc;                 // wavefront, the lane's row and chunk slot in a DMA instruction
+        int rofs[2], xbase, ybase;     // LDS read offsets
+        // the block the DMA works for: the lane's sources of k-step 0, its sources in the last
+        // k-step where Y is shorter than K (clamped), the warm-up row
         const uint16_t* xg[8];
         const uint16_t* yg[8];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const int row = (w * 8 + q) * 8 + lr;
-            const int kc = pc ^ swz(row);
-            xg[q] = X + (int64_t)(r0 + row) * ldx + kc * 8;
-            if (Y2) {                               // gated pair
-                bool valid;
-                yg[q] = paired_row(Y, Y2, ldy, c0, row, 0x7fffffff, valid) + kc * 8;
-            } else {
-                const int yrow = c0 + row < rows_y ? c0 + row : rows_y - 1;        // (the clamp: see above)
-                yg[q] = Y + (int64_t)yrow * ldy + kc * 8;
-            }
-        }
-        // Y shorter than the loop's K: the lane's sources in the last k-step, clamped
-        const int KT_ = K / kBlockK;
-        const bool ytail = YTAIL && K_y >= 0 && K_y < K;
         const uint16_t* yg_tail[8];
-        if (YTAIL) {
+        const uint16_t* warm;
+        int64_t warm_stride;
+        int KT_;
+        bool ytail;
+        // MFMA operands of the two k-slices of a step: fy[s][t], fx[s][t] for slice s
+        bf16x8_t fy[2][8], fx[2][8];
+
+        __device__ __forceinline__ explicit Pipe(unsigned char* smem_) : smem(smem_) {
+            const int tid = threadIdx.x, lane = tid & 63;
+            w = uniform(tid >> 6);
+            const int wr = w & 1, wc = w >> 1;
+            const int l15 = lane & 15, g = lane >> 4;
+            // One DMA instruction moves 8 rows x 128 bytes: lane -> (row = lane / 8, LDS chunk slot
+            // = lane % 8); the lane fetches the global chunk that belongs in its slot.  Wave w owns
+            // rows [64 w, 64 w + 64) of both operand tiles: 8 instructions per operand per k-step.
+            lr = lane >> 3;
+            pc = lane & 7;
+            // Operand reads.  A k-step is two slices of 32 k; lane (row l15 of a 16-row tile,
+            // k-group g) reads the 16-byte chunk 4 s + g of its row: one read per operand.
+#pragma unroll
+            for (int s = 0; s < 2; ++s) rofs[s] = ((4 * s + g) ^ swz(l15)) * 16;
+            xbase = (wr * 128 + l15) * 128;
+            ybase = 2 * kTileBytes + (wc * kGroupC + l15) * 128;
+        }
+        __device__ __forceinline__ void target(const Block& b) {
+            KT_ = b.K / kBlockK;
+            ytail = YTAIL && b.K_y >= 0 && b.K_y < b.K;
+            warm = b.warm;
+            warm_stride = b.warm_stride;
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 const int row = (w * 8 + q) * 8 + lr;
-                const int k = (KT_ - 1) * kBlockK + (pc ^ swz(row)) * 8;
-                const int yrow = c0 + row < rows_y ? c0 + row : rows_y - 1;
-                yg_tail[q] = Y + (int64_t)yrow * ldy + (ytail && k >= K_y ? K_y - 8 : k);
+                const int kc = pc ^ swz(row);
+                xg[q] = b.X + (int64_t)(b.r0 + row) * b.ldx + kc * 8;
+                if (b.Y2) {                         // gated pair
+                    bool valid;
+                    yg[q] = paired_row(b.Y, b.Y2, b.ldy, b.c0, row, 0x7fffffff, valid) + kc * 8;
+                } else {
+                    const int yrow = b.c0 + row < b.rows_y ? b.c0 + row : b.rows_y - 1;    // (the clamp: see Block)
+                    yg[q] = b.Y + (int64_t)yrow * b.ldy + kc * 8;
+                    if (YTAIL) {
+                        const int k = (KT_ - 1) * kBlockK + kc * 8;
+                        yg_tail[q] = b.Y + (int64_t)yrow * b.ldy + (ytail && k >= b.K_y ? b.K_y - 8 : k);
+                    }
+                }
             }
         }
-        auto ysrc = [&](int q, int kt) -> const uint16_t* {
+        __device__ __forceinline__ const uint16_t* ysrc(int q, int kt) const {
             if (YTAIL) return (ytail && kt == KT_ - 1) ? yg_tail[q] : yg[q] + kt * kBlockK;
             return yg[q] + kt * kBlockK;
-        };
-        auto issue_loads = [&](int stage, int kt) {
+        }
+        __device__ __forceinline__ void issue_loads(int stage, int kt) {
             unsigned char* xs = smem + stage * kTileBytes + w * 8192;
             unsigned char* ys = smem + 2 * kTileBytes + stage * kTileBytes + w * 8192;
 #pragma unroll
@@ -755,56 +808,43 @@ struct DirectCore {
                 dma_to_lds<16>(xg[q] + kt * kBlockK, xs + q * 1024);
                 dma_to_lds<16>(ysrc(q, kt), ys + q * 1024);
             }
-        };
-
-        // Operand reads.  A k-step is two slices of 32 k; lane (row l15 of a 16-row tile, k-group g)
-        // reads the 16-byte chunk 4 s + g of its row: one read per operand.
-        int rofs[2];
-#pragma unroll
-        for (int s = 0; s < 2; ++s) rofs[s] = ((4 * s + g) ^ swz(l15)) * 16;
-        const int xbase = (wr * 128 + l15) * 128;
-        const int ybase = 2 * kTileBytes + (wc * kGroupC + l15) * 128;
-
-        // MFMA operands of the two k-slices of a step: fy[s][t], fx[s][t] for slice s.
-        bf16x8_t fy[2][8], fx[2][8];
+        }
         // item 0..7: the Y operand of accumulator row t = item, 8..15: the X operand of column t
-        auto read_item = [&](int stage, int s, int item) {
+        __device__ __forceinline__ void read_item(int stage, int s, int item) {
             const unsigned char* base = smem + stage * kTileBytes + rofs[s];
             if (item < 8) fy[s][item] = *reinterpret_cast<const bf16x8_t*>(base + ybase + item * 2048);
             else fx[s][item - 8] = *reinterpret_cast<const bf16x8_t*>(base + xbase + (item - 8) * 2048);
-        };
+        }
         // the four MFMAs of slot i (0..15) of a slice
-        auto mfma_quad = [&](int s, int i) {
+        __device__ __forceinline__ void mfma_quad(acc_t (&acc)[kMT][kNT], int s, int i) {
             const int mt = i >> 1, n0 = (i & 1) * 4;
 #pragma unroll
             for (int d = 0; d < 4; ++d)
                 acc[mt][n0 + d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fy[s][mt], fx[s][n0 + d],
                                                                           acc[mt][n0 + d], 0, 0, 0);
-        };
-
-        const int KT = K / kBlockK;
+        }
         // One 4-byte DMA per wavefront and k-step into a landing area nobody reads: it only pulls
-        // the line into L2.  `warm` (see warm_row) must be a valid row pointer in every lane.
-        unsigned char* const dump = smem + kStageBytes + w * 256;
-        auto warm_step = [&](int kt) {
+        // the line into L2.  `warm` must be a valid row pointer in every lane.  Steps beyond the
+        // targeted block's last are steps of `ahead`, the block after it in a chain (or clamped).
+        __device__ __forceinline__ void warm_step(int kt, const Block* ahead) {
+            unsigned char* const dump = smem + kStageBytes + w * 256;
+            if (ahead != nullptr && kt >= KT_) {
+                // (the next block's first steps: whole k-steps of Y, K >= 256)
+                dma_to_lds<4>(ahead->warm + (kt - KT_) * ahead->warm_stride, dump);
+                return;
+            }
             // (with a Y that lacks k of the last step, that step is not warmed: the lane's line
             // may lie beyond K_y)
-            const int last = ytail && KT > 1 ? KT - 2 : KT - 1;
+            const int last = ytail && KT_ > 1 ? KT_ - 2 : KT_ - 1;
             const int kk = kt < last ? kt : last;
             dma_to_lds<4>(warm + kk * warm_stride, dump);
-        };
+        }
         // Joins the wavefronts once this wavefront's DMA of the next stage has landed.  The warm-up
         // load issued after that DMA may still be in flight (loads complete in order).
-        auto stage_barrier = [&](bool one_behind) {
+        static __device__ __forceinline__ void stage_barrier(bool one_behind) {
             if (one_behind) asm volatile("s_waitcnt vmcnt(1) lgkmcnt(0)\n\ts_barrier" ::: "memory");
             else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        };
-        for (int p = 2; p < 2 + kWarmAhead; ++p) warm_step(p);
-        issue_loads(0, 0);
-        __syncthreads();                       // waits for the DMA (vmcnt) and joins the waves
-        if (KT > 1) issue_loads(1, 1);
-#pragma unroll
-        for (int item = 0; item < 16; ++item) read_item(0, 0, item);
+        }
 
         // One k-step = two slices of 64 MFMAs, each slice sixteen fenced slots of four MFMAs (64
         // cycles) plus the memory instructions that ride along, in this order:
@@ -819,36 +859,37 @@ struct DirectCore {
         // back to back and the matrix pipe idles behind their issue).  Inside a slot the MFMAs
         // go first (the sched_group_barrier calls): the wait the compiler puts before a slot's
         // first MFMA then covers reads issued long ago, not the slot's own (1.5 % of the kernel).
-        // LOADS: step kt + 2 exists.  NEXT: step kt + 1 exists.  The tail steps skip the DMA so
-        // that none is in flight when the workgroup ends.
+        // kt: the step computed (its stage is kt & 1).  LOADS: the DMA of step dkt + 2 of the
+        // targeted block is issued (dkt = kt, or kt - KT when the target is the next block of a
+        // chain).  NEXT: step kt + 1 exists.  Steps without LOADS leave no DMA in flight.
         // BEHIND: the previous k-step issued a warm-up load after its DMA.
-        auto kstep = [&](int kt, auto loads, auto next, bool behind) {
-            constexpr bool LOADS = decltype(loads)::value, NEXT = decltype(next)::value;
-            const int cur = kt & 1;
-            unsigned char* const xs = smem + cur * kTileBytes + w * 8192;
-            unsigned char* const ys = smem + 2 * kTileBytes + cur * kTileBytes + w * 8192;
+        template <bool LOADS, bool NEXT>
+        __device__ __forceinline__ void kstep(acc_t (&acc)[kMT][kNT], int kt, int dkt, bool behind,
+                                              const Block* ahead) {
+            const int cur_stage = kt & 1;
+            unsigned char* const xs = smem + cur_stage * kTileBytes + w * 8192;
+            unsigned char* const ys = smem + 2 * kTileBytes + cur_stage * kTileBytes + w * 8192;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                mfma_quad(0, i);
-                read_item(cur, 1, 2 * i);
-                read_item(cur, 1, 2 * i + 1);
+                mfma_quad(acc, 0, i);
+                read_item(cur_stage, 1, 2 * i);
+                read_item(cur_stage, 1, 2 * i + 1);
                 __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
             for (int i = 8; i < 16; ++i) {
-                mfma_quad(0, i);
+                mfma_quad(acc, 0, i);
                 __builtin_amdgcn_sched_barrier(0);
             }
             stage_barrier(behind);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                mfma_quad(1, i);
-                if (LOADS)
-                    dma_to_lds<16>(xg[i] + (kt + 2) * kBlockK, xs + i * 1024);
-                if (NEXT) read_item(cur ^ 1, 0, i);
+                mfma_quad(acc, 1, i);
+                if (LOADS) dma_to_lds<16>(xg[i] + (dkt + 2) * kBlockK, xs + i * 1024);
+                if (NEXT) read_item(cur_stage ^ 1, 0, i);
                 __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
                 if (LOADS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
                 if (NEXT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
@@ -856,25 +897,73 @@ struct DirectCore {
             }
 #pragma unroll
             for (int i = 8; i < 16; ++i) {
-                mfma_quad(1, i);
-                if (LOADS)
-                    dma_to_lds<16>(ysrc(i - 8, kt + 2), ys + (i - 8) * 1024);
-                if (NEXT) read_item(cur ^ 1, 0, i);
+                mfma_quad(acc, 1, i);
+                if (LOADS) dma_to_lds<16>(ysrc(i - 8, dkt + 2), ys + (i - 8) * 1024);
+                if (NEXT) read_item(cur_stage ^ 1, 0, i);
                 __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
                 if (LOADS) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
                 if (NEXT) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (LOADS) warm_step(kt + 2 + kWarmAhead);
-        };
-        // a step's barrier may leave one load in flight iff the step before it had LOADS and warmed
-        int kt = 0;
-        for (; kt + 2 < KT; ++kt) kstep(kt, std::true_type{}, std::true_type{}, kt > 0);
-        if (KT >= 2) {
-            kstep(kt, std::false_type{}, std::true_type{}, kt > 0);
-            ++kt;
+            if (LOADS) warm_step(dkt + 2 + kWarmAhead, ahead);
         }
-        kstep(kt, std::false_type{}, std::false_type{}, false);
+
+        // ---- one block per workgroup
+        __device__ __forceinline__ void single(const Block& b, acc_t (&acc)[kMT][kNT]) {
+            const int KT = b.K / kBlockK;
+            target(b);
+            for (int p = 2; p < 2 + kWarmAhead; ++p) warm_step(p, nullptr);
+            issue_loads(0, 0);
+            __syncthreads();                   // waits for the DMA (vmcnt) and joins the waves
+            if (KT > 1) issue_loads(1, 1);
+#pragma unroll
+            for (int item = 0; item < 16; ++item) read_item(0, 0, item);
+            // a step's barrier may leave one load in flight iff the step before it had LOADS and warmed
+            int kt = 0;
+            for (; kt + 2 < KT; ++kt) kstep<true, true>(acc, kt, kt, kt > 0, nullptr);
+            if (KT >= 2) {
+                kstep<false, true>(acc, kt, kt, kt > 0, nullptr);
+                ++kt;
+            }
+            kstep<false, false>(acc, kt, kt, false, nullptr);
+        }
+
+        // ---- a chain of blocks
+        __device__ __forceinline__ void start(const Block& first) {
+            target(first);
+            for (int p = 2; p < 2 + kWarmAhead; ++p) warm_step(p, nullptr);
+            issue_loads(0, 0);
+            issue_loads(1, 1);
+        }
+        // acc += the product of `cur`, whose first two k-steps are in flight or have landed and
+        // which is the targeted block; fetches the first two k-steps of `next` and targets it.
+        __device__ __forceinline__ void run(const Block& cur, const Block& next, acc_t (&acc)[kMT][kNT]) {
+            const int KT = uniform(cur.K / kBlockK);
+            // waits for the DMA (and for the stores of the epilogue before) and joins the waves
+            stage_barrier(false);
+#pragma unroll
+            for (int item = 0; item < 16; ++item) read_item(0, 0, item);
+            int kt = 0;
+            for (; kt + 2 < KT; ++kt) kstep<true, true>(acc, kt, kt, kt > 0, &next);
+            target(next);
+            kstep<true, true>(acc, kt, -2, true, nullptr);
+            kstep<true, false>(acc, kt + 1, -1, true, nullptr);
+        }
+        __device__ __forceinline__ void finish() { stage_barrier(false); }
+    };
+
+    // One block on its own.  GUARD must be false.
+    template <bool GUARD, bool YTAIL = false>
+    static __device__ __forceinline__ void gemm(const uint16_t* __restrict__ X, int64_t ldx,
+                                                int /*rows_x*/, const uint16_t* __restrict__ Y,
+                                                int64_t ldy, int rows_y, int K, int r0, int c0,
+                                                unsigned char* smem, acc_t (&acc)[kMT][kNT],
+                                                const uint16_t* warm, int64_t warm_stride = kBlockK,
+                                                const uint16_t* Y2 = nullptr, int K_y = -1) {
+        static_assert(!GUARD, "the DMA cores have no bounds checks");
+        const Block b = {X, ldx, Y, ldy, rows_y, K, r0, c0, warm, warm_stride, Y2, K_y};
+        Pipe<YTAIL> pipe(smem);
+        pipe.single(b, acc);
     }
 };
 
@@ -882,6 +971,11 @@ struct DirectCore {
 // Epilogues shared by the kernels built on the cores (written against the cores' layout traits)
 // ---------------------------------------------------------------------------------------------
 constexpr int kTurnPitch = 272;     // bytes per row of the LDS turn-around area: 256 + 16 of padding
+// LDS of a kernel whose workgroups run chains of blocks on DirectCore (gemm_chain): the epilogue's
+// turn-around area (4 wavefronts x 16 rows) lies behind the stages and the warm-up landing area,
+// which belong to the next block's DMA while the epilogue runs.
+constexpr int kChainTurnOffset = kLdsBytes;
+constexpr int kChainLdsBytes = kChainTurnOffset + 4 * 16 * kTurnPitch;
 
 template <class Core>
 __device__ __forceinline__ void zero_acc(typename Core::acc_t (&acc)[Core::kMT][Core::kNT]) {
@@ -898,14 +992,17 @@ __device__ __forceinline__ void zero_acc(typename Core::acc_t (&acc)[Core::kMT][
 // scatter 8-byte pieces over many rows per instruction: each wavefront instead turns its
 // kTile x 128 pieces around in LDS (free once the k-loop is over; each wavefront has its own region
 // and LDS serves a wavefront's accesses in order, so no barrier is needed) and stores whole
-// 256-byte row segments.  GUARD: rows >= rows_out and 8-column chunks beyond cols_out are not written.
+// 256-byte row segments (non-temporal stores: the output is a stream that nothing reads back while
+// it is in L2, and it would push operand lines out of there; -1 % on the K = 4096 products).
+// `smem`: 4 * kTile * kTurnPitch bytes of LDS for this.
+// GUARD: rows >= rows_out and 8-column chunks beyond cols_out are not written.
 template <class Core, bool GUARD>
 __device__ __forceinline__ void store_block_bf16(const typename Core::acc_t (&acc)[Core::kMT][Core::kNT],
                                                  uint16_t* __restrict__ D, int64_t ldd, int r0,
                                                  int c0, int rows_out, int cols_out,
                                                  unsigned char* smem) {
     const typename Core::Lane lp;
-    unsigned char* const tw = smem + (threadIdx.x >> 6) * (32 * kTurnPitch);
+    unsigned char* const tw = smem + (threadIdx.x >> 6) * (Core::kTile * kTurnPitch);
     const int lrow = lp.lane >> 4, lcol = lp.lane & 15;            // 4 rows x 16 chunks of 16 B
     const int gc = c0 + lp.wc * kGroupC + lcol * 8;
 #pragma unroll
@@ -925,7 +1022,7 @@ __device__ __forceinline__ void store_block_bf16(const typename Core::acc_t (&ac
             const int gr = r0 + lp.rbase(nt) + row;
             const u32x4_t v = *reinterpret_cast<const u32x4_t*>(tw + row * kTurnPitch + lcol * 16);
             if (!GUARD || (gr < rows_out && gc + 8 <= cols_out))
-                *reinterpret_cast<u32x4_t*>(D + (int64_t)gr * ldd + gc) = v;
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(D + (int64_t)gr * ldd + gc));
         }
     }
 }

@@ -47,40 +47,63 @@ ProfScope::~ProfScope() {
     g_prof_spans.push_back(ProfSpan{a, b, kind});
 }
 
-// Register-resident MFMA loop for alst_debug_mfma_rate: every wavefront multiplies four A and four
-// B operand registers it made itself into 16 accumulator tiles (256 accumulator registers, as the
-// block GEMMs), with no memory traffic at all.  data = 0: small integers, 1: uniform in [-1, 1).
+// Register-resident MFMA loops for alst_debug_mfma_rate: every wavefront multiplies A and B operand
+// registers it made itself into 256 accumulator registers (as the block GEMMs), with no memory
+// traffic at all.  FORM16 = false: v_mfma_f32_32x32x16_bf16, 4 x 4 operands, 16 accumulator tiles;
+// true: v_mfma_f32_16x16x32_bf16, 8 x 8 operands, 64 tiles.  One pass of the loop body is 2^21 flop
+// per wavefront either way.  data = 0: small integers, 1: uniform in [-1, 1).
 __device__ __forceinline__ uint32_t mix32(uint32_t x) {
     x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
     return x;
 }
+template <bool FORM16>
 __global__ __launch_bounds__(256) void mfma_rate_kernel(float* __restrict__ out, int iters, int data) {
-    bf16x8_t a[4], b[4];
+    constexpr int kOps = FORM16 ? 8 : 4;
+    bf16x8_t a[kOps], b[kOps];
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < kOps; ++t)
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const uint32_t ha = mix32((threadIdx.x * 8 + t) * 8 + j), hb = mix32((threadIdx.x * 8 + 4 + t + 77777) * 8 + j);
+            const uint32_t ha = mix32((threadIdx.x * 16 + t) * 8 + j), hb = mix32((threadIdx.x * 16 + 8 + t + 77777) * 8 + j);
             a[t][j] = (__bf16)(data == 0 ? (float)(ha & 3) : ((int)(ha & 0xffff) - 32768) / 32768.0f);
             b[t][j] = (__bf16)(data == 0 ? (float)(hb & 3) : ((int)(hb & 0xffff) - 32768) / 32768.0f);
         }
-    f32x16_t acc[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
-    for (int it = 0; it < iters; ++it) {
-#pragma unroll
-        for (int rep = 0; rep < 4; ++rep)
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 3], b[(i >> 2) & 3], acc[i], 0, 0, 0);
-    }
     float s = 0.f;
+    if (FORM16) {
+        f32x4_t acc[64];
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
+        for (int i = 0; i < 64; ++i)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) s += acc[i][j];
+            for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int rep = 0; rep < 2; ++rep)
+#pragma unroll
+                for (int i = 0; i < 64; ++i)
+                    acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i & 7], b[i >> 3], acc[i], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 64; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s += acc[i][j];
+    } else {
+        f32x16_t acc[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int rep = 0; rep < 4; ++rep)
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 3], b[(i >> 2) & 3], acc[i], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) s += acc[i][j];
+    }
     out[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
@@ -140,23 +163,25 @@ int alst_debug_block_tile(int tiles_r, int tiles_c, int parts, int bid, int* par
     return grid_for_patches(total);
 }
 
-// Sustained rate of the bf16 matrix instruction the block GEMMs use, on this device now: 256
-// workgroups of 4 wavefronts (one per SIMD of every compute unit) run 64 * iters
-// v_mfma_f32_32x32x16_bf16 each out of registers.  data = 0: small-integer operands, 1: random
-// operands in [-1, 1) (the rate depends on the operand bits through the power the multipliers
-// draw).  scratch: 256 * 256 floats of device memory, overwritten.  Synchronises the stream.
+// Sustained rate of the bf16 matrix instructions the block GEMMs use, on this device now: 256
+// workgroups of 4 wavefronts (one per SIMD of every compute unit) run iters * 2^21 flop each out
+// of registers.  data bit 0: 0 = small-integer operands, 1 = random operands in [-1, 1) (the rate
+// depends on the operand bits through the power the multipliers draw); data bit 1: 0 =
+// v_mfma_f32_32x32x16_bf16 (64 per pass), 1 = v_mfma_f32_16x16x32_bf16 (128 per pass).
+// scratch: 256 * 256 floats of device memory, overwritten.  Synchronises the stream.
 int alst_debug_mfma_rate(int data, int iters, float* scratch, double* tflops, void* stream) {
     if (!scratch || !tflops) return ALST_ERR_NULL;
-    if (iters < 1 || iters > (1 << 22) || (data != 0 && data != 1)) return ALST_ERR_SHAPE;
+    if (iters < 1 || iters > (1 << 22) || data < 0 || data > 3) return ALST_ERR_SHAPE;
     hipStream_t s = (hipStream_t)stream;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) {
         if (e0) (void)hipEventDestroy(e0);
         return ALST_ERR_HIP;
     }
-    hipLaunchKernelGGL(mfma_rate_kernel, dim3(256), dim3(256), 0, s, scratch, iters < 64 ? iters : 64, data);   // warm-up
+    auto* const kernel = (data & 2) ? mfma_rate_kernel<true> : mfma_rate_kernel<false>;
+    hipLaunchKernelGGL(kernel, dim3(256), dim3(256), 0, s, scratch, iters < 64 ? iters : 64, data & 1);   // warm-up
     (void)hipEventRecord(e0, s);
-    hipLaunchKernelGGL(mfma_rate_kernel, dim3(256), dim3(256), 0, s, scratch, iters, data);
+    hipLaunchKernelGGL(kernel, dim3(256), dim3(256), 0, s, scratch, iters, data & 1);
     (void)hipEventRecord(e1, s);
     float ms = 0.f;
     int rc = ALST_OK;
@@ -165,7 +190,7 @@ int alst_debug_mfma_rate(int data, int iters, float* scratch, double* tflops, vo
         rc = ALST_ERR_HIP;
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
-    // per launch: 256 workgroups x 4 wavefronts x iters x 64 instructions x 2 * 32 * 32 * 16 flop
+    // per launch: 256 workgroups x 4 wavefronts x iters x 2^21 flop (64 x 2 * 32 * 32 * 16 = 128 x 2 * 16 * 16 * 32)
     *tflops = rc == ALST_OK ? 256.0 * 4.0 * (double)iters * 64.0 * 32768.0 / ((double)ms * 1e9) : 0.0;
     return rc;
 }

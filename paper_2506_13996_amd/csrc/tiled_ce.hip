@@ -689,7 +689,7 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
                 const int row = it * 4 + lrow;
                 const u32x4_t v = *reinterpret_cast<const u32x4_t*>(tw + row * kTurnPitch + lcol * 16);
                 if (!REDO || p.rowstate[rb + row] != 0)
-                    *reinterpret_cast<u32x4_t*>(out + (int64_t)row * p.Vp) = v;
+                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(out + (int64_t)row * p.Vp));
             }
         }
         if (MODE != MODE_BWD) {

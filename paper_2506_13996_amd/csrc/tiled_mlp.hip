@@ -22,6 +22,7 @@
 // by the k-major cores: x and dy straight from the caller's arrays, a and [dg | du] from the
 // group's buffers.
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include <mutex>
 #include <stdint.h>
 #include <math.h>
@@ -147,6 +148,55 @@ __global__ __launch_bounds__(Core::kThreads) void linear_kernel(const LinearBatc
         Core::template gemm<GUARD>(p.X, p.ldx, p.rows_x, p.Y, p.ldy, p.rows_y, p.K, r0, c0, smem, acc, warm);
     }
     store_block_bf16<Core, GUARD>(acc, p.D, p.ldd, r0, c0, p.rows_out, p.cols_out, smem);
+}
+
+// The k-contiguous products on persistent workgroups: one workgroup per compute unit walks the
+// launch's blocks bid = blockIdx.x, blockIdx.x + gridDim.x, ... (the same block numbering as
+// linear_kernel, so the 32 workgroups of an XCD still share a patch) and fetches the first two
+// k-steps of its next block while the current block's last two k-steps and epilogue run
+// (DirectCore::Pipe).  total = the launch's block numbers (grid_for_patches).  Every product of
+// the launch has the same K, a multiple of 128 and >= 256.
+__global__ __launch_bounds__(DirectCore::kThreads) void linear_chain_kernel(const LinearBatch b, int total) {
+    typedef DirectCore Core;
+    extern __shared__ __align__(16) unsigned char smem[];
+    // the next block number from `bid` on that is not padding, or -1
+    auto next_block = [&](int bid, Core::Block& blk, int& which) {
+        for (; bid < total; bid += gridDim.x) {
+            int tr, tc, PR, PC;
+            if (!b.map.locate(bid, which, tr, tc, PR, PC)) continue;
+            const LinearParams& p = b.p[which];
+            const int r0 = tr * kBlockR, c0 = tc * kBlockC;
+            blk = {uniform(p.X), uniform(p.ldx), uniform(p.Y), uniform(p.ldy), uniform(p.rows_y), uniform(p.K),
+                   uniform(r0), uniform(c0), warm_row(PR, PC, p.X, p.ldx, r0, tr, p.Y, p.ldy, c0, tc), kBlockK,
+                   nullptr, -1};
+            which = uniform(which);
+            return uniform(bid);
+        }
+        return -1;
+    };
+    Core::Block cur, nxt;
+    int which, which_next = 0;
+    int bid = next_block(blockIdx.x, cur, which);
+    if (bid < 0) return;
+    Core::Pipe<false> pipe(smem);
+    pipe.start(cur);
+    while (bid >= 0) {
+        const int nbid = next_block(bid + gridDim.x, nxt, which_next);
+        if (nbid < 0) {            // the last block: the chain's fetch goes to this block again, unused
+            nxt = cur;
+            which_next = which;
+        }
+        typename Core::acc_t acc[Core::kMT][Core::kNT];
+        zero_acc<Core>(acc);
+        pipe.run(cur, nxt, acc);
+        const LinearParams& p = b.p[which];
+        store_block_bf16<Core, false>(acc, p.D, p.ldd, cur.r0, cur.c0, p.rows_out, p.cols_out,
+                                      smem + kChainTurnOffset);
+        cur = nxt;
+        which = which_next;
+        bid = nbid;
+    }
+    pipe.finish();
 }
 
 // Gate and up projections of a tile with the SwiGLU in the epilogue: the block's Y rows are the
@@ -323,6 +373,7 @@ static int prepare_mlp_kernels_on_current_device() {
     int rc = ALST_OK;
     auto acc = [&](int r) { if (r != ALST_OK) rc = r; };
     acc(allow_big_lds(linear_kernel<DirectCore, false>));
+    acc(allow_big_lds(linear_chain_kernel, kChainLdsBytes));
     acc(allow_big_lds(linear_kernel<StagedCore, true>));
     acc(allow_big_lds(linear_kernel<MixedCore, false>));
     acc(allow_big_lds(linear_kernel<StagedMixedCore, true>));
@@ -368,9 +419,15 @@ static int launch_linear(const LinearParams* ps, int n, hipStream_t s) {
     const int blocks = grid_for_patches(patches);
     ProfScope pr(PROF_MLP_LINEAR, s);
     const bool mixed = ps[0].y_kmajor != 0;           // the products of one launch are of one kind
+    // persistent workgroups that fetch their next block early: one K, whole pairs of k-steps
+    bool chain = ps[0].K % (2 * kBlockK) == 0 && ps[0].K >= 4 * kBlockK;
+    for (int i = 1; i < n; ++i) chain = chain && ps[i].K == ps[0].K;
     if (direct && mixed)
         hipLaunchKernelGGL((linear_kernel<MixedCore, false>), dim3((unsigned)blocks),
                            dim3(MixedCore::kThreads), kLdsBytes, s, b);
+    else if (direct && chain)
+        hipLaunchKernelGGL(linear_chain_kernel, dim3((unsigned)std::min(blocks, persistent_grid())),
+                           dim3(DirectCore::kThreads), kChainLdsBytes, s, b, blocks);
     else if (direct)
         hipLaunchKernelGGL((linear_kernel<DirectCore, false>), dim3((unsigned)blocks),
                            dim3(DirectCore::kThreads), kLdsBytes, s, b);
@@ -801,3 +858,4 @@ int alst_tiled_linear_backward(const void* x, const void* W, const void* dy, int
 }
 
 }  // extern "C"
+

@@ -47,6 +47,9 @@ CASES = [
     # unguarded core + the 12 rows left over on the guarded one
     ("aligned_ragged_rows", 1100, 256, 512, 512),
     ("aligned_few_rows", 40, 256, 256, 64),
+    # 4 x 97 output blocks on 256 persistent workgroups: chains of two blocks (the second fetched
+    # during the first one's last k-steps), chains of one, and padding block numbers in between
+    ("chained_blocks", 1024, 384, 24832, 1024),
 ]
 
 

@@ -433,11 +433,11 @@ def test_rows_outside_the_exponent_window_are_redone_with_their_exact_maximum():
 def test_mfma_rate_aid_reports_a_plausible_rate():
     """The benchmarking aid behind bench.py's `mfma_sustained`: a register-resident loop of the
     matrix instruction; its rate lies between a tenth of and just above the published 2.5 PFLOP/s."""
-    for data in (0, 1):
+    for data in (0, 1, 2, 3):          # bit 0: operand data, bit 1: instruction form
         r = B.alst_debug_mfma_rate(data, 5000)
         assert 250.0 < r < 2700.0, (data, r)
     with pytest.raises(B.AlstError):
-        B.alst_debug_mfma_rate(2, 5000)
+        B.alst_debug_mfma_rate(4, 5000)
     with pytest.raises(B.AlstError):
         B.alst_debug_mfma_rate(1, 0)
 
