@@ -934,20 +934,28 @@ struct DirectCore {
             for (int p = 2; p < 2 + kWarmAhead; ++p) warm_step(p, nullptr);
             issue_loads(0, 0);
             issue_loads(1, 1);
+            asm volatile("s_waitcnt vmcnt(16)" ::: "memory");     // step 0 has landed (loads complete in order)
         }
-        // acc += the product of `cur`, whose first two k-steps are in flight or have landed and
-        // which is the targeted block; fetches the first two k-steps of `next` and targets it.
+        // acc += the product of `cur`, the targeted block, whose k-step 0 this wavefront's DMA has
+        // landed and whose k-step 1 is in flight; fetches the first two k-steps of `next`, targets
+        // it and returns when this wavefront's part of its k-step 0 has landed.  The stores of the
+        // caller's epilogue are never waited for on their own: the barrier of the next block's
+        // k-step 0, half a step in, covers them together with the DMA of its k-step 1.
         __device__ __forceinline__ void run(const Block& cur, const Block& next, acc_t (&acc)[kMT][kNT]) {
             const int KT = uniform(cur.K / kBlockK);
-            // waits for the DMA (and for the stores of the epilogue before) and joins the waves
-            stage_barrier(false);
+            // every wavefront's part of k-step 0 has landed, and all are done with the block before
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 #pragma unroll
             for (int item = 0; item < 16; ++item) read_item(0, 0, item);
             int kt = 0;
+            for (; kt + 2 + kWarmAhead < KT; ++kt) kstep<true, true>(acc, kt, kt, kt > 0, nullptr);
+            // (the warm-up loads of these steps are for the first steps of `next`)
             for (; kt + 2 < KT; ++kt) kstep<true, true>(acc, kt, kt, kt > 0, &next);
             target(next);
             kstep<true, true>(acc, kt, -2, true, nullptr);
             kstep<true, false>(acc, kt + 1, -1, true, nullptr);
+            // all but the 16 DMA instructions of the last half step and the warm-up load behind them
+            asm volatile("s_waitcnt vmcnt(17)" ::: "memory");
         }
         __device__ __forceinline__ void finish() { stage_barrier(false); }
     };
