@@ -107,6 +107,8 @@ int alst_version(void);
  *   2 * Kg * (Vp + H)   bf16 dZ rows and dense hidden rows of the Kg rows in flight: Kg = Tp with
  *                       ALST_FLAG_TILE_SCRATCH, else Tp * clamp(16384 / Tp, 1, 8) (a group of tiles)
  *   4 * V * H           fp32 dW sums (absent for fp32 overwrite output, whose sums live in dW)
+ *   2 * Vp * H          bf16 copy of W transposed, made once per call that computes gradients (the
+ *                       dHidden product then reads both its operands along their rows)
  *   8 * (Vp / 128) * Tp   softmax partials of one tile
  * and with ALST_FLAG_FORWARD_ONLY only the last one and 2 * Tp * H remain.
  */

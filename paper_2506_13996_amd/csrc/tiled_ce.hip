@@ -97,7 +97,7 @@ struct Layout {
     int64_t dh_patches;    //          most patches (over all ranges) a tile of any number of rows needs
     int64_t dh_part_rows;  //          most rows of fp32 partial products (0: never cut)
     size_t header, tinfo, loss_rows, lse, idx, block_cnt, block_ofs, zlabel, yc, ref, frow, rowstate,
-        pm, ps, hc, stash, part, acc, total;
+        pm, ps, hc, stash, wt, part, acc, total;
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -163,6 +163,8 @@ static Layout make_layout(int64_t N, int64_t H, int64_t V, int64_t tile, uint32_
     // the two operands of the group's dW product as they are (k = dense row, the slow index)
     L.hc = take((size_t)L.Kg * L.Hk * 2);
     L.stash = take(fwd_only ? 0 : (size_t)L.Kg * L.Vp * 2);
+    // W transposed, [H, Vp] with zeros beyond V: the second operand of dH = dZ W, k-contiguous
+    L.wt = take(fwd_only ? 0 : (size_t)H * L.Vp * 2);
     {   // dHidden: the launch and the partial products are sized for the worst tile
         const PatchGrid pg = choose_patches((int)(L.Tp / kBlockR), (int)((H + kBlockC - 1) / kBlockC));
         L.dh_PR = pg.PR; L.dh_PC = pg.PC;
@@ -705,7 +707,7 @@ __global__ __launch_bounds__(Core::kThreads) void logits_kernel(const LogitsPara
 
 struct DHiddenParams {
     const uint16_t* dz;      // [Kg, Vp]     dense rows of the dW group; the tile starts at its k offset
-    const uint16_t* W;       // [V, H]       as it is: the k-major operand (k = vocabulary id)
+    const uint16_t* Wt;      // [H, Vp]      W transposed (k = vocabulary id contiguous), zero beyond V
     uint16_t* dH_t;          // [N, H]       whole dHidden; dense row i goes to row idx[i]
     const int32_t* idx;
     const TileInfo* info;
@@ -717,12 +719,49 @@ struct DHiddenParams {
     int PR, PC;              // patch shape of the block -> tile mapping
 };
 
-// r = token row (lane dimension), c = hidden index (register dimension), k = vocabulary.
+// Wt[h][v] = W[v][h], zero for V <= v < Vp: made once per call that computes gradients, so that
+// dH = dZ W runs with both operands k-contiguous (the fastest of the block GEMM's layouts: 4 % on
+// this product) for the price of reading and writing W once.  One workgroup turns a 64 x 64 piece
+// around in LDS; grid = (Vp / 64, ceil(H / 64)).
+__global__ __launch_bounds__(256) void transpose_w_kernel(const uint16_t* __restrict__ W, int V, int H, int Vp,
+                                                          uint16_t* __restrict__ Wt) {
+    __shared__ uint16_t piece[64][64 + 2];
+    const int v0 = blockIdx.x * 64, h0 = blockIdx.y * 64;
+    const int t = threadIdx.x;
+    // in: 64 rows (v) x 8 chunks of 8 h; thread -> (row t / 8 + 32 j, chunk t % 8)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int v = t / 8 + 32 * j, hc = (t % 8) * 8;
+        u32x4_t x = {0u, 0u, 0u, 0u};
+        if (v0 + v < V && h0 + hc < H)        // H is a multiple of 8: whole chunks
+            x = *reinterpret_cast<const u32x4_t*>(W + (int64_t)(v0 + v) * H + h0 + hc);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            piece[v][hc + 2 * q] = (uint16_t)(x[q] & 0xffffu);
+            piece[v][hc + 2 * q + 1] = (uint16_t)(x[q] >> 16);
+        }
+    }
+    __syncthreads();
+    // out: 64 rows (h) x 8 chunks of 8 v
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int h = t / 8 + 32 * j, vc = (t % 8) * 8;
+        if (h0 + h >= H) continue;
+        u32x4_t y;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            y[q] = (uint32_t)piece[vc + 2 * q][h] | ((uint32_t)piece[vc + 2 * q + 1][h] << 16);
+        *reinterpret_cast<u32x4_t*>(Wt + (int64_t)(h0 + h) * Vp + v0 + vc) = y;
+    }
+}
+
+// r = token row (lane dimension), c = hidden index (register dimension), k = vocabulary; both
+// operands k-contiguous (dZ rows and the rows of W transposed).
 // The output has only (T / 256) * (H / 256) blocks, each with a long contraction: when that
 // number does not fill the compute units evenly, the contraction is cut into `splits` ranges, each
 // range's blocks write fp32 partial products, and dhidden_reduce_kernel adds them in a fixed
 // order.
-template <class Core, bool GUARD, bool YTAIL>
+template <class Core>
 __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenParams p) {
     constexpr int kMT = Core::kMT, kNT = Core::kNT;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -738,7 +777,7 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
     const int splits = p.info->splits, ksteps = p.info->ksteps;
     if (split >= splits || !tile_in_patch(pg, P - split * np, w, tr, tc)) return;
     const int r0 = tr * kBlockR, c0 = tc * kBlockC;
-    // k runs over V rounded up to whole k-steps: dZ is zero there, rows of W beyond V are not read
+    // k runs over V rounded up to whole k-steps: dZ and Wt are zero there
     const int k0 = split * ksteps * kBlockK;
     const int klen = min(ksteps * kBlockK, (p.V + kBlockK - 1) / kBlockK * kBlockK - k0);     // > 0
 
@@ -746,14 +785,11 @@ __global__ __launch_bounds__(Core::kThreads) void dhidden_kernel(const DHiddenPa
     zero_acc<Core>(acc);
 
     const uint16_t* const dz = p.dz + (int64_t)p.info->kofs * p.Vp + k0;
-    const uint16_t* const Wk = p.W + (int64_t)k0 * p.H;
-    int64_t step = 0;
-    const uint16_t* warm = Core::kCanGuard ? nullptr
-                                           : warm_line_mixed(p.PR, p.PC, dz, p.Vp, r0, tr, Wk, p.H, c0,
-                                                             tc, step, p.H, p.V - k0);
-    // YTAIL: the vocabulary is not whole k-steps and the last range's last step lacks rows of W
-    Core::template gemm<GUARD, YTAIL>(dz, p.Vp, Trc, Wk, p.H, p.H, klen, r0, c0, smem, acc, warm, step,
-                                      nullptr, p.V - k0);
+    const uint16_t* const Wk = p.Wt + k0;
+    // (a hidden size that ends inside the block: the rows of Wt beyond H are read from its last
+    // row, and the epilogue skips those columns)
+    const uint16_t* warm = warm_row(p.PR, p.PC, dz, p.Vp, r0, tr, Wk, p.Vp, c0, tc, nullptr, p.H);
+    Core::template gemm<false>(dz, p.Vp, Trc, Wk, p.Vp, p.H, klen, r0, c0, smem, acc, warm);
 
     const typename Core::Lane lp;
     if (splits > 1) {
@@ -879,8 +915,7 @@ static int prepare_kernels_on_current_device() {
     acc(allow_big_lds(logits_kernel<DirectCore, true, MODE_FWD, true>));
     acc(allow_big_lds(logits_kernel<DirectCore, false, MODE_FUSED, true>));
     acc(allow_big_lds(logits_kernel<DirectCore, true, MODE_FUSED, true>));
-    acc(allow_big_lds(dhidden_kernel<MixedCore, false, false>));
-    acc(allow_big_lds(dhidden_kernel<MixedCore, false, true>));
+    acc(allow_big_lds(dhidden_kernel<DirectCore>));
     acc(allow_big_lds(dw_kernel<KMajorCore, false>));
     return rc;
 }
@@ -1008,6 +1043,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
     int32_t* rowstate = reinterpret_cast<int32_t*>(P.ws + L.rowstate);
     uint16_t* hc = reinterpret_cast<uint16_t*>(P.ws + L.hc);
     uint16_t* stash = reinterpret_cast<uint16_t*>(P.ws + L.stash);
+    uint16_t* wt = reinterpret_cast<uint16_t*>(P.ws + L.wt);
     const bool acc_in_dw = (P.flags & ALST_FLAG_DW_FP32) && !(P.flags & ALST_FLAG_DW_ACCUMULATE);
     float* acc = acc_in_dw ? reinterpret_cast<float*>(P.dW) : reinterpret_cast<float*>(P.ws + L.acc);
 
@@ -1037,9 +1073,15 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
     // are read from each row's last chunk)
     const bool ktail_logits = (H % kBlockK) != 0;
     // (a hidden size that ends inside a block is handled by the unguarded dHidden and dW kernels:
-    // the missing columns of W and of the dense hidden rows are read from the last ones and the
-    // results discarded; a vocabulary that is not whole k-steps by the unguarded dHidden kernel:
-    // the rows W lacks in the last k-step are read from its last row and meet zeros of dZ)
+    // the missing rows of W transposed / columns of the dense hidden rows are read from the last
+    // ones and the results discarded; a vocabulary that is not whole k-steps: dZ and W transposed
+    // are zero up to the padded vocabulary)
+    if (do_bwd) {
+        ProfScope small_(PROF_OTHER, s);
+        hipLaunchKernelGGL(transpose_w_kernel, dim3((unsigned)(Vp / 64), (unsigned)((H + 63) / 64)), dim3(256), 0,
+                           s, reinterpret_cast<const uint16_t*>(P.W), V, H, Vp, wt);
+        ALST_HIP(hipGetLastError());
+    }
 
     // The host does not know M: it walks ceil(N / T) tiles, the most there can be; the kernels of
     // a tile beyond the dense rows find Tc = 0 on the device and leave at once.
@@ -1082,7 +1124,7 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
 
         {
             DHiddenParams dp;
-            dp.dz = stash; dp.W = P.W; dp.dH_t = P.dHidden; dp.idx = idx_t;
+            dp.dz = stash; dp.Wt = wt; dp.dH_t = P.dHidden; dp.idx = idx_t;
             dp.info = info; dp.hdr = hdr; dp.frow = frow;
             dp.part = reinterpret_cast<float*>(P.ws + L.part);
             dp.Tp = Tp; dp.H = H; dp.V = V; dp.Vp = Vp;
@@ -1090,12 +1132,8 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
             // enough workgroups for whatever number of rows and ranges the tile turns out to have
             const int grid = grid_for_patches(L.dh_patches);
             ProfScope ps_(PROF_DHIDDEN, s);
-            if (V % kBlockK != 0)
-                hipLaunchKernelGGL((dhidden_kernel<MixedCore, false, true>), dim3(grid),
-                                   dim3(MixedCore::kThreads), kLdsBytes, s, dp);
-            else
-                hipLaunchKernelGGL((dhidden_kernel<MixedCore, false, false>), dim3(grid),
-                                   dim3(MixedCore::kThreads), kLdsBytes, s, dp);
+            hipLaunchKernelGGL((dhidden_kernel<DirectCore>), dim3(grid), dim3(DirectCore::kThreads), kLdsBytes,
+                               s, dp);
             if (L.dh_part_rows > 0)
                 hipLaunchKernelGGL(dhidden_reduce_kernel, dim3(Tr), dim3(256), 0, s, dp.part, H, idx_t,
                                    info, hdr, frow, P.dHidden);

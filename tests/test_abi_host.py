@@ -64,15 +64,16 @@ def test_workspace_is_independent_of_n_beyond_12_bytes_per_row(lib):
 
 def test_workspace_follows_the_tile_as_documented(lib):
     """The large terms of the workspace (alst.h): 2 Kg (Vp + H) bytes of dZ and dense hidden rows,
-    4 V H of dW sums, 8 (Vp / 128) Tp of softmax partials; Kg is one tile under
-    ALST_FLAG_TILE_SCRATCH and a group of tiles (about 16384 rows) without it."""
+    4 V H of dW sums, 2 Vp H of W transposed, 8 (Vp / 128) Tp of softmax partials; Kg is one tile
+    under ALST_FLAG_TILE_SCRATCH and a group of tiles (about 16384 rows) without it."""
     H, V, N = 4096, 128256, 131072
     Vp = (V + 255) // 256 * 256
     small = 12 * N + 12 * N // 1024 + 64 * 1024          # the O(N) part and the roundings to 256 bytes
 
     def expect(T, kg, acc=True, part_rows=0):
         Tp = (T + 255) // 256 * 256
-        return 2 * kg * (Vp + H) + (4 * V * H if acc else 0) + 8 * (Vp // 128) * Tp + 20 * Tp + 4 * part_rows * H
+        return (2 * kg * (Vp + H) + (4 * V * H if acc else 0) + 2 * Vp * H + 8 * (Vp // 128) * Tp + 20 * Tp
+                + 4 * part_rows * H)
 
     for T, g in ((128, 8), (2048, 8), (4096, 4), (8192, 2), (16384, 1), (32768, 1)):
         Tp = (T + 255) // 256 * 256
@@ -83,11 +84,13 @@ def test_workspace_follows_the_tile_as_documented(lib):
         lo = expect(T, Tp)
         assert lo <= w1 <= lo + 4 * 8 * Tp * H + small, T       # at most 8 ranges of partial products
         # the tile bounds the dZ scratch: no more than 2 bytes per logit of ONE tile
-        assert w1 - 4 * V * H - 4 * 8 * Tp * H - small <= 2 * Tp * Vp + 2 * Tp * H + 8 * (Vp // 128) * Tp + 20 * Tp
-    # halving the tile halves everything but the dW sums and the O(N) part
+        assert (w1 - 4 * V * H - 2 * Vp * H - 4 * 8 * Tp * H - small
+                <= 2 * Tp * Vp + 2 * Tp * H + 8 * (Vp // 128) * Tp + 20 * Tp)
+    # halving the tile halves everything but the dW sums, W transposed and the O(N) part
     a = B.alst_tiled_ce_workspace_bytes(N, H, V, 4096, B.ALST_FLAG_TILE_SCRATCH | B.ALST_FLAG_DW_FP32)
     b = B.alst_tiled_ce_workspace_bytes(N, H, V, 2048, B.ALST_FLAG_TILE_SCRATCH | B.ALST_FLAG_DW_FP32)
-    assert abs((a - 12 * N) - 2 * (b - 12 * N)) <= 4 * 8 * 2048 * H + small
+    fixed = 12 * N + 2 * Vp * H
+    assert abs((a - fixed) - 2 * (b - fixed)) <= 4 * 8 * 2048 * H + small
     # forward only: no dZ rows, no dW sums, no partial products
     f = B.alst_tiled_ce_workspace_bytes(N, H, V, 4096, B.ALST_FLAG_FORWARD_ONLY)
     assert f <= 2 * 4096 * H + 8 * (Vp // 128) * 4096 + 20 * 4096 + small

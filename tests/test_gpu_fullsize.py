@@ -193,10 +193,12 @@ def test_other_entry_points_and_one_tile_scratch_at_full_size():
     peak = torch.cuda.max_memory_allocated() - base
     # the scratch is 2 bytes per logit of one tile (+ the tile's hidden rows, the softmax partials,
     # the dHidden partial products and the 12 N bytes of per-row state), beside the fp32 dW sums
+    # and the bf16 copy of W transposed
     Vp, Tp = (V + 255) // 256 * 256, (T + 255) // 256 * 256
-    assert ws.numel() <= 2 * Tp * (Vp + H) + 4 * V * H + 8 * (Vp // 128) * Tp + 4 * 8 * Tp * H + 13 * N + (1 << 20)
+    assert ws.numel() <= (2 * Tp * (Vp + H) + 4 * V * H + 2 * Vp * H + 8 * (Vp // 128) * Tp + 4 * 8 * Tp * H
+                          + 13 * N + (1 << 20))
     assert peak < 0.6 * 4 * N * V, (peak, 4 * N * V)
-    assert peak < 0.4 * 4 * N * V, (peak, 4 * N * V)          # measured: about a third
+    assert peak < 0.45 * 4 * N * V, (peak, 4 * N * V)         # measured: 0.38
     oracle_rows = _check_against_golden(name, wl, gold, h, W, y, loss, lse, nv, dH, dW, tag=" tile scratch")
     lse_fused = lse.clone()
     del ws
