@@ -38,8 +38,10 @@ extern "C" {
 /*
  * Bytes of device scratch alst_tiled_mlp_forward (backward = 0) or alst_tiled_mlp_backward
  * (backward = 1) needs, 0 if the shape is invalid.  Pure host arithmetic.  Independent of N:
- * O(tile * I) for the activations of the tiles in flight, plus O(H * I) for the fp32
- * weight-gradient sums in backward.
+ * O(tile * I) for the activations of the tiles in flight, plus O(H * I) in backward: the fp32
+ * weight-gradient sums (12 H I bytes; absent for fp32 overwrite outputs) and, for H and I that
+ * are multiples of 64, bf16 copies of the three weight matrices transposed (6 H I bytes, made once
+ * per call, so that the products with a weight over its row index read it along its rows).
  */
 size_t alst_tiled_mlp_workspace_bytes(int64_t N, int64_t H, int64_t I, int64_t tile, int backward,
                                       uint32_t flags);

@@ -976,6 +976,46 @@ struct DirectCore {
 };
 
 // ---------------------------------------------------------------------------------------------
+// out[c][r] = in[r][c] (bf16), zeros for rows <= r < the 64 rows of the last piece
+// ---------------------------------------------------------------------------------------------
+// Weights that a product contracts over their row index are transposed once per call, so that
+// the product reads both operands along their rows (DirectCore).  in: [rows, ld_in], cols a
+// multiple of 8, 16-byte aligned rows; out: [cols, ld_out], ld_out >= rows rounded up to 64.  One
+// workgroup of 256 turns a 64 x 64 piece around in LDS; grid = (ceil(rows / 64), ceil(cols / 64)).
+static __global__ __launch_bounds__(256) void transpose_bf16_kernel(const uint16_t* __restrict__ in, int rows,
+                                                                    int cols, int64_t ld_in,
+                                                                    uint16_t* __restrict__ out, int64_t ld_out) {
+    __shared__ uint16_t piece[64][64 + 2];
+    const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+    const int t = threadIdx.x;
+    // in: 64 rows x 8 chunks of 8 columns; thread -> (row t / 8 + 32 j, chunk t % 8)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int r = t / 8 + 32 * j, cc = (t % 8) * 8;
+        u32x4_t x = {0u, 0u, 0u, 0u};
+        if (r0 + r < rows && c0 + cc < cols)
+            x = *reinterpret_cast<const u32x4_t*>(in + (int64_t)(r0 + r) * ld_in + c0 + cc);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            piece[r][cc + 2 * q] = (uint16_t)(x[q] & 0xffffu);
+            piece[r][cc + 2 * q + 1] = (uint16_t)(x[q] >> 16);
+        }
+    }
+    __syncthreads();
+    // out: 64 rows (columns of in) x 8 chunks of 8
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int c = t / 8 + 32 * j, rc = (t % 8) * 8;
+        if (c0 + c >= cols) continue;
+        u32x4_t y;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            y[q] = (uint32_t)piece[rc + 2 * q][c] | ((uint32_t)piece[rc + 2 * q + 1][c] << 16);
+        *reinterpret_cast<u32x4_t*>(out + (int64_t)(c0 + c) * ld_out + r0 + rc) = y;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Epilogues shared by the kernels built on the cores (written against the cores' layout traits)
 // ---------------------------------------------------------------------------------------------
 constexpr int kTurnPitch = 272;     // bytes per row of the LDS turn-around area: 256 + 16 of padding

@@ -719,41 +719,9 @@ struct DHiddenParams {
     int PR, PC;              // patch shape of the block -> tile mapping
 };
 
-// Wt[h][v] = W[v][h], zero for V <= v < Vp: made once per call that computes gradients, so that
-// dH = dZ W runs with both operands k-contiguous (the fastest of the block GEMM's layouts: 4 % on
-// this product) for the price of reading and writing W once.  One workgroup turns a 64 x 64 piece
-// around in LDS; grid = (Vp / 64, ceil(H / 64)).
-__global__ __launch_bounds__(256) void transpose_w_kernel(const uint16_t* __restrict__ W, int V, int H, int Vp,
-                                                          uint16_t* __restrict__ Wt) {
-    __shared__ uint16_t piece[64][64 + 2];
-    const int v0 = blockIdx.x * 64, h0 = blockIdx.y * 64;
-    const int t = threadIdx.x;
-    // in: 64 rows (v) x 8 chunks of 8 h; thread -> (row t / 8 + 32 j, chunk t % 8)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int v = t / 8 + 32 * j, hc = (t % 8) * 8;
-        u32x4_t x = {0u, 0u, 0u, 0u};
-        if (v0 + v < V && h0 + hc < H)        // H is a multiple of 8: whole chunks
-            x = *reinterpret_cast<const u32x4_t*>(W + (int64_t)(v0 + v) * H + h0 + hc);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            piece[v][hc + 2 * q] = (uint16_t)(x[q] & 0xffffu);
-            piece[v][hc + 2 * q + 1] = (uint16_t)(x[q] >> 16);
-        }
-    }
-    __syncthreads();
-    // out: 64 rows (h) x 8 chunks of 8 v
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int h = t / 8 + 32 * j, vc = (t % 8) * 8;
-        if (h0 + h >= H) continue;
-        u32x4_t y;
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            y[q] = (uint32_t)piece[vc + 2 * q][h] | ((uint32_t)piece[vc + 2 * q + 1][h] << 16);
-        *reinterpret_cast<u32x4_t*>(Wt + (int64_t)(h0 + h) * Vp + v0 + vc) = y;
-    }
-}
+// dH = dZ W runs with both operands k-contiguous (the fastest of the block GEMM's layouts: 9 % on
+// this product): W transposed, [H, Vp] with zeros for V <= v < Vp, is made once per call that
+// computes gradients (transpose_bf16_kernel), for the price of reading and writing W once.
 
 // r = token row (lane dimension), c = hidden index (register dimension), k = vocabulary; both
 // operands k-contiguous (dZ rows and the rows of W transposed).
@@ -1078,8 +1046,8 @@ static int run(const Problem& P, bool do_fwd, bool do_bwd) {
     // are zero up to the padded vocabulary)
     if (do_bwd) {
         ProfScope small_(PROF_OTHER, s);
-        hipLaunchKernelGGL(transpose_w_kernel, dim3((unsigned)(Vp / 64), (unsigned)((H + 63) / 64)), dim3(256), 0,
-                           s, reinterpret_cast<const uint16_t*>(P.W), V, H, Vp, wt);
+        hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)(Vp / 64), (unsigned)((H + 63) / 64)), dim3(256),
+                           0, s, reinterpret_cast<const uint16_t*>(P.W), V, H, (int64_t)H, wt, (int64_t)Vp);
         ALST_HIP(hipGetLastError());
     }
 

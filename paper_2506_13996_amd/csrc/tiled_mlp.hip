@@ -40,7 +40,8 @@ constexpr int kMlpGroupMax = 8;
 struct MlpLayout {
     int64_t Tp, Kg;        // tile rows rounded up to 256; rows a weight-gradient group can hold
     int g;                 // tiles per weight-gradient group
-    size_t a, da, dgu, acc_g, acc_u, acc_d, total;
+    size_t a, da, dgu, wdt, wgut, acc_g, acc_u, acc_d, total;
+    bool weights_t;        // backward multiplies by transposed copies of the weights
 };
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -60,6 +61,13 @@ static MlpLayout make_mlp_layout(int64_t N, int64_t H, int64_t I, int64_t tile, 
     if (backward) {
         L.da = take((size_t)L.Tp * I * 2);
         L.dgu = take((size_t)L.Kg * 2 * I * 2);
+        // Wd transposed [I, H] and [Wg | Wu] transposed [H, 2 I], made once per call: da = dy Wd and
+        // dx = [dg | du] [Wg ; Wu] then read both operands along their rows (the fastest layout
+        // of the block GEMM).  For H and I that are whole k-steps; else the weights are read as
+        // they are.
+        L.weights_t = H % kBlockK == 0 && I % kBlockK == 0;
+        L.wdt = take(L.weights_t ? (size_t)I * H * 2 : 0);
+        L.wgut = take(L.weights_t ? (size_t)H * 2 * I * 2 : 0);
         // fp32 overwrite outputs hold the sums themselves
         const bool in_out = (flags & ALST_FLAG_DW_FP32) && !(flags & ALST_FLAG_DW_ACCUMULATE);
         L.acc_g = take(in_out ? 0 : (size_t)I * H * 4);
@@ -594,6 +602,17 @@ static int run_mlp_backward(const MlpProblem& P) {
     const int H = (int)P.H, I = (int)P.I;
     const int64_t I2 = 2 * (int64_t)I;
 
+    uint16_t* wdt = reinterpret_cast<uint16_t*>(P.ws + L.wdt);
+    uint16_t* wgut = reinterpret_cast<uint16_t*>(P.ws + L.wgut);
+    if (L.weights_t) {
+        ProfScope ps(PROF_MLP_OTHER, s);
+        const dim3 gd((unsigned)((H + 63) / 64), (unsigned)((I + 63) / 64)), gi(gd.y, gd.x);
+        hipLaunchKernelGGL(transpose_bf16_kernel, gd, dim3(256), 0, s, P.Wd, H, I, (int64_t)I, wdt, (int64_t)H);
+        hipLaunchKernelGGL(transpose_bf16_kernel, gi, dim3(256), 0, s, P.Wg, I, H, (int64_t)H, wgut, I2);
+        hipLaunchKernelGGL(transpose_bf16_kernel, gi, dim3(256), 0, s, P.Wu, I, H, (int64_t)H, wgut + I, I2);
+        ALST_HIP(hipGetLastError());
+    }
+
     const int64_t T = P.tile < P.N ? P.tile : P.N;
     const int64_t ntiles = (P.N + T - 1) / T;
     int kofs = 0;                                   // rows of the group so far
@@ -614,17 +633,24 @@ static int run_mlp_backward(const MlpProblem& P) {
         {   // da = dy_t Wd (contraction over H), then g and u again with a, dg, du made in the epilogue
             LinearParams lp = {};
             lp.X = dy_t; lp.ldx = H; lp.rows_x = T_cur; lp.K = H;
-            lp.Y = P.Wd; lp.ldy = I; lp.rows_y = I; lp.y_kmajor = 1;       // Wd [H, I]: k = h
+            if (L.weights_t) { lp.Y = wdt; lp.ldy = H; lp.rows_y = I; }            // Wd^T [I, H]
+            else { lp.Y = P.Wd; lp.ldy = I; lp.rows_y = I; lp.y_kmajor = 1; }      // Wd [H, I]: k = h
             lp.D = da; lp.ldd = I; lp.rows_out = Tr; lp.cols_out = I;
             rc = launch_linear(lp, s);
             if (rc == ALST_OK) rc = launch_gated(P, x_t, T_cur, Tr, da, a_t, dgu_t, s);
             if (rc != ALST_OK) return rc;
         }
-        {   // dx = dg Wg + du Wu: two contractions over I summed in the accumulators
+        {   // dx = dg Wg + du Wu
             LinearParams lp = {};
-            lp.X = dgu_t; lp.ldx = I2; lp.rows_x = Tr; lp.K = I;
-            lp.Y = P.Wg; lp.ldy = H; lp.rows_y = H; lp.y_kmajor = 1;       // Wg [I, H]: k = i
-            lp.X2 = dgu_t + I; lp.Y2 = P.Wu;
+            lp.X = dgu_t; lp.ldx = I2; lp.rows_x = Tr;
+            if (L.weights_t) {
+                // one contraction over the 2 I columns of [dg | du] against [Wg | Wu]^T [H, 2 I]
+                lp.K = (int)I2; lp.Y = wgut; lp.ldy = I2; lp.rows_y = H;
+            } else {
+                // two contractions over I summed in the accumulators, the weights as they are
+                lp.K = I; lp.Y = P.Wg; lp.ldy = H; lp.rows_y = H; lp.y_kmajor = 1;     // Wg [I, H]: k = i
+                lp.X2 = dgu_t + I; lp.Y2 = P.Wu;
+            }
             lp.D = P.dx + i0 * P.H; lp.ldd = H; lp.rows_out = T_cur; lp.cols_out = H;
             rc = launch_linear(lp, s);
             if (rc != ALST_OK) return rc;
