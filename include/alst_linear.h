@@ -26,7 +26,10 @@ extern "C" {
 #endif
 
 /* Bytes of device scratch for forward (backward = 0: always 0) or backward (backward = 1);
- * independent of N and of the tile.  Pure host arithmetic; 0 also for an invalid shape. */
+ * independent of N and of the tile: 4 M K for the fp32 dW sums (absent for fp32 overwrite output,
+ * whose sums live in dW) and, for M a multiple of 64, 2 M K for a bf16 copy of W transposed (made
+ * once per call, so that dx = dy W reads both operands along their rows).  Pure host arithmetic;
+ * 0 also for an invalid shape. */
 size_t alst_tiled_linear_workspace_bytes(int64_t N, int64_t K, int64_t M, int64_t tile, int backward,
                                          uint32_t flags);
 

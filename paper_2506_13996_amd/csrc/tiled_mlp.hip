@@ -694,7 +694,8 @@ static int run_mlp_backward(const MlpProblem& P) {
 struct LinLayout {
     int64_t Tp;
     int g;                 // tiles per weight-gradient group
-    size_t acc, total;
+    size_t acc, wt, total;
+    bool weight_t;         // backward multiplies dy by a transposed copy of W
 };
 
 static LinLayout make_lin_layout(int64_t N, int64_t K, int64_t M, int64_t tile, bool backward,
@@ -709,6 +710,11 @@ static LinLayout make_lin_layout(int64_t N, int64_t K, int64_t M, int64_t tile, 
     if (backward) {
         const bool in_out = (flags & ALST_FLAG_DW_FP32) && !(flags & ALST_FLAG_DW_ACCUMULATE);
         L.acc = take(in_out ? 0 : (size_t)M * K * 4);
+        // W transposed [K, M], made once per call: dx = dy W then reads both operands along their
+        // rows (the fastest layout of the block GEMM).  For M a multiple of 64; else W is read
+        // as it is.
+        L.weight_t = M % kBlockK == 0;
+        L.wt = take(L.weight_t ? (size_t)K * M * 2 : 0);
     }
     L.total = o;
     return L;
@@ -774,6 +780,13 @@ static int run_lin_backward(const LinProblem& P) {
     const int K = (int)P.K, M = (int)P.M;
     const int64_t T = P.tile < P.N ? P.tile : P.N;
     const int64_t ntiles = (P.N + T - 1) / T;
+    uint16_t* wt = reinterpret_cast<uint16_t*>(P.ws + L.wt);
+    if (L.weight_t) {
+        ProfScope ps(PROF_MLP_OTHER, s);
+        hipLaunchKernelGGL(transpose_bf16_kernel, dim3((unsigned)((M + 63) / 64), (unsigned)((K + 63) / 64)),
+                           dim3(256), 0, s, P.W, M, K, (int64_t)K, wt, (int64_t)M);
+        ALST_HIP(hipGetLastError());
+    }
     int kofs = 0;                                   // rows of the group so far
     int64_t group_row0 = 0;
     for (int64_t t = 0; t < ntiles; ++t) {
@@ -783,7 +796,8 @@ static int run_lin_backward(const LinProblem& P) {
         if (slot == 0) { kofs = 0; group_row0 = i0; }
         LinearParams lp = {};
         lp.X = P.dy + i0 * P.M; lp.ldx = M; lp.rows_x = T_cur; lp.K = M;
-        lp.Y = P.W; lp.ldy = K; lp.rows_y = K; lp.y_kmajor = 1;           // W [M, K]: k = m
+        if (L.weight_t) { lp.Y = wt; lp.ldy = M; lp.rows_y = K; }         // W^T [K, M]
+        else { lp.Y = P.W; lp.ldy = K; lp.rows_y = K; lp.y_kmajor = 1; }  // W [M, K]: k = m
         lp.D = P.dx + i0 * P.K; lp.ldd = K; lp.rows_out = T_cur; lp.cols_out = K;
         rc = launch_linear(lp, s);
         if (rc != ALST_OK) return rc;

@@ -89,7 +89,7 @@ int main() {
                                                        fake(0x70000), fake(0x80000), fake(0x90000),
                                                        fake(0xa0000), wb - 1, f, nullptr) == ALST_ERR_WORKSPACE);
                         const size_t wl = alst_tiled_linear_workspace_bytes(N, H, I, T, 1, f);
-                        EXPECT((wl == 0) == (f == ALST_FLAG_DW_FP32));
+                        EXPECT((wl == 0) == (f == ALST_FLAG_DW_FP32 && I % 64 != 0));     // sums in dW, W as it is
                         if (wl)
                             EXPECT(alst_tiled_linear_backward(fake(0x10000), fake(0x20000), fake(0x30000), N,
                                                               H, I, T, fake(0x40000), fake(0x50000),

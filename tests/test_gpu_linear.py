@@ -73,12 +73,14 @@ def test_linear_flags_and_workspace_contract():
     base = (torch.randn(264, 128, generator=torch.Generator().manual_seed(1)) * float(np.abs(rW).max())).cuda()
     _, _, acc = _run(x, W, dy, 256, flags=B.ALST_FLAG_DW_FP32 | B.ALST_FLAG_DW_ACCUMULATE, init=base)
     assert G.grad_err(acc - base.cpu().numpy().astype(np.float64), rW) <= TOL
-    # forward needs no workspace; backward's is independent of N
+    # forward needs no workspace; backward's is independent of N: the fp32 dW sums and, for an
+    # output width that is a multiple of 64, the bf16 copy of W transposed
     assert B.alst_tiled_linear_workspace_bytes(10 ** 6, 4096, 4096, 4096, False) == 0
     a = B.alst_tiled_linear_workspace_bytes(8192, 4096, 4096, 4096, True)
-    assert a == B.alst_tiled_linear_workspace_bytes(10 ** 6, 4096, 4096, 4096, True) == 4 * 4096 * 4096
-    # the fp32 sums live in dW itself for fp32 overwrite output: no scratch at all
-    assert B.alst_tiled_linear_workspace_bytes(8192, 4096, 4096, 4096, True, B.ALST_FLAG_DW_FP32) == 0
+    assert a == B.alst_tiled_linear_workspace_bytes(10 ** 6, 4096, 4096, 4096, True) == 6 * 4096 * 4096
+    # the fp32 sums live in dW itself for fp32 overwrite output
+    assert B.alst_tiled_linear_workspace_bytes(8192, 4096, 4096, 4096, True, B.ALST_FLAG_DW_FP32) == 2 * 4096 * 4096
+    assert B.alst_tiled_linear_workspace_bytes(8192, 4096, 4104, 4096, True, B.ALST_FLAG_DW_FP32) == 0
 
 
 def test_linear_random_shapes_against_oracle():
