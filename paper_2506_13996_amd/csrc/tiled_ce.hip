@@ -32,9 +32,10 @@
 //                        the group's dense rows, fp32)
 //
 // After the last tile: loss = sum(per-row loss) / M in a fixed order, dW = (g/M) acc.
-// The contractions share the block GEMM of gemm_tile.h in its three operand layouts: logits with
-// both operands k-contiguous, dHidden with dZ k-contiguous and W k-major (as it is), dW with both
-// operands k-major (the group's dense hidden rows and dZ rows as they are).  Nothing is transposed.
+// The contractions share the block GEMM of gemm_tile.h: logits and dHidden with both operands
+// k-contiguous (dHidden against a copy of W transposed once per call), dW with both operands
+// k-major (the group's dense hidden rows and dZ rows as they are).  No per-tile array is
+// transposed.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <math.h>

@@ -9,11 +9,13 @@
 //   forward    a  = silu(x Wg^T) * (x Wu^T)   gated_kernel: both products in one block, SwiGLU in
 //                                             the epilogue, g and u never reach memory
 //              y  = a Wd^T
-//   backward   da = dy Wd                     Wd as it is: the k-major operand (k = h)
+//   backward   da = dy Wd                     against Wd^T, transposed once per call
 //              a, [dg | du]                   gated_kernel again (g and u recomputed), its epilogue
 //                                             reads da; written into the rows of the tile's group
-//              dx = dg Wg + du Wu             one launch, two contractions over I into the same
-//                                             accumulators, Wg and Wu as they are (k = i)
+//              dx = dg Wg + du Wu             one contraction over the 2 I columns of [dg | du]
+//                                             against [Wg | Wu]^T, transposed once per call
+//                                             (H or I not a multiple of 64: the weights as they are,
+//                                             k-major operands, dx as two contractions over I)
 //   per group  dWg += dg^T x, dWu += du^T x, dWd += dy^T a   (fp32, contraction over the group's rows)
 //
 // As in the cross-entropy path the weight gradients are accumulated once per group of tiles
@@ -737,7 +739,7 @@ static int validate_lin(const LinProblem& P, size_t workspace_bytes, bool backwa
     if (P.flags & ~(ALST_FLAG_DW_FP32 | ALST_FLAG_DW_ACCUMULATE)) return ALST_ERR_UNSUPPORTED;
     if (P.N < 1 || P.K < 1 || P.M < 1 || P.tile < 1) return ALST_ERR_SHAPE;
     if (P.N > (int64_t)1 << 30 || P.K > (int64_t)1 << 20 || P.M > (int64_t)1 << 24) return ALST_ERR_SHAPE;
-    // the only scratch is the fp32 dW sums, which live in dW itself for fp32 overwrite output
+    // (forward needs no scratch)
     if (make_lin_layout(P.N, P.K, P.M, P.tile, backward, P.flags).total > 0 && !P.ws) return ALST_ERR_NULL;
     if (P.K % 8 != 0 || P.M % 8 != 0) return ALST_ERR_ALIGN;
     const void* ptrs[] = {P.x, P.W, P.dy, P.y, P.dx, P.dW, P.ws};
