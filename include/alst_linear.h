@@ -11,10 +11,11 @@
  *
  * bf16 operands, fp32 accumulation; dW is accumulated over the tiles in fp32.  Conventions are
  * those of alst.h (device pointers, dense row-major, K and M multiples of 8, 16-byte aligned base
- * pointers, caller-owned workspace, asynchronous on `stream`, alst_status return values).  x, W
- * and dy are read as they are by every product (nothing is copied or transposed), so the forward
- * pass needs no workspace and the backward pass only the fp32 dW sums (4 M K bytes; none with
- * fp32 overwrite output, whose sums live in dW).  `workspace` may be NULL when none is needed.
+ * pointers, caller-owned workspace, asynchronous on `stream`, alst_status return values).  x and
+ * dy are read as they are by every product (no activation is copied or transposed), so the forward
+ * pass needs no workspace; the backward pass needs the fp32 dW sums (4 M K bytes; none with fp32
+ * overwrite output, whose sums live in dW) and, for M a multiple of 64, a bf16 copy of W transposed
+ * (2 M K bytes, made once per call).  `workspace` may be NULL when none is needed.
  */
 #ifndef ALST_LINEAR_H
 #define ALST_LINEAR_H
