@@ -50,6 +50,8 @@ CASES = [
     # 4 x 97 output blocks on 256 persistent workgroups: chains of two blocks (the second fetched
     # during the first one's last k-steps), chains of one, and padding block numbers in between
     ("chained_blocks", 1024, 384, 24832, 1024),
+    # 4 x 257 blocks: chains of four and five
+    ("long_chains", 1024, 256, 65792, 1024),
 ]
 
 
