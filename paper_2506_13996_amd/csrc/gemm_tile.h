@@ -668,8 +668,10 @@ typedef KMajorDirectT<false> MixedCore;
 // DirectCore: 4 wavefronts, global -> LDS DMA, aligned shapes only, both operands k-contiguous,
 // v_mfma_f32_16x16x32_bf16
 // ---------------------------------------------------------------------------------------------
-// The 16 x 16 x 32 form sustains about 5 % more than the 32 x 32 x 16 form on this chip under the
-// same power limit (measured with register-resident operands and in this kernel).
+// Against the same pipeline on the 32 x 32 x 16 form a plain product of the logits shape is 8 %
+// faster (16-row operand reads, half the address arithmetic per k-step; with register-resident
+// operands the two forms are level to 4 % apart).  It is the fastest of the cores, so products
+// over a weight's row index are run on it against a copy of the weight transposed once per call.
 struct DirectCore {
     static constexpr int kThreads = 256;
     static constexpr int kMT = 8;     // 16-wide c tiles per wavefront
