@@ -137,7 +137,7 @@ __device__ __forceinline__ const uint16_t* warm_row(int PR, int PC, const uint16
     if (l < nx) return X + (int64_t)(r0 + (tc % PC) * nx + l) * ldx;
     if (Y2) {
         bool valid;
-        return paired_row(Y, Y2, ldy, c0, (tr % PR) * ny + (l - nx), 0x7fffffff, valid);
+        return paired_row(Y, Y2, ldy, c0, (tr % PR) * ny + (l - nx), rows_y, valid);
     }
     const int row = c0 + (tr % PR) * ny + (l - nx);
     return Y + (int64_t)(row < rows_y ? row : rows_y - 1) * ldy;      // as the DMA: clamped to Y
@@ -712,7 +712,8 @@ struct DirectCore {
     // beyond it (the logits of a hidden size that is not whole k-steps, X being the library's own
     // zero-padded copy of the hidden rows): the chunks of a row of Y beyond K_y are read from the
     // row's last chunk (K_y a multiple of 8) and meet zeros of X.
-    // Y2: gated pair, see paired_row.
+    // Y2: gated pair, see paired_row; rows_y is then the rows of Y and of Y2, the rows of the pair
+    // beyond it are read from row 0 (finite data) and the caller discards those columns.
     // warm (see warm_row): the lane's warm-up row; warm_stride = elements between its line of one
     // k-step and the next.
     struct Block {
@@ -787,7 +788,7 @@ struct DirectCore {
                 xg[q] = b.X + (int64_t)(b.r0 + row) * b.ldx + kc * 8;
                 if (b.Y2) {                         // gated pair
                     bool valid;
-                    yg[q] = paired_row(b.Y, b.Y2, b.ldy, b.c0, row, 0x7fffffff, valid) + kc * 8;
+                    yg[q] = paired_row(b.Y, b.Y2, b.ldy, b.c0, row, b.rows_y, valid) + kc * 8;   // (missing rows: row 0)
                 } else {
                     const int yrow = b.c0 + row < b.rows_y ? b.c0 + row : b.rows_y - 1;    // (the clamp: see Block)
                     yg[q] = b.Y + (int64_t)yrow * b.ldy + kc * 8;

@@ -228,8 +228,11 @@ struct GatedParams {
     PatchGrid grid;
 };
 
-template <class Core, bool GUARD, bool BWD>
+// CGUARD: I ends inside the block's 128 columns (the unguarded core reads row 0 of Wg / Wu in place
+// of the missing rows; the epilogue skips those columns).
+template <class Core, bool GUARD, bool BWD, bool CGUARD = false>
 __global__ __launch_bounds__(Core::kThreads) void gated_kernel(const GatedParams p) {
+    constexpr bool kCheckCols = GUARD || CGUARD;
     constexpr int kMT = Core::kMT, kNT = Core::kNT;
     static_assert(kMT * Core::kTile == kGroupC, "a wavefront's 128 Y rows: 64 of Wg, then the same 64 of Wu");
     constexpr int kHalfMT = kMT / 2;       // accumulator tiles mt < kHalfMT hold g, tile mt + kHalfMT the u of the same elements
@@ -244,7 +247,7 @@ __global__ __launch_bounds__(Core::kThreads) void gated_kernel(const GatedParams
 
     const uint16_t* warm = Core::kCanGuard ? nullptr
                                            : warm_row(p.grid.PR, p.grid.PC, p.X, p.ldx, r0, tr, p.Wg,
-                                                      p.ldw, c0, tc, p.Wu);
+                                                      p.ldw, c0, tc, p.Wu, p.I);
     Core::template gemm<GUARD>(p.X, p.ldx, p.rows_x, p.Wg, p.ldw, p.I, p.K, r0, c0, smem, acc, warm,
                                kBlockK, p.Wu);
 
@@ -256,7 +259,7 @@ __global__ __launch_bounds__(Core::kThreads) void gated_kernel(const GatedParams
     unsigned char* const tw = smem + (threadIdx.x >> 6) * (32 * kTurnPitch);
     const int lrow = lp.lane >> 3, lcol = lp.lane & 7;             // 8 rows x 8 chunks of 16 B
     const int gc = (c0 >> 1) + lp.wc * 64 + lcol * 8;              // this lane's 8 columns of I
-    const bool col_ok = !GUARD || gc + 8 <= p.I;
+    const bool col_ok = !kCheckCols || gc + 8 <= p.I;
     const u32x4_t zero4 = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int nt = 0; nt < kNT; ++nt) {
@@ -272,7 +275,7 @@ __global__ __launch_bounds__(Core::kThreads) void gated_kernel(const GatedParams
             for (int it = 0; it < kTile / 8; ++it) {
                 const int row = it * 8 + lrow;
                 const u32x4_t val = *reinterpret_cast<const u32x4_t*>(tw + row * kTurnPitch + lcol * 16);
-                if (!GUARD || (row0 + row < p.rows_out && col_ok))
+                if (!kCheckCols || (row0 + row < p.rows_out && col_ok))
                     *reinterpret_cast<u32x4_t*>(dst + (int64_t)(row0 + row) * ld + gc) = val;
             }
         };
@@ -281,7 +284,7 @@ __global__ __launch_bounds__(Core::kThreads) void gated_kernel(const GatedParams
 #pragma unroll
             for (int it = 0; it < kTile / 8; ++it) {
                 const int row = it * 8 + lrow;
-                const bool ok = !GUARD || (row0 + row < p.rows_out && col_ok);
+                const bool ok = !kCheckCols || (row0 + row < p.rows_out && col_ok);
                 const u32x4_t val = ok ? *reinterpret_cast<const u32x4_t*>(p.da + (int64_t)(row0 + row) * p.I + gc)
                                        : zero4;
                 *reinterpret_cast<u32x4_t*>(tw + row * kTurnPitch + lcol * 16) = val;
@@ -390,6 +393,8 @@ static int prepare_mlp_kernels_on_current_device() {
     acc(allow_big_lds(gated_kernel<DirectCore, false, false>));
     acc(allow_big_lds(gated_kernel<StagedCore, true, false>));
     acc(allow_big_lds(gated_kernel<DirectCore, false, true>));
+    acc(allow_big_lds(gated_kernel<DirectCore, false, false, true>));
+    acc(allow_big_lds(gated_kernel<DirectCore, false, true, true>));
     acc(allow_big_lds(gated_kernel<StagedCore, true, true>));
     acc(allow_big_lds(wgrad_kernel<KMajorCore, false>));
     acc(allow_big_lds(wgrad_kernel<StagedKMajorCore, true>));
@@ -538,9 +543,18 @@ static int launch_gated(const MlpProblem& P, const uint16_t* x_t, int T_cur, int
     gp.da = da; gp.a = a; gp.dgu = dgu; gp.rows_out = Tr;
     gp.grid = choose_patches(Tr / kBlockR, (int)((P.I + 127) / 128));
     const int blocks = grid_for_patches(gp.grid.patches());
-    const bool direct = T_cur % kBlockR == 0 && P.I % 128 == 0 && P.H % kBlockK == 0;
+    // the unguarded core needs whole blocks of rows and whole k-steps; an I that ends inside a
+    // block's 128 columns is handled by its epilogue
+    const bool direct = T_cur % kBlockR == 0 && P.H % kBlockK == 0;
+    const bool cguard = P.I % 128 != 0;
     ProfScope pr(PROF_MLP_LINEAR, s);
-    if (direct && da)
+    if (direct && cguard && da)
+        hipLaunchKernelGGL((gated_kernel<DirectCore, false, true, true>), dim3((unsigned)blocks),
+                           dim3(DirectCore::kThreads), kLdsBytes, s, gp);
+    else if (direct && cguard)
+        hipLaunchKernelGGL((gated_kernel<DirectCore, false, false, true>), dim3((unsigned)blocks),
+                           dim3(DirectCore::kThreads), kLdsBytes, s, gp);
+    else if (direct && da)
         hipLaunchKernelGGL((gated_kernel<DirectCore, false, true>), dim3((unsigned)blocks),
                            dim3(DirectCore::kThreads), kLdsBytes, s, gp);
     else if (direct)

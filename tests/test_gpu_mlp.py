@@ -47,6 +47,10 @@ CASES = [
     # gradients take the whole k-steps on the unguarded core and the 12 rows left over on the other
     ("aligned_ragged_rows", 1100, 256, 512, 512),
     ("aligned_few_rows", 40, 256, 256, 64),       # fewer rows than one k-step
+    # whole blocks of rows and whole k-steps of H, but I ends inside a block's 128 columns (and is
+    # not whole k-steps): gate/up on the unguarded core with the column guard in its epilogue
+    ("intermediate_ends_inside_a_block", 768, 256, 328, 256),
+    ("intermediate_192", 512, 128, 192, 256),     # I a multiple of 64: the transposed-weight products too
 ]
 
 
