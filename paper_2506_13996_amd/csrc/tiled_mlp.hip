@@ -228,35 +228,21 @@ struct GatedParams {
     PatchGrid grid;
 };
 
-// CGUARD: I ends inside the block's 128 columns (the unguarded core reads row 0 of Wg / Wu in place
-// of the missing rows; the epilogue skips those columns).
-template <class Core, bool GUARD, bool BWD, bool CGUARD = false>
-__global__ __launch_bounds__(Core::kThreads) void gated_kernel(const GatedParams p) {
-    constexpr bool kCheckCols = GUARD || CGUARD;
+// The SwiGLU epilogue of a block whose accumulators hold g (tiles mt < kMT / 2) and u (tile mt + kMT / 2)
+// of the same elements.  CHECK: rows >= rows_out and 8-column chunks beyond I are neither read nor
+// written.  tw: this wavefront's LDS turn-around region (kTile rows of kTurnPitch bytes).
+template <class Core, bool BWD, bool CHECK>
+__device__ __forceinline__ void gated_epilogue(const GatedParams& p,
+                                               const typename Core::acc_t (&acc)[Core::kMT][Core::kNT],
+                                               int r0, int c0, unsigned char* tw) {
     constexpr int kMT = Core::kMT, kNT = Core::kNT;
-    static_assert(kMT * Core::kTile == kGroupC, "a wavefront's 128 Y rows: 64 of Wg, then the same 64 of Wu");
-    constexpr int kHalfMT = kMT / 2;       // accumulator tiles mt < kHalfMT hold g, tile mt + kHalfMT the u of the same elements
-    extern __shared__ __align__(16) unsigned char smem[];
-    int P, w, tr, tc;
-    patch_of_block(blockIdx.x, P, w);
-    if (P >= p.grid.patches() || !tile_in_patch(p.grid, P, w, tr, tc)) return;
-    const int r0 = tr * kBlockR, c0 = tc * kBlockC;      // c0 / 2 = first of the block's 128 columns of I
-
-    typename Core::acc_t acc[kMT][kNT];
-    zero_acc<Core>(acc);
-
-    const uint16_t* warm = Core::kCanGuard ? nullptr
-                                           : warm_row(p.grid.PR, p.grid.PC, p.X, p.ldx, r0, tr, p.Wg,
-                                                      p.ldw, c0, tc, p.Wu, p.I);
-    Core::template gemm<GUARD>(p.X, p.ldx, p.rows_x, p.Wg, p.ldw, p.I, p.K, r0, c0, smem, acc, warm,
-                               kBlockK, p.Wu);
-
+    constexpr int kHalfMT = kMT / 2;
+    constexpr bool kCheckCols = CHECK;
     // Per wavefront and accumulator column nt: kTile rows x 64 columns of I.  Everything that goes
     // to or comes from memory is turned around in the wavefront's own LDS region (as in
     // store_block_bf16) so that global accesses are whole 128-byte row segments.
     const typename Core::Lane lp;
     constexpr int kRuns = Core::kRuns, kTile = Core::kTile;
-    unsigned char* const tw = smem + (threadIdx.x >> 6) * (32 * kTurnPitch);
     const int lrow = lp.lane >> 3, lcol = lp.lane & 7;             // 8 rows x 8 chunks of 16 B
     const int gc = (c0 >> 1) + lp.wc * 64 + lcol * 8;              // this lane's 8 columns of I
     const bool col_ok = !kCheckCols || gc + 8 <= p.I;
@@ -317,6 +303,67 @@ __global__ __launch_bounds__(Core::kThreads) void gated_kernel(const GatedParams
             store_rows(ou, p.dgu + p.I, 2 * (int64_t)p.I);
         }
     }
+}
+
+// CGUARD: I ends inside the block's 128 columns (the unguarded core reads row 0 of Wg / Wu in place
+// of the missing rows; the epilogue skips those columns).
+template <class Core, bool GUARD, bool BWD, bool CGUARD = false>
+__global__ __launch_bounds__(Core::kThreads) void gated_kernel(const GatedParams p) {
+    constexpr int kMT = Core::kMT, kNT = Core::kNT;
+    static_assert(kMT * Core::kTile == kGroupC, "a wavefront's 128 Y rows: 64 of Wg, then the same 64 of Wu");
+    extern __shared__ __align__(16) unsigned char smem[];
+    int P, w, tr, tc;
+    patch_of_block(blockIdx.x, P, w);
+    if (P >= p.grid.patches() || !tile_in_patch(p.grid, P, w, tr, tc)) return;
+    const int r0 = tr * kBlockR, c0 = tc * kBlockC;      // c0 / 2 = first of the block's 128 columns of I
+
+    typename Core::acc_t acc[kMT][kNT];
+    zero_acc<Core>(acc);
+
+    const uint16_t* warm = Core::kCanGuard ? nullptr
+                                           : warm_row(p.grid.PR, p.grid.PC, p.X, p.ldx, r0, tr, p.Wg,
+                                                      p.ldw, c0, tc, p.Wu, p.I);
+    Core::template gemm<GUARD>(p.X, p.ldx, p.rows_x, p.Wg, p.ldw, p.I, p.K, r0, c0, smem, acc, warm,
+                               kBlockK, p.Wu);
+    gated_epilogue<Core, BWD, GUARD || CGUARD>(p, acc, r0, c0, smem + (threadIdx.x >> 6) * (32 * kTurnPitch));
+}
+
+// The same on persistent workgroups of the unguarded core (see linear_chain_kernel): K = H a
+// multiple of 128 and >= 256.  total = the launch's block numbers.
+template <bool BWD, bool CGUARD>
+__global__ __launch_bounds__(DirectCore::kThreads) void gated_chain_kernel(const GatedParams p, int total) {
+    typedef DirectCore Core;
+    extern __shared__ __align__(16) unsigned char smem[];
+    auto next_block = [&](int bid, Core::Block& blk) {
+        for (; bid < total; bid += gridDim.x) {
+            int P, w, tr, tc;
+            patch_of_block(bid, P, w);
+            if (P >= p.grid.patches() || !tile_in_patch(p.grid, P, w, tr, tc)) continue;
+            const int r0 = tr * kBlockR, c0 = tc * kBlockC;
+            blk = {uniform(p.X), p.ldx, uniform(p.Wg), p.ldw, p.I, p.K, uniform(r0), uniform(c0),
+                   warm_row(p.grid.PR, p.grid.PC, p.X, p.ldx, r0, tr, p.Wg, p.ldw, c0, tc, p.Wu, p.I), kBlockK,
+                   uniform(p.Wu), -1};
+            return uniform(bid);
+        }
+        return -1;
+    };
+    Core::Block cur, nxt;
+    int bid = next_block(blockIdx.x, cur);
+    if (bid < 0) return;
+    Core::Pipe<false> pipe(smem);
+    pipe.start(cur);
+    unsigned char* const tw = smem + kChainTurnOffset + (threadIdx.x >> 6) * (Core::kTile * kTurnPitch);
+    while (bid >= 0) {
+        const int nbid = next_block(bid + gridDim.x, nxt);
+        if (nbid < 0) nxt = cur;        // the last block: the chain's fetch goes to this block again, unused
+        typename Core::acc_t acc[Core::kMT][Core::kNT];
+        zero_acc<Core>(acc);
+        pipe.run(cur, nxt, acc);
+        gated_epilogue<Core, BWD, CGUARD>(p, acc, cur.r0, cur.c0, tw);
+        cur = nxt;
+        bid = nbid;
+    }
+    pipe.finish();
 }
 
 struct WgradParams {
@@ -395,6 +442,10 @@ static int prepare_mlp_kernels_on_current_device() {
     acc(allow_big_lds(gated_kernel<DirectCore, false, true>));
     acc(allow_big_lds(gated_kernel<DirectCore, false, false, true>));
     acc(allow_big_lds(gated_kernel<DirectCore, false, true, true>));
+    acc(allow_big_lds(gated_chain_kernel<false, false>, kChainLdsBytes));
+    acc(allow_big_lds(gated_chain_kernel<true, false>, kChainLdsBytes));
+    acc(allow_big_lds(gated_chain_kernel<false, true>, kChainLdsBytes));
+    acc(allow_big_lds(gated_chain_kernel<true, true>, kChainLdsBytes));
     acc(allow_big_lds(gated_kernel<StagedCore, true, true>));
     acc(allow_big_lds(wgrad_kernel<KMajorCore, false>));
     acc(allow_big_lds(wgrad_kernel<StagedKMajorCore, true>));
@@ -547,8 +598,16 @@ static int launch_gated(const MlpProblem& P, const uint16_t* x_t, int T_cur, int
     // block's 128 columns is handled by its epilogue
     const bool direct = T_cur % kBlockR == 0 && P.H % kBlockK == 0;
     const bool cguard = P.I % 128 != 0;
+    // persistent workgroups that fetch their next block early: whole pairs of k-steps
+    const bool chain = direct && P.H % (2 * kBlockK) == 0 && P.H >= 4 * kBlockK;
     ProfScope pr(PROF_MLP_LINEAR, s);
-    if (direct && cguard && da)
+    if (chain) {
+        const dim3 grid((unsigned)std::min(blocks, persistent_grid())), block(DirectCore::kThreads);
+        if (cguard && da) hipLaunchKernelGGL((gated_chain_kernel<true, true>), grid, block, kChainLdsBytes, s, gp, blocks);
+        else if (cguard) hipLaunchKernelGGL((gated_chain_kernel<false, true>), grid, block, kChainLdsBytes, s, gp, blocks);
+        else if (da) hipLaunchKernelGGL((gated_chain_kernel<true, false>), grid, block, kChainLdsBytes, s, gp, blocks);
+        else hipLaunchKernelGGL((gated_chain_kernel<false, false>), grid, block, kChainLdsBytes, s, gp, blocks);
+    } else if (direct && cguard && da)
         hipLaunchKernelGGL((gated_kernel<DirectCore, false, true, true>), dim3((unsigned)blocks),
                            dim3(DirectCore::kThreads), kLdsBytes, s, gp);
     else if (direct && cguard)
