@@ -32,7 +32,7 @@ MI355X_BF16_MFMA_PEAK_TFLOPS = 2500.0      # dense bf16, vendor figure
 # and says so in `traffic_source`; for any other workload or tile the field is null.
 TRAFFIC_PROFILE = "profiles/bench_llama8b_128k_hbm_traffic.txt"
 PROFILED_TRAFFIC_BYTES_PER_LAUNCH = {
-    "llama8b_128k": {"logits_gemm": 6.806e9, "dhidden_gemm": 5.907e9, "dw_gemm": 25.269e9},
+    "llama8b_128k": {"logits_gemm": 6.806e9, "dhidden_gemm": 5.916e9, "dw_gemm": 25.573e9},
 }
 OTHER_STEPS, OTHER_WARMUP = 3, 1
 
